@@ -1,0 +1,34 @@
+"""CPU oracle for the TriSpec verification pass.  TEST INFRASTRUCTURE ONLY.
+
+Plain numpy, fp64, no blocking, no fusion: the definition written out so it
+can be checked against the paper by eye.  Only tests, the smoke check and the
+bench's cpu_baseline leg may import this package; the product path (the HIP
+library and its Python binding) never does, and shares no code with it.
+
+Pins (tests/test_oracle_*.py): brute-force sequential autoregressive forwards,
+an independent torch-CPU forward, closed forms for RMSNorm / RoPE / softmax
+statistics, the set-min definitions of tau_a and tau_m (paper Eq. 7, Eq. 9)
+enumerated exhaustively, and the invariants at lambda = 0 and lambda > 1.
+No function here is "parity unpinned".
+"""
+from .forward import (  # noqa: F401
+    OracleWeights,
+    bf16_round,
+    rmsnorm,
+    rope_angles,
+    apply_rope,
+    causal_forward,
+    verify_forward,
+    ancestor_sets,
+)
+from .decision import (  # noqa: F401
+    CRIT_MARGIN,
+    CRIT_TOP1,
+    node_stats,
+    decide,
+    chain_tau_a,
+    chain_tau_m,
+    chain_round_output,
+    tie_flags,
+    prune_reroot,
+)

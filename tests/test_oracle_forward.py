@@ -1,0 +1,147 @@
+"""Pins for the oracle's forward passes.
+
+* tree-masked cached pass == brute-force sequential causal forwards (paper Eq. 2 / Eq. 5:
+  one parallel pass returns the k+1 next-token distributions);
+* textbook causal forward == an independent forward assembled from torch library routines;
+* structural invariants: cache split, non-ancestor independence, relabelling, chain == path.
+"""
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from oracle import OracleWeights, causal_forward, verify_forward
+from workloads import (ModelShape, WeightSource, gen_chain, gen_context_tokens, gen_draft_tokens,
+                       gen_tree, tree_depths)
+from helpers import MICRO, oracle_weights, path_to, prefill
+
+VARIANTS = [
+    MICRO,
+    MICRO.with_(name="mha", n_q_heads=4, n_kv_heads=4),
+    MICRO.with_(name="mqa", n_q_heads=4, n_kv_heads=1),
+    MICRO.with_(name="wide_q", n_q_heads=6, n_kv_heads=2, head_dim=16),   # nq*d != hidden
+    MICRO.with_(name="bf16", dtype="bf16"),
+    MICRO.with_(name="three_layers", n_layers=3, rope_base=5e5),
+]
+
+
+def torch_causal_forward(shape, seed, tokens, positions):
+    """Independent fp64 forward built from torch library routines (f32 storage mode)."""
+    ws = WeightSource(shape, seed)
+    t = lambda name, l=0: torch.from_numpy(ws.get(name, l).astype(np.float64))
+    T = len(tokens)
+    nq, nkv, d = shape.n_q_heads, shape.n_kv_heads, shape.head_dim
+    x = F.embedding(torch.as_tensor(np.asarray(tokens), dtype=torch.long), t("embed"))
+    inv = torch.tensor(shape.rope_base, dtype=torch.float64) ** (-torch.arange(0, d, 2, dtype=torch.float64) / d)
+    ang = torch.as_tensor(np.asarray(positions), dtype=torch.float64)[:, None] * inv[None]
+    rot = torch.polar(torch.ones_like(ang), ang)  # e^{i angle}, [T, d/2]
+
+    def rope(u):  # [T, heads, d]; pairs (j, j+d/2) as complex numbers
+        z = torch.complex(u[..., : d // 2], u[..., d // 2:]) * rot[:, None, :]
+        return torch.cat([z.real, z.imag], dim=-1)
+
+    for l in range(shape.n_layers):
+        h = F.rms_norm(x, (shape.hidden,), t("norm_attn", l), shape.rms_eps)
+        q = rope(F.linear(h, t("wq", l)).view(T, nq, d)).transpose(0, 1)   # [nq, T, d]
+        k = rope(F.linear(h, t("wk", l)).view(T, nkv, d)).transpose(0, 1)
+        v = F.linear(h, t("wv", l)).view(T, nkv, d).transpose(0, 1)
+        k = k.repeat_interleave(nq // nkv, dim=0)
+        v = v.repeat_interleave(nq // nkv, dim=0)
+        o = F.scaled_dot_product_attention(q[None], k[None], v[None], is_causal=True)[0]
+        x = x + F.linear(o.transpose(0, 1).reshape(T, nq * d), t("wo", l))
+        h = F.rms_norm(x, (shape.hidden,), t("norm_ffn", l), shape.rms_eps)
+        x = x + F.linear(F.silu(F.linear(h, t("w_gate", l))) * F.linear(h, t("w_up", l)), t("w_down", l))
+    h = F.rms_norm(x, (shape.hidden,), t("final_norm"), shape.rms_eps)
+    return F.linear(h, t("lm_head")).numpy()
+
+
+@pytest.mark.parametrize("shape", [v for v in VARIANTS if v.dtype == "f32"], ids=lambda s: s.name)
+def test_causal_forward_equals_torch_library_forward(shape):
+    seed = 11
+    toks = gen_context_tokens(shape.vocab, 13, seed)
+    pos = np.arange(13) + 5
+    got = causal_forward(oracle_weights(shape, seed), shape, toks, positions=pos)["logits"]
+    want = torch_causal_forward(shape, seed, toks, pos)
+    assert np.max(np.abs(got - want)) < 1e-10
+
+
+@pytest.mark.parametrize("shape", VARIANTS, ids=lambda s: s.name)
+def test_tree_pass_equals_sequential_autoregressive_forwards(shape):
+    seed, C, M = 5, 9, 11
+    W = oracle_weights(shape, seed)
+    ctx = gen_context_tokens(shape.vocab, C, seed)
+    parents = gen_tree(M, 4, 3, seed)
+    toks = gen_draft_tokens(parents, shape.vocab, seed)
+    pos = C + tree_depths(parents)
+    Kc, Vc = prefill(shape, seed, ctx)
+    out = verify_forward(W, shape, Kc, Vc, toks, parents, pos)
+    for i in range(M):
+        seq = list(ctx) + [int(toks[j]) for j in path_to(parents, i)]
+        ref = causal_forward(W, shape, seq, last_only=True)
+        assert np.max(np.abs(out["logits"][i] - ref["logits"][0])) < 1e-9, i
+        # what the pass appends to the cache for node i is what a prefill would have stored
+        assert np.max(np.abs(out["k_new"][:, :, i] - ref["K"][:, :, -1])) < 1e-10
+        assert np.max(np.abs(out["v_new"][:, :, i] - ref["V"][:, :, -1])) < 1e-10
+
+
+def test_cache_split_invariance():
+    """(C=12, chain of 6) == (C=8, the last 4 context tokens as extra chain nodes) == (C=0, all nodes)."""
+    shape, seed = MICRO, 3
+    W = oracle_weights(shape, seed)
+    ctx = gen_context_tokens(shape.vocab, 12, seed)
+    chain = gen_draft_tokens(gen_chain(6), shape.vocab, seed)
+    Kc, Vc = prefill(shape, seed, ctx)
+    a = verify_forward(W, shape, Kc, Vc, chain, gen_chain(6), 12 + np.arange(6))["logits"]
+    Kc8, Vc8 = prefill(shape, seed, ctx[:8])
+    toks_b = np.concatenate([ctx[8:], chain])
+    b = verify_forward(W, shape, Kc8, Vc8, toks_b, gen_chain(10), 8 + np.arange(10))["logits"]
+    K0, V0 = prefill(shape, seed, ctx[:0])
+    toks_c = np.concatenate([ctx, chain])
+    c = verify_forward(W, shape, K0, V0, toks_c, gen_chain(18), np.arange(18))["logits"]
+    assert np.max(np.abs(a - b[4:])) < 1e-10
+    assert np.max(np.abs(a - c[12:])) < 1e-10
+
+
+def test_non_ancestor_independence_and_relabelling():
+    shape, seed, C, M = MICRO, 8, 6, 12
+    W = oracle_weights(shape, seed)
+    ctx = gen_context_tokens(shape.vocab, C, seed)
+    Kc, Vc = prefill(shape, seed, ctx)
+    parents = gen_tree(M, 4, 3, seed)
+    toks = gen_draft_tokens(parents, shape.vocab, seed)
+    pos = C + tree_depths(parents)
+    base = verify_forward(W, shape, Kc, Vc, toks, parents, pos)["logits"]
+    for j in range(1, M):
+        t2 = toks.copy(); t2[j] = (t2[j] + 1) % shape.vocab
+        out = verify_forward(W, shape, Kc, Vc, t2, parents, pos)["logits"]
+        for i in range(M):
+            if j in path_to(parents, i):
+                assert not np.array_equal(out[i], base[i])
+            else:
+                assert np.array_equal(out[i], base[i]), (i, j)
+    # another topological order permutes outputs only
+    g = np.random.default_rng(0)
+    keys = tree_depths(parents) + g.uniform(0, 0.9, M)  # random order within a level
+    order = np.argsort(keys, kind="stable")
+    new_id = np.empty(M, dtype=int); new_id[order] = np.arange(M)
+    p2 = np.array([-1 if parents[o] < 0 else new_id[parents[o]] for o in order])
+    out2 = verify_forward(W, shape, Kc, Vc, toks[order], p2, pos[order])["logits"]
+    assert np.max(np.abs(out2 - base[order])) < 1e-12
+
+
+def test_single_path_tree_equals_chain_and_position_shift():
+    shape, seed, C = MICRO, 21, 7
+    W = oracle_weights(shape, seed)
+    ctx = gen_context_tokens(shape.vocab, C, seed)
+    Kc, Vc = prefill(shape, seed, ctx)
+    parents = gen_tree(9, 3, 3, seed)
+    toks = gen_draft_tokens(parents, shape.vocab, seed)
+    full = verify_forward(W, shape, Kc, Vc, toks, parents, C + tree_depths(parents))["logits"]
+    leaf = 8
+    p = path_to(parents, leaf)
+    chain = verify_forward(W, shape, Kc, Vc, toks[p], gen_chain(len(p)), C + np.arange(len(p)))["logits"]
+    assert np.max(np.abs(chain - full[p])) < 1e-10
+    # rotary shift invariance: everything moved by +1000 positions, cache re-prefilled there
+    Ks, Vs = prefill(shape, seed, ctx, start_pos=1000)
+    sh = verify_forward(W, shape, Ks, Vs, toks, parents, 1000 + C + tree_depths(parents))["logits"]
+    assert np.max(np.abs(sh - full)) < 1e-8
