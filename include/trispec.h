@@ -1,0 +1,222 @@
+/*
+ * trispec.h — C ABI of the MI355X (gfx950) verification pass of TriSpec,
+ * ternary speculative decoding with a lightweight proxy verifier.
+ *
+ * One call, trispec_verify(), runs what the paper calls Verify(M, X + [x_1..x_k]):
+ * a single parallel forward of a decoder-only verifier (the proxy M_p, Sec. 3.2
+ * Eq. 5, or the target M_t, Sec. 2.1 Eq. 2 / Sec. 3.2 Eq. 10) over a chain or
+ * tree of drafted tokens against an existing KV cache, fused with the per-token
+ * decision of Sec. 3.2: greedy acceptance s_i and tau_a (Eq. 6 greedy form,
+ * Eq. 7), the top-1/top-2 margin predicate g and the trusted prefix tau_m
+ * (Eq. 8, Eq. 9), and the routing into Case I (proxy finishes the round) or
+ * Case II (escalate to the target).
+ *
+ * Conventions
+ *  - Plain C.  Every call returns 0 (TRISPEC_OK) or a negative TRISPEC_E* code;
+ *    nothing throws or aborts across this boundary.
+ *  - "device" pointers are HIP device memory owned by the caller; "host" pointers
+ *    are ordinary host memory.  The library owns only small host descriptors.
+ *  - trispec_verify() / trispec_decide() allocate nothing, never synchronise
+ *    with the host, and enqueue all work on the caller's stream; results land in
+ *    caller-owned device buffers when the stream reaches them.
+ *  - Matrices are row-major [out, in] (y = x W^T), dtype per trispec_model_config.
+ *  - Node order: node 0 is the root (the last committed token, whose KV is not in
+ *    the cache yet); parents[i] < i; M = n_nodes <= TRISPEC_MAX_NODES per sequence.
+ */
+#ifndef TRISPEC_H
+#define TRISPEC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TRISPEC_MAX_NODES 64   /* nodes per sequence (ancestor mask = one 64-bit word) */
+#define TRISPEC_MAX_BATCH 8
+#define TRISPEC_MAX_ROWS 256   /* batch * n_nodes */
+
+enum {
+  TRISPEC_OK = 0,
+  TRISPEC_ENULL = -1,        /* a required pointer is NULL */
+  TRISPEC_ESHAPE = -2,       /* model shape not supported by the kernels */
+  TRISPEC_ENODES = -3,       /* n_nodes / batch out of range */
+  TRISPEC_ETREE = -4,        /* parents[] is not a topologically ordered tree */
+  TRISPEC_EFORCED = -5,      /* n_forced out of range or forced nodes are not a chain */
+  TRISPEC_ECAPACITY = -6,    /* ctx_len + n_nodes exceeds the cache capacity */
+  TRISPEC_EWORKSPACE = -7,   /* workspace missing, misaligned or too small */
+  TRISPEC_EARG = -8,         /* any other invalid argument (criterion, threshold NaN, ...) */
+  TRISPEC_EMISMATCH = -9,    /* kv cache was created for another model / batch */
+  TRISPEC_ELAUNCH = -10      /* the HIP runtime refused a launch (hipGetLastError) */
+};
+
+enum { TRISPEC_F32 = 0, TRISPEC_BF16 = 1 };
+
+/* Trust predicate g (Sec. 3.2 Eq. 8; alternatives in Sec. 4.3 "Routing Criteria"). */
+enum {
+  TRISPEC_CRIT_MARGIN = 0,   /* g = 1{ top1(p) - top2(p) >= threshold }  (the paper's default) */
+  TRISPEC_CRIT_TOP1 = 1      /* g = 1{ top1(p) >= threshold }            (max-softmax confidence) */
+};
+
+typedef struct {             /* plain data, copied by trispec_model_create */
+  int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
+  int32_t dtype;             /* TRISPEC_F32 | TRISPEC_BF16: weights, KV cache, matmul operands */
+  float rms_eps;
+  float rope_base;
+} trispec_model_config;
+
+typedef struct {             /* device pointers into caller-owned memory */
+  const void *embed;         /* [vocab, hidden] */
+  const void *lm_head;       /* [vocab, hidden] (may alias embed) */
+  const void *final_norm;    /* [hidden] */
+  /* host arrays of n_layers device pointers each: */
+  const void *const *wq;     /* [n_q_heads*head_dim, hidden] */
+  const void *const *wk;     /* [n_kv_heads*head_dim, hidden] */
+  const void *const *wv;     /* [n_kv_heads*head_dim, hidden] */
+  const void *const *wo;     /* [hidden, n_q_heads*head_dim] */
+  const void *const *w_gate; /* [ffn, hidden] */
+  const void *const *w_up;   /* [ffn, hidden] */
+  const void *const *w_down; /* [hidden, ffn] */
+  const void *const *norm_attn; /* [hidden] */
+  const void *const *norm_ffn;  /* [hidden] */
+} trispec_weights;
+
+typedef struct trispec_model trispec_model;
+typedef struct trispec_kv trispec_kv;
+typedef struct trispec_timer trispec_timer;
+
+/*
+ * The verifier M_p or M_t (Sec. 3 intro): a pre-norm decoder with RMSNorm, rotary
+ * position embedding (rotate-half pairing (j, j + head_dim/2), angle
+ * position * rope_base^(-2j/head_dim)), grouped-query attention and a SwiGLU FFN.
+ * Copies the config and the pointer tables (not the weights); the weights must
+ * outlive the model.  Makes no HIP call.
+ * Supported: head_dim in {64, 128}; n_q_heads a multiple of n_kv_heads;
+ * bf16 additionally needs hidden, ffn and n_q_heads*head_dim multiples of 64 and
+ * n_kv_heads*head_dim a multiple of 32.
+ * Errors: TRISPEC_ENULL, TRISPEC_ESHAPE.
+ */
+int trispec_model_create(const trispec_model_config *cfg, const trispec_weights *w,
+                         trispec_model **out);
+int trispec_model_destroy(trispec_model *m);
+
+/*
+ * KV cache of the prefix X (Sec. 2.1: the pass conditions on X).  Caller-owned
+ * device buffers, both of trispec_kv_bytes() bytes, dtype of the model:
+ *   K: [n_layers][batch][n_kv_heads][capacity][head_dim]   keys after rotary embedding
+ *   V: [n_layers][batch][n_kv_heads][head_dim][capacity]   values, TRANSPOSED
+ *      (position-contiguous, so the P.V product reads matrix-core operands directly)
+ * capacity must be a multiple of 64.  ctx_len[b] (host, [batch]) = tokens already cached.
+ * trispec_verify writes the draft nodes' K/V into slots [ctx_len, ctx_len + n_nodes)
+ * and does not advance ctx_len, so a verify call is repeatable.
+ * Errors: TRISPEC_ENULL, TRISPEC_ENODES (batch), TRISPEC_ECAPACITY.
+ */
+int trispec_kv_bytes(const trispec_model *m, int32_t batch, int32_t capacity, size_t *bytes);
+int trispec_kv_create(const trispec_model *m, void *k_dev, void *v_dev, int32_t batch,
+                      int32_t capacity, trispec_kv **out);
+int trispec_kv_set_len(trispec_kv *kv, const int32_t *ctx_len_host);
+int trispec_kv_destroy(trispec_kv *kv);
+
+/* Device scratch needed by trispec_verify for up to `batch` sequences of up to
+ * `max_nodes` nodes (256-byte aligned buffer).  Errors: TRISPEC_ENULL, TRISPEC_ENODES. */
+int trispec_workspace_bytes(const trispec_model *m, int32_t batch, int32_t max_nodes,
+                            size_t *bytes);
+
+typedef struct {
+  int32_t criterion;         /* TRISPEC_CRIT_* */
+  int32_t n_forced;          /* >= 1: nodes 0..n_forced-1 are a chain of already approved
+                                tokens (Case II re-rooting, Eq. 10); the walk starts at
+                                node n_forced-1 and forced nodes do not count as accepted */
+  void *workspace;           /* device */
+  size_t workspace_bytes;
+  float *debug_logits;       /* optional device [batch, n_nodes, vocab] fp32; NULL on the hot path */
+  void *stream;              /* hipStream_t; NULL = the default stream */
+  trispec_timer *timer;      /* optional per-kernel timer (measurement only); NULL on the hot path */
+} trispec_verify_opts;
+
+#define TRISPEC_PATH_STRIDE (TRISPEC_MAX_NODES)
+
+typedef struct {             /* device pointers, caller-owned; any may be NULL to skip it */
+  int32_t *accepted_len;     /* [batch]  min(tau_a, tau_m): approved draft tokens (Eq. 7, Eq. 9) */
+  int32_t *token;            /* [batch]  Case I: the verifier's own token x_{tau_a+1} (correction or
+                                         bonus); Case II: -1 */
+  int32_t *escalate;         /* [batch]  1 iff tau_a >= tau_m (Case II: hand over to the target) */
+  int32_t *path;             /* [batch, TRISPEC_PATH_STRIDE] node ids v_0..v_len of the approved
+                                         path, then -1 */
+  int32_t *argmax;           /* [batch, n_nodes] verifier top-1 token at each node */
+  float *confidence;         /* [batch, n_nodes] top-1 softmax probability */
+  float *margin;             /* [batch, n_nodes] top-1 minus top-2 probability (Eq. 8) */
+  int32_t *status;           /* [1] device-side error bits: 1 = a draft token id outside [0, vocab) */
+} trispec_verify_out;
+
+/*
+ * One verification pass + decision (Sec. 3.2; Algorithm 1 "Verify" and the routing
+ * that follows it).
+ *   draft_tokens  device [batch, n_nodes]  token of each node (node 0 = root)
+ *   tree_parents  host   [batch, n_nodes]  parents[0] = -1, 0 <= parents[i] < i
+ *   positions     device [batch, n_nodes]  absolute rotary position (ctx_len + depth)
+ *   threshold     lambda of Eq. 8.  0 => every node trusted => never escalates =>
+ *                 the standard greedy acceptance of a target pass.
+ * Node i attends to cache slots [0, ctx_len) and to the draft nodes on its root
+ * path (itself included).  The distribution p_{j+1} of the paper is the one emitted
+ * at path node v_j; the walk tests g(p_{j+1}) BEFORE looking for the child that
+ * matches argmax p_{j+1}, because tau_a = tau_m is Case II.  Duplicate sibling
+ * tokens: lowest node id wins.  Equal top logits: lowest token id is the argmax and
+ * the margin is 0.
+ * Errors (all detected on the host before anything is enqueued): TRISPEC_ENULL,
+ * TRISPEC_ENODES, TRISPEC_ETREE, TRISPEC_EFORCED, TRISPEC_ECAPACITY,
+ * TRISPEC_EWORKSPACE, TRISPEC_EARG, TRISPEC_EMISMATCH; TRISPEC_ELAUNCH afterwards.
+ */
+int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens,
+                   const int32_t *tree_parents, const int32_t *positions, int32_t n_nodes,
+                   float threshold, const trispec_verify_opts *opts,
+                   const trispec_verify_out *out);
+
+/*
+ * Re-run only the decision (Eq. 7-9 and routing) from the per-node statistics the
+ * last trispec_verify left in this workspace — threshold / criterion sweeps.
+ * batch / n_nodes / workspace must be those of that verify call (the statistics are found
+ * by offset); calling it on a workspace no verify has filled yields unspecified decisions.
+ * Same argument meaning and host-side errors as trispec_verify.
+ */
+int trispec_decide(trispec_model *m, int32_t batch, const int32_t *draft_tokens,
+                   const int32_t *tree_parents, int32_t n_nodes, float threshold,
+                   const trispec_verify_opts *opts, const trispec_verify_out *out);
+
+/*
+ * Measurement aid: HIP events recorded on the pass's own stream around every launch of one
+ * kernel class, so a benchmark can price that kernel against the HBM roofline.
+ *   TRISPEC_K_GEMM  the weight-streaming projection / FFN matmul (4 launches per layer)
+ *   TRISPEC_K_HEAD  the fused LM-head + softmax-statistics kernel (1 launch per pass)
+ *   TRISPEC_K_ATTN  the tree-masked attention kernel (1 launch per layer)
+ * create/destroy make HIP event calls (not for the hot path).  read() needs the stream to be
+ * idle (caller synchronises); it returns the number of timed launches since the last reset,
+ * their summed duration and the summed algorithmic HBM bytes of those launches (weights or
+ * K/V read once).  Launches beyond `capacity` are not timed.
+ * Errors: TRISPEC_ENULL, TRISPEC_EARG, TRISPEC_ELAUNCH (event call failed).
+ */
+enum { TRISPEC_K_GEMM = 0, TRISPEC_K_HEAD = 1, TRISPEC_K_ATTN = 2 };
+int trispec_timer_create(int32_t kernel_class, int32_t capacity, trispec_timer **out);
+int trispec_timer_reset(trispec_timer *t);
+int trispec_timer_read(trispec_timer *t, int32_t *n_launches, double *total_ms, double *total_bytes);
+int trispec_timer_destroy(trispec_timer *t);
+
+/* Test hook: byte offset and size, inside the workspace of a verify call with these
+ * (batch, n_nodes), of a named intermediate of the LAST layer ("x" residual stream fp32,
+ * "h" normalised operand, "q", "attn_out", "act", "node_l1", "node_l2", "node_sum",
+ * "node_idx").  Errors: TRISPEC_ENULL, TRISPEC_ENODES, TRISPEC_EARG (unknown name). */
+int trispec_workspace_region(const trispec_model *m, int32_t batch, int32_t n_nodes,
+                             const char *name, size_t *offset, size_t *bytes);
+
+/* Algorithmic HBM bytes of one verify pass at this shape: layer weights once + LM head
+ * once + context K/V once + draft K/V written (the figure the roofline is priced on). */
+int trispec_pass_bytes(const trispec_model *m, int32_t batch, int32_t n_nodes,
+                       const int32_t *ctx_len_host, double *bytes);
+
+const char *trispec_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TRISPEC_H */

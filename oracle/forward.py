@@ -13,12 +13,14 @@ fixes.  Two functions compute it:
 * `verify_forward` — the same model over the M tree nodes against a given KV
   cache; node i attends to the whole context and to its ancestors and itself.
 
-Storage modes.  "f32": nothing is rounded (all fp64).  "bf16": the values a
-bf16 model stores or feeds to a matrix multiply are rounded to bf16
-(round-to-nearest-even) at fixed points — post-norm activations, post-rotary
-q and k, v, the attention output, the SiLU(gate)*up product — while sums,
-norms, rotary math, softmax and logits stay unrounded.  Attention
-probabilities are NOT rounded.
+Storage modes.  "f32": nothing is rounded (all fp64).  "bf16": what the model
+STORES is bf16 — the weights (already rounded by whoever supplies them) and the
+KV cache: keys (after the rotary embedding) and values are rounded to bf16
+(round-to-nearest-even) where they ENTER the cache, so whatever a pass reads
+back from the cache (the context) is rounded, while the tokens of the pass
+itself attend to each other with their unrounded keys and values.  Nothing
+else is rounded: activations, attention probabilities, sums, norms, rotary
+math, softmax and logits stay fp64.
 """
 from __future__ import annotations
 
@@ -103,12 +105,17 @@ def _lm_head(h: np.ndarray, W: OracleWeights, vocab: int) -> np.ndarray:
 
 def causal_forward(W: OracleWeights, shape, tokens: Sequence[int],
                    positions: Optional[Sequence[int]] = None,
-                   last_only: bool = False) -> Dict[str, np.ndarray]:
+                   last_only: bool = False, n_cached: int = 0) -> Dict[str, np.ndarray]:
     """Plain causal decoder forward over tokens[0..T-1].
 
     Returns logits [T, V] (or [1, V] for the last row if last_only), and the
     per-layer post-rotary keys / values K, V: [L, n_kv, T, d] as a cache would
-    store them.
+    store them (rounded to the storage type).
+
+    n_cached models a cache boundary for the bf16 storage mode: tokens [0, n_cached)
+    were processed by an earlier pass, so queries at t >= n_cached see those keys /
+    values as the cache holds them (rounded); every other (query, key) pair belongs to
+    one pass and uses unrounded values.  With f32 storage it has no effect.
     """
     rnd = bf16_round if shape.dtype == "bf16" else _identity
     T = len(tokens)
@@ -120,28 +127,30 @@ def causal_forward(W: OracleWeights, shape, tokens: Sequence[int],
     Ks = np.empty((shape.n_layers, nkv, T, d))
     Vs = np.empty((shape.n_layers, nkv, T, d))
     for l in range(shape.n_layers):
-        h = rnd(rmsnorm(x, W("norm_attn", l), shape.rms_eps))
+        h = rmsnorm(x, W("norm_attn", l), shape.rms_eps)
         q = (h @ W("wq", l).T).reshape(T, nq, d)
         k = (h @ W("wk", l).T).reshape(T, nkv, d)
         v = (h @ W("wv", l).T).reshape(T, nkv, d)
-        q = rnd(apply_rope(q, ang))
-        k = rnd(apply_rope(k, ang))
-        v = rnd(v)
-        Ks[l] = k.transpose(1, 0, 2)
-        Vs[l] = v.transpose(1, 0, 2)
+        q = apply_rope(q, ang)
+        k = apply_rope(k, ang)
+        Ks[l] = rnd(k).transpose(1, 0, 2)
+        Vs[l] = rnd(v).transpose(1, 0, 2)
         o = np.zeros((T, nq, d))
         for t in range(T):
+            nc = n_cached if t >= n_cached else 0     # keys this query reads back from the cache
+            kt = np.concatenate([rnd(k[:nc]), k[nc: t + 1]], axis=0)
+            vt = np.concatenate([rnd(v[:nc]), v[nc: t + 1]], axis=0)
             for a in range(nq):
                 g = a // group
-                s = (k[: t + 1, g] @ q[t, a]) / np.sqrt(d)
-                o[t, a] = _softmax(s) @ v[: t + 1, g]
-        x = x + rnd(o.reshape(T, nq * d)) @ W("wo", l).T
-        h = rnd(rmsnorm(x, W("norm_ffn", l), shape.rms_eps))
-        act = rnd(_silu(h @ W("w_gate", l).T) * (h @ W("w_up", l).T))
+                s = (kt[:, g] @ q[t, a]) / np.sqrt(d)
+                o[t, a] = _softmax(s) @ vt[:, g]
+        x = x + o.reshape(T, nq * d) @ W("wo", l).T
+        h = rmsnorm(x, W("norm_ffn", l), shape.rms_eps)
+        act = _silu(h @ W("w_gate", l).T) * (h @ W("w_up", l).T)
         x = x + act @ W("w_down", l).T
     if last_only:
         x = x[-1:]
-    hf = rnd(rmsnorm(x, W("final_norm"), shape.rms_eps))
+    hf = rmsnorm(x, W("final_norm"), shape.rms_eps)
     return {"logits": _lm_head(hf, W, shape.vocab), "K": Ks, "V": Vs}
 
 
@@ -164,7 +173,7 @@ def ancestor_sets(parents: Sequence[int]) -> List[List[int]]:
 
 def verify_forward(W: OracleWeights, shape, k_ctx, v_ctx, tokens: Sequence[int],
                    parents: Sequence[int], positions: Sequence[int],
-                   keep_hidden: bool = False) -> Dict[str, np.ndarray]:
+                   keep_hidden: bool = False, trace: Optional[list] = None) -> Dict[str, np.ndarray]:
     """One verification pass (Eq. 2 / Eq. 5): the M tree nodes against a cache.
 
     k_ctx, v_ctx: either arrays [L, n_kv, C, d] or callables layer -> [n_kv, C, d]
@@ -172,7 +181,11 @@ def verify_forward(W: OracleWeights, shape, k_ctx, v_ctx, tokens: Sequence[int],
     Node i attends to every context key and to the keys of its ancestors and itself.
 
     Returns logits [M, V]; k_new, v_new [L, n_kv, M, d] (what the pass appends to
-    the cache at slots C..C+M-1); optionally the per-layer residual stream.
+    the cache at slots C..C+M-1, rounded to the storage type; the nodes themselves attend
+    to each other with the unrounded values); optionally the per-layer residual stream.  If `trace`
+    is a list, one dict of intermediates per layer is appended to it (q, k, v as fed to
+    attention, the unrounded attention output o, the residual stream after attention and
+    after the FFN, the SiLU(gate)*up product).
     """
     rnd = bf16_round if shape.dtype == "bf16" else _identity
     M = len(tokens)
@@ -187,15 +200,14 @@ def verify_forward(W: OracleWeights, shape, k_ctx, v_ctx, tokens: Sequence[int],
     for l in range(shape.n_layers):
         kc = np.asarray(k_ctx(l) if callable(k_ctx) else k_ctx[l], dtype=np.float64)
         vc = np.asarray(v_ctx(l) if callable(v_ctx) else v_ctx[l], dtype=np.float64)
-        h = rnd(rmsnorm(x, W("norm_attn", l), shape.rms_eps))
+        h = rmsnorm(x, W("norm_attn", l), shape.rms_eps)
         q = (h @ W("wq", l).T).reshape(M, nq, d)
         k = (h @ W("wk", l).T).reshape(M, nkv, d)
         v = (h @ W("wv", l).T).reshape(M, nkv, d)
-        q = rnd(apply_rope(q, ang))
-        k = rnd(apply_rope(k, ang))
-        v = rnd(v)
-        k_new[l] = k.transpose(1, 0, 2)
-        v_new[l] = v.transpose(1, 0, 2)
+        q = apply_rope(q, ang)
+        k = apply_rope(k, ang)
+        k_new[l] = rnd(k).transpose(1, 0, 2)      # what enters the cache
+        v_new[l] = rnd(v).transpose(1, 0, 2)
         o = np.zeros((M, nq, d))
         for i in range(M):
             for a in range(nq):
@@ -204,13 +216,17 @@ def verify_forward(W: OracleWeights, shape, k_ctx, v_ctx, tokens: Sequence[int],
                 vals = np.concatenate([vc[g], v[anc[i], g]], axis=0)
                 s = (keys @ q[i, a]) / np.sqrt(d)
                 o[i, a] = _softmax(s) @ vals
-        x = x + rnd(o.reshape(M, nq * d)) @ W("wo", l).T
-        h = rnd(rmsnorm(x, W("norm_ffn", l), shape.rms_eps))
-        act = rnd(_silu(h @ W("w_gate", l).T) * (h @ W("w_up", l).T))
+        x = x + o.reshape(M, nq * d) @ W("wo", l).T
+        x_mid = x
+        h = rmsnorm(x, W("norm_ffn", l), shape.rms_eps)
+        act = _silu(h @ W("w_gate", l).T) * (h @ W("w_up", l).T)
         x = x + act @ W("w_down", l).T
+        if trace is not None:
+            trace.append({"q": q, "k": k, "v": v, "o": o.reshape(M, nq * d), "x_mid": x_mid,
+                          "act": act, "x": x})
         if keep_hidden:
             hidden.append(x.copy())
-    hf = rnd(rmsnorm(x, W("final_norm"), shape.rms_eps))
+    hf = rmsnorm(x, W("final_norm"), shape.rms_eps)
     out = {"logits": _lm_head(hf, W, shape.vocab), "k_new": k_new, "v_new": v_new,
            "final_hidden": hf}
     if keep_hidden:

@@ -1,0 +1,300 @@
+"""ctypes binding of libtrispec.so: argument marshalling only.
+
+Every step of the verification pass runs in the HIP kernels behind the C ABI
+(include/trispec.h).  torch is used for device memory and the stream, nothing
+else.  There is no CPU fallback: if the shared library is missing, importing
+the binding's entry points raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Callable, Dict, List, Optional, Sequence
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtrispec.so")
+
+TRISPEC_F32, TRISPEC_BF16 = 0, 1
+CRIT_MARGIN, CRIT_TOP1 = 0, 1
+MAX_NODES, MAX_BATCH, MAX_ROWS, PATH_STRIDE = 64, 8, 256, 64
+
+EXPORTS = [
+    "trispec_model_create", "trispec_model_destroy", "trispec_kv_bytes", "trispec_kv_create",
+    "trispec_kv_set_len", "trispec_kv_destroy", "trispec_workspace_bytes",
+    "trispec_workspace_region", "trispec_pass_bytes", "trispec_verify", "trispec_decide",
+    "trispec_strerror", "trispec_timer_create", "trispec_timer_reset", "trispec_timer_read",
+    "trispec_timer_destroy",
+]
+K_GEMM, K_HEAD, K_ATTN = 0, 1, 2
+
+
+class ModelConfig(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in
+                ("n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim", "ffn", "vocab", "dtype")] + \
+               [("rms_eps", C.c_float), ("rope_base", C.c_float)]
+
+
+_PP = C.POINTER(C.c_void_p)
+
+
+class Weights(C.Structure):
+    _fields_ = [("embed", C.c_void_p), ("lm_head", C.c_void_p), ("final_norm", C.c_void_p)] + \
+               [(n, _PP) for n in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "norm_attn", "norm_ffn")]
+
+
+class VerifyOpts(C.Structure):
+    _fields_ = [("criterion", C.c_int32), ("n_forced", C.c_int32), ("workspace", C.c_void_p),
+                ("workspace_bytes", C.c_size_t), ("debug_logits", C.c_void_p), ("stream", C.c_void_p),
+                ("timer", C.c_void_p)]
+
+
+class VerifyOut(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in
+                ("accepted_len", "token", "escalate", "path", "argmax", "confidence", "margin", "status")]
+
+
+class TriSpecError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"trispec error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded library; raises if it has not been built (python -m paper_2601_23180_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} not found: build it with `python -m paper_2601_23180_amd.build` "
+                "(there is no CPU fallback)")
+        l = C.CDLL(LIB_PATH)
+        l.trispec_strerror.restype = C.c_char_p
+        l.trispec_strerror.argtypes = [C.c_int]
+        for name in EXPORTS:
+            if name != "trispec_strerror":
+                getattr(l, name).restype = C.c_int
+        l.trispec_model_create.argtypes = [C.POINTER(ModelConfig), C.POINTER(Weights), C.POINTER(C.c_void_p)]
+        l.trispec_model_destroy.argtypes = [C.c_void_p]
+        l.trispec_kv_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
+        l.trispec_kv_create.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                        C.POINTER(C.c_void_p)]
+        l.trispec_kv_set_len.argtypes = [C.c_void_p, C.POINTER(C.c_int32)]
+        l.trispec_kv_destroy.argtypes = [C.c_void_p]
+        l.trispec_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
+        l.trispec_workspace_region.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_char_p,
+                                               C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
+        l.trispec_pass_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_int32),
+                                         C.POINTER(C.c_double)]
+        l.trispec_verify.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_int32), C.c_void_p,
+                                     C.c_int32, C.c_float, C.POINTER(VerifyOpts), C.POINTER(VerifyOut)]
+        l.trispec_decide.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.POINTER(C.c_int32), C.c_int32,
+                                     C.c_float, C.POINTER(VerifyOpts), C.POINTER(VerifyOut)]
+        l.trispec_timer_create.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]
+        l.trispec_timer_reset.argtypes = [C.c_void_p]
+        l.trispec_timer_read.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_double),
+                                         C.POINTER(C.c_double)]
+        l.trispec_timer_destroy.argtypes = [C.c_void_p]
+        _lib = l
+    return _lib
+
+
+def check(rc: int) -> None:
+    if rc != 0:
+        raise TriSpecError(rc, lib().trispec_strerror(rc).decode())
+
+
+def _torch_dtype(dtype: int):
+    return torch.float32 if dtype == TRISPEC_F32 else torch.bfloat16
+
+
+_LAYER_NAMES = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "norm_attn", "norm_ffn")
+
+
+class Model:
+    """trispec_model over device tensors the caller supplies.
+
+    tensors: {"embed", "lm_head", "final_norm": tensor, "wq".. : list of n_layers tensors}
+    (row-major [out, in], on the GPU, dtype matching `dtype`).  The object keeps them alive.
+    """
+
+    def __init__(self, *, n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab, dtype,
+                 rms_eps, rope_base, tensors: Dict[str, object]):
+        self.cfg = ModelConfig(n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab, dtype,
+                               rms_eps, rope_base)
+        self.tensors = tensors
+        self.dtype = dtype
+        w = Weights()
+        w.embed = tensors["embed"].data_ptr()
+        w.lm_head = tensors["lm_head"].data_ptr()
+        w.final_norm = tensors["final_norm"].data_ptr()
+        self._tables = []
+        for n in _LAYER_NAMES:
+            arr = (C.c_void_p * n_layers)(*[t.data_ptr() for t in tensors[n]])
+            self._tables.append(arr)
+            setattr(w, n, C.cast(arr, _PP))
+        self.handle = C.c_void_p()
+        check(lib().trispec_model_create(C.byref(self.cfg), C.byref(w), C.byref(self.handle)))
+
+    def workspace_bytes(self, batch: int, max_nodes: int) -> int:
+        n = C.c_size_t()
+        check(lib().trispec_workspace_bytes(self.handle, batch, max_nodes, C.byref(n)))
+        return n.value
+
+    def workspace_region(self, batch: int, n_nodes: int, name: str):
+        off, n = C.c_size_t(), C.c_size_t()
+        check(lib().trispec_workspace_region(self.handle, batch, n_nodes, name.encode(), C.byref(off), C.byref(n)))
+        return off.value, n.value
+
+    def pass_bytes(self, batch: int, n_nodes: int, ctx_len: Sequence[int]) -> float:
+        arr = (C.c_int32 * batch)(*ctx_len)
+        out = C.c_double()
+        check(lib().trispec_pass_bytes(self.handle, batch, n_nodes, arr, C.byref(out)))
+        return out.value
+
+    def close(self):
+        if self.handle:
+            lib().trispec_model_destroy(self.handle)
+            self.handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class KVCache:
+    """trispec_kv over two device tensors:
+    K [L, B, n_kv, capacity, d] (post-rotary keys) and V [L, B, n_kv, d, capacity] (transposed)."""
+
+    def __init__(self, model: Model, batch: int, capacity: int, k: Optional[torch.Tensor] = None,
+                 v: Optional[torch.Tensor] = None, device="cuda"):
+        c = model.cfg
+        n = C.c_size_t()
+        check(lib().trispec_kv_bytes(model.handle, batch, capacity, C.byref(n)))
+        dt = _torch_dtype(c.dtype)
+        self.k = k if k is not None else torch.zeros((c.n_layers, batch, c.n_kv_heads, capacity, c.head_dim),
+                                                      dtype=dt, device=device)
+        self.v = v if v is not None else torch.zeros((c.n_layers, batch, c.n_kv_heads, c.head_dim, capacity),
+                                                      dtype=dt, device=device)
+        assert self.k.is_contiguous() and self.v.is_contiguous()
+        assert self.k.numel() * self.k.element_size() == n.value == self.v.numel() * self.v.element_size()
+        self.model, self.batch, self.capacity = model, batch, capacity
+        self.handle = C.c_void_p()
+        check(lib().trispec_kv_create(model.handle, self.k.data_ptr(), self.v.data_ptr(), batch, capacity,
+                                      C.byref(self.handle)))
+        self.ctx_len = [0] * batch
+
+    def set_len(self, ctx_len: Sequence[int]) -> None:
+        arr = (C.c_int32 * self.batch)(*ctx_len)
+        check(lib().trispec_kv_set_len(self.handle, arr))
+        self.ctx_len = list(ctx_len)
+
+    def close(self):
+        if self.handle:
+            lib().trispec_kv_destroy(self.handle)
+            self.handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class KernelTimer:
+    """HIP-event timer around every launch of one kernel class (measurement only)."""
+
+    def __init__(self, kernel_class: int, capacity: int):
+        self.handle = C.c_void_p()
+        check(lib().trispec_timer_create(kernel_class, capacity, C.byref(self.handle)))
+
+    def reset(self):
+        check(lib().trispec_timer_reset(self.handle))
+
+    def read(self):
+        """(launches, total ms, total algorithmic bytes); synchronise the stream first."""
+        n, ms, by = C.c_int32(), C.c_double(), C.c_double()
+        check(lib().trispec_timer_read(self.handle, C.byref(n), C.byref(ms), C.byref(by)))
+        return n.value, ms.value, by.value
+
+    def __del__(self):
+        try:
+            if self.handle:
+                lib().trispec_timer_destroy(self.handle)
+                self.handle = C.c_void_p()
+        except Exception:
+            pass
+
+
+class Verifier:
+    """Pre-allocated workspace and output buffers for repeated trispec_verify calls."""
+
+    def __init__(self, model: Model, batch: int, max_nodes: int, debug_logits: bool = False, device="cuda"):
+        self.model, self.batch, self.max_nodes = model, batch, max_nodes
+        self.ws_bytes = model.workspace_bytes(batch, max_nodes)
+        self.workspace = torch.zeros(self.ws_bytes + 256, dtype=torch.uint8, device=device)
+        pad = (-self.workspace.data_ptr()) % 256
+        self._ws_ptr = self.workspace.data_ptr() + pad
+        i32 = dict(dtype=torch.int32, device=device)
+        f32 = dict(dtype=torch.float32, device=device)
+        self.out = {
+            "accepted_len": torch.zeros(batch, **i32), "token": torch.zeros(batch, **i32),
+            "escalate": torch.zeros(batch, **i32), "path": torch.zeros((batch, PATH_STRIDE), **i32),
+            "argmax": torch.zeros((batch, max_nodes), **i32), "confidence": torch.zeros((batch, max_nodes), **f32),
+            "margin": torch.zeros((batch, max_nodes), **f32), "status": torch.zeros(1, **i32),
+        }
+        self.logits = torch.zeros((batch, max_nodes, model.cfg.vocab), **f32) if debug_logits else None
+        self.timer = None   # optional KernelTimer attached to every verify call
+
+    def _opts(self, criterion, n_forced, stream, want_logits):
+        o = VerifyOpts()
+        o.criterion, o.n_forced = criterion, n_forced
+        o.workspace, o.workspace_bytes = self._ws_ptr, self.ws_bytes
+        o.debug_logits = self.logits.data_ptr() if (want_logits and self.logits is not None) else None
+        s = stream if stream is not None else torch.cuda.current_stream()
+        o.stream = s.cuda_stream
+        o.timer = self.timer.handle if self.timer is not None else None
+        return o
+
+    def _out(self, n_nodes):
+        o = VerifyOut()
+        for name, t in self.out.items():
+            setattr(o, name, t.data_ptr())
+        return o
+
+    def verify(self, kv: KVCache, draft_tokens: torch.Tensor, tree_parents: np.ndarray,
+               positions: torch.Tensor, threshold: float, criterion: int = CRIT_MARGIN, n_forced: int = 1,
+               stream=None, want_logits: bool = True) -> Dict[str, torch.Tensor]:
+        """draft_tokens / positions: int32 device tensors [batch, n_nodes]; tree_parents: host int32
+        [batch, n_nodes].  n_nodes must equal max_nodes (the output buffers are laid out for it)."""
+        n_nodes = draft_tokens.shape[-1]
+        assert n_nodes == self.max_nodes and draft_tokens.dtype == torch.int32 and positions.dtype == torch.int32
+        par = np.ascontiguousarray(tree_parents, dtype=np.int32)
+        opts, out = self._opts(criterion, n_forced, stream, want_logits), self._out(n_nodes)
+        check(lib().trispec_verify(self.model.handle, kv.handle, draft_tokens.data_ptr(),
+                                   par.ctypes.data_as(C.POINTER(C.c_int32)), positions.data_ptr(), n_nodes,
+                                   float(threshold), C.byref(opts), C.byref(out)))
+        return self.out
+
+    def decide(self, draft_tokens: torch.Tensor, tree_parents: np.ndarray, threshold: float,
+               criterion: int = CRIT_MARGIN, n_forced: int = 1, stream=None) -> Dict[str, torch.Tensor]:
+        n_nodes = draft_tokens.shape[-1]
+        par = np.ascontiguousarray(tree_parents, dtype=np.int32)
+        opts, out = self._opts(criterion, n_forced, stream, False), self._out(n_nodes)
+        check(lib().trispec_decide(self.model.handle, self.batch, draft_tokens.data_ptr(),
+                                   par.ctypes.data_as(C.POINTER(C.c_int32)), n_nodes, float(threshold),
+                                   C.byref(opts), C.byref(out)))
+        return self.out
+
+    def region(self, name: str, n_nodes: Optional[int] = None) -> torch.Tensor:
+        """Raw bytes of a named workspace region (test hook)."""
+        off, n = self.model.workspace_region(self.batch, n_nodes or self.max_nodes, name)
+        base = self._ws_ptr - self.workspace.data_ptr()
+        return self.workspace[base + off: base + off + n]

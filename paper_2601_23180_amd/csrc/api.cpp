@@ -1,0 +1,584 @@
+// Host side of the C ABI: validation, workspace carve-up, launch sequence of one pass.
+// No allocation, no synchronisation and no HIP call other than kernel launches on the hot path.
+#include <math.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "internal.hpp"
+
+using namespace ts;
+
+struct trispec_model {
+  trispec_model_config cfg;
+  const void *embed, *lm_head, *final_norm;
+  std::vector<const void *> wq, wk, wv, wo, w_gate, w_up, w_down, norm_attn, norm_ffn;
+};
+
+struct trispec_kv {
+  const trispec_model *model;
+  void *k, *v;
+  int32_t batch, capacity;
+  int32_t ctx_len[kMaxBatch];
+};
+
+struct trispec_timer {
+  int32_t kernel_class, capacity, count;
+  double bytes;
+  std::vector<hipEvent_t> start, stop;
+};
+
+namespace {
+
+// Records an event pair around one launch when a timer of this class is attached.
+struct TimedLaunch {
+  trispec_timer *t;
+  hipStream_t st;
+  bool on;
+  TimedLaunch(trispec_timer *timer, int cls, hipStream_t s, double bytes) : t(timer), st(s), on(false) {
+    if (t && t->kernel_class == cls && t->count < t->capacity) {
+      on = true;
+      t->bytes += bytes;
+      (void)hipEventRecord(t->start[t->count], st);
+    }
+  }
+  ~TimedLaunch() {
+    if (on) {
+      (void)hipEventRecord(t->stop[t->count], st);
+      ++t->count;
+    }
+  }
+};
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline size_t esize(int dtype) { return dtype == TRISPEC_F32 ? 4 : 2; }
+
+int rows_pad_for(int rows) {
+  if (rows <= 32) return 32;
+  if (rows <= 64) return 64;
+  if (rows <= 128) return 128;
+  return 256;
+}
+
+// Workspace regions, in order.  Offsets are a pure function of (model, batch, max_nodes).
+struct Layout {
+  size_t anc, parent, status, cos_t, sin_t, x, h, q, qkv_f32, attn_out, act, part, attn_o, attn_m, attn_l,
+      head_l1, head_l2, head_sum, head_idx, node_l1, node_l2, node_sum, node_idx, logits, total;
+  int rows_max, rows_pad_max, head_tiles;
+};
+
+int max_gemm_cols(const trispec_model_config &c) {
+  int qkv = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
+  int m = qkv;
+  if (c.hidden > m) m = c.hidden;
+  if (2 * c.ffn > m) m = 2 * c.ffn;
+  return m;
+}
+
+// k-splits for one matmul: enough workgroups to fill the chip, k slices >= 256 deep.
+int pick_splits(int dtype, int n_total, int k) {
+  if (dtype == TRISPEC_F32) return 1;
+  const int tiles = (n_total + kGemmTileN - 1) / kGemmTileN;
+  int s = (1024 + tiles - 1) / tiles;
+  const int max_by_k = k / 256 > 0 ? k / 256 : 1;
+  if (s > max_by_k) s = max_by_k;
+  if (s > kMaxSplitK) s = kMaxSplitK;
+  if (s < 1) s = 1;
+  return s;
+}
+int k_per_split(int k, int s) { return (int)align_up((size_t)(k + s - 1) / s, 64); }
+
+Layout make_layout(const trispec_model_config &c, int batch, int max_nodes) {
+  Layout L;
+  memset(&L, 0, sizeof(L));
+  const int rows = batch * max_nodes;
+  const int rp = rows_pad_for(rows);
+  const size_t es = esize(c.dtype);
+  const int qd = c.n_q_heads * c.head_dim;
+  L.rows_max = rows;
+  L.rows_pad_max = rp;
+  L.head_tiles = c.dtype == TRISPEC_F32 ? 1 : (c.vocab + kGemmTileN - 1) / kGemmTileN;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+  L.anc = take(sizeof(uint64_t) * kMaxRows);
+  L.parent = take(sizeof(int32_t) * kMaxRows);
+  L.status = take(256);
+  L.cos_t = take(sizeof(float) * rows * (c.head_dim / 2));
+  L.sin_t = take(sizeof(float) * rows * (c.head_dim / 2));
+  L.x = take(sizeof(float) * (size_t)rp * c.hidden);
+  // matmul / attention operands: fp32 models one panel; bf16 models a hi and a lo bf16 panel
+  const size_t np = c.dtype == TRISPEC_F32 ? 1 : 2;
+  L.h = take(np * es * (size_t)rp * c.hidden);
+  L.q = take(np * es * (size_t)rp * qd);
+  L.qkv_f32 = take(c.dtype == TRISPEC_F32 ? 0 : sizeof(float) * (size_t)rows * (qd + 2 * c.n_kv_heads * c.head_dim));
+  L.attn_out = take(np * es * (size_t)rp * qd);
+  L.act = take(np * es * (size_t)rp * c.ffn);
+  // split-K partials: the largest of S*N over the four matmuls of a layer
+  size_t part = 0;
+  const int ns[4] = {(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim, c.hidden, 2 * c.ffn, c.hidden};
+  const int ks[4] = {c.hidden, qd, c.hidden, c.ffn};
+  for (int i = 0; i < 4; ++i) {
+    size_t p = (size_t)pick_splits(c.dtype, ns[i], ks[i]) * ns[i];
+    if (p > part) part = p;
+  }
+  L.part = take(sizeof(float) * part * rp);
+  const int group = c.n_q_heads / c.n_kv_heads;
+  const size_t prow = (size_t)batch * c.n_kv_heads * kMaxAttnSplits * group * max_nodes;
+  L.attn_o = take(sizeof(float) * prow * c.head_dim);
+  L.attn_m = take(sizeof(float) * prow);
+  L.attn_l = take(sizeof(float) * prow);
+  const size_t hs = (size_t)rows * L.head_tiles;
+  L.head_l1 = take(sizeof(float) * hs);
+  L.head_l2 = take(sizeof(float) * hs);
+  L.head_sum = take(sizeof(float) * hs);
+  L.head_idx = take(sizeof(int32_t) * hs);
+  L.node_l1 = take(sizeof(float) * kMaxRows);
+  L.node_l2 = take(sizeof(float) * kMaxRows);
+  L.node_sum = take(sizeof(float) * kMaxRows);
+  L.node_idx = take(sizeof(int32_t) * kMaxRows);
+  L.logits = take(c.dtype == TRISPEC_F32 ? sizeof(float) * (size_t)rows * c.vocab : 0);
+  L.total = off;
+  return L;
+}
+
+int check_shape(const trispec_model_config &c) {
+  if (c.n_layers < 1 || c.hidden < 1 || c.n_q_heads < 1 || c.n_kv_heads < 1 || c.ffn < 1 || c.vocab < 2)
+    return TRISPEC_ESHAPE;
+  if (c.head_dim != 64 && c.head_dim != 128) return TRISPEC_ESHAPE;
+  if (c.n_q_heads % c.n_kv_heads != 0) return TRISPEC_ESHAPE;
+  if (c.dtype != TRISPEC_F32 && c.dtype != TRISPEC_BF16) return TRISPEC_ESHAPE;
+  if (!(c.rms_eps >= 0.f) || !(c.rope_base > 0.f)) return TRISPEC_ESHAPE;
+  if (c.dtype == TRISPEC_BF16) {
+    const int qd = c.n_q_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim;
+    if (c.hidden % 64 || c.ffn % 64 || qd % 64 || kvd % 32) return TRISPEC_ESHAPE;
+  }
+  return TRISPEC_OK;
+}
+
+// parents -> ancestor-or-self bit masks; validates topological order and the forced chain.
+int build_nodes(const int32_t *parents, int batch, int n_nodes, int n_forced, NodeTable &tab) {
+  for (int b = 0; b < batch; ++b) {
+    const int32_t *p = parents + (size_t)b * n_nodes;
+    if (p[0] != -1) return TRISPEC_ETREE;
+    for (int i = 0; i < n_nodes; ++i) {
+      if (i > 0 && (p[i] < 0 || p[i] >= i)) return TRISPEC_ETREE;
+      if (i > 0 && i < n_forced && p[i] != i - 1) return TRISPEC_EFORCED;
+      const uint64_t up = i == 0 ? 0ull : tab.anc[b * n_nodes + p[i]];
+      tab.anc[b * n_nodes + i] = up | (1ull << i);
+      tab.parent[b * n_nodes + i] = p[i];
+    }
+  }
+  return TRISPEC_OK;
+}
+
+int check_opts(const trispec_verify_opts *o, float threshold) {
+  if (!o) return TRISPEC_ENULL;
+  if (o->criterion != TRISPEC_CRIT_MARGIN && o->criterion != TRISPEC_CRIT_TOP1) return TRISPEC_EARG;
+  if (threshold != threshold) return TRISPEC_EARG;
+  if (!o->workspace) return TRISPEC_EWORKSPACE;
+  if (((uintptr_t)o->workspace) & 255) return TRISPEC_EWORKSPACE;
+  return TRISPEC_OK;
+}
+
+DecideArgs make_decide(const Layout &L, char *ws, const int32_t *tokens, int batch, int n_nodes,
+                       float threshold, const trispec_verify_opts *o, const trispec_verify_out *out) {
+  DecideArgs d;
+  d.tokens = tokens;
+  d.parent = (const int32_t *)(ws + L.parent);
+  d.batch = batch;
+  d.n_nodes = n_nodes;
+  d.n_forced = o->n_forced;
+  d.criterion = o->criterion;
+  d.threshold = threshold;
+  d.node_l1 = (float *)(ws + L.node_l1);
+  d.node_l2 = (float *)(ws + L.node_l2);
+  d.node_sum = (float *)(ws + L.node_sum);
+  d.node_idx = (int32_t *)(ws + L.node_idx);
+  d.status_src = (const int32_t *)(ws + L.status);
+  d.out = *out;
+  return d;
+}
+
+}  // namespace
+
+extern "C" {
+
+int trispec_model_create(const trispec_model_config *cfg, const trispec_weights *w, trispec_model **out) {
+  if (!cfg || !w || !out) return TRISPEC_ENULL;
+  const int rc = check_shape(*cfg);
+  if (rc) return rc;
+  if (!w->embed || !w->lm_head || !w->final_norm || !w->wq || !w->wk || !w->wv || !w->wo || !w->w_gate ||
+      !w->w_up || !w->w_down || !w->norm_attn || !w->norm_ffn)
+    return TRISPEC_ENULL;
+  const int L = cfg->n_layers;
+  for (int l = 0; l < L; ++l)
+    if (!w->wq[l] || !w->wk[l] || !w->wv[l] || !w->wo[l] || !w->w_gate[l] || !w->w_up[l] || !w->w_down[l] ||
+        !w->norm_attn[l] || !w->norm_ffn[l])
+      return TRISPEC_ENULL;
+  trispec_model *m = new (std::nothrow) trispec_model;
+  if (!m) return TRISPEC_EARG;
+  m->cfg = *cfg;
+  m->embed = w->embed;
+  m->lm_head = w->lm_head;
+  m->final_norm = w->final_norm;
+  m->wq.assign(w->wq, w->wq + L);
+  m->wk.assign(w->wk, w->wk + L);
+  m->wv.assign(w->wv, w->wv + L);
+  m->wo.assign(w->wo, w->wo + L);
+  m->w_gate.assign(w->w_gate, w->w_gate + L);
+  m->w_up.assign(w->w_up, w->w_up + L);
+  m->w_down.assign(w->w_down, w->w_down + L);
+  m->norm_attn.assign(w->norm_attn, w->norm_attn + L);
+  m->norm_ffn.assign(w->norm_ffn, w->norm_ffn + L);
+  *out = m;
+  return TRISPEC_OK;
+}
+
+int trispec_model_destroy(trispec_model *m) {
+  delete m;
+  return TRISPEC_OK;
+}
+
+int trispec_kv_bytes(const trispec_model *m, int32_t batch, int32_t capacity, size_t *bytes) {
+  if (!m || !bytes) return TRISPEC_ENULL;
+  if (batch < 1 || batch > kMaxBatch) return TRISPEC_ENODES;
+  if (capacity < 64 || capacity % 64) return TRISPEC_ECAPACITY;
+  const trispec_model_config &c = m->cfg;
+  *bytes = (size_t)c.n_layers * batch * c.n_kv_heads * capacity * c.head_dim * esize(c.dtype);
+  return TRISPEC_OK;
+}
+
+int trispec_kv_create(const trispec_model *m, void *k_dev, void *v_dev, int32_t batch, int32_t capacity,
+                      trispec_kv **out) {
+  if (!m || !k_dev || !v_dev || !out) return TRISPEC_ENULL;
+  size_t bytes;
+  const int rc = trispec_kv_bytes(m, batch, capacity, &bytes);
+  if (rc) return rc;
+  if ((((uintptr_t)k_dev) | ((uintptr_t)v_dev)) & 15) return TRISPEC_EARG;
+  trispec_kv *kv = new (std::nothrow) trispec_kv;
+  if (!kv) return TRISPEC_EARG;
+  kv->model = m;
+  kv->k = k_dev;
+  kv->v = v_dev;
+  kv->batch = batch;
+  kv->capacity = capacity;
+  for (int b = 0; b < kMaxBatch; ++b) kv->ctx_len[b] = 0;
+  *out = kv;
+  return TRISPEC_OK;
+}
+
+int trispec_kv_set_len(trispec_kv *kv, const int32_t *ctx_len_host) {
+  if (!kv || !ctx_len_host) return TRISPEC_ENULL;
+  for (int b = 0; b < kv->batch; ++b)
+    if (ctx_len_host[b] < 0 || ctx_len_host[b] > kv->capacity) return TRISPEC_ECAPACITY;
+  for (int b = 0; b < kv->batch; ++b) kv->ctx_len[b] = ctx_len_host[b];
+  return TRISPEC_OK;
+}
+
+int trispec_kv_destroy(trispec_kv *kv) {
+  delete kv;
+  return TRISPEC_OK;
+}
+
+int trispec_workspace_bytes(const trispec_model *m, int32_t batch, int32_t max_nodes, size_t *bytes) {
+  if (!m || !bytes) return TRISPEC_ENULL;
+  if (batch < 1 || batch > kMaxBatch || max_nodes < 1 || max_nodes > kMaxNodes ||
+      batch * max_nodes > kMaxRows)
+    return TRISPEC_ENODES;
+  *bytes = make_layout(m->cfg, batch, max_nodes).total;
+  return TRISPEC_OK;
+}
+
+// Test hook: where a named intermediate lives inside the workspace.
+int trispec_workspace_region(const trispec_model *m, int32_t batch, int32_t max_nodes, const char *name,
+                             size_t *offset, size_t *bytes) {
+  if (!m || !name || !offset || !bytes) return TRISPEC_ENULL;
+  if (batch < 1 || batch > kMaxBatch || max_nodes < 1 || max_nodes > kMaxNodes ||
+      batch * max_nodes > kMaxRows)
+    return TRISPEC_ENODES;
+  const Layout L = make_layout(m->cfg, batch, max_nodes);
+  const trispec_model_config &c = m->cfg;
+  const size_t es = esize(c.dtype);
+  const size_t rp = L.rows_pad_max;
+  const size_t np = c.dtype == TRISPEC_F32 ? 1 : 2;
+  struct { const char *n; size_t o, b; } tab[] = {
+      {"x", L.x, sizeof(float) * rp * c.hidden},
+      {"h", L.h, np * es * rp * c.hidden},
+      {"q", L.q, np * es * rp * c.n_q_heads * c.head_dim},
+      {"attn_out", L.attn_out, np * es * rp * c.n_q_heads * c.head_dim},
+      {"act", L.act, np * es * rp * c.ffn},
+      {"node_l1", L.node_l1, sizeof(float) * kMaxRows},
+      {"node_l2", L.node_l2, sizeof(float) * kMaxRows},
+      {"node_sum", L.node_sum, sizeof(float) * kMaxRows},
+      {"node_idx", L.node_idx, sizeof(int32_t) * kMaxRows},
+  };
+  for (auto &t : tab)
+    if (!strcmp(t.n, name)) {
+      *offset = t.o;
+      *bytes = t.b;
+      return TRISPEC_OK;
+    }
+  return TRISPEC_EARG;
+}
+
+int trispec_pass_bytes(const trispec_model *m, int32_t batch, int32_t n_nodes, const int32_t *ctx_len_host,
+                       double *bytes) {
+  if (!m || !ctx_len_host || !bytes) return TRISPEC_ENULL;
+  if (batch < 1 || batch > kMaxBatch || n_nodes < 1 || n_nodes > kMaxNodes) return TRISPEC_ENODES;
+  const trispec_model_config &c = m->cfg;
+  const double w = (double)esize(c.dtype);
+  const double qd = (double)c.n_q_heads * c.head_dim, kvd = (double)c.n_kv_heads * c.head_dim;
+  const double per_layer = 2.0 * c.hidden * qd + 2.0 * c.hidden * kvd + 3.0 * (double)c.hidden * c.ffn +
+                           2.0 * c.hidden;
+  double kv = 0;
+  for (int b = 0; b < batch; ++b) kv += 2.0 * ((double)ctx_len_host[b] + n_nodes) * kvd;
+  *bytes = (c.n_layers * per_layer + (double)c.vocab * c.hidden + c.n_layers * kv) * w;
+  return TRISPEC_OK;
+}
+
+int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens,
+                   const int32_t *tree_parents, const int32_t *positions, int32_t n_nodes, float threshold,
+                   const trispec_verify_opts *opts, const trispec_verify_out *out) {
+  if (!m || !kv || !draft_tokens || !tree_parents || !positions || !out) return TRISPEC_ENULL;
+  int rc = check_opts(opts, threshold);
+  if (rc) return rc;
+  if (kv->model != m) return TRISPEC_EMISMATCH;
+  const trispec_model_config &c = m->cfg;
+  const int B = kv->batch;
+  if (n_nodes < 1 || n_nodes > kMaxNodes || B * n_nodes > kMaxRows) return TRISPEC_ENODES;
+  if (opts->n_forced < 1 || opts->n_forced > n_nodes) return TRISPEC_EFORCED;
+  const int group = c.n_q_heads / c.n_kv_heads;
+  if (c.dtype == TRISPEC_BF16 && group * n_nodes > 256) return TRISPEC_ENODES;
+  int max_keys = 0;
+  for (int b = 0; b < B; ++b) {
+    if (kv->ctx_len[b] + n_nodes > kv->capacity) return TRISPEC_ECAPACITY;
+    if (kv->ctx_len[b] > max_keys) max_keys = kv->ctx_len[b];
+  }
+  if (c.dtype == TRISPEC_F32 && max_keys + n_nodes > 12288) return TRISPEC_ECAPACITY;
+  NodeTable tab;
+  memset(&tab, 0, sizeof(tab));
+  rc = build_nodes(tree_parents, B, n_nodes, opts->n_forced, tab);
+  if (rc) return rc;
+  const Layout L = make_layout(c, B, n_nodes);
+  if (opts->workspace_bytes < L.total) return TRISPEC_EWORKSPACE;
+
+  hipStream_t st = (hipStream_t)opts->stream;
+  char *ws = (char *)opts->workspace;
+  const int rows = B * n_nodes, rp = rows_pad_for(rows);
+  const size_t es = esize(c.dtype);
+  const int qd = c.n_q_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim;
+  float *x = (float *)(ws + L.x);
+  void *h = ws + L.h, *q = ws + L.q, *attn_out = ws + L.attn_out, *act = ws + L.act;
+  float *part = (float *)(ws + L.part);
+  float *cos_t = (float *)(ws + L.cos_t), *sin_t = (float *)(ws + L.sin_t);
+  int32_t *status = (int32_t *)(ws + L.status);
+  CtxLens ctx;
+  for (int b = 0; b < kMaxBatch; ++b) ctx.v[b] = b < B ? kv->ctx_len[b] : 0;
+
+  (void)hipGetLastError();
+  launch_setup(st, tab, rows, (uint64_t *)(ws + L.anc), (int32_t *)(ws + L.parent), status);
+  launch_rope_table(st, positions, rows, c.head_dim, c.rope_base, cos_t, sin_t);
+  const size_t pan_h = (size_t)rp * c.hidden, pan_q = (size_t)rp * qd, pan_f = (size_t)rp * c.ffn;
+  launch_embed_norm(st, c.dtype, draft_tokens, m->embed, m->norm_attn[0], rows, c.hidden, c.vocab,
+                    c.rms_eps, x, h, pan_h, status);
+
+  auto gemm = [&](const void *xin, size_t xpanel, int k, int n_seg, const void *w0, int n0, const void *w1, int n1,
+                  const void *w2, int n2) -> int {
+    GemmArgs g;
+    memset(&g, 0, sizeof(g));
+    g.x = xin;
+    g.x_panel = xpanel;
+    g.seg[0] = {w0, n0, 0};
+    g.seg[1] = {w1, n1, n0};
+    g.seg[2] = {w2, n2, n0 + n1};
+    g.n_seg = n_seg;
+    g.n_total = n0 + n1 + n2;
+    g.k = k;
+    g.rows = rows;
+    g.rows_pad = rp;
+    g.n_splits = pick_splits(c.dtype, g.n_total, k);
+    g.k_per_split = k_per_split(k, g.n_splits);
+    g.n_splits = (k + g.k_per_split - 1) / g.k_per_split;
+    g.out = part;
+    TimedLaunch tl(opts->timer, TRISPEC_K_GEMM, st, (double)g.n_total * k * es);
+    if (c.dtype == TRISPEC_F32) launch_gemm_f32(st, g); else launch_gemm_bf16(st, g);
+    return g.n_splits;
+  };
+
+  // attention split: about 256 keys per workgroup, at most kMaxAttnSplits
+  AttnArgs at;
+  memset(&at, 0, sizeof(at));
+  at.q = q;
+  at.panel = pan_q;
+  at.anc = (const uint64_t *)(ws + L.anc);
+  at.ctx = ctx;
+  at.batch = B; at.n_nodes = n_nodes; at.n_q_heads = c.n_q_heads; at.n_kv_heads = c.n_kv_heads;
+  at.head_dim = c.head_dim; at.capacity = kv->capacity;
+  {
+    int kps = 256;
+    while ((max_keys + kps - 1) / kps > kMaxAttnSplits) kps *= 2;
+    at.keys_per_split = kps;
+    at.n_splits = (max_keys + kps - 1) / kps;
+    if (at.n_splits < 1) at.n_splits = 1;
+  }
+  float *qkv_f32 = c.dtype == TRISPEC_F32 ? nullptr : (float *)(ws + L.qkv_f32);
+  at.qkv = qkv_f32;
+  at.part_o = (float *)(ws + L.attn_o);
+  at.part_m = (float *)(ws + L.attn_m);
+  at.part_l = (float *)(ws + L.attn_l);
+  at.out = attn_out;
+  const size_t kv_layer = (size_t)B * c.n_kv_heads * kv->capacity * c.head_dim * es;
+
+  for (int l = 0; l < c.n_layers; ++l) {
+    int s = gemm(h, pan_h, c.hidden, 3, m->wq[l], qd, m->wk[l], kvd, m->wv[l], kvd);
+    char *kl = (char *)kv->k + (size_t)l * kv_layer, *vl = (char *)kv->v + (size_t)l * kv_layer;
+    launch_qkv_epilogue(st, c.dtype, part, s, rows, rp, c.n_q_heads, c.n_kv_heads, c.head_dim, cos_t, sin_t,
+                        n_nodes, ctx, kv->capacity, q, pan_q, qkv_f32, kl, vl);
+    at.k_cache = kl;
+    at.v_cache = vl;
+    {
+      double kvb = 0;
+      for (int b = 0; b < B; ++b) kvb += 2.0 * (kv->ctx_len[b] + n_nodes) * kvd * es;
+      TimedLaunch tl(opts->timer, TRISPEC_K_ATTN, st, kvb);
+      if (c.dtype == TRISPEC_F32) launch_attn_f32(st, at); else launch_attn_bf16(st, at);
+    }
+    s = gemm(attn_out, pan_q, qd, 1, m->wo[l], c.hidden, nullptr, 0, nullptr, 0);
+    launch_reduce_residual_norm(st, c.dtype, part, s, rows, rp, c.hidden, m->norm_ffn[l], c.rms_eps, x, h, pan_h);
+    s = gemm(h, pan_h, c.hidden, 2, m->w_gate[l], c.ffn, m->w_up[l], c.ffn, nullptr, 0);
+    launch_reduce_swiglu(st, c.dtype, part, s, rows, rp, c.ffn, act, pan_f);
+    s = gemm(act, pan_f, c.ffn, 1, m->w_down[l], c.hidden, nullptr, 0, nullptr, 0);
+    const void *next_norm = (l + 1 < c.n_layers) ? m->norm_attn[l + 1] : m->final_norm;
+    launch_reduce_residual_norm(st, c.dtype, part, s, rows, rp, c.hidden, next_norm, c.rms_eps, x, h, pan_h);
+  }
+
+  // LM head -> per-row statistics (never the probabilities)
+  HeadStats hs;
+  hs.l1 = (float *)(ws + L.head_l1);
+  hs.l2 = (float *)(ws + L.head_l2);
+  hs.sumexp = (float *)(ws + L.head_sum);
+  hs.idx = (int32_t *)(ws + L.head_idx);
+  hs.n_tiles = L.head_tiles;
+  {
+    GemmArgs g;
+    memset(&g, 0, sizeof(g));
+    g.x = h;
+    g.x_panel = pan_h;
+    g.seg[0] = {m->lm_head, c.vocab, 0};
+    g.n_seg = 1;
+    g.n_total = c.vocab;
+    g.k = c.hidden;
+    g.rows = rows;
+    g.rows_pad = rp;
+    g.n_splits = 1;
+    g.k_per_split = (int)align_up(c.hidden, 64);
+    TimedLaunch tl(opts->timer, TRISPEC_K_HEAD, st, (double)c.vocab * c.hidden * es);
+    if (c.dtype == TRISPEC_F32) {
+      float *logits = opts->debug_logits ? opts->debug_logits : (float *)(ws + L.logits);
+      g.out = logits;
+      launch_gemm_f32(st, g);
+      launch_stats_from_logits(st, logits, rows, c.vocab, hs);
+    } else {
+      launch_lmhead_bf16(st, g, hs, opts->debug_logits);
+    }
+  }
+  launch_stats_reduce(st, hs, rows, (float *)(ws + L.node_l1), (float *)(ws + L.node_l2),
+                      (float *)(ws + L.node_sum), (int32_t *)(ws + L.node_idx));
+  DecideArgs d = make_decide(L, ws, draft_tokens, B, n_nodes, threshold, opts, out);
+  launch_decide(st, d);
+  return hipGetLastError() == hipSuccess ? TRISPEC_OK : TRISPEC_ELAUNCH;
+}
+
+int trispec_decide(trispec_model *m, int32_t batch, const int32_t *draft_tokens, const int32_t *tree_parents,
+                   int32_t n_nodes, float threshold, const trispec_verify_opts *opts,
+                   const trispec_verify_out *out) {
+  if (!m || !draft_tokens || !tree_parents || !out) return TRISPEC_ENULL;
+  int rc = check_opts(opts, threshold);
+  if (rc) return rc;
+  if (batch < 1 || batch > kMaxBatch || n_nodes < 1 || n_nodes > kMaxNodes || batch * n_nodes > kMaxRows)
+    return TRISPEC_ENODES;
+  if (opts->n_forced < 1 || opts->n_forced > n_nodes) return TRISPEC_EFORCED;
+  NodeTable tab;
+  memset(&tab, 0, sizeof(tab));
+  rc = build_nodes(tree_parents, batch, n_nodes, opts->n_forced, tab);
+  if (rc) return rc;
+  const Layout L = make_layout(m->cfg, batch, n_nodes);
+  if (opts->workspace_bytes < L.total) return TRISPEC_EWORKSPACE;
+  hipStream_t st = (hipStream_t)opts->stream;
+  char *ws = (char *)opts->workspace;
+  (void)hipGetLastError();
+  DecideArgs d = make_decide(L, ws, draft_tokens, batch, n_nodes, threshold, opts, out);
+  launch_decide(st, d);
+  return hipGetLastError() == hipSuccess ? TRISPEC_OK : TRISPEC_ELAUNCH;
+}
+
+int trispec_timer_create(int32_t kernel_class, int32_t capacity, trispec_timer **out) {
+  if (!out) return TRISPEC_ENULL;
+  if (kernel_class < TRISPEC_K_GEMM || kernel_class > TRISPEC_K_ATTN || capacity < 1 || capacity > (1 << 20))
+    return TRISPEC_EARG;
+  trispec_timer *t = new (std::nothrow) trispec_timer;
+  if (!t) return TRISPEC_EARG;
+  t->kernel_class = kernel_class;
+  t->capacity = capacity;
+  t->count = 0;
+  t->bytes = 0;
+  t->start.resize(capacity);
+  t->stop.resize(capacity);
+  for (int i = 0; i < capacity; ++i)
+    if (hipEventCreate(&t->start[i]) != hipSuccess || hipEventCreate(&t->stop[i]) != hipSuccess) {
+      delete t;
+      return TRISPEC_ELAUNCH;
+    }
+  *out = t;
+  return TRISPEC_OK;
+}
+
+int trispec_timer_reset(trispec_timer *t) {
+  if (!t) return TRISPEC_ENULL;
+  t->count = 0;
+  t->bytes = 0;
+  return TRISPEC_OK;
+}
+
+int trispec_timer_read(trispec_timer *t, int32_t *n_launches, double *total_ms, double *total_bytes) {
+  if (!t || !n_launches || !total_ms || !total_bytes) return TRISPEC_ENULL;
+  double ms = 0;
+  for (int i = 0; i < t->count; ++i) {
+    float e = 0.f;
+    if (hipEventElapsedTime(&e, t->start[i], t->stop[i]) != hipSuccess) return TRISPEC_ELAUNCH;
+    ms += e;
+  }
+  *n_launches = t->count;
+  *total_ms = ms;
+  *total_bytes = t->bytes;
+  return TRISPEC_OK;
+}
+
+int trispec_timer_destroy(trispec_timer *t) {
+  if (!t) return TRISPEC_OK;
+  for (size_t i = 0; i < t->start.size(); ++i) {
+    (void)hipEventDestroy(t->start[i]);
+    (void)hipEventDestroy(t->stop[i]);
+  }
+  delete t;
+  return TRISPEC_OK;
+}
+
+const char *trispec_strerror(int code) {
+  switch (code) {
+    case TRISPEC_OK: return "ok";
+    case TRISPEC_ENULL: return "a required pointer is NULL";
+    case TRISPEC_ESHAPE: return "model shape not supported";
+    case TRISPEC_ENODES: return "n_nodes or batch out of range";
+    case TRISPEC_ETREE: return "tree_parents is not a topologically ordered tree";
+    case TRISPEC_EFORCED: return "n_forced out of range or forced nodes are not a chain";
+    case TRISPEC_ECAPACITY: return "ctx_len + n_nodes exceeds the cache capacity";
+    case TRISPEC_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case TRISPEC_EARG: return "invalid argument";
+    case TRISPEC_EMISMATCH: return "kv cache belongs to another model";
+    case TRISPEC_ELAUNCH: return "HIP launch failed";
+    default: return "unknown error";
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,125 @@
+// Internal declarations shared by the host orchestration (api.cpp) and the kernel
+// translation units.  Nothing here is part of the C ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "trispec.h"
+
+namespace ts {
+
+typedef __bf16 bf16;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+constexpr int kMaxRows = TRISPEC_MAX_ROWS;
+constexpr int kMaxBatch = TRISPEC_MAX_BATCH;
+constexpr int kMaxNodes = TRISPEC_MAX_NODES;
+constexpr int kMaxSplitK = 32;       // k-splits of one matmul
+constexpr int kMaxAttnSplits = 64;   // context splits of one attention call
+constexpr int kGemmTileN = 128;      // output columns per workgroup (4 waves x 32)
+
+// Per-call node table, passed to the set-up kernel by value (3 KB < 4 KB kernarg limit).
+struct NodeTable {
+  uint64_t anc[kMaxRows];   // bit j set <=> node j (same sequence) is an ancestor-or-self
+  int32_t parent[kMaxRows];
+};
+
+struct CtxLens {
+  int32_t v[kMaxBatch];
+};
+
+// One weight-streaming matmul  out[s][r][col] = sum_{k in split s} X[r][k] * W[col][k].
+struct GemmSeg {
+  const void *w;   // [n_rows, K]
+  int32_t n_rows;
+  int32_t col0;    // first output column of this segment
+};
+struct GemmArgs {
+  const void *x;       // [rows_pad, K] activation operand: fp32, or bf16 hi panel followed,
+                       // x_panel elements later, by the bf16 lo panel
+  size_t x_panel;
+  GemmSeg seg[3];
+  int32_t n_seg;
+  int32_t n_total;     // total output columns
+  int32_t k;           // reduction length
+  int32_t rows;        // valid rows
+  int32_t rows_pad;    // multiple of 32
+  int32_t k_per_split; // multiple of 64
+  int32_t n_splits;
+  float *out;          // [n_splits][rows_pad][n_total]
+};
+
+// Per (row, column tile) statistics of the LM-head logits.
+struct HeadStats {
+  float *l1;      // largest logit
+  float *l2;      // second largest logit (-inf if none)
+  float *sumexp;  // sum over the tile of exp(logit - l1)
+  int32_t *idx;   // column of l1 (lowest column among equals)
+  int32_t n_tiles;
+};
+
+struct AttnArgs {
+  const void *q;        // [rows_pad, nq*d] (bf16: hi panel, lo panel `panel` elements later)
+  size_t panel;         // operand panel stride of q and out, in elements
+  const void *k_cache;  // this layer: [B][nkv][cap][d]
+  const void *v_cache;  // this layer: [B][nkv][d][cap]
+  const uint64_t *anc;  // [B*M]
+  const float *qkv;     // [B*M][(nq + 2 nkv) * d] this layer's q, k (rotated) and v in fp32
+  CtxLens ctx;
+  int32_t batch, n_nodes, n_q_heads, n_kv_heads, head_dim, capacity;
+  int32_t keys_per_split;   // multiple of 64
+  int32_t n_splits;
+  float *part_o;        // [B][nkv][n_splits][group*M][d]  unnormalised
+  float *part_m;        // [B][nkv][n_splits][group*M]     running max
+  float *part_l;        // [B][nkv][n_splits][group*M]     sum of exp
+  void *out;            // [rows_pad, nq*d]
+};
+
+struct DecideArgs {
+  const int32_t *tokens;   // device [B*M]
+  const int32_t *parent;   // device [B*M] (workspace copy)
+  int32_t batch, n_nodes, n_forced, criterion;
+  float threshold;
+  // per-node statistics (workspace)
+  float *node_l1, *node_l2, *node_sum;
+  int32_t *node_idx;
+  const int32_t *status_src;   // device status word of the pass (workspace)
+  trispec_verify_out out;
+};
+
+// ---- launchers (one per kernel family); all enqueue on `st` and return nothing:
+// the caller checks hipGetLastError once at the end of the pass.
+void launch_setup(hipStream_t st, const NodeTable &tab, int rows, uint64_t *anc, int32_t *parent,
+                  int32_t *status);
+void launch_rope_table(hipStream_t st, const int32_t *positions, int rows, int head_dim, float base,
+                       float *cos_t, float *sin_t);
+void launch_embed_norm(hipStream_t st, int dtype, const int32_t *tokens, const void *embed,
+                       const void *norm_w, int rows, int hidden, int vocab, float eps, float *x,
+                       void *h, size_t panel, int32_t *status);
+void launch_qkv_epilogue(hipStream_t st, int dtype, const float *part, int n_splits, int rows,
+                         int rows_pad, int n_q_heads, int n_kv_heads, int head_dim,
+                         const float *cos_t, const float *sin_t, int n_nodes, CtxLens ctx,
+                         int capacity, void *q_out, size_t panel, float *qkv_f32, void *k_cache,
+                         void *v_cache);
+void launch_reduce_residual_norm(hipStream_t st, int dtype, const float *part, int n_splits, int rows,
+                                 int rows_pad, int hidden, const void *norm_w, float eps, float *x,
+                                 void *h, size_t panel);
+void launch_reduce_swiglu(hipStream_t st, int dtype, const float *part, int n_splits, int rows,
+                          int rows_pad, int ffn, void *act, size_t panel);
+void launch_gemm_f32(hipStream_t st, const GemmArgs &a);
+void launch_gemm_bf16(hipStream_t st, const GemmArgs &a);
+void launch_lmhead_bf16(hipStream_t st, const GemmArgs &a, const HeadStats &hs, float *debug_logits);
+void launch_stats_from_logits(hipStream_t st, const float *logits, int rows, int vocab,
+                              const HeadStats &hs);
+void launch_attn_f32(hipStream_t st, const AttnArgs &a);
+void launch_attn_bf16(hipStream_t st, const AttnArgs &a);
+void launch_stats_reduce(hipStream_t st, const HeadStats &hs, int rows, float *node_l1, float *node_l2,
+                         float *node_sum, int32_t *node_idx);
+void launch_decide(hipStream_t st, const DecideArgs &a);
+
+}  // namespace ts

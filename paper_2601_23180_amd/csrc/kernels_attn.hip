@@ -1,0 +1,378 @@
+// Tree-masked grouped-query attention of the draft nodes over (context cache + draft nodes).
+//
+// Node i of sequence b attends to cache slots [0, ctx_len_b) and to every draft node j on its
+// root path (bit j of anc[i]).  K is cached [slot][d]; V is cached transposed [d][slot] so that
+// both products read matrix-core operands with 16-byte loads.
+//
+// bf16 path, two parts.  (1) Context: one workgroup per (context split, kv head, sequence) streams
+// the cached K/V — no mask is needed there, every context key is visible to every node.
+// (2) Draft nodes: at most 64 keys, of which a node sees only its ancestors; the merge kernel
+// evaluates them in fp32 straight from this pass's unrounded q/k/v projections (the cache gets
+// bf16 copies for later rounds, but the pass itself never reads them back) and folds them in as
+// one more softmax partial.
+// Context kernel:  The `group` query heads that
+// share the kv head, times the M nodes, form one panel of query rows; four wavefronts each own
+// up to two 32-row blocks of it.  Per 64-key tile, K and V^T are staged in LDS (double buffered),
+// S^T = K Q^T and O^T += V^T P^T run on the matrix cores in the transposed form, which puts one
+// query row per lane: the online-softmax max / sum are per-lane scalars plus one exchange between
+// the two lane halves.  Q and P are fed as a bf16 high part plus a bf16 low part (two MFMAs each),
+// so both products carry ~16 bits of the activation and the result is reproducible against an
+// unrounded reference; K and V are the bf16 values the cache stores.
+// A merge kernel combines the splits in ascending order.
+#include "device_util.hpp"
+
+namespace ts {
+
+// ------------------------------------------------------------------ fp32 path (small models)
+// One wavefront per (row, query head).  Scores of all allowed keys go to LDS, then a plain
+// two-pass softmax and the value sum with one lane per output feature.
+constexpr int kAttnF32MaxKeys = 12288;
+
+__global__ __launch_bounds__(64) void k_attn_f32(AttnArgs a) {
+  extern __shared__ float sc[];
+  const int r = blockIdx.x, head = blockIdx.y, lane = threadIdx.x;
+  const int d = a.head_dim, group = a.n_q_heads / a.n_kv_heads, kvh = head / group;
+  const int b = r / a.n_nodes, node = r - b * a.n_nodes;
+  const int ctx = a.ctx.v[b];
+  const int n_keys = ctx + a.n_nodes;
+  const uint64_t mask = a.anc[r];
+  const float *q = (const float *)a.q + (size_t)r * a.n_q_heads * d + (size_t)head * d;
+  const float *kc = (const float *)a.k_cache + ((size_t)b * a.n_kv_heads + kvh) * a.capacity * d;
+  const float *vc = (const float *)a.v_cache + ((size_t)b * a.n_kv_heads + kvh) * d * a.capacity;
+  const float scale = 1.0f / sqrtf((float)d);
+  float mx = -INFINITY;
+  for (int k = lane; k < n_keys; k += 64) {
+    const bool ok = (k < ctx) || ((mask >> (k - ctx)) & 1ull);
+    float s = -INFINITY;
+    if (ok) {
+      const float *kr = kc + (size_t)k * d;
+      float acc = 0.f;
+      for (int j = 0; j < d; ++j) acc += q[j] * kr[j];
+      s = acc * scale;
+    }
+    sc[k] = s;
+    mx = fmaxf(mx, s);
+  }
+  mx = wave_max(mx);
+  float sum = 0.f;
+  for (int k = lane; k < n_keys; k += 64) {
+    const float p = (sc[k] == -INFINITY) ? 0.f : expf(sc[k] - mx);
+    sc[k] = p;
+    sum += p;
+  }
+  sum = wave_sum(sum);
+  __syncthreads();
+  float *o = (float *)a.out + (size_t)r * a.n_q_heads * d + (size_t)head * d;
+  for (int j = lane; j < d; j += 64) {
+    const float *vr = vc + (size_t)j * a.capacity;
+    float acc = 0.f;
+    for (int k = 0; k < n_keys; ++k) acc += sc[k] * vr[k];
+    o[j] = acc / sum;
+  }
+}
+
+void launch_attn_f32(hipStream_t st, const AttnArgs &a) {
+  int max_keys = 0;
+  for (int b = 0; b < a.batch; ++b) max_keys = max(max_keys, a.ctx.v[b] + a.n_nodes);
+  hipLaunchKernelGGL(k_attn_f32, dim3(a.batch * a.n_nodes, a.n_q_heads), dim3(64),
+                     (size_t)max_keys * sizeof(float), st, a);
+}
+
+// ------------------------------------------------------------------ bf16 path
+constexpr int KT = 64;                      // keys per tile
+template <int D>
+struct AttnLds {
+  static constexpr int kStrideK = D * 2 + 16;     // bytes per key row of the K tile
+  static constexpr int kStrideV = KT * 2 + 8;     // bytes per feature row of the V^T tile
+  static constexpr int kBytesK = KT * kStrideK;
+  static constexpr int kBytesV = D * kStrideV;
+  static constexpr int kBuf = kBytesK + kBytesV;  // one stage
+};
+
+template <int D, int RBW>
+__global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
+  using L = AttnLds<D>;
+  __shared__ __attribute__((aligned(16))) unsigned char lds[2 * L::kBuf];
+  const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int ln = lane & 31, g = lane >> 5;
+  const int M = a.n_nodes, group = a.n_q_heads / a.n_kv_heads;
+  const int p_rows = group * M;
+  const int ctx = a.ctx.v[b];
+  const int n_keys = ctx;            // context only; the draft nodes are handled by the merge kernel
+  const int k_begin = split * a.keys_per_split;
+  const int k_end = min(n_keys, k_begin + a.keys_per_split);
+  const size_t part_base = ((size_t)b * a.n_kv_heads + kvh) * a.n_splits + split;
+
+  // ---- this lane's query rows
+  int prow[RBW];
+  bf16x8 qf[RBW][D / 16], ql[RBW][D / 16];
+#pragma unroll
+  for (int i = 0; i < RBW; ++i) {
+    const int rb = wave + 4 * i;
+    const int p = rb * 32 + ln;
+    prow[i] = p;
+#pragma unroll
+    for (int t = 0; t < D / 16; ++t)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { qf[i][t][e] = (bf16)0.f; ql[i][t][e] = (bf16)0.f; }
+    if (p < p_rows) {
+      const int al = p / M, node = p - al * M;
+      const int r = b * M + node;
+      const bf16 *q = (const bf16 *)a.q + (size_t)r * a.n_q_heads * D + (size_t)(kvh * group + al) * D;
+#pragma unroll
+      for (int t = 0; t < D / 16; ++t) {
+        qf[i][t] = *(const bf16x8 *)(q + 16 * t + 8 * g);
+        ql[i][t] = *(const bf16x8 *)(q + a.panel + 16 * t + 8 * g);
+      }
+    }
+  }
+
+  if (k_begin >= k_end) {   // empty split: neutral partial
+#pragma unroll
+    for (int i = 0; i < RBW; ++i)
+      if (prow[i] < p_rows && g == 0) {
+        a.part_m[part_base * p_rows + prow[i]] = -INFINITY;
+        a.part_l[part_base * p_rows + prow[i]] = 0.f;
+      }
+    return;
+  }
+
+  const bf16 *kc = (const bf16 *)a.k_cache + ((size_t)b * a.n_kv_heads + kvh) * a.capacity * D;
+  const bf16 *vc = (const bf16 *)a.v_cache + ((size_t)b * a.n_kv_heads + kvh) * D * a.capacity;
+  const float scale = 1.0f / sqrtf((float)D);
+
+  // ---- tile staging: K tile = KT rows of D*2 bytes (16-byte vectors), V^T tile = D rows of KT*2 bytes
+  constexpr int KV_PER_T = KT * D * 2 / 16 / 256;   // 16-byte vectors per thread, each of K and V^T
+  uint4 kreg[KV_PER_T], vreg[KV_PER_T];
+  auto load_tile = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < KV_PER_T; ++i) {
+      const int v = tid + 256 * i;
+      {  // K: vector v -> key v / (D/8), 16-byte column v % (D/8)
+        const int key = v / (D / 8), c = v % (D / 8);
+        // slots past n_keys are never written; they stay in bounds (capacity is a multiple of KT)
+        kreg[i] = *(const uint4 *)(kc + (size_t)(k0 + key) * D + c * 8);
+      }
+      {  // V^T: vector v -> feature v / (KT/8), 8 keys starting at (v % (KT/8)) * 8
+        const int f = v / (KT / 8), c = v % (KT / 8);
+        uint4 t = *(const uint4 *)(vc + (size_t)f * a.capacity + k0 + c * 8);
+        const int kfirst = k0 + c * 8;
+        if (kfirst + 8 > n_keys) {   // zero the values of slots that hold no token
+          uint32_t w[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            if (kfirst + e >= n_keys) w[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
+          t = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+        vreg[i] = t;
+      }
+    }
+  };
+  auto store_tile = [&](int buf) {
+    unsigned char *base = lds + buf * L::kBuf;
+#pragma unroll
+    for (int i = 0; i < KV_PER_T; ++i) {
+      const int v = tid + 256 * i;
+      {
+        const int key = v / (D / 8), c = v % (D / 8);
+        *(uint4 *)(base + key * L::kStrideK + c * 16) = kreg[i];
+      }
+      {
+        const int f = v / (KT / 8), c = v % (KT / 8);
+        uint2 *dst = (uint2 *)(base + L::kBytesK + f * L::kStrideV + c * 16);
+        dst[0] = make_uint2(vreg[i].x, vreg[i].y);
+        dst[1] = make_uint2(vreg[i].z, vreg[i].w);
+      }
+    }
+  };
+
+  // ---- running state per row block: one query row per lane (both lane halves hold the same row)
+  float m_run[RBW], l_run[RBW];
+  f32x16 oacc[RBW][D / 32];
+#pragma unroll
+  for (int i = 0; i < RBW; ++i) {
+    m_run[i] = -INFINITY;
+    l_run[i] = 0.f;
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) oacc[i][db][e] = 0.f;
+  }
+
+  const int n_tiles = (k_end - k_begin + KT - 1) / KT;
+  load_tile(k_begin);
+  store_tile(0);
+  __syncthreads();
+
+  for (int t = 0; t < n_tiles; ++t) {
+    const int k0 = k_begin + t * KT;
+    const int buf = t & 1;
+    if (t + 1 < n_tiles) load_tile(k0 + KT);
+    const unsigned char *kb = lds + buf * L::kBuf;
+    const unsigned char *vb = kb + L::kBytesK;
+    const bool need_mask = (k0 + KT > n_keys);
+
+#pragma unroll
+    for (int i = 0; i < RBW; ++i) {
+      if ((wave + 4 * i) * 32 >= p_rows) continue;   // wave-uniform
+      // S^T[key][row] for the two 32-key sub-tiles
+      f32x16 s[KT / 32];
+#pragma unroll
+      for (int ks = 0; ks < KT / 32; ++ks) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s[ks][e] = 0.f;
+#pragma unroll
+        for (int tt = 0; tt < D / 16; ++tt) {
+          const bf16x8 kf = *(const bf16x8 *)(kb + (ks * 32 + ln) * L::kStrideK + (16 * tt + 8 * g) * 2);
+          s[ks] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[i][tt], s[ks], 0, 0, 0);
+          s[ks] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, ql[i][tt], s[ks], 0, 0, 0);
+        }
+      }
+      // scale, mask, tile max
+      float tmax = -INFINITY;
+#pragma unroll
+      for (int ks = 0; ks < KT / 32; ++ks)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int key = k0 + ks * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
+          float v = s[ks][e] * scale;
+          if (need_mask) v = (key < n_keys) ? v : -INFINITY;
+          s[ks][e] = v;
+          tmax = fmaxf(tmax, v);
+        }
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+      const float m_new = fmaxf(m_run[i], tmax);
+      const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = expf(m_run[i] - m_safe);   // exp(-inf) = 0 on the first tile
+      m_run[i] = m_new;
+      float psum = 0.f;
+      bf16x8 phi[KT / 16], plo[KT / 16];
+#pragma unroll
+      for (int ks = 0; ks < KT / 32; ++ks)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const float p = expf(s[ks][e] - m_safe);   // exp(-inf) = 0 for masked keys
+          psum += p;
+          const bf16 hi = (bf16)p;
+          const bf16 lo = (bf16)(p - (float)hi);
+          phi[ks * 2 + (e >> 3)][e & 7] = hi;
+          plo[ks * 2 + (e >> 3)][e & 7] = lo;
+        }
+      l_run[i] = l_run[i] * alpha + psum;
+      // O^T[feature][row] = alpha * O^T + V^T P^T
+#pragma unroll
+      for (int db = 0; db < D / 32; ++db) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) oacc[i][db][e] *= alpha;
+#pragma unroll
+        for (int u = 0; u < KT / 16; ++u) {
+          // key slots of lane half g at step u: 16u + 4g + {0..3} and 16u + 8 + 4g + {0..3}
+          const unsigned char *vp = vb + (db * 32 + ln) * L::kStrideV + (16 * u + 4 * g) * 2;
+          const uint2 v0 = *(const uint2 *)vp;
+          const uint2 v1 = *(const uint2 *)(vp + 16);
+          const uint4 vv = make_uint4(v0.x, v0.y, v1.x, v1.y);
+          const bf16x8 vf = *(const bf16x8 *)&vv;
+          oacc[i][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, phi[u], oacc[i][db], 0, 0, 0);
+          oacc[i][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, plo[u], oacc[i][db], 0, 0, 0);
+        }
+      }
+    }
+    if (t + 1 < n_tiles) store_tile(buf ^ 1);
+    __syncthreads();
+  }
+
+  // ---- write the split's partial: O[row][feature] unnormalised, m, l
+#pragma unroll
+  for (int i = 0; i < RBW; ++i) {
+    const int p = prow[i];
+    if (p >= p_rows) continue;
+    const float l_tot = l_run[i] + __shfl_xor(l_run[i], 32, 64);
+    if (g == 0) {
+      a.part_m[part_base * p_rows + p] = m_run[i];
+      a.part_l[part_base * p_rows + p] = l_tot;
+    }
+    float *o = a.part_o + (part_base * p_rows + p) * D;
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        f32x4 v;
+        v[0] = oacc[i][db][4 * q4 + 0]; v[1] = oacc[i][db][4 * q4 + 1];
+        v[2] = oacc[i][db][4 * q4 + 2]; v[3] = oacc[i][db][4 * q4 + 3];
+        *(f32x4 *)(o + db * 32 + 8 * q4 + 4 * g) = v;
+      }
+  }
+}
+
+// Combine the context splits of one (row, query head), ascending split order, with the draft-node
+// part: for every ancestor-or-self j of the node, score = q . k_j / sqrt(d) and value v_j, all
+// taken in fp32 from this pass's projections (a.qkv: [row][(nq + 2 nkv) * d], q and k already
+// rotated).  One thread per output feature.
+template <int D>
+__global__ __launch_bounds__(D) void k_attn_merge(AttnArgs a) {
+  __shared__ float sc[kMaxNodes];
+  __shared__ float red[2];
+  const int r = blockIdx.x, head = blockIdx.y, f = threadIdx.x;
+  const int M = a.n_nodes, group = a.n_q_heads / a.n_kv_heads;
+  const int b = r / M, node = r - b * M;
+  const int kvh = head / group, al = head - kvh * group;
+  const int p_rows = group * M, p = al * M + node;
+  const size_t base = ((size_t)b * a.n_kv_heads + kvh) * a.n_splits;
+  const int n_total = (a.n_q_heads + 2 * a.n_kv_heads) * D;
+  const uint64_t mask = a.anc[r];
+  const float scale = 1.0f / sqrtf((float)D);
+  const float qf = a.qkv[(size_t)r * n_total + head * D + f];
+  float m_tot = -INFINITY;
+  for (int j = 0; j <= node; ++j) {       // ancestors have lower node ids
+    if (!((mask >> j) & 1ull)) continue;  // uniform over the workgroup
+    const float kf = a.qkv[(size_t)(b * M + j) * n_total + (a.n_q_heads + kvh) * D + f];
+    float v = wave_sum(qf * kf);
+    if (D > 64) {
+      __syncthreads();
+      if ((f & 63) == 0) red[f >> 6] = v;
+      __syncthreads();
+      v = red[0] + red[1];
+    }
+    v *= scale;
+    if (f == 0) sc[j] = v;
+    m_tot = fmaxf(m_tot, v);
+  }
+  __syncthreads();
+  for (int s = 0; s < a.n_splits; ++s) m_tot = fmaxf(m_tot, a.part_m[(base + s) * p_rows + p]);
+  float num = 0.f, den = 0.f;
+  for (int s = 0; s < a.n_splits; ++s) {
+    const float ms = a.part_m[(base + s) * p_rows + p];
+    if (ms == -INFINITY) continue;
+    const float w = expf(ms - m_tot);
+    num += a.part_o[((base + s) * p_rows + p) * D + f] * w;
+    den += a.part_l[(base + s) * p_rows + p] * w;
+  }
+  for (int j = 0; j <= node; ++j) {
+    if (!((mask >> j) & 1ull)) continue;
+    const float w = expf(sc[j] - m_tot);
+    num += w * a.qkv[(size_t)(b * M + j) * n_total + (a.n_q_heads + a.n_kv_heads + kvh) * D + f];
+    den += w;
+  }
+  store_act((bf16 *)a.out, a.panel, (size_t)r * a.n_q_heads * D + (size_t)head * D + f, num / den);
+}
+
+template <int D>
+static void launch_attn_bf16_d(hipStream_t st, const AttnArgs &a) {
+  const int group = a.n_q_heads / a.n_kv_heads;
+  const int p_rows = group * a.n_nodes;
+  const int nrb = (p_rows + 31) / 32;
+  dim3 grid(a.n_splits, a.n_kv_heads, a.batch);
+  if (nrb <= 4)
+    hipLaunchKernelGGL((k_attn_bf16<D, 1>), grid, dim3(256), 0, st, a);
+  else
+    hipLaunchKernelGGL((k_attn_bf16<D, 2>), grid, dim3(256), 0, st, a);
+  hipLaunchKernelGGL(k_attn_merge<D>, dim3(a.batch * a.n_nodes, a.n_q_heads), dim3(D), 0, st, a);
+}
+
+void launch_attn_bf16(hipStream_t st, const AttnArgs &a) {
+  if (a.head_dim == 128) launch_attn_bf16_d<128>(st, a);
+  else launch_attn_bf16_d<64>(st, a);
+}
+
+}  // namespace ts

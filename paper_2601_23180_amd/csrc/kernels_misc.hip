@@ -1,0 +1,338 @@
+// Small kernels of the verification pass: set-up, rotary table, embedding + RMSNorm,
+// split-K reductions with their fused epilogues (rotary + KV append, residual + RMSNorm,
+// SiLU*up), vocabulary statistics reduction and the routing decision.
+// Templated on the activation / storage type AT (float for fp32 models, bf16 otherwise).
+#include "device_util.hpp"
+
+namespace ts {
+
+// ------------------------------------------------------------------ set-up
+__global__ void k_setup(NodeTable tab, int rows, uint64_t *anc, int32_t *parent, int32_t *status) {
+  const int i = threadIdx.x;
+  if (i < rows) {
+    anc[i] = tab.anc[i];
+    parent[i] = tab.parent[i];
+  }
+  if (i == 0) *status = 0;
+}
+
+void launch_setup(hipStream_t st, const NodeTable &tab, int rows, uint64_t *anc, int32_t *parent,
+                  int32_t *status) {
+  hipLaunchKernelGGL(k_setup, dim3(1), dim3(kMaxRows), 0, st, tab, rows, anc, parent, status);
+}
+
+// angle[r][j] = position_r * base^(-2j/d), evaluated in fp64 so that large positions keep
+// their phase; the table holds fp32 cos / sin.
+__global__ void k_rope_table(const int32_t *positions, int head_dim, float base, float *cos_t,
+                             float *sin_t) {
+  const int r = blockIdx.x, j = threadIdx.x;
+  const int half = head_dim >> 1;
+  if (j >= half) return;
+  const double inv = pow((double)base, -2.0 * (double)j / (double)head_dim);
+  const double ang = (double)positions[r] * inv;
+  cos_t[r * half + j] = (float)cos(ang);
+  sin_t[r * half + j] = (float)sin(ang);
+}
+
+void launch_rope_table(hipStream_t st, const int32_t *positions, int rows, int head_dim, float base,
+                       float *cos_t, float *sin_t) {
+  hipLaunchKernelGGL(k_rope_table, dim3(rows), dim3(head_dim / 2), 0, st, positions, head_dim, base,
+                     cos_t, sin_t);
+}
+
+// ------------------------------------------------------------------ embedding + first RMSNorm
+template <typename AT>
+__global__ __launch_bounds__(256) void k_embed_norm(const int32_t *tokens, const AT *embed,
+                                                    const AT *norm_w, int hidden, int vocab, float eps,
+                                                    float *x, AT *h, size_t panel, int32_t *status) {
+  __shared__ float red[4];
+  const int r = blockIdx.x;
+  int tok = tokens[r];
+  if (tok < 0 || tok >= vocab) {
+    if (threadIdx.x == 0) atomicOr(status, 1);
+    tok = 0;
+  }
+  const AT *e = embed + (size_t)tok * hidden;
+  float *xr = x + (size_t)r * hidden;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < hidden; i += 256) {
+    const float v = to_f32(e[i]);
+    xr[i] = v;
+    ss += v * v;
+  }
+  ss = block_sum<4>(ss, red);
+  const float rstd = 1.0f / sqrtf(ss / (float)hidden + eps);
+  for (int i = threadIdx.x; i < hidden; i += 256)
+    store_act(h, panel, (size_t)r * hidden + i, to_f32(e[i]) * rstd * to_f32(norm_w[i]));
+}
+
+void launch_embed_norm(hipStream_t st, int dtype, const int32_t *tokens, const void *embed,
+                       const void *norm_w, int rows, int hidden, int vocab, float eps, float *x,
+                       void *h, size_t panel, int32_t *status) {
+  if (dtype == TRISPEC_F32)
+    hipLaunchKernelGGL(k_embed_norm<float>, dim3(rows), dim3(256), 0, st, tokens, (const float *)embed,
+                       (const float *)norm_w, hidden, vocab, eps, x, (float *)h, panel, status);
+  else
+    hipLaunchKernelGGL(k_embed_norm<bf16>, dim3(rows), dim3(256), 0, st, tokens, (const bf16 *)embed,
+                       (const bf16 *)norm_w, hidden, vocab, eps, x, (bf16 *)h, panel, status);
+}
+
+// Sum of the split-K partials of one output element, ascending split order.
+__device__ __forceinline__ float sum_splits(const float *part, int n_splits, size_t slice, size_t off) {
+  float v = part[off];
+  for (int s = 1; s < n_splits; ++s) v += part[(size_t)s * slice + off];
+  return v;
+}
+
+// ------------------------------------------------------------------ QKV epilogue
+// One workgroup per (row, head).  Sums the partials of the head's columns, applies the rotary
+// embedding to q and k heads (pair (j, j + d/2)); q goes to the attention operand buffer, k and v
+// are rounded to the cache's storage type and written to slot ctx_len + node (v transposed).
+template <typename AT>
+__global__ void k_qkv_epilogue(const float *part, int n_splits, int rows_pad, int n_q_heads,
+                               int n_kv_heads, int head_dim, const float *cos_t, const float *sin_t,
+                               int n_nodes, CtxLens ctx, int capacity, AT *q_out, size_t panel,
+                               float *qkv_f32, AT *k_cache, AT *v_cache) {
+  const int r = blockIdx.x, hh = blockIdx.y, j = threadIdx.x;
+  const int half = head_dim >> 1;
+  if (j >= half) return;
+  const int n_total = (n_q_heads + 2 * n_kv_heads) * head_dim;
+  const size_t slice = (size_t)rows_pad * n_total;
+  const size_t off = (size_t)r * n_total + (size_t)hh * head_dim + j;
+  float a = sum_splits(part, n_splits, slice, off);
+  float b = sum_splits(part, n_splits, slice, off + half);
+  const int bidx = r / n_nodes, node = r - bidx * n_nodes;
+  const int slot = ctx.v[bidx] + node;
+  if (hh < n_q_heads + n_kv_heads) {
+    const float c = cos_t[r * half + j], s = sin_t[r * half + j];
+    const float ra = a * c - b * s;
+    const float rb = b * c + a * s;
+    a = ra; b = rb;
+  }
+  if (qkv_f32 != nullptr) {   // unrounded copy for the draft-node part of the attention
+    qkv_f32[off] = a;
+    qkv_f32[off + half] = b;
+  }
+  if (hh < n_q_heads) {
+    const size_t qi = (size_t)r * n_q_heads * head_dim + (size_t)hh * head_dim + j;
+    store_act(q_out, panel, qi, a);
+    store_act(q_out, panel, qi + half, b);
+  } else if (hh < n_q_heads + n_kv_heads) {
+    const int kvh = hh - n_q_heads;
+    AT *k = k_cache + (((size_t)bidx * n_kv_heads + kvh) * capacity + slot) * head_dim;
+    k[j] = from_f32<AT>(a);
+    k[j + half] = from_f32<AT>(b);
+  } else {
+    const int kvh = hh - n_q_heads - n_kv_heads;
+    AT *v = v_cache + ((size_t)bidx * n_kv_heads + kvh) * head_dim * capacity;
+    v[(size_t)j * capacity + slot] = from_f32<AT>(a);
+    v[(size_t)(j + half) * capacity + slot] = from_f32<AT>(b);
+  }
+}
+
+void launch_qkv_epilogue(hipStream_t st, int dtype, const float *part, int n_splits, int rows,
+                         int rows_pad, int n_q_heads, int n_kv_heads, int head_dim,
+                         const float *cos_t, const float *sin_t, int n_nodes, CtxLens ctx,
+                         int capacity, void *q_out, size_t panel, float *qkv_f32, void *k_cache,
+                         void *v_cache) {
+  dim3 grid(rows, n_q_heads + 2 * n_kv_heads), block(head_dim / 2);
+  if (dtype == TRISPEC_F32)
+    hipLaunchKernelGGL(k_qkv_epilogue<float>, grid, block, 0, st, part, n_splits, rows_pad, n_q_heads,
+                       n_kv_heads, head_dim, cos_t, sin_t, n_nodes, ctx, capacity, (float *)q_out, panel,
+                       qkv_f32, (float *)k_cache, (float *)v_cache);
+  else
+    hipLaunchKernelGGL(k_qkv_epilogue<bf16>, grid, block, 0, st, part, n_splits, rows_pad, n_q_heads,
+                       n_kv_heads, head_dim, cos_t, sin_t, n_nodes, ctx, capacity, (bf16 *)q_out, panel,
+                       qkv_f32, (bf16 *)k_cache, (bf16 *)v_cache);
+}
+
+// ------------------------------------------------------------------ residual + RMSNorm
+// x[r] += sum of partials; h[r] = x[r] * rstd * w (as an operand pair).  One workgroup per row.
+template <typename AT>
+__global__ __launch_bounds__(256) void k_reduce_residual_norm(const float *part, int n_splits,
+                                                              int rows_pad, int hidden, const AT *norm_w,
+                                                              float eps, float *x, AT *h, size_t panel) {
+  __shared__ float red[4];
+  const int r = blockIdx.x;
+  const size_t slice = (size_t)rows_pad * hidden;
+  float *xr = x + (size_t)r * hidden;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < hidden; i += 256) {
+    const float v = xr[i] + sum_splits(part, n_splits, slice, (size_t)r * hidden + i);
+    xr[i] = v;
+    ss += v * v;
+  }
+  ss = block_sum<4>(ss, red);
+  const float rstd = 1.0f / sqrtf(ss / (float)hidden + eps);
+  for (int i = threadIdx.x; i < hidden; i += 256)
+    store_act(h, panel, (size_t)r * hidden + i, xr[i] * rstd * to_f32(norm_w[i]));
+}
+
+void launch_reduce_residual_norm(hipStream_t st, int dtype, const float *part, int n_splits, int rows,
+                                 int rows_pad, int hidden, const void *norm_w, float eps, float *x,
+                                 void *h, size_t panel) {
+  if (dtype == TRISPEC_F32)
+    hipLaunchKernelGGL(k_reduce_residual_norm<float>, dim3(rows), dim3(256), 0, st, part, n_splits,
+                       rows_pad, hidden, (const float *)norm_w, eps, x, (float *)h, panel);
+  else
+    hipLaunchKernelGGL(k_reduce_residual_norm<bf16>, dim3(rows), dim3(256), 0, st, part, n_splits,
+                       rows_pad, hidden, (const bf16 *)norm_w, eps, x, (bf16 *)h, panel);
+}
+
+// ------------------------------------------------------------------ SiLU(gate) * up
+// partial columns [0, F) are the gate projection, [F, 2F) the up projection.
+template <typename AT>
+__global__ __launch_bounds__(256) void k_reduce_swiglu(const float *part, int n_splits, int rows_pad,
+                                                       int ffn, AT *act, size_t panel) {
+  const int r = blockIdx.y;
+  const int f = blockIdx.x * 256 + threadIdx.x;
+  if (f >= ffn) return;
+  const size_t slice = (size_t)rows_pad * 2 * ffn;
+  const size_t off = (size_t)r * 2 * ffn + f;
+  const float g = sum_splits(part, n_splits, slice, off);
+  const float u = sum_splits(part, n_splits, slice, off + ffn);
+  const float silu = g / (1.0f + expf(-g));
+  store_act(act, panel, (size_t)r * ffn + f, silu * u);
+}
+
+void launch_reduce_swiglu(hipStream_t st, int dtype, const float *part, int n_splits, int rows,
+                          int rows_pad, int ffn, void *act, size_t panel) {
+  dim3 grid((ffn + 255) / 256, rows);
+  if (dtype == TRISPEC_F32)
+    hipLaunchKernelGGL(k_reduce_swiglu<float>, grid, dim3(256), 0, st, part, n_splits, rows_pad, ffn,
+                       (float *)act, panel);
+  else
+    hipLaunchKernelGGL(k_reduce_swiglu<bf16>, grid, dim3(256), 0, st, part, n_splits, rows_pad, ffn,
+                       (bf16 *)act, panel);
+}
+
+// ------------------------------------------------------------------ fp32 reference-precision matmul
+// One wavefront per (output column, group of 8 rows); lanes stride the reduction.
+__global__ __launch_bounds__(64) void k_gemm_f32(GemmArgs a) {
+  const int col = blockIdx.x;
+  const int r0 = blockIdx.y * 8;
+  int s = 0;
+  while (s + 1 < a.n_seg && col >= a.seg[s + 1].col0) ++s;
+  const float *w = (const float *)a.seg[s].w + (size_t)(col - a.seg[s].col0) * a.k;
+  const float *x = (const float *)a.x;
+  float acc[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+  for (int k = threadIdx.x; k < a.k; k += 64) {
+    const float wv = w[k];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (r0 + j < a.rows) acc[j] += x[(size_t)(r0 + j) * a.k + k] * wv;
+  }
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const float v = wave_sum(acc[j]);
+    if (threadIdx.x == 0 && r0 + j < a.rows) a.out[(size_t)(r0 + j) * a.n_total + col] = v;
+  }
+}
+
+void launch_gemm_f32(hipStream_t st, const GemmArgs &a) {
+  hipLaunchKernelGGL(k_gemm_f32, dim3(a.n_total, (a.rows + 7) / 8), dim3(64), 0, st, a);
+}
+
+// ------------------------------------------------------------------ vocabulary statistics
+// fp32 models: scan a row of materialised logits.  One workgroup per row, 256 threads, each
+// scanning a contiguous slab in ascending order.
+__global__ __launch_bounds__(256) void k_stats_from_logits(const float *logits, int vocab, HeadStats hs) {
+  __shared__ Top2 sm[4];
+  const int r = blockIdx.x;
+  const float *row = logits + (size_t)r * vocab;
+  const int per = (vocab + 255) / 256;
+  const int lo = threadIdx.x * per, hi = min(vocab, lo + per);
+  Top2 t = top2_empty();
+  for (int c = lo; c < hi; ++c) top2_push(t, row[c], c);
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) t = top2_merge(t, top2_shfl_xor(t, o));
+  if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = t;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    Top2 a = sm[0];
+    for (int w = 1; w < 4; ++w) a = top2_merge(a, sm[w]);
+    hs.l1[r] = a.l1; hs.l2[r] = a.l2; hs.sumexp[r] = a.s; hs.idx[r] = a.idx;
+  }
+}
+
+void launch_stats_from_logits(hipStream_t st, const float *logits, int rows, int vocab,
+                              const HeadStats &hs) {
+  hipLaunchKernelGGL(k_stats_from_logits, dim3(rows), dim3(256), 0, st, logits, vocab, hs);
+}
+
+// Merge the per-tile statistics of every row: one wavefront per row, lanes stride the tiles.
+__global__ __launch_bounds__(64) void k_stats_reduce(HeadStats hs, float *node_l1, float *node_l2,
+                                                     float *node_sum, int32_t *node_idx) {
+  const int r = blockIdx.x;
+  Top2 t = top2_empty();
+  for (int i = threadIdx.x; i < hs.n_tiles; i += 64) {
+    Top2 b;
+    const size_t o = (size_t)r * hs.n_tiles + i;
+    b.l1 = hs.l1[o]; b.l2 = hs.l2[o]; b.s = hs.sumexp[o]; b.idx = hs.idx[o];
+    t = top2_merge(t, b);
+  }
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) t = top2_merge(t, top2_shfl_xor(t, o));
+  if (threadIdx.x == 0) {
+    node_l1[r] = t.l1; node_l2[r] = t.l2; node_sum[r] = t.s; node_idx[r] = t.idx;
+  }
+}
+
+void launch_stats_reduce(hipStream_t st, const HeadStats &hs, int rows, float *node_l1, float *node_l2,
+                         float *node_sum, int32_t *node_idx) {
+  hipLaunchKernelGGL(k_stats_reduce, dim3(rows), dim3(64), 0, st, hs, node_l1, node_l2, node_sum,
+                     node_idx);
+}
+
+// ------------------------------------------------------------------ decision
+// One workgroup per sequence.  Threads fill the per-node outputs; thread 0 then walks the tree:
+// at the current node test the trust predicate first (tau_a = tau_m is an escalation), then
+// follow the lowest-numbered child whose draft token equals the verifier's argmax.
+__global__ __launch_bounds__(64) void k_decide(DecideArgs a) {
+  __shared__ float s_conf[kMaxNodes], s_margin[kMaxNodes];
+  __shared__ int s_arg[kMaxNodes], s_tok[kMaxNodes], s_par[kMaxNodes];
+  const int b = blockIdx.x, i = threadIdx.x, M = a.n_nodes;
+  if (i < M) {
+    const int r = b * M + i;
+    const float s = a.node_sum[r];
+    const float conf = 1.0f / s;                                   // exp(l1 - l1) / sum
+    const float p2 = expf(a.node_l2[r] - a.node_l1[r]) / s;        // 0 when there is no second entry
+    s_conf[i] = conf;
+    s_margin[i] = conf - p2;
+    s_arg[i] = a.node_idx[r];
+    s_tok[i] = a.tokens[r];
+    s_par[i] = a.parent[r];
+    if (a.out.argmax) a.out.argmax[r] = s_arg[i];
+    if (a.out.confidence) a.out.confidence[r] = conf;
+    if (a.out.margin) a.out.margin[r] = s_margin[i];
+  }
+  if (a.out.path) a.out.path[b * TRISPEC_PATH_STRIDE + i] = -1;
+  __syncthreads();
+  if (i != 0) return;
+  int cur = a.n_forced - 1, acc = 0, token = -1, esc = 0;
+  if (a.out.path) a.out.path[b * TRISPEC_PATH_STRIDE] = cur;
+  for (int step = 0; step <= M; ++step) {
+    const float stat = (a.criterion == TRISPEC_CRIT_MARGIN) ? s_margin[cur] : s_conf[cur];
+    if (!(stat >= a.threshold)) { esc = 1; token = -1; break; }
+    const int t = s_arg[cur];
+    int nxt = -1;
+    for (int c = cur + 1; c < M; ++c)
+      if (s_par[c] == cur && s_tok[c] == t) { nxt = c; break; }
+    if (nxt < 0) { token = t; break; }
+    cur = nxt;
+    ++acc;
+    if (a.out.path) a.out.path[b * TRISPEC_PATH_STRIDE + acc] = cur;
+  }
+  if (b == 0 && a.out.status) *a.out.status = *a.status_src;
+  if (a.out.accepted_len) a.out.accepted_len[b] = acc;
+  if (a.out.token) a.out.token[b] = token;
+  if (a.out.escalate) a.out.escalate[b] = esc;
+}
+
+void launch_decide(hipStream_t st, const DecideArgs &a) {
+  hipLaunchKernelGGL(k_decide, dim3(a.batch), dim3(64), 0, st, a);
+}
+
+}  // namespace ts

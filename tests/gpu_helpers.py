@@ -1,0 +1,95 @@
+"""GPU-side test helpers: build a device model + cache from the seeded generators, run the
+HIP path and the oracle on the same inputs."""
+import numpy as np
+import torch
+
+from oracle import (CRIT_MARGIN, OracleWeights, causal_forward, decide, node_stats, tie_flags,
+                    verify_forward)
+from paper_2601_23180_amd import KVCache, Model, Verifier, fill_kv_layer, model_from_arrays
+from workloads import WeightSource, gen_kv_cache, tree_depths
+
+
+def device_model(shape, seed):
+    ws = WeightSource(shape, seed)
+    get = ws.bits if shape.dtype == "bf16" else ws.get
+    return model_from_arrays(shape, get)
+
+
+def capacity_for(n):
+    return (n + 63) // 64 * 64
+
+
+class Case:
+    """One verify problem: a model, per-sequence context K/V (oracle layout [L, n_kv, C, d]),
+    draft tokens / parents / positions per sequence."""
+
+    def __init__(self, shape, seed, k_ctx, v_ctx, tokens, parents, positions):
+        self.shape, self.seed = shape, seed
+        self.k_ctx, self.v_ctx = k_ctx, v_ctx           # lists over batch
+        self.tokens = np.asarray(tokens, dtype=np.int32).reshape(len(k_ctx), -1)
+        self.parents = np.asarray(parents, dtype=np.int32).reshape(len(k_ctx), -1)
+        self.positions = np.asarray(positions, dtype=np.int32).reshape(len(k_ctx), -1)
+        self.batch, self.n_nodes = self.tokens.shape
+        self.ctx_len = [k.shape[2] for k in k_ctx]
+
+    def run_oracle(self):
+        W = OracleWeights(WeightSource(self.shape, self.seed).get)
+        outs = []
+        for b in range(self.batch):
+            o = verify_forward(W, self.shape, self.k_ctx[b], self.v_ctx[b], self.tokens[b], self.parents[b],
+                               self.positions[b])
+            o["stats"] = node_stats(o["logits"])
+            outs.append(o)
+        return outs
+
+    def run_gpu(self, threshold, criterion=CRIT_MARGIN, n_forced=1, model=None, want_logits=True):
+        model = model or device_model(self.shape, self.seed)
+        cap = capacity_for(max(self.ctx_len) + self.n_nodes)
+        kv = KVCache(model, self.batch, cap)
+        # poison the unused slots so that a kernel reading them shows up
+        kv.k.fill_(float("nan")); kv.v.fill_(float("nan"))
+        for l in range(self.shape.n_layers):
+            for b in range(self.batch):
+                C = self.ctx_len[b]
+                kt = torch.from_numpy(np.asarray(self.k_ctx[b][l], dtype=np.float32)).cuda().to(kv.k.dtype)
+                vt = torch.from_numpy(np.asarray(self.v_ctx[b][l], dtype=np.float32)).cuda().to(kv.v.dtype)
+                kv.k[l, b, :, :C, :] = kt
+                kv.v[l, b, :, :, :C] = vt.transpose(-1, -2)
+        kv.set_len(self.ctx_len)
+        ver = Verifier(model, self.batch, self.n_nodes, debug_logits=want_logits)
+        tok = torch.from_numpy(self.tokens).cuda()
+        pos = torch.from_numpy(self.positions).cuda()
+        out = ver.verify(kv, tok, self.parents, pos, threshold, criterion, n_forced)
+        torch.cuda.synchronize()
+        res = {k: v.cpu().numpy().copy() for k, v in out.items()}
+        if want_logits:
+            res["logits"] = ver.logits.cpu().numpy().copy()
+        res["_ver"], res["_kv"], res["_model"], res["_tok"] = ver, kv, model, tok
+        return res
+
+
+def oracle_decision(case, oracle_out, b, threshold, criterion, n_forced=1):
+    st = oracle_out[b]["stats"]
+    return decide(case.tokens[b], case.parents[b], st["argmax"], st["conf"], st["margin"], threshold,
+                  criterion, n_forced)
+
+
+def compare_decisions(case, gpu, oracle_out, threshold, criterion, n_forced=1):
+    """Bit-exact accepted_len / token / escalate / path / argmax unless the oracle flags a tie
+    (statistic within 1e-3 of the threshold, or top-2 logit gap below 1e-3) on a node the walk
+    can reach; returns the number of tie-excused sequences."""
+    excused = 0
+    for b in range(case.batch):
+        st = oracle_out[b]["stats"]
+        flags = tie_flags(st, threshold, criterion)
+        want = oracle_decision(case, oracle_out, b, threshold, criterion, n_forced)
+        got_path = [int(v) for v in gpu["path"][b] if v >= 0]
+        same = (int(gpu["accepted_len"][b]) == want["accepted_len"] and int(gpu["token"][b]) == want["token"]
+                and int(gpu["escalate"][b]) == want["escalate"] and got_path == want["path"])
+        touched = set(want["path"]) | set(got_path)
+        if not same:
+            assert any(flags[i] for i in touched), (b, want, got_path, gpu["accepted_len"][b], gpu["token"][b])
+            excused += 1
+        gap_ok = (st["l1"] - st["l2"]) >= 1e-3
+        assert np.array_equal(gpu["argmax"][b][gap_ok], st["argmax"][gap_ok])
+    return excused

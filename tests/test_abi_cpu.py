@@ -1,0 +1,130 @@
+"""CPU-only checks of the C ABI: the library loads, exports every symbol the header declares,
+and the host-side validation returns the documented error codes without touching a GPU."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2601_23180_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_symbols():
+    src = open(os.path.join(ROOT, "include", "trispec.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(trispec_[a-z_]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.lib()
+    syms = header_symbols()
+    assert len(syms) >= 11
+    for s in syms:
+        assert hasattr(lib, s), s
+    assert sorted(B.EXPORTS) == syms
+
+
+def _cfg(**kw):
+    base = dict(n_layers=2, hidden=256, n_q_heads=4, n_kv_heads=2, head_dim=64, ffn=512, vocab=4096,
+                dtype=B.TRISPEC_F32, rms_eps=1e-6, rope_base=1e4)
+    base.update(kw)
+    return B.ModelConfig(*[base[k] for k, _ in B.ModelConfig._fields_])
+
+
+def _fake_weights(n_layers):
+    w = B.Weights()
+    fake = 0x1000
+    w.embed = w.lm_head = w.final_norm = fake
+    keep = []
+    for n in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "norm_attn", "norm_ffn"):
+        arr = (C.c_void_p * n_layers)(*([fake] * n_layers))
+        keep.append(arr)
+        setattr(w, n, C.cast(arr, C.POINTER(C.c_void_p)))
+    return w, keep
+
+
+def _model(**kw):
+    cfg = _cfg(**kw)
+    w, keep = _fake_weights(cfg.n_layers)
+    h = C.c_void_p()
+    rc = B.lib().trispec_model_create(C.byref(cfg), C.byref(w), C.byref(h))
+    return rc, h, keep
+
+
+def test_model_create_validation():
+    lib = B.lib()
+    assert lib.trispec_model_create(None, None, None) == -1
+    assert _model()[0] == 0
+    assert _model(head_dim=96)[0] == -2
+    assert _model(n_q_heads=5)[0] == -2
+    assert _model(dtype=7)[0] == -2
+    assert _model(dtype=B.TRISPEC_BF16, hidden=250)[0] == -2
+    cfg = _cfg()
+    w, keep = _fake_weights(2)
+    w.lm_head = None
+    h = C.c_void_p()
+    assert lib.trispec_model_create(C.byref(cfg), C.byref(w), C.byref(h)) == -1
+    assert b"NULL" in lib.trispec_strerror(-1)
+
+
+def test_kv_and_workspace_sizes():
+    lib = B.lib()
+    rc, m, keep = _model()
+    n = C.c_size_t()
+    assert lib.trispec_kv_bytes(m, 1, 256, C.byref(n)) == 0
+    assert n.value == 2 * 1 * 2 * 256 * 64 * 4
+    assert lib.trispec_kv_bytes(m, 1, 100, C.byref(n)) == -6      # capacity not a multiple of 64
+    assert lib.trispec_kv_bytes(m, 9, 256, C.byref(n)) == -3
+    assert lib.trispec_workspace_bytes(m, 1, 9, C.byref(n)) == 0 and n.value > 0
+    small = n.value
+    assert lib.trispec_workspace_bytes(m, 4, 60, C.byref(n)) == 0 and n.value > small
+    assert lib.trispec_workspace_bytes(m, 1, 65, C.byref(n)) == -3
+    assert lib.trispec_workspace_bytes(m, 8, 64, C.byref(n)) == -3  # 512 rows
+    d = C.c_double()
+    ctx = (C.c_int32 * 1)(128)
+    assert lib.trispec_pass_bytes(m, 1, 9, ctx, C.byref(d)) == 0
+    per_layer = 2 * 256 * 256 + 2 * 256 * 128 + 3 * 256 * 512 + 2 * 256
+    assert d.value == (2 * per_layer + 4096 * 256 + 2 * 2 * (128 + 9) * 128) * 4
+    lib.trispec_model_destroy(m)
+
+
+def _verify_rc(m, kv, parents, n_nodes, *, threshold=0.5, criterion=0, n_forced=1, ws=0x10000,
+               ws_bytes=1 << 40, tokens=0x2000, positions=0x3000):
+    o = B.VerifyOpts(criterion, n_forced, ws, ws_bytes, None, None, None)
+    out = B.VerifyOut()
+    par = np.asarray(parents, dtype=np.int32)
+    return B.lib().trispec_verify(m, kv, tokens, par.ctypes.data_as(C.POINTER(C.c_int32)), positions,
+                                  n_nodes, threshold, C.byref(o), C.byref(out))
+
+
+def test_verify_rejects_bad_arguments_before_any_launch():
+    lib = B.lib()
+    rc, m, keep = _model()
+    kv = C.c_void_p()
+    assert lib.trispec_kv_create(m, 0x4000, 0x8000, 1, 256, C.byref(kv)) == 0
+    assert lib.trispec_kv_set_len(kv, (C.c_int32 * 1)(300)) == -6
+    assert lib.trispec_kv_set_len(kv, (C.c_int32 * 1)(250)) == 0
+    chain = [-1, 0, 1, 2]
+    assert _verify_rc(m, kv, chain, 4, tokens=None) == -1
+    assert _verify_rc(m, kv, chain, 0) == -3
+    assert _verify_rc(m, kv, list(range(-1, 64)), 65) == -3
+    assert _verify_rc(m, kv, [0, 0, 1, 2], 4) == -4            # parents[0] must be -1
+    assert _verify_rc(m, kv, [-1, 0, 2, 1], 4) == -4           # parents[i] < i
+    assert _verify_rc(m, kv, [-1, 0, -1, 1], 4) == -4
+    assert _verify_rc(m, kv, chain, 4, n_forced=0) == -5
+    assert _verify_rc(m, kv, chain, 4, n_forced=5) == -5
+    assert _verify_rc(m, kv, [-1, 0, 0, 1], 4, n_forced=3) == -5   # forced nodes must be a chain
+    assert _verify_rc(m, kv, chain, 4, criterion=3) == -8
+    assert _verify_rc(m, kv, chain, 4, threshold=float("nan")) == -8
+    assert _verify_rc(m, kv, chain, 4, ws=None) == -7
+    assert _verify_rc(m, kv, chain, 4, ws=0x10010) == -7           # misaligned
+    assert _verify_rc(m, kv, chain, 4, ws_bytes=1024) == -7
+    assert _verify_rc(m, kv, list(range(-1, 6)), 7) == -6          # 250 + 7 > 256
+    rc2, m2, keep2 = _model()
+    assert _verify_rc(m2, kv, chain, 4) == -9                      # cache of another model
+    lib.trispec_kv_destroy(kv)
+    lib.trispec_model_destroy(m)
+    lib.trispec_model_destroy(m2)

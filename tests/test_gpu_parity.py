@@ -1,0 +1,217 @@
+"""GPU parity: the HIP path behind the C ABI against the CPU oracle, element by element,
+on the same seeded inputs.  Bars (written out here):
+
+* logits: fp32 models max |diff| <= 1e-4; bf16 models max |diff| <= 2e-2 * max |oracle logit|
+  per row (the path actually lands near 1e-5 relative, asserted as <= 2e-3 absolute);
+* argmax / accepted_len / token / escalate / path: bit-exact, except on sequences whose walk
+  touches a node the ORACLE flags as a tie (routing statistic within 1e-3 of the threshold, or
+  top-2 logit gap below 1e-3);
+* confidence / margin: |diff| <= 1e-3;
+* K/V written to the cache: equal to the oracle's bf16-rounded values except for isolated
+  one-ulp rounding flips (<= 0.5 % of the elements).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import (CRIT_MARGIN, CRIT_TOP1, bf16_round, decide, node_stats, prune_reroot, tie_flags,
+                    verify_forward)
+from workloads import (SHAPES, ModelShape, gen_chain, gen_context_tokens, gen_draft_tokens,
+                       gen_eagle2_tree, gen_tree, tree_depths)
+from helpers import oracle_weights, path_to, prefill
+from gpu_helpers import Case, compare_decisions, device_model, oracle_decision
+
+pytestmark = pytest.mark.gpu
+
+
+def logits_ok(shape, got, want):
+    diff = np.abs(got - want).max(axis=-1)
+    if shape.dtype == "f32":
+        assert diff.max() <= 1e-4, diff.max()
+    else:
+        assert np.all(diff <= 2e-2 * np.abs(want).max(axis=-1))
+        assert diff.max() <= 2e-3, diff.max()
+
+
+def stats_ok(gpu, oracle_out, b):
+    st = oracle_out[b]["stats"]
+    assert np.abs(gpu["confidence"][b] - st["conf"]).max() <= 1e-3
+    assert np.abs(gpu["margin"][b] - st["margin"]).max() <= 1e-3
+
+
+def make_case(shape, seed, ctx_lens, parents_list, start_pos=0, plant=None):
+    """Real KV: oracle prefill of seeded context tokens (per sequence)."""
+    ks, vs, toks, poss = [], [], [], []
+    for b, (C, par) in enumerate(zip(ctx_lens, parents_list)):
+        ctx = gen_context_tokens(shape.vocab, C, seed + 100 * b)
+        K, V = prefill(shape, seed, ctx)
+        ks.append(K); vs.append(V)
+        toks.append(gen_draft_tokens(par, shape.vocab, seed + 7 * b))
+        poss.append(C + tree_depths(par))
+    case = Case(shape, seed, ks, vs, np.stack(toks), np.stack(parents_list), np.stack(poss))
+    if plant is not None:
+        plant_paths(case, plant)
+    return case
+
+
+def plant_paths(case, leaves):
+    """Make the drafts along root->leaf (one leaf per sequence) the oracle's own greedy tokens
+    for the first `r` steps, so accepted_len covers the whole range."""
+    W = oracle_weights(case.shape, case.seed)
+    for b, (leaf, r) in enumerate(leaves):
+        p = path_to(case.parents[b], leaf)
+        for a, c in list(zip(p[:-1], p[1:]))[:r]:
+            lg = verify_forward(W, case.shape, case.k_ctx[b], case.v_ctx[b], case.tokens[b], case.parents[b],
+                                case.positions[b])["logits"]
+            case.tokens[b][c] = node_stats(lg)["argmax"][a]
+
+
+def full_check(case, thresholds=(0.0, 0.3, 0.5, 0.9, 1.5), n_forced=1):
+    oracle_out = case.run_oracle()
+    gpu = case.run_gpu(thresholds[0], CRIT_MARGIN, n_forced)
+    assert gpu["status"][0] == 0
+    for b in range(case.batch):
+        logits_ok(case.shape, gpu["logits"][b], oracle_out[b]["logits"])
+        stats_ok(gpu, oracle_out, b)
+    excused = compare_decisions(case, gpu, oracle_out, thresholds[0], CRIT_MARGIN, n_forced)
+    # threshold / criterion sweeps re-run only the decision from the stored statistics
+    ver, tok = gpu["_ver"], gpu["_tok"]
+    for crit in (CRIT_MARGIN, CRIT_TOP1):
+        for lam in thresholds:
+            out = ver.decide(tok, case.parents, lam, crit, n_forced)
+            torch.cuda.synchronize()
+            res = {k: v.cpu().numpy() for k, v in out.items()}
+            excused += compare_decisions(case, res, oracle_out, lam, crit, n_forced)
+    return gpu, oracle_out, excused
+
+
+# ------------------------------------------------------------------ BASELINE config 1
+
+
+def test_config1_tiny_fp32_chain_threshold_half():
+    shape = SHAPES["tiny"]
+    case = make_case(shape, 1001, [128], [gen_chain(9)])
+    gpu, oracle_out, _ = full_check(case, thresholds=(0.5, 0.0, 1.5))
+    # invariants (re-decided at the end of full_check with lambda = 1.5 last for TOP1)
+    out = gpu["_ver"].decide(gpu["_tok"], case.parents, 1.5, CRIT_MARGIN)
+    torch.cuda.synchronize()
+    assert out["accepted_len"].item() == 0 and out["escalate"].item() == 1 and out["token"].item() == -1
+
+
+@pytest.mark.parametrize("r", [0, 3, 8])
+def test_config1_planted_chain_accepts_r_tokens(r):
+    shape = SHAPES["tiny"]
+    case = make_case(shape, 1001, [128], [gen_chain(9)], plant=[(8, r)])
+    gpu, oracle_out, excused = full_check(case, thresholds=(0.0, 0.5))
+    out = gpu["_ver"].decide(gpu["_tok"], case.parents, 0.0, CRIT_MARGIN)
+    torch.cuda.synchronize()
+    want = oracle_decision(case, oracle_out, 0, 0.0, CRIT_MARGIN)
+    assert want["accepted_len"] >= r and want["escalate"] == 0
+    assert out["accepted_len"].item() == want["accepted_len"] and out["token"].item() == want["token"]
+    if r == 8:   # all-accepted chain at threshold 0: bonus token from the last node
+        assert out["accepted_len"].item() == 8
+        assert out["path"][0, :9].tolist() == list(range(9))
+
+
+# ------------------------------------------------------------------ small bf16 models, many shapes
+
+TB = SHAPES["tiny_bf16"]
+BF16_CASES = [
+    # (id, shape, ctx_lens, tree builder)
+    ("chain9", TB, [128], lambda s: gen_chain(9)),
+    ("tree60_two_splits", TB, [200], lambda s: gen_tree(60, 8, 4, s)),
+    ("tree60_group4_rb2", TB.with_(n_q_heads=8), [300], lambda s: gen_tree(60, 8, 4, s)),
+    ("eagle2_tree", TB, [77], lambda s: gen_eagle2_tree(s)),
+    ("max_nodes_64", TB, [130], lambda s: gen_tree(64, 8, 4, s)),
+    ("single_node", TB, [64], lambda s: gen_chain(1)),
+    ("empty_context", TB, [0], lambda s: gen_tree(20, 5, 3, s)),
+    ("many_splits", TB.with_(n_layers=1), [1100], lambda s: gen_tree(33, 8, 4, s)),
+    ("head_dim64_mha", TB.with_(head_dim=64, n_q_heads=4, n_kv_heads=4), [100], lambda s: gen_tree(40, 6, 4, s)),
+    ("mqa_group8", TB.with_(n_q_heads=8, n_kv_heads=1, head_dim=64), [90], lambda s: gen_tree(30, 6, 4, s)),
+    ("ragged_vocab_ffn", TB.with_(vocab=4001, ffn=576, hidden=320), [150], lambda s: gen_tree(45, 8, 4, s)),
+    ("three_layers_base5e5", TB.with_(n_layers=3, rope_base=5e5), [65], lambda s: gen_tree(17, 8, 2, s)),
+    ("batch3_ragged_ctx", TB, [10, 131, 64], lambda s: gen_tree(30, 6, 4, s)),
+    ("batch4_rows240", TB.with_(n_layers=1), [40, 0, 129, 77], lambda s: gen_tree(60, 8, 4, s)),
+    ("batch2_rows128", TB.with_(n_layers=1), [70, 33], lambda s: gen_tree(50, 8, 4, s)),
+]
+
+
+@pytest.mark.parametrize("name,shape,ctx_lens,tree", BF16_CASES, ids=[c[0] for c in BF16_CASES])
+def test_bf16_small_models(name, shape, ctx_lens, tree):
+    seed = 40 + len(name)
+    parents = [tree(seed + b) for b in range(len(ctx_lens))]
+    depth = [tree_depths(p) for p in parents]
+    plant = [(int(np.argmax(d)), min(3, int(d.max()))) for d in depth]
+    case = make_case(shape, seed, ctx_lens, parents, plant=plant)
+    gpu, oracle_out, excused = full_check(case)
+    # the planted prefix is accepted at lambda = 0
+    out = gpu["_ver"].decide(gpu["_tok"], case.parents, 0.0, CRIT_MARGIN)
+    torch.cuda.synchronize()
+    for b in range(case.batch):
+        assert out["accepted_len"][b].item() >= plant[b][1] or excused
+        assert out["accepted_len"][b].item() <= depth[b].max()
+
+
+def test_cache_append_matches_oracle_rounding():
+    shape = TB
+    case = make_case(shape, 9, [100], [gen_tree(24, 6, 3, 9)])
+    oracle_out = case.run_oracle()
+    gpu = case.run_gpu(0.5)
+    kv, C, M = gpu["_kv"], 100, 24
+    k_new = kv.k[:, 0, :, C:C + M, :].float().cpu().numpy()                      # [L, nkv, M, d]
+    v_new = kv.v[:, 0, :, :, C:C + M].float().cpu().numpy().transpose(0, 1, 3, 2)
+    for got, want in ((k_new, oracle_out[0]["k_new"]), (v_new, oracle_out[0]["v_new"])):
+        mism = got != want
+        assert mism.mean() <= 5e-3
+        # a mismatch is a one-ulp rounding flip of a value that differs by ~1e-5 of the typical
+        # magnitude before rounding, never more
+        assert np.all(np.abs(got - want)[mism] <= np.abs(want[mism]) * 2.0 ** -7 + 3e-5 * np.abs(want).max())
+    # slots outside [C, C+M) were not touched (still the poison written by the harness)
+    assert torch.isnan(kv.k[:, 0, :, C + M:, :].float()).all()
+    assert torch.isnan(kv.v[:, 0, :, :, C + M:].float()).all()
+    # context slots unchanged
+    assert not torch.isnan(kv.k[:, 0, :, :C, :].float()).any()
+
+
+def test_verify_is_repeatable_and_deterministic():
+    shape = TB
+    case = make_case(shape, 3, [150], [gen_tree(60, 8, 4, 3)])
+    gpu = case.run_gpu(0.4)
+    ver, kv, tok = gpu["_ver"], gpu["_kv"], gpu["_tok"]
+    pos = torch.from_numpy(case.positions).cuda()
+    first = {k: v.clone() for k, v in ver.out.items()}
+    logits = ver.logits.clone()
+    for _ in range(3):
+        ver.verify(kv, tok, case.parents, pos, 0.4)
+        torch.cuda.synchronize()
+        for k, v in ver.out.items():
+            assert torch.equal(v, first[k]), k
+        assert torch.equal(ver.logits, logits)
+
+
+def test_out_of_range_token_sets_status_and_does_not_fault():
+    shape = TB.with_(n_layers=1)
+    case = make_case(shape, 4, [64], [gen_chain(5)])
+    case.tokens[0][2] = shape.vocab + 5
+    gpu = case.run_gpu(0.5)
+    assert gpu["status"][0] == 1
+    assert np.isfinite(gpu["confidence"]).all()
+
+
+def test_case2_prune_and_reroot_target_pass():
+    """Case II: the proxy approved path v_0..v_tau_m; the target pass sees the path as a forced
+    chain plus the subtree under v_tau_m (Eq. 10) and must make the oracle's decision."""
+    shape = TB
+    seed = 12
+    parents = gen_tree(40, 7, 3, seed)
+    depth = tree_depths(parents)
+    leaf = int(np.argmax(depth))
+    case = make_case(shape, seed, [90], [parents], plant=[(leaf, 5)])
+    path = path_to(parents, leaf)[:3]                      # proxy trusted two drafts, then escalated
+    pr = prune_reroot(case.tokens[0], parents, case.positions[0], path)
+    sub = Case(shape, seed, case.k_ctx, case.v_ctx, pr["tokens"], pr["parents"], pr["positions"])
+    gpu, oracle_out, excused = full_check(sub, thresholds=(0.0,), n_forced=pr["n_forced"])
+    want = oracle_decision(sub, oracle_out, 0, 0.0, CRIT_MARGIN, pr["n_forced"])
+    assert want["accepted_len"] >= 3 and want["escalate"] == 0          # the rest of the planted path
+    assert gpu["accepted_len"][0] == want["accepted_len"] and gpu["token"][0] == want["token"]
+    assert [int(v) for v in gpu["path"][0] if v >= 0][0] == pr["n_forced"] - 1

@@ -77,7 +77,7 @@ def test_tree_pass_equals_sequential_autoregressive_forwards(shape):
     out = verify_forward(W, shape, Kc, Vc, toks, parents, pos)
     for i in range(M):
         seq = list(ctx) + [int(toks[j]) for j in path_to(parents, i)]
-        ref = causal_forward(W, shape, seq, last_only=True)
+        ref = causal_forward(W, shape, seq, last_only=True, n_cached=C)
         assert np.max(np.abs(out["logits"][i] - ref["logits"][0])) < 1e-9, i
         # what the pass appends to the cache for node i is what a prefill would have stored
         assert np.max(np.abs(out["k_new"][:, :, i] - ref["K"][:, :, -1])) < 1e-10
