@@ -1,0 +1,185 @@
+#!/usr/bin/env python3
+"""Benchmark of the TriSpec verification pass on one MI355X.
+
+A step = one trispec_verify() call: the whole hot path (embedding, every layer's projections,
+tree-masked attention and FFN, fused LM head, decision) over one batch of synthetic input that
+is already resident in HBM.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E vendor peak
+
+# name -> (shape key, batch, ctx_len, n_nodes, tree kind)
+WORKLOADS = {
+    "qwen3_8b_tree60_ctx4096": ("qwen3_8b", 1, 4096, 60, "tree"),        # BASELINE config 3 (headline)
+    "qwen3_0p6b_chain8_ctx2048": ("qwen3_0p6b", 1, 2048, 9, "chain"),    # BASELINE config 2
+    "qwen3_1p7b_tree60_ctx8192": ("qwen3_1p7b", 1, 8192, 60, "tree"),    # BASELINE config 4, proxy
+    "qwen3_8b_tree60_ctx8192": ("qwen3_8b", 1, 8192, 60, "tree"),        # BASELINE config 4, target
+    "llama3_8b_b4_tree60_ctx16384": ("llama3_8b", 4, 16384, 60, "tree"),  # BASELINE config 5
+    "tiny_bf16_tree60_ctx256": ("tiny_bf16", 1, 256, 60, "tree"),        # plumbing check only
+    "qwen3_8b_4layers_tree60_ctx4096": ("qwen3_8b_L4", 1, 4096, 60, "tree"),  # kernel tuning aid (not a result)
+}
+
+
+def build_inputs(shape, batch, ctx, n_nodes, kind, seed):
+    import torch
+    from paper_2601_23180_amd import KVCache, Verifier, fill_kv_layer, model_from_arrays
+    from workloads import (WeightSource, gen_chain, gen_draft_tokens, gen_kv_cache, gen_tree, tree_depths)
+
+    ws = WeightSource(shape, seed)
+    t0 = time.time()
+    model = model_from_arrays(shape, ws.bits if shape.dtype == "bf16" else ws.get)
+    cap = (ctx + n_nodes + 63) // 64 * 64
+    kv = KVCache(model, batch, cap)
+    for l in range(shape.n_layers):
+        k, v = gen_kv_cache(shape, batch, ctx, seed, l)
+        fill_kv_layer(kv, l, k, v)
+    kv.set_len([ctx] * batch)
+    parents = np.stack([gen_chain(n_nodes) if kind == "chain" else gen_tree(n_nodes, 8, 4, seed + b)
+                        for b in range(batch)])
+    tokens = np.stack([gen_draft_tokens(parents[b], shape.vocab, seed + b) for b in range(batch)])
+    positions = np.stack([ctx + tree_depths(parents[b]) for b in range(batch)]).astype(np.int32)
+    ver = Verifier(model, batch, n_nodes)
+    tok = torch.from_numpy(tokens).cuda()
+    pos = torch.from_numpy(positions).cuda()
+    torch.cuda.synchronize()
+    return dict(model=model, kv=kv, ver=ver, tok=tok, pos=pos, parents=parents, tokens=tokens,
+                positions=positions, setup_s=time.time() - t0)
+
+
+def cpu_baseline(shape, batch, ctx, n_nodes, kind, seed):
+    """The oracle as it stands, timed on the host cores on a bounded sample of the workload:
+    the full-width model cut to 1 and to 2 layers (full LM head both times), sequence 0 only;
+    the per-layer time is the difference and the whole pass is extrapolated from it."""
+    from oracle import OracleWeights, verify_forward
+    from workloads import WeightSource, gen_chain, gen_draft_tokens, gen_kv_cache, gen_tree, tree_depths
+
+    ws = WeightSource(shape, seed)
+    cache = {}
+
+    def get(name, layer):   # weights generated outside the timed region
+        return cache[(name, layer)]
+
+    for name in ("embed", "lm_head", "final_norm"):
+        cache[(name, 0)] = ws.get(name, 0)
+    for l in range(2):
+        for name in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "norm_attn", "norm_ffn"):
+            cache[(name, l)] = ws.get(name, l)
+    kvs = [tuple(a[0] for a in gen_kv_cache(shape, 1, ctx, seed, l)) for l in range(2)]
+    parents = gen_chain(n_nodes) if kind == "chain" else gen_tree(n_nodes, 8, 4, seed)
+    tokens = gen_draft_tokens(parents, shape.vocab, seed)
+    positions = ctx + tree_depths(parents)
+    W = OracleWeights(get)
+    times = []
+    for nl in (1, 2):
+        sh = shape.with_(n_layers=nl)
+        t0 = time.perf_counter()
+        verify_forward(W, sh, lambda l: kvs[l][0], lambda l: kvs[l][1], tokens, parents, positions)
+        times.append(time.perf_counter() - t0)
+    per_layer = max(times[1] - times[0], 1e-9)
+    full = (times[0] + (shape.n_layers - 1) * per_layer) * batch
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {"value": batch * (n_nodes - 1) / full, "unit": "draft tokens/s", "cores": int(cores),
+            "kind": "oracle", "seconds_per_pass_extrapolated": full,
+            "sample": f"numpy fp64 oracle, sequence 0, model cut to 1 and 2 layers at full width + full LM head "
+                      f"({times[0]:.2f}s, {times[1]:.2f}s); pass = t1 + (L-1)*(t2-t1), times batch"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="qwen3_8b_tree60_ctx4096", choices=sorted(WORKLOADS))
+    ap.add_argument("--seed", type=int, default=1003)
+    ap.add_argument("--threshold", type=float, default=0.5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs the verification pass on ONE GPU (no sharding, no collectives); "
+                 "use --gpus 1")
+
+    import torch
+    from paper_2601_23180_amd import K_ATTN, K_GEMM, K_HEAD, KernelTimer
+    from workloads import SHAPES
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU (there is no CPU fallback of the product path)")
+    key, batch, ctx, n_nodes, kind = WORKLOADS[args.workload]
+    shape = SHAPES["qwen3_8b"].with_(n_layers=4) if key == "qwen3_8b_L4" else SHAPES[key]
+    inp = build_inputs(shape, batch, ctx, n_nodes, kind, args.seed)
+    ver, kv, tok, pos, parents = inp["ver"], inp["kv"], inp["tok"], inp["pos"], inp["parents"]
+
+    def step():
+        ver.verify(kv, tok, parents, pos, args.threshold, want_logits=False)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms = dt / args.steps * 1e3
+    pass_bytes = inp["model"].pass_bytes(batch, n_nodes, [ctx] * batch)
+
+    # per-kernel durations: HIP events on the pass's stream around every launch of one class,
+    # over `steps` more passes each (same inputs, same launch configuration)
+    kernels = {}
+    for cls, name, per_pass in ((K_GEMM, "gemm", 4 * shape.n_layers), (K_HEAD, "lm_head", 1),
+                                (K_ATTN, "attention", shape.n_layers)):
+        timer = KernelTimer(cls, per_pass * args.steps)
+        ver.timer = timer
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        n, tms, by = timer.read()
+        ver.timer = None
+        kernels[name] = {"launches": n, "avg_us": tms / n * 1e3, "bytes_per_launch": by / n,
+                         "achieved_GBs": by / (tms * 1e-3) / 1e9, "ms_per_pass": tms / args.steps}
+    g = kernels["gemm"]
+    roofline = {"bound": "hbm", "kernel": "k_gemm_bf16 (weight-streaming projection / FFN matmul)",
+                "achieved": g["achieved_GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": g["achieved_GBs"] / HBM_PEAK_GBS, "traffic": None,
+                "avg_launch_us": g["avg_us"], "bytes_per_launch": g["bytes_per_launch"]}
+
+    out = {
+        "metric": "draft_tokens_verified_per_sec", "value": batch * (n_nodes - 1) / (ms * 1e-3),
+        "unit": "draft tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if shape.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "batch": batch, "ctx_len": ctx, "n_nodes": n_nodes,
+                   "tree": kind, "threshold": args.threshold},
+        "verify_latency_ms": ms,
+        "pass_bytes": pass_bytes,
+        "pass_achieved_GBs": pass_bytes / (ms * 1e-3) / 1e9,
+        "pass_frac_of_hbm_peak": pass_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "roofline": roofline,
+        "kernels": kernels,
+        "accepted_len": ver.out["accepted_len"].cpu().tolist(),
+        "escalate": ver.out["escalate"].cpu().tolist(),
+        "setup_seconds": inp["setup_s"],
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(shape, batch, ctx, n_nodes, kind, args.seed)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

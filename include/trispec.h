@@ -48,7 +48,8 @@ enum {
   TRISPEC_EWORKSPACE = -7,   /* workspace missing, misaligned or too small */
   TRISPEC_EARG = -8,         /* any other invalid argument (criterion, threshold NaN, ...) */
   TRISPEC_EMISMATCH = -9,    /* kv cache was created for another model / batch */
-  TRISPEC_ELAUNCH = -10      /* the HIP runtime refused a launch (hipGetLastError) */
+  TRISPEC_ELAUNCH = -10,     /* the HIP runtime refused a launch (hipGetLastError) */
+  TRISPEC_ESTATE = -11       /* trispec_verify on a bf16 model before trispec_model_pack */
 };
 
 enum { TRISPEC_F32 = 0, TRISPEC_BF16 = 1 };
@@ -100,6 +101,21 @@ typedef struct trispec_timer trispec_timer;
 int trispec_model_create(const trispec_model_config *cfg, const trispec_weights *w,
                          trispec_model **out);
 int trispec_model_destroy(trispec_model *m);
+
+/*
+ * bf16 models: one-time repack of the projection, FFN and LM-head matrices into the layout the
+ * weight-streaming kernels read (per 32 output rows and 64 reduction elements, one contiguous
+ * 4 KB block holding the matrix-core operand fragments in lane order, zero-padded rows), so that
+ * every load instruction of the hot path reads 1 KB contiguous.  `packed_dev` is a caller-owned,
+ * 256-byte aligned device buffer of trispec_model_pack_bytes() bytes that must outlive the model;
+ * the repack kernels are enqueued on `stream` (NULL = default stream).  Once that work has
+ * completed the hot path no longer reads wq..w_down and lm_head (the caller may release them);
+ * embed and the norm vectors are still read in place.  fp32 models: pack_bytes is 0 and pack
+ * is a no-op.  Required before trispec_verify on a bf16 model (TRISPEC_ESTATE otherwise).
+ * Errors: TRISPEC_ENULL, TRISPEC_EARG (alignment), TRISPEC_ELAUNCH.
+ */
+int trispec_model_pack_bytes(const trispec_model *m, size_t *bytes);
+int trispec_model_pack(trispec_model *m, void *packed_dev, void *stream);
 
 /*
  * KV cache of the prefix X (Sec. 2.1: the pass conditions on X).  Caller-owned

@@ -86,6 +86,10 @@ class OracleWeights:
     def __call__(self, name: str, layer: int = 0) -> np.ndarray:
         return np.asarray(self._get(name, layer), dtype=np.float64)
 
+    def rows(self, name: str, idx) -> np.ndarray:
+        """Selected rows of a (large) matrix, e.g. the embeddings of the input tokens."""
+        return np.asarray(self._get(name, 0)[np.asarray(idx)], dtype=np.float64)
+
 
 def _lm_head(h: np.ndarray, W: OracleWeights, vocab: int) -> np.ndarray:
     """logits = h @ Wlm^T.  Rows of Wlm are taken in slabs only to bound memory;
@@ -123,7 +127,7 @@ def causal_forward(W: OracleWeights, shape, tokens: Sequence[int],
     group = nq // nkv
     pos = np.arange(T) if positions is None else np.asarray(positions)
     ang = rope_angles(pos, d, shape.rope_base)
-    x = W("embed")[np.asarray(tokens)]
+    x = W.rows("embed", tokens)
     Ks = np.empty((shape.n_layers, nkv, T, d))
     Vs = np.empty((shape.n_layers, nkv, T, d))
     for l in range(shape.n_layers):
@@ -193,7 +197,7 @@ def verify_forward(W: OracleWeights, shape, k_ctx, v_ctx, tokens: Sequence[int],
     group = nq // nkv
     anc = ancestor_sets(parents)
     ang = rope_angles(np.asarray(positions), d, shape.rope_base)
-    x = W("embed")[np.asarray(tokens)]
+    x = W.rows("embed", tokens)
     k_new = np.empty((shape.n_layers, nkv, M, d))
     v_new = np.empty((shape.n_layers, nkv, M, d))
     hidden = []

@@ -26,7 +26,7 @@ EXPORTS = [
     "trispec_kv_set_len", "trispec_kv_destroy", "trispec_workspace_bytes",
     "trispec_workspace_region", "trispec_pass_bytes", "trispec_verify", "trispec_decide",
     "trispec_strerror", "trispec_timer_create", "trispec_timer_reset", "trispec_timer_read",
-    "trispec_timer_destroy",
+    "trispec_timer_destroy", "trispec_model_pack_bytes", "trispec_model_pack",
 ]
 K_GEMM, K_HEAD, K_ATTN = 0, 1, 2
 
@@ -81,6 +81,8 @@ def lib() -> C.CDLL:
                 getattr(l, name).restype = C.c_int
         l.trispec_model_create.argtypes = [C.POINTER(ModelConfig), C.POINTER(Weights), C.POINTER(C.c_void_p)]
         l.trispec_model_destroy.argtypes = [C.c_void_p]
+        l.trispec_model_pack_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_size_t)]
+        l.trispec_model_pack.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         l.trispec_kv_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
         l.trispec_kv_create.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                         C.POINTER(C.c_void_p)]
@@ -140,6 +142,25 @@ class Model:
             setattr(w, n, C.cast(arr, _PP))
         self.handle = C.c_void_p()
         check(lib().trispec_model_create(C.byref(self.cfg), C.byref(w), C.byref(self.handle)))
+        self.packed = None
+
+    def pack(self, release_originals: bool = False, device="cuda") -> None:
+        """Repack the matrices for the streaming kernels (bf16 models; a no-op for fp32).
+        release_originals drops this object's references to wq..w_down / lm_head afterwards."""
+        n = C.c_size_t()
+        check(lib().trispec_model_pack_bytes(self.handle, C.byref(n)))
+        if n.value:
+            self.packed = torch.empty(n.value + 256, dtype=torch.uint8, device=device)
+            ptr = self.packed.data_ptr() + (-self.packed.data_ptr()) % 256
+        else:
+            ptr = None
+        check(lib().trispec_model_pack(self.handle, ptr, torch.cuda.current_stream().cuda_stream))
+        if release_originals and n.value:
+            torch.cuda.current_stream().synchronize()
+            for name in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down"):
+                self.tensors[name] = None
+            if self.tensors["lm_head"] is not self.tensors["embed"]:
+                self.tensors["lm_head"] = None
 
     def workspace_bytes(self, batch: int, max_nodes: int) -> int:
         n = C.c_size_t()

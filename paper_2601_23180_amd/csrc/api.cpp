@@ -14,6 +14,10 @@ struct trispec_model {
   trispec_model_config cfg;
   const void *embed, *lm_head, *final_norm;
   std::vector<const void *> wq, wk, wv, wo, w_gate, w_up, w_down, norm_attn, norm_ffn;
+  // bf16 models: packed copies of the matrices (device, inside the caller's pack buffer)
+  bool packed;
+  const void *p_lm_head;
+  std::vector<const void *> p_wq, p_wk, p_wv, p_wo, p_gate, p_up, p_down;
 };
 
 struct trispec_kv {
@@ -80,14 +84,19 @@ int max_gemm_cols(const trispec_model_config &c) {
 int pick_splits(int dtype, int n_total, int k) {
   if (dtype == TRISPEC_F32) return 1;
   const int tiles = (n_total + kGemmTileN - 1) / kGemmTileN;
-  int s = (1024 + tiles - 1) / tiles;
+  int s = (512 + tiles - 1) / tiles;
   const int max_by_k = k / 256 > 0 ? k / 256 : 1;
   if (s > max_by_k) s = max_by_k;
   if (s > kMaxSplitK) s = kMaxSplitK;
   if (s < 1) s = 1;
   return s;
 }
-int k_per_split(int k, int s) { return (int)align_up((size_t)(k + s - 1) / s, 64); }
+// k slice of one split: a whole number of 256-deep chunks when the reduction allows it (keeps the
+// streaming loop free of bounds logic), else of 64-deep blocks.
+int k_per_split(int k, int s) {
+  const size_t unit = (k % 256 == 0) ? 256 : 64;
+  return (int)align_up((size_t)(k + s - 1) / s, unit);
+}
 
 Layout make_layout(const trispec_model_config &c, int batch, int max_nodes) {
   Layout L;
@@ -231,12 +240,71 @@ int trispec_model_create(const trispec_model_config *cfg, const trispec_weights 
   m->w_down.assign(w->w_down, w->w_down + L);
   m->norm_attn.assign(w->norm_attn, w->norm_attn + L);
   m->norm_ffn.assign(w->norm_ffn, w->norm_ffn + L);
+  m->packed = false;
+  m->p_lm_head = nullptr;
   *out = m;
   return TRISPEC_OK;
 }
 
 int trispec_model_destroy(trispec_model *m) {
   delete m;
+  return TRISPEC_OK;
+}
+
+// Packed-buffer layout: per layer wq, wk, wv, wo, w_gate, w_up, w_down, then the LM head.
+static size_t pack_plan(const trispec_model_config &c, std::vector<size_t> *offs) {
+  const int qd = c.n_q_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim;
+  const int rows[7] = {qd, kvd, kvd, c.hidden, c.ffn, c.ffn, c.hidden};
+  const int ks[7] = {c.hidden, c.hidden, c.hidden, qd, c.hidden, c.hidden, c.ffn};
+  size_t off = 0;
+  for (int l = 0; l < c.n_layers; ++l)
+    for (int i = 0; i < 7; ++i) {
+      if (offs) offs->push_back(off);
+      off += packed_weight_bytes(rows[i], ks[i]);
+    }
+  if (offs) offs->push_back(off);
+  off += packed_weight_bytes(c.vocab, c.hidden);
+  return off;
+}
+
+int trispec_model_pack_bytes(const trispec_model *m, size_t *bytes) {
+  if (!m || !bytes) return TRISPEC_ENULL;
+  *bytes = m->cfg.dtype == TRISPEC_BF16 ? pack_plan(m->cfg, nullptr) : 0;
+  return TRISPEC_OK;
+}
+
+int trispec_model_pack(trispec_model *m, void *packed_dev, void *stream) {
+  if (!m) return TRISPEC_ENULL;
+  if (m->cfg.dtype != TRISPEC_BF16) { m->packed = true; return TRISPEC_OK; }
+  if (!packed_dev) return TRISPEC_ENULL;
+  if (((uintptr_t)packed_dev) & 255) return TRISPEC_EARG;
+  const trispec_model_config &c = m->cfg;
+  const int qd = c.n_q_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim;
+  std::vector<size_t> offs;
+  pack_plan(c, &offs);
+  hipStream_t st = (hipStream_t)stream;
+  char *base = (char *)packed_dev;
+  (void)hipGetLastError();
+  const int L = c.n_layers;
+  m->p_wq.resize(L); m->p_wk.resize(L); m->p_wv.resize(L); m->p_wo.resize(L);
+  m->p_gate.resize(L); m->p_up.resize(L); m->p_down.resize(L);
+  for (int l = 0; l < L; ++l) {
+    const void *src[7] = {m->wq[l], m->wk[l], m->wv[l], m->wo[l], m->w_gate[l], m->w_up[l], m->w_down[l]};
+    const int rows[7] = {qd, kvd, kvd, c.hidden, c.ffn, c.ffn, c.hidden};
+    const int ks[7] = {c.hidden, c.hidden, c.hidden, qd, c.hidden, c.hidden, c.ffn};
+    const void **dst[7] = {&m->p_wq[l], &m->p_wk[l], &m->p_wv[l], &m->p_wo[l], &m->p_gate[l], &m->p_up[l],
+                           &m->p_down[l]};
+    for (int i = 0; i < 7; ++i) {
+      void *o = base + offs[(size_t)l * 7 + i];
+      launch_pack_weights(st, src[i], rows[i], ks[i], o);
+      *dst[i] = o;
+    }
+  }
+  void *o = base + offs[(size_t)L * 7];
+  launch_pack_weights(st, m->lm_head, c.vocab, c.hidden, o);
+  m->p_lm_head = o;
+  if (hipGetLastError() != hipSuccess) return TRISPEC_ELAUNCH;
+  m->packed = true;
   return TRISPEC_OK;
 }
 
@@ -345,6 +413,7 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
   if (rc) return rc;
   if (kv->model != m) return TRISPEC_EMISMATCH;
   const trispec_model_config &c = m->cfg;
+  if (c.dtype == TRISPEC_BF16 && !m->packed) return TRISPEC_ESTATE;
   const int B = kv->batch;
   if (n_nodes < 1 || n_nodes > kMaxNodes || B * n_nodes > kMaxRows) return TRISPEC_ENODES;
   if (opts->n_forced < 1 || opts->n_forced > n_nodes) return TRISPEC_EFORCED;
@@ -431,7 +500,9 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
   const size_t kv_layer = (size_t)B * c.n_kv_heads * kv->capacity * c.head_dim * es;
 
   for (int l = 0; l < c.n_layers; ++l) {
-    int s = gemm(h, pan_h, c.hidden, 3, m->wq[l], qd, m->wk[l], kvd, m->wv[l], kvd);
+    const bool pk = c.dtype == TRISPEC_BF16;
+    int s = gemm(h, pan_h, c.hidden, 3, pk ? m->p_wq[l] : m->wq[l], qd, pk ? m->p_wk[l] : m->wk[l], kvd,
+                 pk ? m->p_wv[l] : m->wv[l], kvd);
     char *kl = (char *)kv->k + (size_t)l * kv_layer, *vl = (char *)kv->v + (size_t)l * kv_layer;
     launch_qkv_epilogue(st, c.dtype, part, s, rows, rp, c.n_q_heads, c.n_kv_heads, c.head_dim, cos_t, sin_t,
                         n_nodes, ctx, kv->capacity, q, pan_q, qkv_f32, kl, vl);
@@ -443,11 +514,12 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
       TimedLaunch tl(opts->timer, TRISPEC_K_ATTN, st, kvb);
       if (c.dtype == TRISPEC_F32) launch_attn_f32(st, at); else launch_attn_bf16(st, at);
     }
-    s = gemm(attn_out, pan_q, qd, 1, m->wo[l], c.hidden, nullptr, 0, nullptr, 0);
+    s = gemm(attn_out, pan_q, qd, 1, pk ? m->p_wo[l] : m->wo[l], c.hidden, nullptr, 0, nullptr, 0);
     launch_reduce_residual_norm(st, c.dtype, part, s, rows, rp, c.hidden, m->norm_ffn[l], c.rms_eps, x, h, pan_h);
-    s = gemm(h, pan_h, c.hidden, 2, m->w_gate[l], c.ffn, m->w_up[l], c.ffn, nullptr, 0);
+    s = gemm(h, pan_h, c.hidden, 2, pk ? m->p_gate[l] : m->w_gate[l], c.ffn, pk ? m->p_up[l] : m->w_up[l], c.ffn,
+             nullptr, 0);
     launch_reduce_swiglu(st, c.dtype, part, s, rows, rp, c.ffn, act, pan_f);
-    s = gemm(act, pan_f, c.ffn, 1, m->w_down[l], c.hidden, nullptr, 0, nullptr, 0);
+    s = gemm(act, pan_f, c.ffn, 1, pk ? m->p_down[l] : m->w_down[l], c.hidden, nullptr, 0, nullptr, 0);
     const void *next_norm = (l + 1 < c.n_layers) ? m->norm_attn[l + 1] : m->final_norm;
     launch_reduce_residual_norm(st, c.dtype, part, s, rows, rp, c.hidden, next_norm, c.rms_eps, x, h, pan_h);
   }
@@ -464,7 +536,7 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
     memset(&g, 0, sizeof(g));
     g.x = h;
     g.x_panel = pan_h;
-    g.seg[0] = {m->lm_head, c.vocab, 0};
+    g.seg[0] = {c.dtype == TRISPEC_BF16 ? m->p_lm_head : m->lm_head, c.vocab, 0};
     g.n_seg = 1;
     g.n_total = c.vocab;
     g.k = c.hidden;
@@ -577,6 +649,7 @@ const char *trispec_strerror(int code) {
     case TRISPEC_EARG: return "invalid argument";
     case TRISPEC_EMISMATCH: return "kv cache belongs to another model";
     case TRISPEC_ELAUNCH: return "HIP launch failed";
+    case TRISPEC_ESTATE: return "bf16 model has not been packed (trispec_model_pack)";
     default: return "unknown error";
   }
 }

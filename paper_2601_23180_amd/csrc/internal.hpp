@@ -35,7 +35,7 @@ struct CtxLens {
 
 // One weight-streaming matmul  out[s][r][col] = sum_{k in split s} X[r][k] * W[col][k].
 struct GemmSeg {
-  const void *w;   // [n_rows, K]
+  const void *w;   // bf16 models: the PACKED copy of the [n_rows, K] matrix; fp32: the matrix
   int32_t n_rows;
   int32_t col0;    // first output column of this segment
 };
@@ -112,6 +112,8 @@ void launch_reduce_residual_norm(hipStream_t st, int dtype, const float *part, i
 void launch_reduce_swiglu(hipStream_t st, int dtype, const float *part, int n_splits, int rows,
                           int rows_pad, int ffn, void *act, size_t panel);
 void launch_gemm_f32(hipStream_t st, const GemmArgs &a);
+size_t packed_weight_bytes(int n_rows, int k);
+void launch_pack_weights(hipStream_t st, const void *w, int n_rows, int k, void *out);
 void launch_gemm_bf16(hipStream_t st, const GemmArgs &a);
 void launch_lmhead_bf16(hipStream_t st, const GemmArgs &a, const HeadStats &hs, float *debug_logits);
 void launch_stats_from_logits(hipStream_t st, const float *logits, int rows, int vocab,

@@ -3,9 +3,13 @@
 //   out[split][r][n] = sum_{k in split} X[r][k] * W[n][k]        r < rows_pad <= 256
 //
 // At these row counts the product is bound by streaming W from HBM once, so the layout serves
-// the W stream: every wavefront owns 32 output columns (= 32 rows of W) and pulls them straight
-// from global memory into registers, 64 contiguous bytes per lane per 64-deep k block (each W
-// row is consumed in whole 128-byte lines); W never passes through LDS and is never re-read.
+// the W stream.  W is read from the PACKED copy made once by k_pack_weights: for every 32-row
+// sub-tile s and 64-deep k block kb, one contiguous 4 KB block holding the four MFMA B-operand
+// fragments of that (s, kb) in lane order.  A wavefront owns one sub-tile (32 output columns) and
+// pulls its blocks straight from global memory into registers — every load instruction reads
+// 1 KB contiguous (8 whole 128-byte lines), a sub-tile's k range is one contiguous run, W never
+// passes through LDS and is never re-read.  (Reading row-major W with the same operand layout
+// touches 32 rows x 32 bytes per instruction and reaches ~75 % of the contiguous rate.)
 // The small activation panel X is what all four wavefronts share: it is staged through LDS in
 // chunks of KC reduction elements, double buffered, with a 16-byte row pad that makes the
 // 16-byte operand reads conflict free.  X arrives as two bf16 panels, hi and lo (hi + lo carries
@@ -26,7 +30,9 @@
 
 namespace ts {
 
-template <int MB, int KC, bool HEAD>
+// RAGGED: some k split is not a whole number of KC chunks (odd shapes only; the model shapes this
+// is tuned for never need it).  The fast variant has no bounds logic at all in the stream.
+template <int MB, int KC, bool HEAD, bool RAGGED>
 __global__ __launch_bounds__(256) void k_gemm_bf16(GemmArgs a, HeadStats hs, float *dbg) {
   constexpr int KB = KC / 64;                 // 64-deep k blocks per chunk
   constexpr int STRIDE = KC * 2 + 16;         // LDS bytes per activation row
@@ -55,7 +61,11 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(GemmArgs a, HeadStats hs, flo
   const int seg_col0 = sidx == 0 ? a.seg[0].col0 : (sidx == 1 ? a.seg[1].col0 : a.seg[2].col0);
   const int nloc = n0 - seg_col0 + ln;
   const bool n_ok = active && nloc < seg_rows;
-  const bf16 *wrow = wseg + (size_t)min(max(nloc, 0), seg_rows - 1) * a.k + k_begin + 32 * g;
+  // packed sub-tile of this wavefront (clamped to the segment's last one: always valid memory;
+  // rows past the segment's end are zero in the packed copy)
+  const int n_sub_seg = (seg_rows + 31) >> 5;
+  const int sub = min(max((n0 - seg_col0) >> 5, 0), n_sub_seg - 1);
+  const bf16 *wrow = wseg + ((size_t)sub * (a.k >> 6) + (k_begin >> 6)) * 2048 + lane * 8;
   const bf16 *xg = (const bf16 *)a.x + k_begin;
 
   f32x16 acc[MB];
@@ -64,26 +74,38 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(GemmArgs a, HeadStats hs, flo
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[mb][e] = 0.f;
 
-  bf16x8 w0[KB][4], w1[KB][4];
+  // The streaming loop is kept free of branches around loads: a load behind a branch makes the
+  // wait-count analysis assume it may not have been issued, which turns every wait into "drain
+  // everything" and serialises the stream.
+  //
+  // Fast variant (every k split is a whole, even number of KC chunks), per chunk c:
+  //   1. X registers (chunk c+1, fetched during chunk c-1) -> LDS stage (c+1)&1
+  //   2. issue the X loads of chunk c+2
+  //   3. per 64-deep block: 4 x MB x 2 MFMAs on W set c&1, then refill that block of the set
+  //      with chunk c+2 — so a W load has two chunks of compute to arrive
+  //   4. workgroup barrier
+  // sched_barrier pins the load issue points; the compiler would otherwise sink every load to
+  // just before its first use and expose the whole memory latency once per chunk.
+  bf16x8 w[2][KB][4];
   uint4 xr[2][XV];
 
-  auto load_w = [&](bf16x8 (&w)[KB][4], int c) {
-    if (!active) return;
+  auto load_w_block = [&](int set, int c, int kb) {   // W rows of this wavefront, block kb of chunk c
+    const int k = c * KC + kb * 64;
+    const bf16 *p = wrow + (size_t)((!RAGGED || k < klen) ? (k >> 6) : 0) * 2048;
 #pragma unroll
-    for (int kb = 0; kb < KB; ++kb)
-      if (c * KC + kb * 64 < klen) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) w[kb][j] = *(const bf16x8 *)(wrow + c * KC + kb * 64 + 8 * j);
-      }
+    for (int j = 0; j < 4; ++j) w[set][kb][j] = *(const bf16x8 *)(p + 512 * j);
   };
   auto load_x = [&](int c) {
 #pragma unroll
     for (int i = 0; i < XV; ++i) {
       const int v = tid + 256 * i;
       const int row = v / (KC / 8), col = c * KC + (v % (KC / 8)) * 8;
-      const bf16 *src = xg + (size_t)row * a.k + col;
-      xr[0][i] = (col < klen) ? *(const uint4 *)src : make_uint4(0, 0, 0, 0);
-      xr[1][i] = (col < klen) ? *(const uint4 *)(src + a.x_panel) : make_uint4(0, 0, 0, 0);
+      const bool ok = !RAGGED || col < klen;
+      const bf16 *src = xg + (size_t)row * a.k + (ok ? col : 0);
+      const uint4 hi = *(const uint4 *)src;
+      const uint4 lo = *(const uint4 *)(src + a.x_panel);
+      xr[0][i] = ok ? hi : make_uint4(0, 0, 0, 0);
+      xr[1][i] = ok ? lo : make_uint4(0, 0, 0, 0);
     }
   };
   auto store_x = [&](int buf) {
@@ -95,46 +117,89 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(GemmArgs a, HeadStats hs, flo
       *(uint4 *)(lds + buf * BUF + PANEL + row * STRIDE + cv * 16) = xr[1][i];
     }
   };
-  auto compute = [&](const bf16x8 (&w)[KB][4], int c, int buf) {
-    if (!active) return;
-    const unsigned char *xb = lds + buf * BUF + ln * STRIDE + 64 * g;
+  auto mfma_block = [&](int set, int kb, int buf) {
+    const unsigned char *xb = lds + buf * BUF + ln * STRIDE + 64 * g + kb * 128;
 #pragma unroll
-    for (int kb = 0; kb < KB; ++kb)
-      if (c * KC + kb * 64 < klen) {
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-          for (int mb = 0; mb < MB; ++mb) {
-            const unsigned char *xp = xb + mb * 32 * STRIDE + kb * 128 + j * 16;
-            const bf16x8 xhi = *(const bf16x8 *)xp;
-            const bf16x8 xlo = *(const bf16x8 *)(xp + PANEL);
-            acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xhi, w[kb][j], acc[mb], 0, 0, 0);
-            acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xlo, w[kb][j], acc[mb], 0, 0, 0);
-          }
+      for (int mb = 0; mb < MB; ++mb) {
+        const unsigned char *xp = xb + mb * 32 * STRIDE + j * 16;
+        const bf16x8 xhi = *(const bf16x8 *)xp;
+        const bf16x8 xlo = *(const bf16x8 *)(xp + PANEL);
+        acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xhi, w[set][kb][j], acc[mb], 0, 0, 0);
+        acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xlo, w[set][kb][j], acc[mb], 0, 0, 0);
       }
   };
-  auto step = [&](const bf16x8 (&wc)[KB][4], bf16x8 (&wn)[KB][4], int c) {
-    const bool more = c + 1 < n_chunks;
-    if (more) {
-      load_w(wn, c + 1);
-      load_x(c + 1);
-    }
-    compute(wc, c, c & 1);
-    if (more) store_x((c + 1) & 1);
-    __syncthreads();
-  };
 
-  load_w(w0, 0);
-  load_x(0);
-  store_x(0);
-  __syncthreads();
-  for (int c = 0; c < n_chunks; c += 2) {
-    step(w0, w1, c);
-    if (c + 1 < n_chunks) step(w1, w0, c + 1);
+  if (RAGGED) {
+    // simple one-chunk-ahead loop with bounds logic (odd shapes only)
+    load_x(0);
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb) load_w_block(0, 0, kb);
+    store_x(0);
+    __syncthreads();
+    for (int c = 0; c + 1 < n_chunks; ++c) {
+      load_x(c + 1);
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb) {
+        mfma_block(0, kb, c & 1);
+        load_w_block(0, c + 1, kb);
+      }
+      store_x((c + 1) & 1);
+      __syncthreads();
+    }
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb) mfma_block(0, kb, (n_chunks - 1) & 1);
+  } else {
+    // n_chunks is even and >= 2.  The prologue issues its loads in the order the steady state
+    // does (X of a chunk before the W refill of the same step), so the wait counts merged at the
+    // loop head are the steady-state ones.
+    load_x(0);
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb) load_w_block(0, 0, kb);
+    __builtin_amdgcn_sched_barrier(0);
+    store_x(0);
+    load_x(1);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb) load_w_block(1, 1, kb);
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
+    // chunk pair (c, c+1) with c even: set 0 serves chunk c, set 1 serves chunk c+1
+    for (int c = 0; c + 2 < n_chunks; c += 2) {
+      store_x(1);            // chunk c+1
+      load_x(c + 2);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb) {
+        mfma_block(0, kb, 0);
+        load_w_block(0, c + 2, kb);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      __syncthreads();
+      store_x(0);            // chunk c+2
+      load_x(c + 3);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb) {
+        mfma_block(1, kb, 1);
+        load_w_block(1, c + 3, kb);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      __syncthreads();
+    }
+    // last pair: nothing left to fetch
+    store_x(1);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb) mfma_block(0, kb, 0);
+    __syncthreads();
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb) mfma_block(1, kb, 1);
   }
 
   if (!HEAD) {
-    if (!n_ok) return;
+    if (!n_ok) return;   // clamped duplicate columns and idle wavefronts computed on valid memory
     float *o = a.out + (size_t)split * a.rows_pad * a.n_total + n0 + ln;
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
@@ -177,16 +242,50 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(GemmArgs a, HeadStats hs, flo
   }
 }
 
+// One-time repack of a row-major [n_rows, k] bf16 matrix into the layout above.  One thread per
+// 16-byte piece of the output: piece (s, kb, j, lane) = W[32 s + (lane & 31)][64 kb + 32 (lane >> 5) + 8 j .. + 8].
+__global__ __launch_bounds__(256) void k_pack_weights(const bf16 *w, int n_rows, int k, uint4 *out,
+                                                      size_t n_pieces) {
+  const size_t p = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (p >= n_pieces) return;
+  const int lane = (int)(p & 63), j = (int)((p >> 6) & 3);
+  const size_t blk = p >> 8;
+  const int kblocks = k >> 6;
+  const int kb = (int)(blk % kblocks);
+  const int s = (int)(blk / kblocks);
+  const int row = 32 * s + (lane & 31);
+  const int col = 64 * kb + 32 * (lane >> 5) + 8 * j;
+  uint4 v = make_uint4(0, 0, 0, 0);
+  if (row < n_rows) v = *(const uint4 *)(w + (size_t)row * k + col);
+  out[p] = v;
+}
+
+size_t packed_weight_bytes(int n_rows, int k) { return (size_t)((n_rows + 31) / 32) * (k / 64) * 4096; }
+
+void launch_pack_weights(hipStream_t st, const void *w, int n_rows, int k, void *out) {
+  const size_t n_pieces = packed_weight_bytes(n_rows, k) / 16;
+  hipLaunchKernelGGL(k_pack_weights, dim3((unsigned)((n_pieces + 255) / 256)), dim3(256), 0, st,
+                     (const bf16 *)w, n_rows, k, (uint4 *)out, n_pieces);
+}
+
 template <bool HEAD>
 static void dispatch(hipStream_t st, const GemmArgs &a, const HeadStats &hs, float *dbg) {
   const int tiles = (a.n_total + kGemmTileN - 1) / kGemmTileN;
   dim3 grid(tiles, a.n_splits), block(256);
+#define TS_LAUNCH(MB_, KC_)                                                                         \
+  do {                                                                                              \
+    if (a.k_per_split % (2 * KC_) == 0 && a.k % (2 * KC_) == 0)                                     \
+      hipLaunchKernelGGL((k_gemm_bf16<MB_, KC_, HEAD, false>), grid, block, 0, st, a, hs, dbg);     \
+    else                                                                                            \
+      hipLaunchKernelGGL((k_gemm_bf16<MB_, KC_, HEAD, true>), grid, block, 0, st, a, hs, dbg);      \
+  } while (0)
   switch (a.rows_pad) {
-    case 32: hipLaunchKernelGGL((k_gemm_bf16<1, 256, HEAD>), grid, block, 0, st, a, hs, dbg); break;
-    case 64: hipLaunchKernelGGL((k_gemm_bf16<2, 128, HEAD>), grid, block, 0, st, a, hs, dbg); break;
-    case 128: hipLaunchKernelGGL((k_gemm_bf16<4, 64, HEAD>), grid, block, 0, st, a, hs, dbg); break;
-    default: hipLaunchKernelGGL((k_gemm_bf16<8, 64, HEAD>), grid, block, 0, st, a, hs, dbg); break;
+    case 32: TS_LAUNCH(1, 256); break;
+    case 64: TS_LAUNCH(2, 128); break;
+    case 128: TS_LAUNCH(4, 64); break;
+    default: TS_LAUNCH(8, 64); break;
   }
+#undef TS_LAUNCH
 }
 
 void launch_gemm_bf16(hipStream_t st, const GemmArgs &a) {

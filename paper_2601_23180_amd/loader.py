@@ -19,7 +19,8 @@ def _to_device(a: np.ndarray, bf16: bool, device) -> torch.Tensor:
     return t.to(torch.bfloat16) if bf16 else t
 
 
-def model_from_arrays(shape, get: Callable[[str, int], np.ndarray], device="cuda") -> Model:
+def model_from_arrays(shape, get: Callable[[str, int], np.ndarray], device="cuda",
+                      release_originals: bool = True) -> Model:
     """shape: any object with n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab,
     dtype ("f32" | "bf16"), rms_eps, rope_base.  get(name, layer) returns the tensor as float32
     values or (bf16 models) as uint16 bit patterns."""
@@ -27,10 +28,12 @@ def model_from_arrays(shape, get: Callable[[str, int], np.ndarray], device="cuda
     tensors = {n: _to_device(get(n, 0), bf16, device) for n in ("embed", "lm_head", "final_norm")}
     for n in _LAYER_NAMES:
         tensors[n] = [_to_device(get(n, l), bf16, device) for l in range(shape.n_layers)]
-    return Model(n_layers=shape.n_layers, hidden=shape.hidden, n_q_heads=shape.n_q_heads,
+    m = Model(n_layers=shape.n_layers, hidden=shape.hidden, n_q_heads=shape.n_q_heads,
                  n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim, ffn=shape.ffn, vocab=shape.vocab,
                  dtype=TRISPEC_BF16 if bf16 else TRISPEC_F32, rms_eps=shape.rms_eps,
                  rope_base=shape.rope_base, tensors=tensors)
+    m.pack(release_originals=release_originals)
+    return m
 
 
 def fill_kv_layer(kv: KVCache, layer: int, k: np.ndarray, v: np.ndarray) -> None:
