@@ -1,6 +1,7 @@
 // Host side of the C ABI: validation, workspace carve-up, launch sequence of one pass.
 // No allocation, no synchronisation and no HIP call other than kernel launches on the hot path.
 #include <math.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <new>
@@ -65,49 +66,45 @@ int rows_pad_for(int rows) {
   return 256;
 }
 
-// Workspace regions, in order.  Offsets are a pure function of (model, batch, max_nodes).
+// Workspace regions, in order.  Offsets are a pure function of (model, batch, n_nodes).
 struct Layout {
-  size_t anc, parent, status, cos_t, sin_t, x, h, q, qkv_f32, attn_out, act, part, attn_o, attn_m, attn_l,
-      head_l1, head_l2, head_sum, head_idx, node_l1, node_l2, node_sum, node_idx, logits, total;
-  int rows_max, rows_pad_max, head_tiles;
+  size_t anc, parent, status, cos_t, sin_t, x, rstd, h, q, qkv_f32, attn_out, act, part, counters, ss_part, attn_o, attn_m, attn_l, head_l1, head_l2, head_sum, head_idx, node_l1, node_l2, node_sum,
+      node_idx, logits, total;
+  int rows_max, rows_pad_max, head_tiles, max_tiles;
 };
 
-int max_gemm_cols(const trispec_model_config &c) {
-  int qkv = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
-  int m = qkv;
-  if (c.hidden > m) m = c.hidden;
-  if (2 * c.ffn > m) m = 2 * c.ffn;
-  return m;
-}
-
-// k-splits for one matmul: enough workgroups to fill the chip, k slices >= 256 deep.
-int pick_splits(int dtype, int n_total, int k) {
-  if (dtype == TRISPEC_F32) return 1;
-  const int tiles = (n_total + kGemmTileN - 1) / kGemmTileN;
-  int s = (512 + tiles - 1) / tiles;
-  const int max_by_k = k / 256 > 0 ? k / 256 : 1;
+// k-splits of one bf16 matmul: enough workgroups (tiles x splits) to cover the chip about one and
+// a half times over, every split a whole number of 256-deep steps when the reduction allows it.
+struct SplitPlan {
+  int n_tiles, n_splits, k_per_split;
+};
+SplitPlan plan_gemm(int n_tiles, int k) {
+  SplitPlan p;
+  p.n_tiles = n_tiles;
+  const int unit = (k % 256 == 0) ? 256 : 64;
+  static const int target = getenv("TRISPEC_TARGET_WGS") ? atoi(getenv("TRISPEC_TARGET_WGS")) : 320;
+  int s = (target + n_tiles / 2) / n_tiles;
+  const int max_by_k = k / 512 > 0 ? k / 512 : 1;
   if (s > max_by_k) s = max_by_k;
   if (s > kMaxSplitK) s = kMaxSplitK;
   if (s < 1) s = 1;
-  return s;
+  p.k_per_split = (int)align_up((size_t)(k + s - 1) / s, unit);
+  p.n_splits = (k + p.k_per_split - 1) / p.k_per_split;
+  return p;
 }
-// k slice of one split: a whole number of 256-deep chunks when the reduction allows it (keeps the
-// streaming loop free of bounds logic), else of 64-deep blocks.
-int k_per_split(int k, int s) {
-  const size_t unit = (k % 256 == 0) ? 256 : 64;
-  return (int)align_up((size_t)(k + s - 1) / s, unit);
-}
+inline int tiles_of(int n) { return (n + kGemmTileN - 1) / kGemmTileN; }
 
 Layout make_layout(const trispec_model_config &c, int batch, int max_nodes) {
   Layout L;
   memset(&L, 0, sizeof(L));
   const int rows = batch * max_nodes;
   const int rp = rows_pad_for(rows);
-  const size_t es = esize(c.dtype);
-  const int qd = c.n_q_heads * c.head_dim;
+  const bool f32 = c.dtype == TRISPEC_F32;
+  const int qd = c.n_q_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim;
+  const int nqkv = qd + 2 * kvd;
   L.rows_max = rows;
   L.rows_pad_max = rp;
-  L.head_tiles = c.dtype == TRISPEC_F32 ? 1 : (c.vocab + kGemmTileN - 1) / kGemmTileN;
+  L.head_tiles = f32 ? 1 : tiles_of(c.vocab);
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
   L.anc = take(sizeof(uint64_t) * kMaxRows);
@@ -116,24 +113,34 @@ Layout make_layout(const trispec_model_config &c, int batch, int max_nodes) {
   L.cos_t = take(sizeof(float) * rows * (c.head_dim / 2));
   L.sin_t = take(sizeof(float) * rows * (c.head_dim / 2));
   L.x = take(sizeof(float) * (size_t)rp * c.hidden);
-  // matmul / attention operands: fp32 models one panel; bf16 models a hi and a lo bf16 panel
-  const size_t np = c.dtype == TRISPEC_F32 ? 1 : 2;
-  L.h = take(np * es * (size_t)rp * c.hidden);
-  L.q = take(np * es * (size_t)rp * qd);
-  L.qkv_f32 = take(c.dtype == TRISPEC_F32 ? 0 : sizeof(float) * (size_t)rows * (qd + 2 * c.n_kv_heads * c.head_dim));
-  L.attn_out = take(np * es * (size_t)rp * qd);
-  L.act = take(np * es * (size_t)rp * c.ffn);
-  // split-K partials: the largest of S*N over the four matmuls of a layer
-  size_t part = 0;
-  const int ns[4] = {(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim, c.hidden, 2 * c.ffn, c.hidden};
-  const int ks[4] = {c.hidden, qd, c.hidden, c.ffn};
-  for (int i = 0; i < 4; ++i) {
-    size_t p = (size_t)pick_splits(c.dtype, ns[i], ks[i]) * ns[i];
-    if (p > part) part = p;
+  L.rstd = take(sizeof(float) * rp);
+  // matmul operands: fp32 models one fp32 panel; bf16 models a bf16 hi panel + a bf16 lo panel
+  L.h = take(sizeof(float) * (size_t)rp * c.hidden);
+  L.q = take(f32 ? sizeof(float) * (size_t)rp * qd : 0);
+  L.qkv_f32 = take(f32 ? 0 : sizeof(float) * (size_t)rp * nqkv);
+  L.attn_out = take(sizeof(float) * (size_t)rp * qd);
+  L.act = take(sizeof(float) * (size_t)rp * c.ffn);
+  if (f32) {
+    int m = nqkv;
+    if (c.hidden > m) m = c.hidden;
+    if (2 * c.ffn > m) m = 2 * c.ffn;
+    L.part = take(sizeof(float) * (size_t)rp * m);
+  } else {
+    // split-K partial tiles: the largest of splits x tiles over the four matmuls of a layer
+    const int tl[4] = {tiles_of(nqkv), tiles_of(c.hidden), (c.ffn + 63) / 64, tiles_of(c.hidden)};
+    const int ks[4] = {c.hidden, qd, c.hidden, c.ffn};
+    size_t m = 0;
+    for (int i = 0; i < 4; ++i) {
+      const SplitPlan p = plan_gemm(tl[i], ks[i]);
+      if ((size_t)p.n_splits * p.n_tiles > m) m = (size_t)p.n_splits * p.n_tiles;
+      if (tl[i] > L.max_tiles) L.max_tiles = tl[i];
+    }
+    L.part = take(sizeof(float) * m * rp * kGemmTileN);
   }
-  L.part = take(sizeof(float) * part * rp);
+  L.counters = take(sizeof(int32_t) * (L.max_tiles + 1));
+  L.ss_part = take(sizeof(float) * (size_t)tiles_of(c.hidden) * rp);
   const int group = c.n_q_heads / c.n_kv_heads;
-  const size_t prow = (size_t)batch * c.n_kv_heads * kMaxAttnSplits * group * max_nodes;
+  const size_t prow = f32 ? 0 : (size_t)batch * c.n_kv_heads * kMaxAttnSplits * group * max_nodes;
   L.attn_o = take(sizeof(float) * prow * c.head_dim);
   L.attn_m = take(sizeof(float) * prow);
   L.attn_l = take(sizeof(float) * prow);
@@ -146,7 +153,7 @@ Layout make_layout(const trispec_model_config &c, int batch, int max_nodes) {
   L.node_l2 = take(sizeof(float) * kMaxRows);
   L.node_sum = take(sizeof(float) * kMaxRows);
   L.node_idx = take(sizeof(int32_t) * kMaxRows);
-  L.logits = take(c.dtype == TRISPEC_F32 ? sizeof(float) * (size_t)rows * c.vocab : 0);
+  L.logits = take(f32 ? sizeof(float) * (size_t)rows * c.vocab : 0);
   L.total = off;
   return L;
 }
@@ -367,15 +374,11 @@ int trispec_workspace_region(const trispec_model *m, int32_t batch, int32_t max_
     return TRISPEC_ENODES;
   const Layout L = make_layout(m->cfg, batch, max_nodes);
   const trispec_model_config &c = m->cfg;
-  const size_t es = esize(c.dtype);
   const size_t rp = L.rows_pad_max;
-  const size_t np = c.dtype == TRISPEC_F32 ? 1 : 2;
   struct { const char *n; size_t o, b; } tab[] = {
       {"x", L.x, sizeof(float) * rp * c.hidden},
-      {"h", L.h, np * es * rp * c.hidden},
-      {"q", L.q, np * es * rp * c.n_q_heads * c.head_dim},
-      {"attn_out", L.attn_out, np * es * rp * c.n_q_heads * c.head_dim},
-      {"act", L.act, np * es * rp * c.ffn},
+      {"attn_out", L.attn_out, sizeof(float) * rp * c.n_q_heads * c.head_dim},
+      {"act", L.act, sizeof(float) * rp * c.ffn},
       {"node_l1", L.node_l1, sizeof(float) * kMaxRows},
       {"node_l2", L.node_l2, sizeof(float) * kMaxRows},
       {"node_sum", L.node_sum, sizeof(float) * kMaxRows},
@@ -435,125 +438,190 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
   hipStream_t st = (hipStream_t)opts->stream;
   char *ws = (char *)opts->workspace;
   const int rows = B * n_nodes, rp = rows_pad_for(rows);
+  const bool f32 = c.dtype == TRISPEC_F32;
   const size_t es = esize(c.dtype);
-  const int qd = c.n_q_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim;
+  const int qd = c.n_q_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim, nqkv = qd + 2 * kvd;
   float *x = (float *)(ws + L.x);
-  void *h = ws + L.h, *q = ws + L.q, *attn_out = ws + L.attn_out, *act = ws + L.act;
+  float *rstd = (float *)(ws + L.rstd);
+  void *attn_out = ws + L.attn_out, *act = ws + L.act;
+  const size_t pan_h = (size_t)rp * c.hidden, pan_q = (size_t)rp * qd, pan_f = (size_t)rp * c.ffn;
   float *part = (float *)(ws + L.part);
   float *cos_t = (float *)(ws + L.cos_t), *sin_t = (float *)(ws + L.sin_t);
   int32_t *status = (int32_t *)(ws + L.status);
   CtxLens ctx;
   for (int b = 0; b < kMaxBatch; ++b) ctx.v[b] = b < B ? kv->ctx_len[b] : 0;
-
-  (void)hipGetLastError();
-  launch_setup(st, tab, rows, (uint64_t *)(ws + L.anc), (int32_t *)(ws + L.parent), status);
-  launch_rope_table(st, positions, rows, c.head_dim, c.rope_base, cos_t, sin_t);
-  const size_t pan_h = (size_t)rp * c.hidden, pan_q = (size_t)rp * qd, pan_f = (size_t)rp * c.ffn;
-  launch_embed_norm(st, c.dtype, draft_tokens, m->embed, m->norm_attn[0], rows, c.hidden, c.vocab,
-                    c.rms_eps, x, h, pan_h, status);
-
-  auto gemm = [&](const void *xin, size_t xpanel, int k, int n_seg, const void *w0, int n0, const void *w1, int n1,
-                  const void *w2, int n2) -> int {
-    GemmArgs g;
-    memset(&g, 0, sizeof(g));
-    g.x = xin;
-    g.x_panel = xpanel;
-    g.seg[0] = {w0, n0, 0};
-    g.seg[1] = {w1, n1, n0};
-    g.seg[2] = {w2, n2, n0 + n1};
-    g.n_seg = n_seg;
-    g.n_total = n0 + n1 + n2;
-    g.k = k;
-    g.rows = rows;
-    g.rows_pad = rp;
-    g.n_splits = pick_splits(c.dtype, g.n_total, k);
-    g.k_per_split = k_per_split(k, g.n_splits);
-    g.n_splits = (k + g.k_per_split - 1) / g.k_per_split;
-    g.out = part;
-    TimedLaunch tl(opts->timer, TRISPEC_K_GEMM, st, (double)g.n_total * k * es);
-    if (c.dtype == TRISPEC_F32) launch_gemm_f32(st, g); else launch_gemm_bf16(st, g);
-    return g.n_splits;
-  };
-
-  // attention split: about 256 keys per workgroup, at most kMaxAttnSplits
-  AttnArgs at;
-  memset(&at, 0, sizeof(at));
-  at.q = q;
-  at.panel = pan_q;
-  at.anc = (const uint64_t *)(ws + L.anc);
-  at.ctx = ctx;
-  at.batch = B; at.n_nodes = n_nodes; at.n_q_heads = c.n_q_heads; at.n_kv_heads = c.n_kv_heads;
-  at.head_dim = c.head_dim; at.capacity = kv->capacity;
-  {
-    int kps = 256;
-    while ((max_keys + kps - 1) / kps > kMaxAttnSplits) kps *= 2;
-    at.keys_per_split = kps;
-    at.n_splits = (max_keys + kps - 1) / kps;
-    if (at.n_splits < 1) at.n_splits = 1;
-  }
-  float *qkv_f32 = c.dtype == TRISPEC_F32 ? nullptr : (float *)(ws + L.qkv_f32);
-  at.qkv = qkv_f32;
-  at.part_o = (float *)(ws + L.attn_o);
-  at.part_m = (float *)(ws + L.attn_m);
-  at.part_l = (float *)(ws + L.attn_l);
-  at.out = attn_out;
   const size_t kv_layer = (size_t)B * c.n_kv_heads * kv->capacity * c.head_dim * es;
 
-  for (int l = 0; l < c.n_layers; ++l) {
-    const bool pk = c.dtype == TRISPEC_BF16;
-    int s = gemm(h, pan_h, c.hidden, 3, pk ? m->p_wq[l] : m->wq[l], qd, pk ? m->p_wk[l] : m->wk[l], kvd,
-                 pk ? m->p_wv[l] : m->wv[l], kvd);
-    char *kl = (char *)kv->k + (size_t)l * kv_layer, *vl = (char *)kv->v + (size_t)l * kv_layer;
-    launch_qkv_epilogue(st, c.dtype, part, s, rows, rp, c.n_q_heads, c.n_kv_heads, c.head_dim, cos_t, sin_t,
-                        n_nodes, ctx, kv->capacity, q, pan_q, qkv_f32, kl, vl);
-    at.k_cache = kl;
-    at.v_cache = vl;
-    {
-      double kvb = 0;
-      for (int b = 0; b < B; ++b) kvb += 2.0 * (kv->ctx_len[b] + n_nodes) * kvd * es;
-      TimedLaunch tl(opts->timer, TRISPEC_K_ATTN, st, kvb);
-      if (c.dtype == TRISPEC_F32) launch_attn_f32(st, at); else launch_attn_bf16(st, at);
-    }
-    s = gemm(attn_out, pan_q, qd, 1, pk ? m->p_wo[l] : m->wo[l], c.hidden, nullptr, 0, nullptr, 0);
-    launch_reduce_residual_norm(st, c.dtype, part, s, rows, rp, c.hidden, m->norm_ffn[l], c.rms_eps, x, h, pan_h);
-    s = gemm(h, pan_h, c.hidden, 2, pk ? m->p_gate[l] : m->w_gate[l], c.ffn, pk ? m->p_up[l] : m->w_up[l], c.ffn,
-             nullptr, 0);
-    launch_reduce_swiglu(st, c.dtype, part, s, rows, rp, c.ffn, act, pan_f);
-    s = gemm(act, pan_f, c.ffn, 1, pk ? m->p_down[l] : m->w_down[l], c.hidden, nullptr, 0, nullptr, 0);
-    const void *next_norm = (l + 1 < c.n_layers) ? m->norm_attn[l + 1] : m->final_norm;
-    launch_reduce_residual_norm(st, c.dtype, part, s, rows, rp, c.hidden, next_norm, c.rms_eps, x, h, pan_h);
-  }
-
-  // LM head -> per-row statistics (never the probabilities)
   HeadStats hs;
   hs.l1 = (float *)(ws + L.head_l1);
   hs.l2 = (float *)(ws + L.head_l2);
   hs.sumexp = (float *)(ws + L.head_sum);
   hs.idx = (int32_t *)(ws + L.head_idx);
   hs.n_tiles = L.head_tiles;
+
+  AttnArgs at;
+  memset(&at, 0, sizeof(at));
+  at.anc = (const uint64_t *)(ws + L.anc);
+  at.ctx = ctx;
+  at.batch = B; at.n_nodes = n_nodes; at.n_q_heads = c.n_q_heads; at.n_kv_heads = c.n_kv_heads;
+  at.head_dim = c.head_dim; at.capacity = kv->capacity;
   {
-    GemmArgs g;
-    memset(&g, 0, sizeof(g));
-    g.x = h;
-    g.x_panel = pan_h;
-    g.seg[0] = {c.dtype == TRISPEC_BF16 ? m->p_lm_head : m->lm_head, c.vocab, 0};
-    g.n_seg = 1;
-    g.n_total = c.vocab;
-    g.k = c.hidden;
-    g.rows = rows;
-    g.rows_pad = rp;
-    g.n_splits = 1;
-    g.k_per_split = (int)align_up(c.hidden, 64);
-    TimedLaunch tl(opts->timer, TRISPEC_K_HEAD, st, (double)c.vocab * c.hidden * es);
-    if (c.dtype == TRISPEC_F32) {
-      float *logits = opts->debug_logits ? opts->debug_logits : (float *)(ws + L.logits);
-      g.out = logits;
+    // context split: about 256 keys per workgroup, at most kMaxAttnSplits
+    int kps = 256;
+    while ((max_keys + kps - 1) / kps > kMaxAttnSplits) kps *= 2;
+    at.keys_per_split = kps;
+    at.n_splits = (max_keys + kps - 1) / kps;
+    if (at.n_splits < 1) at.n_splits = 1;
+  }
+  at.part_o = (float *)(ws + L.attn_o);
+  at.part_m = (float *)(ws + L.attn_m);
+  at.part_l = (float *)(ws + L.attn_l);
+  at.out = attn_out;
+  at.out_panel = pan_q;
+  auto attention = [&](char *kl, char *vl) {
+    at.k_cache = kl;
+    at.v_cache = vl;
+    double kvb = 0;
+    for (int b = 0; b < B; ++b) kvb += 2.0 * (kv->ctx_len[b] + n_nodes) * kvd * es;
+    TimedLaunch tl(opts->timer, TRISPEC_K_ATTN, st, kvb);
+    if (f32) launch_attn_f32(st, at); else launch_attn_bf16(st, at);
+  };
+
+  (void)hipGetLastError();
+  launch_setup(st, tab, rows, (uint64_t *)(ws + L.anc), (int32_t *)(ws + L.parent), status);
+  launch_rope_table(st, positions, rows, c.head_dim, c.rope_base, cos_t, sin_t);
+
+  if (f32) {
+    // ---------------- fp32 models: plain kernels, one per step
+    float *h = (float *)(ws + L.h), *q = (float *)(ws + L.q);
+    at.q = q;
+    launch_embed_norm(st, c.dtype, draft_tokens, m->embed, m->norm_attn[0], rows, c.hidden, c.vocab,
+                      c.rms_eps, x, h, 0, nullptr, status);
+    auto gemm = [&](const float *xin, int k, int n_seg, const void *w0, int n0, const void *w1, int n1,
+                    const void *w2, int n2, float *out) {
+      GemmArgs g;
+      memset(&g, 0, sizeof(g));
+      g.x = xin;
+      g.seg[0] = {w0, n0, 0};
+      g.seg[1] = {w1, n1, n0};
+      g.seg[2] = {w2, n2, n0 + n1};
+      g.n_seg = n_seg;
+      g.n_total = n0 + n1 + n2;
+      g.k = k;
+      g.rows = rows;
+      g.rows_pad = rp;
+      g.n_splits = 1;
+      g.out = out;
+      TimedLaunch tl(opts->timer, TRISPEC_K_GEMM, st, (double)g.n_total * k * es);
       launch_gemm_f32(st, g);
+    };
+    for (int l = 0; l < c.n_layers; ++l) {
+      gemm(h, c.hidden, 3, m->wq[l], qd, m->wk[l], kvd, m->wv[l], kvd, part);
+      char *kl = (char *)kv->k + (size_t)l * kv_layer, *vl = (char *)kv->v + (size_t)l * kv_layer;
+      launch_qkv_epilogue(st, c.dtype, part, 1, rows, rp, c.n_q_heads, c.n_kv_heads, c.head_dim, cos_t, sin_t,
+                          n_nodes, ctx, kv->capacity, q, kl, vl);
+      attention(kl, vl);
+      gemm((const float *)attn_out, qd, 1, m->wo[l], c.hidden, nullptr, 0, nullptr, 0, part);
+      launch_reduce_residual_norm(st, c.dtype, part, 1, rows, rp, c.hidden, m->norm_ffn[l], c.rms_eps, x, h);
+      gemm(h, c.hidden, 2, m->w_gate[l], c.ffn, m->w_up[l], c.ffn, nullptr, 0, part);
+      launch_reduce_swiglu(st, c.dtype, part, 1, rows, rp, c.ffn, act);
+      gemm((const float *)act, c.ffn, 1, m->w_down[l], c.hidden, nullptr, 0, nullptr, 0, part);
+      const void *next_norm = (l + 1 < c.n_layers) ? m->norm_attn[l + 1] : m->final_norm;
+      launch_reduce_residual_norm(st, c.dtype, part, 1, rows, rp, c.hidden, next_norm, c.rms_eps, x, h);
+    }
+    float *logits = opts->debug_logits ? opts->debug_logits : (float *)(ws + L.logits);
+    {
+      TimedLaunch tl(opts->timer, TRISPEC_K_HEAD, st, (double)c.vocab * c.hidden * es);
+      gemm(h, c.hidden, 1, m->lm_head, c.vocab, nullptr, 0, nullptr, 0, logits);
       launch_stats_from_logits(st, logits, rows, c.vocab, hs);
-    } else {
-      launch_lmhead_bf16(st, g, hs, opts->debug_logits);
+    }
+  } else {
+    // ---------------- bf16 models: per layer QKV, attention (+ merge), O, gate/up, down
+    void *h = ws + L.h;
+    int32_t *counters = (int32_t *)(ws + L.counters);
+    float *qkv_f32 = (float *)(ws + L.qkv_f32);
+    at.qkv = qkv_f32;
+    launch_zero_counters(st, counters, L.max_tiles + 1);
+    launch_embed_norm(st, c.dtype, draft_tokens, m->embed, m->norm_attn[0], rows, c.hidden, c.vocab, c.rms_eps,
+                      x, h, pan_h, rstd, status);
+    auto base = [&](int epi, const void *xin, size_t xpanel, const float *row_scale, int k, int n_total,
+                    int n_tiles) {
+      GemmArgs g;
+      memset(&g, 0, sizeof(g));
+      g.epi = epi;
+      g.x = xin;
+      g.x_panel = xpanel;
+      g.row_scale = row_scale;
+      g.n_total = n_total;
+      g.k = k;
+      g.rows = rows;
+      g.rows_pad = rp;
+      const SplitPlan p = plan_gemm(n_tiles, k);
+      g.n_tiles = n_tiles;
+      g.n_splits = p.n_splits;
+      g.k_per_split = p.k_per_split;
+      g.part = part;
+      g.counters = counters;
+      return g;
+    };
+    auto resid = [&](GemmArgs &g, const void *next_norm) {
+      g.x_resid = x; g.xw_out = h; g.out_panel = pan_h; g.next_norm_w = next_norm;
+      g.ss_part = (float *)(ws + L.ss_part); g.rstd_out = rstd; g.eps = c.rms_eps;
+    };
+    for (int l = 0; l < c.n_layers; ++l) {
+      char *kl = (char *)kv->k + (size_t)l * kv_layer, *vl = (char *)kv->v + (size_t)l * kv_layer;
+      {
+        GemmArgs g = base(EPI_QKV, h, pan_h, rstd, c.hidden, nqkv, tiles_of(nqkv));
+        g.seg[0] = {m->p_wq[l], qd, 0};
+        g.seg[1] = {m->p_wk[l], kvd, qd};
+        g.seg[2] = {m->p_wv[l], kvd, qd + kvd};
+        g.n_seg = 3;
+        g.cos_t = cos_t; g.sin_t = sin_t; g.qkv_f32 = qkv_f32; g.k_cache = kl; g.v_cache = vl; g.ctx = ctx;
+        g.n_nodes = n_nodes; g.n_q_heads = c.n_q_heads; g.n_kv_heads = c.n_kv_heads; g.head_dim = c.head_dim;
+        g.capacity = kv->capacity;
+        TimedLaunch tl(opts->timer, TRISPEC_K_GEMM, st, (double)nqkv * c.hidden * es);
+        launch_gemm_bf16(st, g);
+      }
+      attention(kl, vl);
+      {
+        GemmArgs g = base(EPI_RESID, attn_out, pan_q, nullptr, qd, c.hidden, tiles_of(c.hidden));
+        g.seg[0] = {m->p_wo[l], c.hidden, 0};
+        g.n_seg = 1;
+        resid(g, m->norm_ffn[l]);
+        TimedLaunch tl(opts->timer, TRISPEC_K_GEMM, st, (double)c.hidden * qd * es);
+        launch_gemm_bf16(st, g);
+      }
+      {
+        GemmArgs g = base(EPI_SWIGLU, h, pan_h, rstd, c.hidden, 2 * c.ffn, (c.ffn + 63) / 64);
+        g.seg[0] = {m->p_gate[l], c.ffn, 0};
+        g.seg[1] = {m->p_up[l], c.ffn, c.ffn};
+        g.n_seg = 2;
+        g.act_out = act; g.ffn = c.ffn; g.out_panel = pan_f;
+        TimedLaunch tl(opts->timer, TRISPEC_K_GEMM, st, 2.0 * c.ffn * c.hidden * es);
+        launch_gemm_bf16(st, g);
+      }
+      {
+        GemmArgs g = base(EPI_RESID, act, pan_f, nullptr, c.ffn, c.hidden, tiles_of(c.hidden));
+        g.seg[0] = {m->p_down[l], c.hidden, 0};
+        g.n_seg = 1;
+        resid(g, (l + 1 < c.n_layers) ? m->norm_attn[l + 1] : m->final_norm);
+        TimedLaunch tl(opts->timer, TRISPEC_K_GEMM, st, (double)c.hidden * c.ffn * es);
+        launch_gemm_bf16(st, g);
+      }
+    }
+    {
+      GemmArgs g = base(EPI_HEAD, h, pan_h, rstd, c.hidden, c.vocab, tiles_of(c.vocab));
+      g.seg[0] = {m->p_lm_head, c.vocab, 0};
+      g.n_seg = 1;
+      g.n_splits = 1;
+      g.k_per_split = (int)align_up(c.hidden, (c.hidden % 256 == 0) ? 256 : 64);
+      g.hs = hs;
+      g.debug_logits = opts->debug_logits;
+      TimedLaunch tl(opts->timer, TRISPEC_K_HEAD, st, (double)c.vocab * c.hidden * es);
+      launch_gemm_bf16(st, g);
     }
   }
+
   launch_stats_reduce(st, hs, rows, (float *)(ws + L.node_l1), (float *)(ws + L.node_l2),
                       (float *)(ws + L.node_sum), (int32_t *)(ws + L.node_idx));
   DecideArgs d = make_decide(L, ws, draft_tokens, B, n_nodes, threshold, opts, out);

@@ -15,19 +15,32 @@ __device__ __forceinline__ float from_f32<float>(float v) { return v; }
 template <>
 __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return (bf16)v; }  // round-to-nearest-even
 
-// Activation operands.  fp32 models keep one fp32 panel.  bf16 models keep every matmul / attention
-// operand as TWO bf16 panels, hi = round(v) and lo = round(v - hi) (hi + lo carries ~16 significant
-// bits), `panel` elements apart; the matrix cores multiply both by the bf16 weights and accumulate
-// in fp32.  No activation is ever rounded to 8 significant bits, so the pass is a smooth function
-// of its inputs and reproducible to ~1e-5 against an unrounded reference.
-__device__ __forceinline__ void store_act(float *base, size_t panel, size_t idx, float v) {
-  (void)panel;
-  base[idx] = v;
+// Data handed from one workgroup to another INSIDE a kernel (split-K partial tiles, per-tile
+// sums) is written and read with agent-scope relaxed atomics: on gfx950 these are ordinary
+// stores / loads that write through, respectively bypass, the per-XCD L2, so they are coherent
+// across the chip without the L2 write-back + invalidate a full __threadfence() costs (measured:
+// two fences per workgroup added ~100 us to a 10 us kernel).  publish_then_count() then makes the
+// stores complete before the tile counter is bumped.
+__device__ __forceinline__ void st_agent(float *p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ void store_act(bf16 *base, size_t panel, size_t idx, float v) {
-  const bf16 hi = (bf16)v;
-  base[idx] = hi;
-  base[panel + idx] = (bf16)(v - (float)hi);
+__device__ __forceinline__ float ld_agent(const float *p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Called by every thread of the workgroup after its st_agent stores.  Returns (to all threads)
+// whether this workgroup was the `expected`-th, i.e. last, to arrive; the counter is reset by the
+// last arriver so that it is zero again for the next launch.
+__device__ __forceinline__ bool publish_then_count(int32_t *counter, int expected, int *s_flag) {
+  __builtin_amdgcn_s_waitcnt(0);   // vmcnt(0): this thread's write-through stores are acknowledged
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int old = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int last = (old == expected - 1);
+    if (last) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    *s_flag = last;
+  }
+  __syncthreads();
+  return *s_flag != 0;
 }
 
 // Sum over a 64-lane wavefront, fixed butterfly order (deterministic).

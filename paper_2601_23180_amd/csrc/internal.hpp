@@ -33,27 +33,6 @@ struct CtxLens {
   int32_t v[kMaxBatch];
 };
 
-// One weight-streaming matmul  out[s][r][col] = sum_{k in split s} X[r][k] * W[col][k].
-struct GemmSeg {
-  const void *w;   // bf16 models: the PACKED copy of the [n_rows, K] matrix; fp32: the matrix
-  int32_t n_rows;
-  int32_t col0;    // first output column of this segment
-};
-struct GemmArgs {
-  const void *x;       // [rows_pad, K] activation operand: fp32, or bf16 hi panel followed,
-                       // x_panel elements later, by the bf16 lo panel
-  size_t x_panel;
-  GemmSeg seg[3];
-  int32_t n_seg;
-  int32_t n_total;     // total output columns
-  int32_t k;           // reduction length
-  int32_t rows;        // valid rows
-  int32_t rows_pad;    // multiple of 32
-  int32_t k_per_split; // multiple of 64
-  int32_t n_splits;
-  float *out;          // [n_splits][rows_pad][n_total]
-};
-
 // Per (row, column tile) statistics of the LM-head logits.
 struct HeadStats {
   float *l1;      // largest logit
@@ -63,9 +42,57 @@ struct HeadStats {
   int32_t n_tiles;
 };
 
+// One weight-streaming matmul  y[r][col] = sum_k X[r][k] * W[col][k]  (see kernels_gemm.hip).
+struct GemmSeg {
+  const void *w;   // bf16 models: the PACKED copy of the [n_rows, K] matrix; fp32: the matrix
+  int32_t n_rows;
+  int32_t col0;    // first output column of this segment
+};
+enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_HEAD = 3 };
+struct GemmArgs {
+  // fp32 reference-precision path: x is [rows_pad, K] fp32, out is [rows][n_total].
+  // bf16 path: x is the bf16 hi panel [rows_pad, K], the lo panel follows x_panel elements later;
+  // row_scale (1/rms per row, or nullptr) multiplies the reduced sums in the epilogue.
+  const void *x;
+  size_t x_panel;
+  const float *row_scale;
+  GemmSeg seg[3];
+  int32_t n_seg;
+  int32_t n_total;     // total output columns (SWIGLU: 2 * ffn)
+  int32_t k;           // reduction length
+  int32_t rows;        // valid rows
+  int32_t rows_pad;    // 32, 64, 128 or 256
+  int32_t k_per_split; // multiple of 64
+  int32_t n_splits;
+  int32_t n_tiles;
+  int32_t epi;
+  float *out;          // fp32 path only
+  float *part;         // [n_splits][n_tiles][rows_pad][128] split-K partial tiles
+  int32_t *counters;   // [n_tiles + 1], zero between launches
+  // QKV epilogue
+  const float *cos_t, *sin_t;
+  float *qkv_f32;      // [rows][n_total] rotated q, k and v in fp32
+  void *k_cache, *v_cache;
+  CtxLens ctx;
+  int32_t n_nodes, n_q_heads, n_kv_heads, head_dim, capacity;
+  // RESID epilogue
+  float *x_resid;      // [rows_pad][n_total] residual stream, updated in place
+  void *xw_out;        // bf16 hi/lo panels [rows_pad][n_total]: x * next norm weight
+  const void *next_norm_w;  // bf16 [n_total]
+  float *ss_part;      // [n_tiles][rows_pad]
+  float *rstd_out;     // [rows_pad]
+  float eps;
+  size_t out_panel;    // panel stride (elements) of xw_out / act_out
+  // SWIGLU epilogue
+  void *act_out;       // bf16 hi/lo panels [rows_pad][ffn]
+  int32_t ffn;
+  // HEAD epilogue
+  HeadStats hs;
+  float *debug_logits;
+};
+
 struct AttnArgs {
-  const void *q;        // [rows_pad, nq*d] (bf16: hi panel, lo panel `panel` elements later)
-  size_t panel;         // operand panel stride of q and out, in elements
+  const void *q;        // fp32 path: [rows_pad, nq*d] fp32 queries (bf16 path reads them from qkv)
   const void *k_cache;  // this layer: [B][nkv][cap][d]
   const void *v_cache;  // this layer: [B][nkv][d][cap]
   const uint64_t *anc;  // [B*M]
@@ -77,7 +104,8 @@ struct AttnArgs {
   float *part_o;        // [B][nkv][n_splits][group*M][d]  unnormalised
   float *part_m;        // [B][nkv][n_splits][group*M]     running max
   float *part_l;        // [B][nkv][n_splits][group*M]     sum of exp
-  void *out;            // [rows_pad, nq*d]
+  void *out;            // fp32 path: [rows_pad, nq*d] fp32; bf16 path: bf16 hi/lo panels
+  size_t out_panel;     // panel stride (elements) of out
 };
 
 struct DecideArgs {
@@ -100,22 +128,21 @@ void launch_rope_table(hipStream_t st, const int32_t *positions, int rows, int h
                        float *cos_t, float *sin_t);
 void launch_embed_norm(hipStream_t st, int dtype, const int32_t *tokens, const void *embed,
                        const void *norm_w, int rows, int hidden, int vocab, float eps, float *x,
-                       void *h, size_t panel, int32_t *status);
+                       void *h, size_t h_panel, float *rstd_out, int32_t *status);
+void launch_zero_counters(hipStream_t st, int32_t *counters, int n_counters);
 void launch_qkv_epilogue(hipStream_t st, int dtype, const float *part, int n_splits, int rows,
                          int rows_pad, int n_q_heads, int n_kv_heads, int head_dim,
                          const float *cos_t, const float *sin_t, int n_nodes, CtxLens ctx,
-                         int capacity, void *q_out, size_t panel, float *qkv_f32, void *k_cache,
-                         void *v_cache);
+                         int capacity, void *q_out, void *k_cache, void *v_cache);
 void launch_reduce_residual_norm(hipStream_t st, int dtype, const float *part, int n_splits, int rows,
                                  int rows_pad, int hidden, const void *norm_w, float eps, float *x,
-                                 void *h, size_t panel);
+                                 void *h);
 void launch_reduce_swiglu(hipStream_t st, int dtype, const float *part, int n_splits, int rows,
-                          int rows_pad, int ffn, void *act, size_t panel);
+                          int rows_pad, int ffn, void *act);
 void launch_gemm_f32(hipStream_t st, const GemmArgs &a);
 size_t packed_weight_bytes(int n_rows, int k);
 void launch_pack_weights(hipStream_t st, const void *w, int n_rows, int k, void *out);
 void launch_gemm_bf16(hipStream_t st, const GemmArgs &a);
-void launch_lmhead_bf16(hipStream_t st, const GemmArgs &a, const HeadStats &hs, float *debug_logits);
 void launch_stats_from_logits(hipStream_t st, const float *logits, int rows, int vocab,
                               const HeadStats &hs);
 void launch_attn_f32(hipStream_t st, const AttnArgs &a);

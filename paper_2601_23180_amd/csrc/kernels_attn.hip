@@ -119,11 +119,21 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
     if (p < p_rows) {
       const int al = p / M, node = p - al * M;
       const int r = b * M + node;
-      const bf16 *q = (const bf16 *)a.q + (size_t)r * a.n_q_heads * D + (size_t)(kvh * group + al) * D;
+      // fp32 query (already rotated) -> bf16 high part + bf16 low part
+      const int n_total = (a.n_q_heads + 2 * a.n_kv_heads) * D;
+      const float *q = a.qkv + (size_t)r * n_total + (size_t)(kvh * group + al) * D;
 #pragma unroll
       for (int t = 0; t < D / 16; ++t) {
-        qf[i][t] = *(const bf16x8 *)(q + 16 * t + 8 * g);
-        ql[i][t] = *(const bf16x8 *)(q + a.panel + 16 * t + 8 * g);
+        const f32x4 q0 = *(const f32x4 *)(q + 16 * t + 8 * g);
+        const f32x4 q1 = *(const f32x4 *)(q + 16 * t + 8 * g + 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const bf16 h0 = (bf16)q0[e], h1 = (bf16)q1[e];
+          qf[i][t][e] = h0;
+          qf[i][t][4 + e] = h1;
+          ql[i][t][e] = (bf16)(q0[e] - (float)h0);
+          ql[i][t][4 + e] = (bf16)(q1[e] - (float)h1);
+        }
       }
     }
   }
@@ -354,7 +364,11 @@ __global__ __launch_bounds__(D) void k_attn_merge(AttnArgs a) {
     num += w * a.qkv[(size_t)(b * M + j) * n_total + (a.n_q_heads + a.n_kv_heads + kvh) * D + f];
     den += w;
   }
-  store_act((bf16 *)a.out, a.panel, (size_t)r * a.n_q_heads * D + (size_t)head * D + f, num / den);
+  const float o = num / den;
+  const bf16 hi = (bf16)o;
+  bf16 *dst = (bf16 *)a.out + (size_t)r * a.n_q_heads * D + (size_t)head * D + f;
+  dst[0] = hi;
+  dst[a.out_panel] = (bf16)(o - (float)hi);
 }
 
 template <int D>

@@ -1,7 +1,7 @@
-// Small kernels of the verification pass: set-up, rotary table, embedding + RMSNorm,
-// split-K reductions with their fused epilogues (rotary + KV append, residual + RMSNorm,
-// SiLU*up), vocabulary statistics reduction and the routing decision.
-// Templated on the activation / storage type AT (float for fp32 models, bf16 otherwise).
+// Small kernels of the verification pass: set-up, rotary table, embedding (+ first RMSNorm
+// statistic), vocabulary statistics reduction and the routing decision; plus the plain fp32
+// pipeline (matmul, rotary + KV append, residual + RMSNorm, SiLU*up as separate simple kernels)
+// that serves fp32 models, where reference precision matters and speed does not.
 #include "device_util.hpp"
 
 namespace ts {
@@ -41,10 +41,13 @@ void launch_rope_table(hipStream_t st, const int32_t *positions, int rows, int h
 }
 
 // ------------------------------------------------------------------ embedding + first RMSNorm
+// x[r] = E[token_r] (fp32 residual stream).  fp32 models: h[r] = x * rstd * w.  bf16 models: the
+// first matmul's operand panels h = x * w as bf16 hi + lo, and rstd[r] for that matmul's epilogue.
 template <typename AT>
 __global__ __launch_bounds__(256) void k_embed_norm(const int32_t *tokens, const AT *embed,
                                                     const AT *norm_w, int hidden, int vocab, float eps,
-                                                    float *x, AT *h, size_t panel, int32_t *status) {
+                                                    float *x, void *h, size_t h_panel, float *rstd_out,
+                                                    int32_t *status) {
   __shared__ float red[4];
   const int r = blockIdx.x;
   int tok = tokens[r];
@@ -62,19 +65,39 @@ __global__ __launch_bounds__(256) void k_embed_norm(const int32_t *tokens, const
   }
   ss = block_sum<4>(ss, red);
   const float rstd = 1.0f / sqrtf(ss / (float)hidden + eps);
-  for (int i = threadIdx.x; i < hidden; i += 256)
-    store_act(h, panel, (size_t)r * hidden + i, to_f32(e[i]) * rstd * to_f32(norm_w[i]));
+  if (rstd_out != nullptr) {
+    if (threadIdx.x == 0) rstd_out[r] = rstd;
+    bf16 *hp = (bf16 *)h + (size_t)r * hidden;
+    for (int i = threadIdx.x; i < hidden; i += 256) {
+      const float v = to_f32(e[i]) * to_f32(norm_w[i]);
+      const bf16 hi = (bf16)v;
+      hp[i] = hi;
+      hp[h_panel + i] = (bf16)(v - (float)hi);
+    }
+  } else {
+    float *hp = (float *)h + (size_t)r * hidden;
+    for (int i = threadIdx.x; i < hidden; i += 256) hp[i] = to_f32(e[i]) * rstd * to_f32(norm_w[i]);
+  }
 }
 
 void launch_embed_norm(hipStream_t st, int dtype, const int32_t *tokens, const void *embed,
                        const void *norm_w, int rows, int hidden, int vocab, float eps, float *x,
-                       void *h, size_t panel, int32_t *status) {
+                       void *h, size_t h_panel, float *rstd_out, int32_t *status) {
   if (dtype == TRISPEC_F32)
     hipLaunchKernelGGL(k_embed_norm<float>, dim3(rows), dim3(256), 0, st, tokens, (const float *)embed,
-                       (const float *)norm_w, hidden, vocab, eps, x, (float *)h, panel, status);
+                       (const float *)norm_w, hidden, vocab, eps, x, h, h_panel, (float *)nullptr, status);
   else
     hipLaunchKernelGGL(k_embed_norm<bf16>, dim3(rows), dim3(256), 0, st, tokens, (const bf16 *)embed,
-                       (const bf16 *)norm_w, hidden, vocab, eps, x, (bf16 *)h, panel, status);
+                       (const bf16 *)norm_w, hidden, vocab, eps, x, h, h_panel, rstd_out, status);
+}
+
+__global__ void k_zero_counters(int32_t *counters, int n_counters) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n_counters) counters[i] = 0;
+}
+
+void launch_zero_counters(hipStream_t st, int32_t *counters, int n_counters) {
+  hipLaunchKernelGGL(k_zero_counters, dim3((n_counters + 255) / 256), dim3(256), 0, st, counters, n_counters);
 }
 
 // Sum of the split-K partials of one output element, ascending split order.
@@ -84,15 +107,13 @@ __device__ __forceinline__ float sum_splits(const float *part, int n_splits, siz
   return v;
 }
 
-// ------------------------------------------------------------------ QKV epilogue
-// One workgroup per (row, head).  Sums the partials of the head's columns, applies the rotary
-// embedding to q and k heads (pair (j, j + d/2)); q goes to the attention operand buffer, k and v
-// are rounded to the cache's storage type and written to slot ctx_len + node (v transposed).
-template <typename AT>
-__global__ void k_qkv_epilogue(const float *part, int n_splits, int rows_pad, int n_q_heads,
-                               int n_kv_heads, int head_dim, const float *cos_t, const float *sin_t,
-                               int n_nodes, CtxLens ctx, int capacity, AT *q_out, size_t panel,
-                               float *qkv_f32, AT *k_cache, AT *v_cache) {
+// ------------------------------------------------------------------ fp32 pipeline: QKV epilogue
+// One workgroup per (row, head): rotary embedding of q and k heads (pair (j, j + d/2)), q to the
+// attention operand buffer, k and v to cache slot ctx_len + node (v transposed).
+__global__ void k_qkv_epilogue_f32(const float *part, int n_splits, int rows_pad, int n_q_heads,
+                                   int n_kv_heads, int head_dim, const float *cos_t, const float *sin_t,
+                                   int n_nodes, CtxLens ctx, int capacity, float *q_out, float *k_cache,
+                                   float *v_cache) {
   const int r = blockIdx.x, hh = blockIdx.y, j = threadIdx.x;
   const int half = head_dim >> 1;
   if (j >= half) return;
@@ -109,49 +130,40 @@ __global__ void k_qkv_epilogue(const float *part, int n_splits, int rows_pad, in
     const float rb = b * c + a * s;
     a = ra; b = rb;
   }
-  if (qkv_f32 != nullptr) {   // unrounded copy for the draft-node part of the attention
-    qkv_f32[off] = a;
-    qkv_f32[off + half] = b;
-  }
   if (hh < n_q_heads) {
-    const size_t qi = (size_t)r * n_q_heads * head_dim + (size_t)hh * head_dim + j;
-    store_act(q_out, panel, qi, a);
-    store_act(q_out, panel, qi + half, b);
+    float *q = q_out + (size_t)r * n_q_heads * head_dim + (size_t)hh * head_dim;
+    q[j] = a;
+    q[j + half] = b;
   } else if (hh < n_q_heads + n_kv_heads) {
     const int kvh = hh - n_q_heads;
-    AT *k = k_cache + (((size_t)bidx * n_kv_heads + kvh) * capacity + slot) * head_dim;
-    k[j] = from_f32<AT>(a);
-    k[j + half] = from_f32<AT>(b);
+    float *k = k_cache + (((size_t)bidx * n_kv_heads + kvh) * capacity + slot) * head_dim;
+    k[j] = a;
+    k[j + half] = b;
   } else {
     const int kvh = hh - n_q_heads - n_kv_heads;
-    AT *v = v_cache + ((size_t)bidx * n_kv_heads + kvh) * head_dim * capacity;
-    v[(size_t)j * capacity + slot] = from_f32<AT>(a);
-    v[(size_t)(j + half) * capacity + slot] = from_f32<AT>(b);
+    float *v = v_cache + ((size_t)bidx * n_kv_heads + kvh) * head_dim * capacity;
+    v[(size_t)j * capacity + slot] = a;
+    v[(size_t)(j + half) * capacity + slot] = b;
   }
 }
 
 void launch_qkv_epilogue(hipStream_t st, int dtype, const float *part, int n_splits, int rows,
                          int rows_pad, int n_q_heads, int n_kv_heads, int head_dim,
                          const float *cos_t, const float *sin_t, int n_nodes, CtxLens ctx,
-                         int capacity, void *q_out, size_t panel, float *qkv_f32, void *k_cache,
-                         void *v_cache) {
+                         int capacity, void *q_out, void *k_cache, void *v_cache) {
+  (void)dtype;
   dim3 grid(rows, n_q_heads + 2 * n_kv_heads), block(head_dim / 2);
-  if (dtype == TRISPEC_F32)
-    hipLaunchKernelGGL(k_qkv_epilogue<float>, grid, block, 0, st, part, n_splits, rows_pad, n_q_heads,
-                       n_kv_heads, head_dim, cos_t, sin_t, n_nodes, ctx, capacity, (float *)q_out, panel,
-                       qkv_f32, (float *)k_cache, (float *)v_cache);
-  else
-    hipLaunchKernelGGL(k_qkv_epilogue<bf16>, grid, block, 0, st, part, n_splits, rows_pad, n_q_heads,
-                       n_kv_heads, head_dim, cos_t, sin_t, n_nodes, ctx, capacity, (bf16 *)q_out, panel,
-                       qkv_f32, (bf16 *)k_cache, (bf16 *)v_cache);
+  hipLaunchKernelGGL(k_qkv_epilogue_f32, grid, block, 0, st, part, n_splits, rows_pad, n_q_heads,
+                     n_kv_heads, head_dim, cos_t, sin_t, n_nodes, ctx, capacity, (float *)q_out,
+                     (float *)k_cache, (float *)v_cache);
 }
 
-// ------------------------------------------------------------------ residual + RMSNorm
-// x[r] += sum of partials; h[r] = x[r] * rstd * w (as an operand pair).  One workgroup per row.
-template <typename AT>
-__global__ __launch_bounds__(256) void k_reduce_residual_norm(const float *part, int n_splits,
-                                                              int rows_pad, int hidden, const AT *norm_w,
-                                                              float eps, float *x, AT *h, size_t panel) {
+// ------------------------------------------------------------------ fp32 pipeline: residual + RMSNorm
+// x[r] += y[r]; h[r] = x[r] * rstd * w.  One workgroup per row.
+__global__ __launch_bounds__(256) void k_reduce_residual_norm_f32(const float *part, int n_splits,
+                                                                  int rows_pad, int hidden,
+                                                                  const float *norm_w, float eps, float *x,
+                                                                  float *h) {
   __shared__ float red[4];
   const int r = blockIdx.x;
   const size_t slice = (size_t)rows_pad * hidden;
@@ -164,26 +176,21 @@ __global__ __launch_bounds__(256) void k_reduce_residual_norm(const float *part,
   }
   ss = block_sum<4>(ss, red);
   const float rstd = 1.0f / sqrtf(ss / (float)hidden + eps);
-  for (int i = threadIdx.x; i < hidden; i += 256)
-    store_act(h, panel, (size_t)r * hidden + i, xr[i] * rstd * to_f32(norm_w[i]));
+  for (int i = threadIdx.x; i < hidden; i += 256) h[(size_t)r * hidden + i] = xr[i] * rstd * norm_w[i];
 }
 
 void launch_reduce_residual_norm(hipStream_t st, int dtype, const float *part, int n_splits, int rows,
                                  int rows_pad, int hidden, const void *norm_w, float eps, float *x,
-                                 void *h, size_t panel) {
-  if (dtype == TRISPEC_F32)
-    hipLaunchKernelGGL(k_reduce_residual_norm<float>, dim3(rows), dim3(256), 0, st, part, n_splits,
-                       rows_pad, hidden, (const float *)norm_w, eps, x, (float *)h, panel);
-  else
-    hipLaunchKernelGGL(k_reduce_residual_norm<bf16>, dim3(rows), dim3(256), 0, st, part, n_splits,
-                       rows_pad, hidden, (const bf16 *)norm_w, eps, x, (bf16 *)h, panel);
+                                 void *h) {
+  (void)dtype;
+  hipLaunchKernelGGL(k_reduce_residual_norm_f32, dim3(rows), dim3(256), 0, st, part, n_splits, rows_pad,
+                     hidden, (const float *)norm_w, eps, x, (float *)h);
 }
 
-// ------------------------------------------------------------------ SiLU(gate) * up
-// partial columns [0, F) are the gate projection, [F, 2F) the up projection.
-template <typename AT>
-__global__ __launch_bounds__(256) void k_reduce_swiglu(const float *part, int n_splits, int rows_pad,
-                                                       int ffn, AT *act, size_t panel) {
+// ------------------------------------------------------------------ fp32 pipeline: SiLU(gate) * up
+// columns [0, F) of y are the gate projection, [F, 2F) the up projection.
+__global__ __launch_bounds__(256) void k_reduce_swiglu_f32(const float *part, int n_splits, int rows_pad,
+                                                           int ffn, float *act) {
   const int r = blockIdx.y;
   const int f = blockIdx.x * 256 + threadIdx.x;
   if (f >= ffn) return;
@@ -192,18 +199,14 @@ __global__ __launch_bounds__(256) void k_reduce_swiglu(const float *part, int n_
   const float g = sum_splits(part, n_splits, slice, off);
   const float u = sum_splits(part, n_splits, slice, off + ffn);
   const float silu = g / (1.0f + expf(-g));
-  store_act(act, panel, (size_t)r * ffn + f, silu * u);
+  act[(size_t)r * ffn + f] = silu * u;
 }
 
 void launch_reduce_swiglu(hipStream_t st, int dtype, const float *part, int n_splits, int rows,
-                          int rows_pad, int ffn, void *act, size_t panel) {
+                          int rows_pad, int ffn, void *act) {
+  (void)dtype;
   dim3 grid((ffn + 255) / 256, rows);
-  if (dtype == TRISPEC_F32)
-    hipLaunchKernelGGL(k_reduce_swiglu<float>, grid, dim3(256), 0, st, part, n_splits, rows_pad, ffn,
-                       (float *)act, panel);
-  else
-    hipLaunchKernelGGL(k_reduce_swiglu<bf16>, grid, dim3(256), 0, st, part, n_splits, rows_pad, ffn,
-                       (bf16 *)act, panel);
+  hipLaunchKernelGGL(k_reduce_swiglu_f32, grid, dim3(256), 0, st, part, n_splits, rows_pad, ffn, (float *)act);
 }
 
 // ------------------------------------------------------------------ fp32 reference-precision matmul
