@@ -116,7 +116,7 @@ Layout make_layout(const trispec_model_config &c, int batch, int max_nodes) {
   L.rstd = take(sizeof(float) * rp);
   // matmul operands: fp32 models one fp32 panel; bf16 models a bf16 hi panel + a bf16 lo panel
   L.h = take(sizeof(float) * (size_t)rp * c.hidden);
-  L.q = take(f32 ? sizeof(float) * (size_t)rp * qd : 0);
+  L.q = take(sizeof(float) * (size_t)rp * qd);
   L.qkv_f32 = take(f32 ? 0 : sizeof(float) * (size_t)rp * nqkv);
   L.attn_out = take(sizeof(float) * (size_t)rp * qd);
   L.act = take(sizeof(float) * (size_t)rp * c.ffn);
@@ -138,7 +138,8 @@ Layout make_layout(const trispec_model_config &c, int batch, int max_nodes) {
     L.part = take(sizeof(float) * m * rp * kGemmTileN);
   }
   L.counters = take(sizeof(int32_t) * (L.max_tiles + 1));
-  L.ss_part = take(sizeof(float) * (size_t)tiles_of(c.hidden) * rp);
+  // sums of squares per (tile, row): two buffers, a matmul reads its producer's while writing its own
+  L.ss_part = take(2 * sizeof(float) * (size_t)tiles_of(c.hidden) * rp);
   const int group = c.n_q_heads / c.n_kv_heads;
   const size_t prow = f32 ? 0 : (size_t)batch * c.n_kv_heads * kMaxAttnSplits * group * max_nodes;
   L.attn_o = take(sizeof(float) * prow * c.head_dim);
@@ -442,7 +443,6 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
   const size_t es = esize(c.dtype);
   const int qd = c.n_q_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim, nqkv = qd + 2 * kvd;
   float *x = (float *)(ws + L.x);
-  float *rstd = (float *)(ws + L.rstd);
   void *attn_out = ws + L.attn_out, *act = ws + L.act;
   const size_t pan_h = (size_t)rp * c.hidden, pan_q = (size_t)rp * qd, pan_f = (size_t)rp * c.ffn;
   float *part = (float *)(ws + L.part);
@@ -541,17 +541,26 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
     int32_t *counters = (int32_t *)(ws + L.counters);
     float *qkv_f32 = (float *)(ws + L.qkv_f32);
     at.qkv = qkv_f32;
+    at.q = ws + L.q;
+    at.q_panel = pan_q;
+    at.n_row_groups = (group * n_nodes + 127) / 128;
     launch_zero_counters(st, counters, L.max_tiles + 1);
+    // ss[0]: written by the embedding (1 tile) and by every down projection; ss[1]: by every O projection
+    const int h_tiles = tiles_of(c.hidden);
+    float *ss0 = (float *)(ws + L.ss_part), *ss1 = ss0 + (size_t)h_tiles * rp;
     launch_embed_norm(st, c.dtype, draft_tokens, m->embed, m->norm_attn[0], rows, c.hidden, c.vocab, c.rms_eps,
-                      x, h, pan_h, rstd, status);
-    auto base = [&](int epi, const void *xin, size_t xpanel, const float *row_scale, int k, int n_total,
-                    int n_tiles) {
+                      x, h, pan_h, ss0, status);
+    int ss0_tiles = 1;
+    auto base = [&](int epi, const void *xin, size_t xpanel, const float *ss_in, int ss_tiles, int k,
+                    int n_total, int n_tiles) {
       GemmArgs g;
       memset(&g, 0, sizeof(g));
       g.epi = epi;
       g.x = xin;
       g.x_panel = xpanel;
-      g.row_scale = row_scale;
+      g.ss_in = ss_in;
+      g.ss_tiles = ss_tiles;
+      g.eps = c.rms_eps;
       g.n_total = n_total;
       g.k = k;
       g.rows = rows;
@@ -564,18 +573,18 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
       g.counters = counters;
       return g;
     };
-    auto resid = [&](GemmArgs &g, const void *next_norm) {
-      g.x_resid = x; g.xw_out = h; g.out_panel = pan_h; g.next_norm_w = next_norm;
-      g.ss_part = (float *)(ws + L.ss_part); g.rstd_out = rstd; g.eps = c.rms_eps;
+    auto resid = [&](GemmArgs &g, const void *next_norm, float *ss_out) {
+      g.x_resid = x; g.xw_out = h; g.out_panel = pan_h; g.next_norm_w = next_norm; g.ss_part = ss_out;
     };
     for (int l = 0; l < c.n_layers; ++l) {
       char *kl = (char *)kv->k + (size_t)l * kv_layer, *vl = (char *)kv->v + (size_t)l * kv_layer;
       {
-        GemmArgs g = base(EPI_QKV, h, pan_h, rstd, c.hidden, nqkv, tiles_of(nqkv));
+        GemmArgs g = base(EPI_QKV, h, pan_h, ss0, ss0_tiles, c.hidden, nqkv, tiles_of(nqkv));
         g.seg[0] = {m->p_wq[l], qd, 0};
         g.seg[1] = {m->p_wk[l], kvd, qd};
         g.seg[2] = {m->p_wv[l], kvd, qd + kvd};
         g.n_seg = 3;
+        g.q_out = ws + L.q; g.q_panel = pan_q;
         g.cos_t = cos_t; g.sin_t = sin_t; g.qkv_f32 = qkv_f32; g.k_cache = kl; g.v_cache = vl; g.ctx = ctx;
         g.n_nodes = n_nodes; g.n_q_heads = c.n_q_heads; g.n_kv_heads = c.n_kv_heads; g.head_dim = c.head_dim;
         g.capacity = kv->capacity;
@@ -584,15 +593,15 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
       }
       attention(kl, vl);
       {
-        GemmArgs g = base(EPI_RESID, attn_out, pan_q, nullptr, qd, c.hidden, tiles_of(c.hidden));
+        GemmArgs g = base(EPI_RESID, attn_out, pan_q, nullptr, 0, qd, c.hidden, h_tiles);
         g.seg[0] = {m->p_wo[l], c.hidden, 0};
         g.n_seg = 1;
-        resid(g, m->norm_ffn[l]);
+        resid(g, m->norm_ffn[l], ss1);
         TimedLaunch tl(opts->timer, TRISPEC_K_GEMM, st, (double)c.hidden * qd * es);
         launch_gemm_bf16(st, g);
       }
       {
-        GemmArgs g = base(EPI_SWIGLU, h, pan_h, rstd, c.hidden, 2 * c.ffn, (c.ffn + 63) / 64);
+        GemmArgs g = base(EPI_SWIGLU, h, pan_h, ss1, h_tiles, c.hidden, 2 * c.ffn, (c.ffn + 63) / 64);
         g.seg[0] = {m->p_gate[l], c.ffn, 0};
         g.seg[1] = {m->p_up[l], c.ffn, c.ffn};
         g.n_seg = 2;
@@ -601,16 +610,17 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
         launch_gemm_bf16(st, g);
       }
       {
-        GemmArgs g = base(EPI_RESID, act, pan_f, nullptr, c.ffn, c.hidden, tiles_of(c.hidden));
+        GemmArgs g = base(EPI_RESID, act, pan_f, nullptr, 0, c.ffn, c.hidden, h_tiles);
         g.seg[0] = {m->p_down[l], c.hidden, 0};
         g.n_seg = 1;
-        resid(g, (l + 1 < c.n_layers) ? m->norm_attn[l + 1] : m->final_norm);
+        resid(g, (l + 1 < c.n_layers) ? m->norm_attn[l + 1] : m->final_norm, ss0);
+        ss0_tiles = h_tiles;
         TimedLaunch tl(opts->timer, TRISPEC_K_GEMM, st, (double)c.hidden * c.ffn * es);
         launch_gemm_bf16(st, g);
       }
     }
     {
-      GemmArgs g = base(EPI_HEAD, h, pan_h, rstd, c.hidden, c.vocab, tiles_of(c.vocab));
+      GemmArgs g = base(EPI_HEAD, h, pan_h, ss0, ss0_tiles, c.hidden, c.vocab, tiles_of(c.vocab));
       g.seg[0] = {m->p_lm_head, c.vocab, 0};
       g.n_seg = 1;
       g.n_splits = 1;

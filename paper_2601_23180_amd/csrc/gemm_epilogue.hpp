@@ -1,0 +1,201 @@
+// Epilogue of the weight-streaming matmul kernels (see kernels_gemm.hip): shared by the
+// 4-wavefront / 128-column and the 8-wavefront / 256-column variants.
+#pragma once
+
+#include "device_util.hpp"
+
+namespace ts {
+
+// acc[mb][e] of lane (ln, g) of wavefront `wave` holds y[mb*32 + 8*(e/4) + 4*g + e%4][wave*32 + ln]
+// of this workgroup's (tile, split).  lds: at least MB*32*(TN+4)*4 bytes, free for reuse (every
+// wavefront has passed a barrier after its last operand read).  s_rs: 1/rms per input row.
+template <int MB, int EPI, int NW>
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, f32x16 (&acc)[MB], unsigned char *lds,
+                                              int *s_last, const float *s_rs, int tile, int split) {
+  constexpr int TN = NW * 32, NT = NW * 64;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int ln = lane & 31, g = lane >> 5;
+  if (EPI == EPI_HEAD) {
+    // ---- per row, reduce this tile's 128 logits to (l1, column, l2, sum exp)
+    float *tl = (float *)lds;
+    constexpr int PARTS = TN / 16;   // threads scanning one row, 16 columns each
+    const int srow = tid / PARTS, part = tid % PARTS;
+    // (row_scale is applied when the tile is read back: the scan thread owns one row)
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      __syncthreads();
+#pragma unroll
+      for (int e = 0; e < 16; ++e)
+        tl[(8 * (e >> 2) + 4 * g + (e & 3)) * (TN + 4) + wave * 32 + ln] = acc[mb][e];
+      __syncthreads();
+      const int r = mb * 32 + srow;
+      const float rsc = (a.ss_in != nullptr && r < a.rows) ? s_rs[r] : 1.0f;
+      Top2 t = top2_empty();
+      const int cbase = tile * TN + part * 16;
+#pragma unroll
+      for (int c = 0; c < 16; ++c) {
+        const float v = tl[srow * (TN + 4) + part * 16 + c] * rsc;
+        if (cbase + c < a.n_total) {
+          top2_push(t, v, cbase + c);
+          if (a.debug_logits != nullptr && r < a.rows) a.debug_logits[(size_t)r * a.n_total + cbase + c] = v;
+        }
+      }
+#pragma unroll
+      for (int o = 1; o < PARTS; o <<= 1) t = top2_merge(t, top2_shfl_xor(t, o));
+      if (part == 0 && r < a.rows) {
+        const size_t o = (size_t)r * a.hs.n_tiles + tile;
+        a.hs.l1[o] = t.l1; a.hs.l2[o] = t.l2; a.hs.sumexp[o] = t.s; a.hs.idx[o] = t.idx;
+      }
+    }
+    return;
+  }
+
+  // ---- hand the tile to the epilogue.  One split: through LDS, no global round trip.  Several
+  // splits: write-through partial tiles part[split][tile][row][128] + a counter per tile; only
+  // the last workgroup to arrive goes on.
+  constexpr int EPI_LD = TN + 4;       // floats per row of the LDS tile
+  float *tl = (float *)lds;
+  const bool single = a.n_splits == 1;
+  const size_t tile_elems = (size_t)a.rows_pad * TN;
+  __syncthreads();   // every wavefront is done reading the last X stage
+  if (single) {
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e)
+        tl[(mb * 32 + 8 * (e >> 2) + 4 * g + (e & 3)) * EPI_LD + wave * 32 + ln] = acc[mb][e];
+    __syncthreads();
+  } else {
+    float *o = a.part + ((size_t)split * a.n_tiles + tile) * tile_elems + wave * 32 + ln;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int r = mb * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
+        if (r < a.rows) st_agent(o + (size_t)r * TN, acc[mb][e]);
+      }
+    if (!publish_then_count(&a.counters[tile], a.n_splits, s_last)) return;
+  }
+  // The partial tiles were written through to memory (st_agent) and nobody on this chip has read
+  // these lines before, so plain vector loads see them.
+  const float *p0 = a.part + (size_t)tile * tile_elems;
+  const size_t split_stride = (size_t)a.n_tiles * tile_elems;
+  auto reduced4 = [&](int r, int c) {   // 4 consecutive columns, splits summed in ascending order
+    if (single) return *(const f32x4 *)(tl + r * EPI_LD + c);
+    const float *p = p0 + (size_t)r * TN + c;
+    f32x4 v = *(const f32x4 *)p;
+    for (int s = 1; s < a.n_splits; ++s) v += *(const f32x4 *)(p + (size_t)s * split_stride);
+    return v;
+  };
+  if (EPI == EPI_QKV) {
+    // a tile is one head (d = 128) or two heads (d = 64); thread = (row, 4 rotation pairs)
+    const int d = a.head_dim, half = d >> 1;
+    const int n_q = a.n_q_heads, n_kv = a.n_kv_heads;
+    const int quads = TN / 8;                               // 4-pair groups per row
+    for (int t = tid; t < a.rows * quads; t += NT) {
+      const int r = t / quads, qi = t - r * quads;
+      const int hl = (qi * 4) / half, j = qi * 4 - hl * half;   // head within the tile, first pair
+      const int c_lo = hl * d + j;                          // tile-local column of the low elements
+      const int col = tile * TN + c_lo;             // global column
+      if (col >= a.n_total) continue;
+      const int hh = col / d;                               // global head index (q heads, k heads, v heads)
+      const float rsc = s_rs[r];
+      f32x4 lo = reduced4(r, c_lo) * rsc, hi = reduced4(r, c_lo + half) * rsc;
+      const int b = r / a.n_nodes, node = r - b * a.n_nodes;
+      const int slot = a.ctx.v[b] + node;
+      if (hh < n_q + n_kv) {
+        const f32x4 c = *(const f32x4 *)(a.cos_t + r * half + j), sn = *(const f32x4 *)(a.sin_t + r * half + j);
+        const f32x4 rl = lo * c - hi * sn, rh = hi * c + lo * sn;
+        lo = rl; hi = rh;
+      }
+      *(f32x4 *)(a.qkv_f32 + (size_t)r * a.n_total + col) = lo;
+      *(f32x4 *)(a.qkv_f32 + (size_t)r * a.n_total + col + half) = hi;
+      if (hh < n_q) {   // matrix-core operand of the context attention: bf16 hi + lo
+        bf16x4 lh, ll, hh4, hl4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          lh[e] = (bf16)lo[e]; ll[e] = (bf16)(lo[e] - (float)lh[e]);
+          hh4[e] = (bf16)hi[e]; hl4[e] = (bf16)(hi[e] - (float)hh4[e]);
+        }
+        bf16 *qo = (bf16 *)a.q_out + (size_t)r * n_q * d + col;
+        *(bf16x4 *)qo = lh;
+        *(bf16x4 *)(qo + a.q_panel) = ll;
+        *(bf16x4 *)(qo + half) = hh4;
+        *(bf16x4 *)(qo + half + a.q_panel) = hl4;
+      }
+      if (hh >= n_q && hh < n_q + n_kv) {
+        bf16 *kc = (bf16 *)a.k_cache + (((size_t)b * n_kv + (hh - n_q)) * a.capacity + slot) * d;
+        bf16x4 l4, h4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { l4[e] = (bf16)lo[e]; h4[e] = (bf16)hi[e]; }
+        *(bf16x4 *)(kc + j) = l4;
+        *(bf16x4 *)(kc + j + half) = h4;
+      } else if (hh >= n_q + n_kv) {
+        bf16 *vc = (bf16 *)a.v_cache + ((size_t)b * n_kv + (hh - n_q - n_kv)) * d * a.capacity;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          vc[(size_t)(j + e) * a.capacity + slot] = (bf16)lo[e];
+          vc[(size_t)(j + e + half) * a.capacity + slot] = (bf16)hi[e];
+        }
+      }
+    }
+    return;
+  }
+
+  if (EPI == EPI_SWIGLU) {
+    // columns [0, TN/2) of the tile are gate, [TN/2, TN) the matching up columns
+    constexpr int FQ = TN / 8;   // float4 groups of features per row (TN/2 gate + TN/2 up columns)
+    for (int t = tid; t < a.rows * FQ; t += NT) {
+      const int r = t / FQ, f = (t % FQ) * 4;
+      const int feat = tile * (TN / 2) + f;
+      if (feat >= a.ffn) continue;
+      const float rsc = s_rs[r];
+      const f32x4 gt = reduced4(r, f) * rsc, up = reduced4(r, TN / 2 + f) * rsc;
+      bf16x4 hi, lo;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float o = gt[e] / (1.0f + expf(-gt[e])) * up[e];
+        hi[e] = (bf16)o;
+        lo[e] = (bf16)(o - (float)hi[e]);
+      }
+      bf16 *dst = (bf16 *)a.act_out + (size_t)r * a.ffn + feat;
+      *(bf16x4 *)dst = hi;
+      *(bf16x4 *)(dst + a.out_panel) = lo;
+    }
+    return;
+  }
+
+  // ---- EPI_RESID: x += y; per-row sum of squares of the new x over this tile's columns.
+  // TN/4 consecutive lanes (4 columns each) cover one row of the tile.
+  {
+    constexpr int LPR = TN / 4, RPP = NT / LPR;   // lanes per row, rows per pass
+    float *ssp = a.ss_part + (size_t)tile * a.rows_pad;
+    const int c = (tid % LPR) * 4, col = tile * TN + c;
+    for (int r = tid / LPR; r < a.rows_pad; r += RPP) {
+      float ss = 0.f;
+      if (r < a.rows && col < a.n_total) {
+        float *xp = a.x_resid + (size_t)r * a.n_total + col;
+        const f32x4 v = *(const f32x4 *)xp + reduced4(r, c);
+        *(f32x4 *)xp = v;
+        ss = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+        // operand of the next matmul: x * (next RMSNorm weight), as bf16 hi + lo
+        const bf16x4 nw = *(const bf16x4 *)((const bf16 *)a.next_norm_w + col);
+        bf16x4 hi, lo;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float o = v[e] * (float)nw[e];
+          hi[e] = (bf16)o;
+          lo[e] = (bf16)(o - (float)hi[e]);
+        }
+        bf16 *dst = (bf16 *)a.xw_out + (size_t)r * a.n_total + col;
+        *(bf16x4 *)dst = hi;
+        *(bf16x4 *)(dst + a.out_panel) = lo;
+      }
+#pragma unroll
+      for (int o = LPR / 2; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+      if (tid % LPR == 0 && r < a.rows) ssp[r] = ss;   // read by the next kernel
+    }
+  }
+}
+
+}  // namespace ts

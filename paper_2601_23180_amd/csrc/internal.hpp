@@ -51,11 +51,13 @@ struct GemmSeg {
 enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_HEAD = 3 };
 struct GemmArgs {
   // fp32 reference-precision path: x is [rows_pad, K] fp32, out is [rows][n_total].
-  // bf16 path: x is the bf16 hi panel [rows_pad, K], the lo panel follows x_panel elements later;
-  // row_scale (1/rms per row, or nullptr) multiplies the reduced sums in the epilogue.
+  // bf16 path: x is the bf16 hi panel [rows_pad, K], the lo panel follows x_panel elements later.
+  // ss_in (or nullptr): [ss_tiles][rows_pad] sums of squares of the rows of the un-normalised
+  // input; the epilogue multiplies the reduced sums by 1/sqrt(sum/K + eps).
   const void *x;
   size_t x_panel;
-  const float *row_scale;
+  const float *ss_in;
+  int32_t ss_tiles;
   GemmSeg seg[3];
   int32_t n_seg;
   int32_t n_total;     // total output columns (SWIGLU: 2 * ffn)
@@ -72,6 +74,8 @@ struct GemmArgs {
   // QKV epilogue
   const float *cos_t, *sin_t;
   float *qkv_f32;      // [rows][n_total] rotated q, k and v in fp32
+  void *q_out;         // bf16 hi/lo panels [rows_pad][nq*d] of the rotated queries
+  size_t q_panel;
   void *k_cache, *v_cache;
   CtxLens ctx;
   int32_t n_nodes, n_q_heads, n_kv_heads, head_dim, capacity;
@@ -79,8 +83,7 @@ struct GemmArgs {
   float *x_resid;      // [rows_pad][n_total] residual stream, updated in place
   void *xw_out;        // bf16 hi/lo panels [rows_pad][n_total]: x * next norm weight
   const void *next_norm_w;  // bf16 [n_total]
-  float *ss_part;      // [n_tiles][rows_pad]
-  float *rstd_out;     // [rows_pad]
+  float *ss_part;      // [n_tiles][rows_pad] sums of squares of the updated rows, per tile
   float eps;
   size_t out_panel;    // panel stride (elements) of xw_out / act_out
   // SWIGLU epilogue
@@ -92,7 +95,9 @@ struct GemmArgs {
 };
 
 struct AttnArgs {
-  const void *q;        // fp32 path: [rows_pad, nq*d] fp32 queries (bf16 path reads them from qkv)
+  const void *q;        // fp32 path: [rows_pad, nq*d] fp32 queries; bf16 path: bf16 hi panel, lo q_panel later
+  size_t q_panel;
+  int32_t n_row_groups; // ceil(group * n_nodes / 128): query rows per workgroup = 128
   const void *k_cache;  // this layer: [B][nkv][cap][d]
   const void *v_cache;  // this layer: [B][nkv][d][cap]
   const uint64_t *anc;  // [B*M]
@@ -128,7 +133,7 @@ void launch_rope_table(hipStream_t st, const int32_t *positions, int rows, int h
                        float *cos_t, float *sin_t);
 void launch_embed_norm(hipStream_t st, int dtype, const int32_t *tokens, const void *embed,
                        const void *norm_w, int rows, int hidden, int vocab, float eps, float *x,
-                       void *h, size_t h_panel, float *rstd_out, int32_t *status);
+                       void *h, size_t h_panel, float *ss_out, int32_t *status);
 void launch_zero_counters(hipStream_t st, int32_t *counters, int n_counters);
 void launch_qkv_epilogue(hipStream_t st, int dtype, const float *part, int n_splits, int rows,
                          int rows_pad, int n_q_heads, int n_kv_heads, int head_dim,

@@ -93,7 +93,8 @@ template <int D, int RBW>
 __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
   using L = AttnLds<D>;
   __shared__ __attribute__((aligned(16))) unsigned char lds[2 * L::kBuf];
-  const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  const int split = blockIdx.x, kvh = blockIdx.y;
+  const int b = blockIdx.z / a.n_row_groups, rg = blockIdx.z - b * a.n_row_groups;   // sequence, group of 128 query rows
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ln = lane & 31, g = lane >> 5;
   const int M = a.n_nodes, group = a.n_q_heads / a.n_kv_heads;
@@ -109,7 +110,7 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
   bf16x8 qf[RBW][D / 16], ql[RBW][D / 16];
 #pragma unroll
   for (int i = 0; i < RBW; ++i) {
-    const int rb = wave + 4 * i;
+    const int rb = rg * 4 * RBW + wave + 4 * i;
     const int p = rb * 32 + ln;
     prow[i] = p;
 #pragma unroll
@@ -119,21 +120,12 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
     if (p < p_rows) {
       const int al = p / M, node = p - al * M;
       const int r = b * M + node;
-      // fp32 query (already rotated) -> bf16 high part + bf16 low part
-      const int n_total = (a.n_q_heads + 2 * a.n_kv_heads) * D;
-      const float *q = a.qkv + (size_t)r * n_total + (size_t)(kvh * group + al) * D;
+      // rotated query as bf16 high part + bf16 low part (written by the QKV epilogue)
+      const bf16 *q = (const bf16 *)a.q + (size_t)r * a.n_q_heads * D + (size_t)(kvh * group + al) * D;
 #pragma unroll
       for (int t = 0; t < D / 16; ++t) {
-        const f32x4 q0 = *(const f32x4 *)(q + 16 * t + 8 * g);
-        const f32x4 q1 = *(const f32x4 *)(q + 16 * t + 8 * g + 4);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const bf16 h0 = (bf16)q0[e], h1 = (bf16)q1[e];
-          qf[i][t][e] = h0;
-          qf[i][t][4 + e] = h1;
-          ql[i][t][e] = (bf16)(q0[e] - (float)h0);
-          ql[i][t][4 + e] = (bf16)(q1[e] - (float)h1);
-        }
+        qf[i][t] = *(const bf16x8 *)(q + 16 * t + 8 * g);
+        ql[i][t] = *(const bf16x8 *)(q + a.q_panel + 16 * t + 8 * g);
       }
     }
   }
@@ -225,7 +217,7 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
 
 #pragma unroll
     for (int i = 0; i < RBW; ++i) {
-      if ((wave + 4 * i) * 32 >= p_rows) continue;   // wave-uniform
+      if ((rg * 4 * RBW + wave + 4 * i) * 32 >= p_rows) continue;   // wave-uniform
       // S^T[key][row] for the two 32-key sub-tiles
       f32x16 s[KT / 32];
 #pragma unroll
@@ -254,7 +246,7 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
       tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
       const float m_new = fmaxf(m_run[i], tmax);
       const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = expf(m_run[i] - m_safe);   // exp(-inf) = 0 on the first tile
+      const float alpha = __expf(m_run[i] - m_safe);   // exp(-inf) = 0 on the first tile
       m_run[i] = m_new;
       float psum = 0.f;
       bf16x8 phi[KT / 16], plo[KT / 16];
@@ -262,7 +254,7 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
       for (int ks = 0; ks < KT / 32; ++ks)
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          const float p = expf(s[ks][e] - m_safe);   // exp(-inf) = 0 for masked keys
+          const float p = __expf(s[ks][e] - m_safe);   // exp(-inf) = 0 for masked keys
           psum += p;
           const bf16 hi = (bf16)p;
           const bf16 lo = (bf16)(p - (float)hi);
@@ -349,14 +341,34 @@ __global__ __launch_bounds__(D) void k_attn_merge(AttnArgs a) {
     m_tot = fmaxf(m_tot, v);
   }
   __syncthreads();
-  for (int s = 0; s < a.n_splits; ++s) m_tot = fmaxf(m_tot, a.part_m[(base + s) * p_rows + p]);
+  // context splits, 16 at a time so that the loads of a group are independent and in flight
+  // together; combined in ascending split order
+  for (int s0 = 0; s0 < a.n_splits; s0 += 16) {
+    float pm[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+      pm[i] = (s0 + i < a.n_splits) ? a.part_m[(base + s0 + i) * p_rows + p] : -INFINITY;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) m_tot = fmaxf(m_tot, pm[i]);
+  }
   float num = 0.f, den = 0.f;
-  for (int s = 0; s < a.n_splits; ++s) {
-    const float ms = a.part_m[(base + s) * p_rows + p];
-    if (ms == -INFINITY) continue;
-    const float w = expf(ms - m_tot);
-    num += a.part_o[((base + s) * p_rows + p) * D + f] * w;
-    den += a.part_l[(base + s) * p_rows + p] * w;
+  for (int s0 = 0; s0 < a.n_splits; s0 += 16) {
+    float pm[16], pl[16], po[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const bool ok = s0 + i < a.n_splits;
+      const size_t idx = (base + (ok ? s0 + i : 0)) * p_rows + p;
+      pm[i] = ok ? a.part_m[idx] : -INFINITY;
+      pl[i] = a.part_l[idx];
+      po[i] = a.part_o[idx * D + f];
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      if (pm[i] == -INFINITY) continue;   // empty split: its o / l were never written
+      const float w = expf(pm[i] - m_tot);
+      num += po[i] * w;
+      den += pl[i] * w;
+    }
   }
   for (int j = 0; j <= node; ++j) {
     if (!((mask >> j) & 1ull)) continue;
@@ -373,14 +385,8 @@ __global__ __launch_bounds__(D) void k_attn_merge(AttnArgs a) {
 
 template <int D>
 static void launch_attn_bf16_d(hipStream_t st, const AttnArgs &a) {
-  const int group = a.n_q_heads / a.n_kv_heads;
-  const int p_rows = group * a.n_nodes;
-  const int nrb = (p_rows + 31) / 32;
-  dim3 grid(a.n_splits, a.n_kv_heads, a.batch);
-  if (nrb <= 4)
-    hipLaunchKernelGGL((k_attn_bf16<D, 1>), grid, dim3(256), 0, st, a);
-  else
-    hipLaunchKernelGGL((k_attn_bf16<D, 2>), grid, dim3(256), 0, st, a);
+  dim3 grid(a.n_splits, a.n_kv_heads, a.batch * a.n_row_groups);
+  hipLaunchKernelGGL((k_attn_bf16<D, 1>), grid, dim3(256), 0, st, a);
   hipLaunchKernelGGL(k_attn_merge<D>, dim3(a.batch * a.n_nodes, a.n_q_heads), dim3(D), 0, st, a);
 }
 

@@ -1,7 +1,7 @@
 // Weight-streaming small-M matmul on the matrix cores (bf16 weights, fp32 accumulate) with the
 // surrounding element-wise work fused in.
 //
-//   y[r][n] = row_scale[r] * sum_k X[r][k] * W[n][k]        r < rows_pad <= 256
+//   y[r][n] = rstd[r] * sum_k X[r][k] * W[n][k]        r < rows_pad <= 256
 //
 // At these row counts the product is bound by streaming W from HBM once, so the layout serves
 // the W stream.  W is read from the PACKED copy made once by k_pack_weights: for every 32-row
@@ -21,7 +21,7 @@
 // staged through LDS in chunks of KC reduction elements, double buffered, rows padded by 16
 // bytes so that the 16-byte operand reads are conflict free.
 // RMSNorm is fused around the matmul: the producer stores x * w_norm (the per-column weight) as
-// the operand panels, and the per-row 1/rms (row_scale) multiplies the reduced sums here.
+// the operand panels, and the per-row 1/rms multiplies the reduced sums in the epilogue here.
 //
 // MFMA 32x32x16: A = X fragment (row = activation row), B = W fragment (column = output
 // column), so accumulator register e of lane (ln, g) holds y[8*(e/4) + 4*g + e%4][ln].  The k
@@ -33,16 +33,19 @@
 // order — so the result does not depend on scheduling — and applies the tile's epilogue:
 //   QKV    rotary embedding, fp32 q/k/v for the attention kernels, bf16 K and V^T cache append
 //   RESID  residual add into the fp32 stream, operand panels (x * next norm weight, hi/lo) for
-//          the next matmul, per-row sum of squares; the last TILE turns the sums into 1/rms
+//          the next matmul, per-row sum of squares of the tile (the consumer turns the tile sums
+//          into 1/rms — a second chip-wide counter here costs more than re-adding 32 numbers)
 //   SWIGLU SiLU(gate) * up as operand panels (a tile holds 64 gate columns and the matching 64
 //          up columns)
 //   HEAD   (LM head, no k split) per-row (largest logit, its column, second largest, sum of exp)
 //          of the tile's 128 logits — the probabilities are never materialised.
-#include "device_util.hpp"
+#include <stdlib.h>
+
+#include "gemm_epilogue.hpp"
 
 namespace ts {
 
-template <int MB, int KC, int EPI, bool RAGGED>
+template <int MB, int KC, int EPI, bool RAGGED, int DEPTH>
 __global__ __launch_bounds__(256) void k_gemm_bf16(GemmArgs a) {
   constexpr int KB = KC / 64;                 // 64-deep k blocks per chunk
   constexpr int STRIDE = KC * 2 + 16;         // LDS bytes per activation row (one panel)
@@ -50,10 +53,9 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(GemmArgs a) {
   constexpr int BUF = 2 * PANEL;
   constexpr int XV = MB * 32 * (KC / 8) / 256;  // 16-byte vectors per thread per chunk, per panel
   constexpr int ROWS_PER_PASS = 256 / (KC / 8); // rows covered by one vector index step
-  constexpr int TILE_LD = 132;                // floats per row of the HEAD logits tile
-  static_assert(2 * BUF >= 32 * TILE_LD * 4, "logits tile must fit the staging LDS");
   __shared__ __attribute__((aligned(16))) unsigned char lds[2 * BUF];
   __shared__ int s_last;
+  __shared__ float s_rs[kMaxRows];   // 1/rms of the rows of the matmul's input
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ln = lane & 31, g = lane >> 5;
@@ -88,6 +90,16 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(GemmArgs a) {
   const int c8 = tid % (KC / 8), r0 = tid / (KC / 8);
   const bf16 *xg = (const bf16 *)a.x + (size_t)r0 * a.k + k_begin + c8 * 8;
 
+  // 1/rms of every row of the matmul's INPUT, from the per-tile sums of squares its producer left
+  // (ascending tile order); used by the epilogue, loaded here so that it overlaps the stream.
+  if (a.ss_in != nullptr) {
+    for (int r = tid; r < a.rows; r += 256) {
+      float ss = 0.f;
+      for (int t = 0; t < a.ss_tiles; ++t) ss += a.ss_in[(size_t)t * a.rows_pad + r];
+      s_rs[r] = 1.0f / sqrtf(ss / (float)a.k + a.eps);
+    }
+  }
+
   f32x16 acc[MB];
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb)
@@ -98,15 +110,17 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(GemmArgs a) {
   // wait-count analysis assume it may not have been issued, which turns every wait into "drain
   // everything" and serialises the stream.
   //
-  // Fast variant (every k split is a whole, even number of KC chunks), per chunk c:
+  // Fast variant (every k split is a whole multiple of DEPTH chunks of KC), per chunk c:
   //   1. X registers (chunk c+1, fetched during chunk c-1) -> LDS stage (c+1)&1
   //   2. issue the X loads of chunk c+2
-  //   3. per 64-deep block: 4 x MB x 2 MFMAs on W set c&1, then refill that block of the set
-  //      with chunk c+2 — so a W load has two chunks of compute to arrive
+  //   3. per 64-deep block: 4 x MB x 2 MFMAs on W set c % DEPTH, then refill that block of the
+  //      set with chunk c+DEPTH — a W load has DEPTH chunks of compute to arrive, and a wavefront
+  //      keeps about DEPTH * KC/64 * 4 KB in flight.  (HBM latency under load is several
+  //      microseconds; at 8 wavefronts per CU it takes this much to keep the stream full.)
   //   4. workgroup barrier
   // sched_barrier pins the load issue points; the compiler would otherwise sink every load to
   // just before its first use and expose the whole memory latency once per chunk.
-  bf16x8 w[2][KB][4];
+  bf16x8 w[DEPTH][KB][4];
   uint4 xr[2][XV];
 
   auto load_w_block = [&](int set, int c, int kb) {
@@ -183,9 +197,9 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(GemmArgs a) {
     }
     compute_chunk(0, (n_chunks - 1) & 1, 0, false);
   } else {
-    // n_chunks is even and >= 2.  The prologue issues its loads in the order the steady state
-    // does (X of a chunk before the W refill of the same step), so the wait counts merged at the
-    // loop head are the steady-state ones.
+    // n_chunks is a multiple of DEPTH (DEPTH even).  The prologue issues its loads in the order
+    // the steady state does (X of a chunk before the W refill of the same step), so the wait
+    // counts merged at the loop head are the steady-state ones.
     load_x(0);
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb) load_w_block(0, 0, kb);
@@ -194,191 +208,35 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(GemmArgs a) {
     load_x(1);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int kb = 0; kb < KB; ++kb) load_w_block(1, 1, kb);
+    for (int d = 1; d < DEPTH; ++d)
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb) load_w_block(d, d, kb);
     __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
-    // chunk pair (c, c+1) with c even: set 0 serves chunk c, set 1 serves chunk c+1
-    for (int c = 0; c + 2 < n_chunks; c += 2) {
-      store_x(1);            // chunk c+1
-      load_x(c + 2);
+    int c0 = 0;
+    for (; c0 + DEPTH < n_chunks; c0 += DEPTH) {
+#pragma unroll
+      for (int d = 0; d < DEPTH; ++d) {
+        store_x((d + 1) & 1);                       // chunk c0+d+1
+        load_x(min(c0 + d + 2, n_chunks - 1));      // clamped, never a branch
+        __builtin_amdgcn_sched_barrier(0);
+        compute_chunk(d, d & 1, c0 + d + DEPTH, true);
+        __syncthreads();
+      }
+    }
+    // last DEPTH chunks: nothing left to fetch from W
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) {
+      if (d + 1 < DEPTH) store_x((d + 1) & 1);
+      if (d + 2 < DEPTH) load_x(c0 + d + 2);
       __builtin_amdgcn_sched_barrier(0);
-      compute_chunk(0, 0, c + 2, true);
-      __syncthreads();
-      store_x(0);            // chunk c+2
-      load_x(c + 3);
-      __builtin_amdgcn_sched_barrier(0);
-      compute_chunk(1, 1, c + 3, true);
-      __syncthreads();
+      compute_chunk(d, d & 1, 0, false);
+      if (d + 1 < DEPTH) __syncthreads();
     }
-    // last pair: nothing left to fetch
-    store_x(1);
-    __builtin_amdgcn_sched_barrier(0);
-    compute_chunk(0, 0, 0, false);
-    __syncthreads();
-    compute_chunk(1, 1, 0, false);
   }
 
-  if (EPI == EPI_HEAD) {
-    // ---- per row, reduce this tile's 128 logits to (l1, column, l2, sum exp)
-    float *tl = (float *)lds;
-    const int srow = tid >> 3, part = tid & 7;
-    // (row_scale is applied when the tile is read back: the scan thread owns one row)
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
-      __syncthreads();
-#pragma unroll
-      for (int e = 0; e < 16; ++e)
-        tl[(8 * (e >> 2) + 4 * g + (e & 3)) * TILE_LD + wave * 32 + ln] = acc[mb][e];
-      __syncthreads();
-      const int r = mb * 32 + srow;
-      const float rsc = (a.row_scale != nullptr && r < a.rows) ? a.row_scale[r] : 1.0f;
-      Top2 t = top2_empty();
-      const int cbase = tile * kGemmTileN + part * 16;
-#pragma unroll
-      for (int c = 0; c < 16; ++c) {
-        const float v = tl[srow * TILE_LD + part * 16 + c] * rsc;
-        if (cbase + c < a.n_total) {
-          top2_push(t, v, cbase + c);
-          if (a.debug_logits != nullptr && r < a.rows) a.debug_logits[(size_t)r * a.n_total + cbase + c] = v;
-        }
-      }
-      t = top2_merge(t, top2_shfl_xor(t, 1));
-      t = top2_merge(t, top2_shfl_xor(t, 2));
-      t = top2_merge(t, top2_shfl_xor(t, 4));
-      if (part == 0 && r < a.rows) {
-        const size_t o = (size_t)r * a.hs.n_tiles + tile;
-        a.hs.l1[o] = t.l1; a.hs.l2[o] = t.l2; a.hs.sumexp[o] = t.s; a.hs.idx[o] = t.idx;
-      }
-    }
-    return;
-  }
-
-  // ---- store the partial tile: part[split][tile][row][128]
-  const size_t tile_elems = (size_t)a.rows_pad * kGemmTileN;
-  {
-    float *o = a.part + ((size_t)split * a.n_tiles + tile) * tile_elems + wave * 32 + ln;
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int r = mb * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
-        if (r < a.rows) st_agent(o + (size_t)r * kGemmTileN, acc[mb][e]);
-      }
-  }
-  // ---- the last workgroup of this tile reduces the splits and runs the epilogue
-  if (!publish_then_count(&a.counters[tile], a.n_splits, &s_last)) return;
-  // The partial tiles were written through to memory (st_agent) and nobody on this chip has read
-  // these lines before, so plain vector loads see them.
-  const float *p0 = a.part + (size_t)tile * tile_elems;
-  const size_t split_stride = (size_t)a.n_tiles * tile_elems;
-  auto reduced4 = [&](int r, int c) {   // 4 consecutive columns, splits summed in ascending order
-    const float *p = p0 + (size_t)r * kGemmTileN + c;
-    f32x4 v = *(const f32x4 *)p;
-    for (int s = 1; s < a.n_splits; ++s) v += *(const f32x4 *)(p + (size_t)s * split_stride);
-    return v;
-  };
-
-  if (EPI == EPI_QKV) {
-    // a tile is one head (d = 128) or two heads (d = 64); thread = (row, 4 rotation pairs)
-    const int d = a.head_dim, half = d >> 1;
-    const int n_q = a.n_q_heads, n_kv = a.n_kv_heads;
-    const int quads = kGemmTileN / 8;                       // 4-pair groups per row
-    for (int t = tid; t < a.rows * quads; t += 256) {
-      const int r = t / quads, qi = t - r * quads;
-      const int hl = (qi * 4) / half, j = qi * 4 - hl * half;   // head within the tile, first pair
-      const int c_lo = hl * d + j;                          // tile-local column of the low elements
-      const int col = tile * kGemmTileN + c_lo;             // global column
-      if (col >= a.n_total) continue;
-      const int hh = col / d;                               // global head index (q heads, k heads, v heads)
-      const float rsc = a.row_scale[r];
-      f32x4 lo = reduced4(r, c_lo) * rsc, hi = reduced4(r, c_lo + half) * rsc;
-      const int b = r / a.n_nodes, node = r - b * a.n_nodes;
-      const int slot = a.ctx.v[b] + node;
-      if (hh < n_q + n_kv) {
-        const f32x4 c = *(const f32x4 *)(a.cos_t + r * half + j), sn = *(const f32x4 *)(a.sin_t + r * half + j);
-        const f32x4 rl = lo * c - hi * sn, rh = hi * c + lo * sn;
-        lo = rl; hi = rh;
-      }
-      *(f32x4 *)(a.qkv_f32 + (size_t)r * a.n_total + col) = lo;
-      *(f32x4 *)(a.qkv_f32 + (size_t)r * a.n_total + col + half) = hi;
-      if (hh >= n_q && hh < n_q + n_kv) {
-        bf16 *kc = (bf16 *)a.k_cache + (((size_t)b * n_kv + (hh - n_q)) * a.capacity + slot) * d;
-        bf16x4 l4, h4;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) { l4[e] = (bf16)lo[e]; h4[e] = (bf16)hi[e]; }
-        *(bf16x4 *)(kc + j) = l4;
-        *(bf16x4 *)(kc + j + half) = h4;
-      } else if (hh >= n_q + n_kv) {
-        bf16 *vc = (bf16 *)a.v_cache + ((size_t)b * n_kv + (hh - n_q - n_kv)) * d * a.capacity;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          vc[(size_t)(j + e) * a.capacity + slot] = (bf16)lo[e];
-          vc[(size_t)(j + e + half) * a.capacity + slot] = (bf16)hi[e];
-        }
-      }
-    }
-    return;
-  }
-
-  if (EPI == EPI_SWIGLU) {
-    // columns [0, 64) of the tile are gate, [64, 128) the matching up columns
-    for (int t = tid; t < a.rows * 16; t += 256) {
-      const int r = t >> 4, f = (t & 15) * 4;
-      const int feat = tile * 64 + f;
-      if (feat >= a.ffn) continue;
-      const float rsc = a.row_scale[r];
-      const f32x4 gt = reduced4(r, f) * rsc, up = reduced4(r, 64 + f) * rsc;
-      bf16x4 hi, lo;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float o = gt[e] / (1.0f + expf(-gt[e])) * up[e];
-        hi[e] = (bf16)o;
-        lo[e] = (bf16)(o - (float)hi[e]);
-      }
-      bf16 *dst = (bf16 *)a.act_out + (size_t)r * a.ffn + feat;
-      *(bf16x4 *)dst = hi;
-      *(bf16x4 *)(dst + a.out_panel) = lo;
-    }
-    return;
-  }
-
-  // ---- EPI_RESID: x += y; per-row sum of squares of the new x over this tile's columns.
-  // A half wavefront (32 lanes x 4 columns) covers one row of the tile.
-  {
-    float *ssp = a.ss_part + (size_t)tile * a.rows_pad;
-    const int c = ln * 4, col = tile * kGemmTileN + c;
-    for (int r = wave * 2 + g; r < a.rows_pad; r += 8) {
-      float ss = 0.f;
-      if (r < a.rows && col < a.n_total) {
-        float *xp = a.x_resid + (size_t)r * a.n_total + col;
-        const f32x4 v = *(const f32x4 *)xp + reduced4(r, c);
-        *(f32x4 *)xp = v;
-        ss = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
-        // operand of the next matmul: x * (next RMSNorm weight), as bf16 hi + lo
-        const bf16x4 nw = *(const bf16x4 *)((const bf16 *)a.next_norm_w + col);
-        bf16x4 hi, lo;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float o = v[e] * (float)nw[e];
-          hi[e] = (bf16)o;
-          lo[e] = (bf16)(o - (float)hi[e]);
-        }
-        bf16 *dst = (bf16 *)a.xw_out + (size_t)r * a.n_total + col;
-        *(bf16x4 *)dst = hi;
-        *(bf16x4 *)(dst + a.out_panel) = lo;
-      }
-#pragma unroll
-      for (int o = 16; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
-      if (ln == 0 && r < a.rows) st_agent(ssp + r, ss);
-    }
-    if (!publish_then_count(&a.counters[a.n_tiles], a.n_tiles, &s_last)) return;
-    // last tile of the launch: 1/rms of every row for the next matmul's prologue
-    for (int r = tid; r < a.rows; r += 256) {
-      float ss = 0.f;
-      for (int t = 0; t < a.n_tiles; ++t) ss += ld_agent(a.ss_part + (size_t)t * a.rows_pad + r);
-      a.rstd_out[r] = 1.0f / sqrtf(ss / (float)a.n_total + a.eps);
-    }
-  }
+  __syncthreads();   // every wavefront is done reading the last X stage
+  gemm_epilogue<MB, EPI, 4>(a, acc, lds, &s_last, s_rs, tile, split);
 }
 
 // One-time repack of a row-major [n_rows, k] bf16 matrix into the layout above.  One thread per
@@ -410,12 +268,15 @@ void launch_pack_weights(hipStream_t st, const void *w, int n_rows, int k, void 
 template <int EPI>
 static void dispatch(hipStream_t st, const GemmArgs &a) {
   dim3 grid(a.n_tiles, a.n_splits), block(256);
+  static const bool depth4 = !(getenv("TRISPEC_DEPTH2"));
 #define TS_LAUNCH(MB_, KC_)                                                                   \
   do {                                                                                        \
-    if (a.k_per_split % (2 * KC_) == 0 && a.k % (2 * KC_) == 0)                               \
-      hipLaunchKernelGGL((k_gemm_bf16<MB_, KC_, EPI, false>), grid, block, 0, st, a);         \
+    if (a.k_per_split % (4 * KC_) == 0 && a.k % (4 * KC_) == 0 && depth4)                     \
+      hipLaunchKernelGGL((k_gemm_bf16<MB_, KC_, EPI, false, 4>), grid, block, 0, st, a);      \
+    else if (a.k_per_split % (2 * KC_) == 0 && a.k % (2 * KC_) == 0)                          \
+      hipLaunchKernelGGL((k_gemm_bf16<MB_, KC_, EPI, false, 2>), grid, block, 0, st, a);      \
     else                                                                                      \
-      hipLaunchKernelGGL((k_gemm_bf16<MB_, KC_, EPI, true>), grid, block, 0, st, a);          \
+      hipLaunchKernelGGL((k_gemm_bf16<MB_, KC_, EPI, true, 1>), grid, block, 0, st, a);       \
   } while (0)
   switch (a.rows_pad) {
     case 32: TS_LAUNCH(1, 256); break;

@@ -42,11 +42,12 @@ void launch_rope_table(hipStream_t st, const int32_t *positions, int rows, int h
 
 // ------------------------------------------------------------------ embedding + first RMSNorm
 // x[r] = E[token_r] (fp32 residual stream).  fp32 models: h[r] = x * rstd * w.  bf16 models: the
-// first matmul's operand panels h = x * w as bf16 hi + lo, and rstd[r] for that matmul's epilogue.
+// first matmul's operand panels h = x * w as bf16 hi + lo, and the row's sum of squares (that
+// matmul's epilogue turns it into 1/rms).
 template <typename AT>
 __global__ __launch_bounds__(256) void k_embed_norm(const int32_t *tokens, const AT *embed,
                                                     const AT *norm_w, int hidden, int vocab, float eps,
-                                                    float *x, void *h, size_t h_panel, float *rstd_out,
+                                                    float *x, void *h, size_t h_panel, float *ss_out,
                                                     int32_t *status) {
   __shared__ float red[4];
   const int r = blockIdx.x;
@@ -65,8 +66,8 @@ __global__ __launch_bounds__(256) void k_embed_norm(const int32_t *tokens, const
   }
   ss = block_sum<4>(ss, red);
   const float rstd = 1.0f / sqrtf(ss / (float)hidden + eps);
-  if (rstd_out != nullptr) {
-    if (threadIdx.x == 0) rstd_out[r] = rstd;
+  if (ss_out != nullptr) {
+    if (threadIdx.x == 0) ss_out[r] = ss;
     bf16 *hp = (bf16 *)h + (size_t)r * hidden;
     for (int i = threadIdx.x; i < hidden; i += 256) {
       const float v = to_f32(e[i]) * to_f32(norm_w[i]);
@@ -82,13 +83,13 @@ __global__ __launch_bounds__(256) void k_embed_norm(const int32_t *tokens, const
 
 void launch_embed_norm(hipStream_t st, int dtype, const int32_t *tokens, const void *embed,
                        const void *norm_w, int rows, int hidden, int vocab, float eps, float *x,
-                       void *h, size_t h_panel, float *rstd_out, int32_t *status) {
+                       void *h, size_t h_panel, float *ss_out, int32_t *status) {
   if (dtype == TRISPEC_F32)
     hipLaunchKernelGGL(k_embed_norm<float>, dim3(rows), dim3(256), 0, st, tokens, (const float *)embed,
                        (const float *)norm_w, hidden, vocab, eps, x, h, h_panel, (float *)nullptr, status);
   else
     hipLaunchKernelGGL(k_embed_norm<bf16>, dim3(rows), dim3(256), 0, st, tokens, (const bf16 *)embed,
-                       (const bf16 *)norm_w, hidden, vocab, eps, x, h, h_panel, rstd_out, status);
+                       (const bf16 *)norm_w, hidden, vocab, eps, x, h, h_panel, ss_out, status);
 }
 
 __global__ void k_zero_counters(int32_t *counters, int n_counters) {
