@@ -73,22 +73,32 @@ struct Layout {
   int rows_max, rows_pad_max, head_tiles, max_tiles;
 };
 
-// k-splits of one bf16 matmul: enough workgroups (tiles x splits) to cover the chip about one and
-// a half times over, every split a whole number of 256-deep steps when the reduction allows it.
+// Decomposition of one bf16 matmul into (128-column tile, k split) workgroups: about kTargetWgs
+// workgroups in all (two fit on a CU), every k split a whole number of 256-deep steps (512 when
+// long enough) when the reduction allows it, and at least 512 deep.
 struct SplitPlan {
-  int n_tiles, n_splits, k_per_split;
+  int tile_n, n_tiles, n_splits, k_per_split;
 };
-SplitPlan plan_gemm(int n_tiles, int k) {
+constexpr int kTargetWgs = 192;
+SplitPlan plan_gemm(int epi, int n_cols, int k, int rows_pad) {
+  (void)rows_pad;
   SplitPlan p;
-  p.n_tiles = n_tiles;
-  const int unit = (k % 256 == 0) ? 256 : 64;
-  static const int target = getenv("TRISPEC_TARGET_WGS") ? atoi(getenv("TRISPEC_TARGET_WGS")) : 320;
-  int s = (target + n_tiles / 2) / n_tiles;
+  p.tile_n = kGemmTileN;
+  // SWIGLU: n_cols = 2 * ffn, a tile holds tile_n/2 gate columns and the matching up columns
+  p.n_tiles = (n_cols + p.tile_n - 1) / p.tile_n;
+  if (epi == EPI_HEAD) {
+    p.n_splits = 1;
+    p.k_per_split = (int)align_up(k, (k % 256 == 0) ? 256 : 64);
+    return p;
+  }
+  int s = (kTargetWgs + p.n_tiles / 2) / p.n_tiles;
   const int max_by_k = k / 512 > 0 ? k / 512 : 1;
   if (s > max_by_k) s = max_by_k;
   if (s > kMaxSplitK) s = kMaxSplitK;
   if (s < 1) s = 1;
-  p.k_per_split = (int)align_up((size_t)(k + s - 1) / s, unit);
+  const int per = (k + s - 1) / s;
+  const int unit = (k % 256 != 0) ? 64 : ((per >= 1024 && k % 512 == 0) ? 512 : 256);
+  p.k_per_split = (int)align_up((size_t)per, unit);
   p.n_splits = (k + p.k_per_split - 1) / p.k_per_split;
   return p;
 }
@@ -104,7 +114,7 @@ Layout make_layout(const trispec_model_config &c, int batch, int max_nodes) {
   const int nqkv = qd + 2 * kvd;
   L.rows_max = rows;
   L.rows_pad_max = rp;
-  L.head_tiles = f32 ? 1 : tiles_of(c.vocab);
+  L.head_tiles = f32 ? 1 : plan_gemm(EPI_HEAD, c.vocab, c.hidden, rp).n_tiles;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
   L.anc = take(sizeof(uint64_t) * kMaxRows);
@@ -126,20 +136,22 @@ Layout make_layout(const trispec_model_config &c, int batch, int max_nodes) {
     if (2 * c.ffn > m) m = 2 * c.ffn;
     L.part = take(sizeof(float) * (size_t)rp * m);
   } else {
-    // split-K partial tiles: the largest of splits x tiles over the four matmuls of a layer
-    const int tl[4] = {tiles_of(nqkv), tiles_of(c.hidden), (c.ffn + 63) / 64, tiles_of(c.hidden)};
+    // split-K partial tiles: the largest of splits x tiles x tile width over the matmuls of a layer
+    const int ep[4] = {EPI_QKV, EPI_RESID, EPI_SWIGLU, EPI_RESID};
+    const int nc[4] = {nqkv, c.hidden, 2 * c.ffn, c.hidden};
     const int ks[4] = {c.hidden, qd, c.hidden, c.ffn};
     size_t m = 0;
     for (int i = 0; i < 4; ++i) {
-      const SplitPlan p = plan_gemm(tl[i], ks[i]);
-      if ((size_t)p.n_splits * p.n_tiles > m) m = (size_t)p.n_splits * p.n_tiles;
-      if (tl[i] > L.max_tiles) L.max_tiles = tl[i];
+      const SplitPlan p = plan_gemm(ep[i], nc[i], ks[i], rp);
+      const size_t e = (size_t)p.n_splits * p.n_tiles * p.tile_n;
+      if (e > m) m = e;
+      if (p.n_tiles > L.max_tiles) L.max_tiles = p.n_tiles;
     }
-    L.part = take(sizeof(float) * m * rp * kGemmTileN);
+    L.part = take(sizeof(float) * m * rp);
   }
   L.counters = take(sizeof(int32_t) * (L.max_tiles + 1));
   // sums of squares per (tile, row): two buffers, a matmul reads its producer's while writing its own
-  L.ss_part = take(2 * sizeof(float) * (size_t)tiles_of(c.hidden) * rp);
+  L.ss_part = take(2 * sizeof(float) * (size_t)tiles_of(c.hidden) * rp);   // sized for the narrower tile
   const int group = c.n_q_heads / c.n_kv_heads;
   const size_t prow = f32 ? 0 : (size_t)batch * c.n_kv_heads * kMaxAttnSplits * group * max_nodes;
   L.attn_o = take(sizeof(float) * prow * c.head_dim);
@@ -169,6 +181,7 @@ int check_shape(const trispec_model_config &c) {
   if (c.dtype == TRISPEC_BF16) {
     const int qd = c.n_q_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim;
     if (c.hidden % 64 || c.ffn % 64 || qd % 64 || kvd % 32) return TRISPEC_ESHAPE;
+    if (c.n_q_heads / c.n_kv_heads > kMaxGroup) return TRISPEC_ESHAPE;
   }
   return TRISPEC_OK;
 }
@@ -477,7 +490,7 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
   at.part_m = (float *)(ws + L.attn_m);
   at.part_l = (float *)(ws + L.attn_l);
   at.out = attn_out;
-  at.out_panel = pan_q;
+  at.out_panel = (size_t)(rp / 32);   // operand layout: number of 32-row blocks
   auto attention = [&](char *kl, char *vl) {
     at.k_cache = kl;
     at.v_cache = vl;
@@ -546,13 +559,12 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
     at.n_row_groups = (group * n_nodes + 127) / 128;
     launch_zero_counters(st, counters, L.max_tiles + 1);
     // ss[0]: written by the embedding (1 tile) and by every down projection; ss[1]: by every O projection
-    const int h_tiles = tiles_of(c.hidden);
-    float *ss0 = (float *)(ws + L.ss_part), *ss1 = ss0 + (size_t)h_tiles * rp;
+    float *ss0 = (float *)(ws + L.ss_part), *ss1 = ss0 + (size_t)tiles_of(c.hidden) * rp;
     launch_embed_norm(st, c.dtype, draft_tokens, m->embed, m->norm_attn[0], rows, c.hidden, c.vocab, c.rms_eps,
-                      x, h, pan_h, ss0, status);
-    int ss0_tiles = 1;
+                      x, h, (size_t)(rp / 32), ss0, status);
+    int ss0_tiles = 1, o_tiles = 1;
     auto base = [&](int epi, const void *xin, size_t xpanel, const float *ss_in, int ss_tiles, int k,
-                    int n_total, int n_tiles) {
+                    int n_total) {
       GemmArgs g;
       memset(&g, 0, sizeof(g));
       g.epi = epi;
@@ -565,13 +577,17 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
       g.k = k;
       g.rows = rows;
       g.rows_pad = rp;
-      const SplitPlan p = plan_gemm(n_tiles, k);
-      g.n_tiles = n_tiles;
+      const SplitPlan p = plan_gemm(epi, n_total, k, rp);
+      g.tile_n = p.tile_n;
+      g.n_tiles = p.n_tiles;
       g.n_splits = p.n_splits;
       g.k_per_split = p.k_per_split;
       g.part = part;
       g.counters = counters;
       return g;
+    };
+    auto launch_gemm = [&](hipStream_t s_, const GemmArgs &g) {
+      launch_gemm_bf16(s_, g);
     };
     auto resid = [&](GemmArgs &g, const void *next_norm, float *ss_out) {
       g.x_resid = x; g.xw_out = h; g.out_panel = pan_h; g.next_norm_w = next_norm; g.ss_part = ss_out;
@@ -579,7 +595,7 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
     for (int l = 0; l < c.n_layers; ++l) {
       char *kl = (char *)kv->k + (size_t)l * kv_layer, *vl = (char *)kv->v + (size_t)l * kv_layer;
       {
-        GemmArgs g = base(EPI_QKV, h, pan_h, ss0, ss0_tiles, c.hidden, nqkv, tiles_of(nqkv));
+        GemmArgs g = base(EPI_QKV, h, pan_h, ss0, ss0_tiles, c.hidden, nqkv);
         g.seg[0] = {m->p_wq[l], qd, 0};
         g.seg[1] = {m->p_wk[l], kvd, qd};
         g.seg[2] = {m->p_wv[l], kvd, qd + kvd};
@@ -589,46 +605,46 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
         g.n_nodes = n_nodes; g.n_q_heads = c.n_q_heads; g.n_kv_heads = c.n_kv_heads; g.head_dim = c.head_dim;
         g.capacity = kv->capacity;
         TimedLaunch tl(opts->timer, TRISPEC_K_GEMM, st, (double)nqkv * c.hidden * es);
-        launch_gemm_bf16(st, g);
+        launch_gemm(st, g);
       }
       attention(kl, vl);
       {
-        GemmArgs g = base(EPI_RESID, attn_out, pan_q, nullptr, 0, qd, c.hidden, h_tiles);
+        GemmArgs g = base(EPI_RESID, attn_out, pan_q, nullptr, 0, qd, c.hidden);
         g.seg[0] = {m->p_wo[l], c.hidden, 0};
         g.n_seg = 1;
         resid(g, m->norm_ffn[l], ss1);
+        o_tiles = g.n_tiles;
         TimedLaunch tl(opts->timer, TRISPEC_K_GEMM, st, (double)c.hidden * qd * es);
-        launch_gemm_bf16(st, g);
+        launch_gemm(st, g);
       }
       {
-        GemmArgs g = base(EPI_SWIGLU, h, pan_h, ss1, h_tiles, c.hidden, 2 * c.ffn, (c.ffn + 63) / 64);
+        GemmArgs g = base(EPI_SWIGLU, h, pan_h, ss1, o_tiles, c.hidden, 2 * c.ffn);
         g.seg[0] = {m->p_gate[l], c.ffn, 0};
         g.seg[1] = {m->p_up[l], c.ffn, c.ffn};
         g.n_seg = 2;
         g.act_out = act; g.ffn = c.ffn; g.out_panel = pan_f;
         TimedLaunch tl(opts->timer, TRISPEC_K_GEMM, st, 2.0 * c.ffn * c.hidden * es);
-        launch_gemm_bf16(st, g);
+        launch_gemm(st, g);
       }
       {
-        GemmArgs g = base(EPI_RESID, act, pan_f, nullptr, 0, c.ffn, c.hidden, h_tiles);
+        GemmArgs g = base(EPI_RESID, act, pan_f, nullptr, 0, c.ffn, c.hidden);
         g.seg[0] = {m->p_down[l], c.hidden, 0};
         g.n_seg = 1;
         resid(g, (l + 1 < c.n_layers) ? m->norm_attn[l + 1] : m->final_norm, ss0);
-        ss0_tiles = h_tiles;
+        ss0_tiles = g.n_tiles;
         TimedLaunch tl(opts->timer, TRISPEC_K_GEMM, st, (double)c.hidden * c.ffn * es);
-        launch_gemm_bf16(st, g);
+        launch_gemm(st, g);
       }
     }
     {
-      GemmArgs g = base(EPI_HEAD, h, pan_h, ss0, ss0_tiles, c.hidden, c.vocab, tiles_of(c.vocab));
+      GemmArgs g = base(EPI_HEAD, h, pan_h, ss0, ss0_tiles, c.hidden, c.vocab);
       g.seg[0] = {m->p_lm_head, c.vocab, 0};
       g.n_seg = 1;
-      g.n_splits = 1;
-      g.k_per_split = (int)align_up(c.hidden, (c.hidden % 256 == 0) ? 256 : 64);
+      hs.n_tiles = g.n_tiles;
       g.hs = hs;
       g.debug_logits = opts->debug_logits;
       TimedLaunch tl(opts->timer, TRISPEC_K_HEAD, st, (double)c.vocab * c.hidden * es);
-      launch_gemm_bf16(st, g);
+      launch_gemm(st, g);
     }
   }
 

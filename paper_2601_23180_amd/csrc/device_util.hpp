@@ -15,6 +15,19 @@ __device__ __forceinline__ float from_f32<float>(float v) { return v; }
 template <>
 __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return (bf16)v; }  // round-to-nearest-even
 
+// Operand layout of a matmul activation [rows_pad = 32 * MB, K] (bf16 hi part + bf16 lo part):
+// the order in which the matrix cores consume it.  For every 64-deep k block `blk`, MFMA step j,
+// 32-row block mb and part p (0 = hi, 1 = lo), one contiguous 1 KB fragment holds the 64 lanes'
+// 16-byte A operands: lane (ln, g) = row 32 mb + ln, k = 64 blk + 32 g + 8 j + 0..7.  A consumer
+// copies whole fragments global -> LDS with fully contiguous loads and reads them back with one
+// conflict-free 16-byte LDS read per lane; producers scatter their outputs into this order once.
+// Returns the element offset of (row r, reduction index k, part p).
+__device__ __forceinline__ size_t ol_offset(int r, int k, int part, int mb_count) {
+  const int blk = k >> 6, g = (k >> 5) & 1, j = (k >> 3) & 3, e = k & 7;
+  const int mb = r >> 5, ln = r & 31;
+  return ((((size_t)blk * 4 + j) * mb_count + mb) * 2 + part) * 512 + (g * 32 + ln) * 8 + e;
+}
+
 // Data handed from one workgroup to another INSIDE a kernel (split-K partial tiles, per-tile
 // sums) is written and read with agent-scope relaxed atomics: on gfx950 these are ordinary
 // stores / loads that write through, respectively bypass, the per-XCD L2, so they are coherent

@@ -6,6 +6,51 @@
 
 namespace ts {
 
+// 1/rms of every row of a matmul's INPUT, from the per-tile sums of squares its producer left.
+// rstd_load only ISSUES loads (wavefront q of the workgroup takes tiles q, q+Q, ...; a lane takes
+// rows lane, lane+64, ...) and is called before the weight stream starts, so that nothing waits
+// for them; rstd_finish, called after the stream, adds them up (plus any tiles beyond the first
+// 8*Q, which only very wide models have) and combines the wavefronts' sums through LDS.  The
+// order of the additions is fixed, so the result does not depend on scheduling.
+template <int NT, int MB>
+__device__ __forceinline__ void rstd_load(const GemmArgs &a, float (&x)[(MB + 1) / 2][8]) {
+  constexpr int Q = NT / 64, RI = (MB + 1) / 2;
+  const int q = threadIdx.x >> 6, r0 = threadIdx.x & 63;
+  if (a.ss_in == nullptr) return;
+#pragma unroll
+  for (int i = 0; i < RI; ++i) {
+    const int r = min(r0 + 64 * i, a.rows_pad - 1);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) x[i][u] = a.ss_in[(size_t)min(q + Q * u, a.ss_tiles - 1) * a.rows_pad + r];
+  }
+}
+
+// s_rsp: NT/64 * kMaxRows floats of LDS.  The caller synchronises the workgroup before s_rs is read.
+template <int NT, int MB>
+__device__ __forceinline__ void rstd_finish(const GemmArgs &a, const float (&x)[(MB + 1) / 2][8], float *s_rsp,
+                                            float *s_rs) {
+  constexpr int Q = NT / 64, RI = (MB + 1) / 2;
+  const int q = threadIdx.x >> 6, r0 = threadIdx.x & 63;
+  if (a.ss_in != nullptr) {
+#pragma unroll
+    for (int i = 0; i < RI; ++i) {
+      float v = 0.f;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v += (q + Q * u < a.ss_tiles) ? x[i][u] : 0.f;
+      const int r = min(r0 + 64 * i, a.rows_pad - 1);
+      for (int t = q + Q * 8; t < a.ss_tiles; t += Q) v += a.ss_in[(size_t)t * a.rows_pad + r];
+      s_rsp[q * kMaxRows + r0 + 64 * i] = v;
+    }
+  }
+  __syncthreads();
+  for (int r = threadIdx.x; r < a.rows; r += NT) {
+    float ss = 0.f;
+#pragma unroll
+    for (int qq = 0; qq < Q; ++qq) ss += s_rsp[qq * kMaxRows + r];
+    s_rs[r] = a.ss_in != nullptr ? 1.0f / sqrtf(ss / (float)a.k + a.eps) : 1.0f;
+  }
+}
+
 // acc[mb][e] of lane (ln, g) of wavefront `wave` holds y[mb*32 + 8*(e/4) + 4*g + e%4][wave*32 + ln]
 // of this workgroup's (tile, split).  lds: at least MB*32*(TN+4)*4 bytes, free for reuse (every
 // wavefront has passed a barrier after its last operand read).  s_rs: 1/rms per input row.
@@ -50,9 +95,9 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, f32x16 (&acc)[M
     return;
   }
 
-  // ---- hand the tile to the epilogue.  One split: through LDS, no global round trip.  Several
-  // splits: write-through partial tiles part[split][tile][row][128] + a counter per tile; only
-  // the last workgroup to arrive goes on.
+  // ---- hand the tile to the epilogue, as an fp32 tile in LDS.  One split: straight from the
+  // accumulators.  Several splits: write-through partial tiles part[split][tile][row][TN] + a
+  // counter per tile; only the last workgroup to arrive goes on.
   constexpr int EPI_LD = TN + 4;       // floats per row of the LDS tile
   float *tl = (float *)lds;
   const bool single = a.n_splits == 1;
@@ -75,25 +120,65 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, f32x16 (&acc)[M
         if (r < a.rows) st_agent(o + (size_t)r * TN, acc[mb][e]);
       }
     if (!publish_then_count(&a.counters[tile], a.n_splits, s_last)) return;
+    // Last workgroup of the tile: sum the splits, in ascending order, into the LDS tile.  The
+    // partial tiles were written through to memory (st_agent) and nobody on this chip has read
+    // these lines before, so plain vector loads see them.  A memory round trip costs far more
+    // than the additions, so the loads of two splits (UB vectors each) are in flight together.
+    constexpr int PER = MB * 32 * (TN / 4) / NT;   // 4-column vectors per thread
+    constexpr int UB = PER < 8 ? PER : 8;
+    const float *p0 = a.part + (size_t)tile * tile_elems + (size_t)tid * 4;
+    const size_t split_stride = (size_t)a.n_tiles * tile_elems;
+#pragma unroll 1
+    for (int ub = 0; ub < PER; ub += UB) {
+      f32x4 sum[UB];
+#pragma unroll
+      for (int u = 0; u < UB; ++u) sum[u] = *(const f32x4 *)(p0 + (size_t)(ub + u) * NT * 4);
+      for (int s = 1; s < a.n_splits; s += 2) {
+        const bool two = s + 1 < a.n_splits;
+        const float *pa = p0 + (size_t)s * split_stride, *pb = pa + (two ? split_stride : 0);
+        f32x4 va[UB], vb[UB];
+#pragma unroll
+        for (int u = 0; u < UB; ++u) {
+          va[u] = *(const f32x4 *)(pa + (size_t)(ub + u) * NT * 4);
+          vb[u] = *(const f32x4 *)(pb + (size_t)(ub + u) * NT * 4);
+        }
+#pragma unroll
+        for (int u = 0; u < UB; ++u) {
+          sum[u] += va[u];
+          if (two) sum[u] += vb[u];
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < UB; ++u) {
+        const int idx = tid + (ub + u) * NT, r = idx / (TN / 4), c = (idx % (TN / 4)) * 4;
+        *(f32x4 *)(tl + r * EPI_LD + c) = sum[u];
+      }
+    }
+    __syncthreads();
   }
-  // The partial tiles were written through to memory (st_agent) and nobody on this chip has read
-  // these lines before, so plain vector loads see them.
-  const float *p0 = a.part + (size_t)tile * tile_elems;
-  const size_t split_stride = (size_t)a.n_tiles * tile_elems;
-  auto reduced4 = [&](int r, int c) {   // 4 consecutive columns, splits summed in ascending order
-    if (single) return *(const f32x4 *)(tl + r * EPI_LD + c);
-    const float *p = p0 + (size_t)r * TN + c;
-    f32x4 v = *(const f32x4 *)p;
-    for (int s = 1; s < a.n_splits; ++s) v += *(const f32x4 *)(p + (size_t)s * split_stride);
-    return v;
+  auto reduced4 = [&](int r, int c) {   // 4 consecutive columns of the reduced tile
+    return *(const f32x4 *)(tl + r * EPI_LD + c);
   };
   if (EPI == EPI_QKV) {
     // a tile is one head (d = 128) or two heads (d = 64); thread = (row, 4 rotation pairs)
     const int d = a.head_dim, half = d >> 1;
     const int n_q = a.n_q_heads, n_kv = a.n_kv_heads;
-    const int quads = TN / 8;                               // 4-pair groups per row
-    for (int t = tid; t < a.rows * quads; t += NT) {
+    constexpr int quads = TN / 8;                           // 4-pair groups per row
+    constexpr int PASSES = MB * 32 * quads / NT;
+    // the rotation tables of every pass first: one memory round trip instead of one per pass
+    f32x4 cs[PASSES], sn[PASSES];
+#pragma unroll
+    for (int u = 0; u < PASSES; ++u) {
+      const int t = tid + u * NT, r = min(t / quads, a.rows - 1), qi = t % quads;
+      const int j = qi * 4 - ((qi * 4) / half) * half;
+      cs[u] = *(const f32x4 *)(a.cos_t + r * half + j);
+      sn[u] = *(const f32x4 *)(a.sin_t + r * half + j);
+    }
+#pragma unroll
+    for (int u = 0; u < PASSES; ++u) {
+      const int t = tid + u * NT;
       const int r = t / quads, qi = t - r * quads;
+      if (r >= a.rows) continue;
       const int hl = (qi * 4) / half, j = qi * 4 - hl * half;   // head within the tile, first pair
       const int c_lo = hl * d + j;                          // tile-local column of the low elements
       const int col = tile * TN + c_lo;             // global column
@@ -104,8 +189,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, f32x16 (&acc)[M
       const int b = r / a.n_nodes, node = r - b * a.n_nodes;
       const int slot = a.ctx.v[b] + node;
       if (hh < n_q + n_kv) {
-        const f32x4 c = *(const f32x4 *)(a.cos_t + r * half + j), sn = *(const f32x4 *)(a.sin_t + r * half + j);
-        const f32x4 rl = lo * c - hi * sn, rh = hi * c + lo * sn;
+        const f32x4 rl = lo * cs[u] - hi * sn[u], rh = hi * cs[u] + lo * sn[u];
         lo = rl; hi = rh;
       }
       *(f32x4 *)(a.qkv_f32 + (size_t)r * a.n_total + col) = lo;
@@ -158,9 +242,9 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, f32x16 (&acc)[M
         hi[e] = (bf16)o;
         lo[e] = (bf16)(o - (float)hi[e]);
       }
-      bf16 *dst = (bf16 *)a.act_out + (size_t)r * a.ffn + feat;
-      *(bf16x4 *)dst = hi;
-      *(bf16x4 *)(dst + a.out_panel) = lo;
+      bf16 *dst = (bf16 *)a.act_out;   // operand layout of the down projection (K = ffn)
+      *(bf16x4 *)(dst + ol_offset(r, feat, 0, MB)) = hi;
+      *(bf16x4 *)(dst + ol_offset(r, feat, 1, MB)) = lo;
     }
     return;
   }
@@ -169,31 +253,43 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, f32x16 (&acc)[M
   // TN/4 consecutive lanes (4 columns each) cover one row of the tile.
   {
     constexpr int LPR = TN / 4, RPP = NT / LPR;   // lanes per row, rows per pass
+    constexpr int PASSES = MB * 32 / RPP, UB = PASSES < 8 ? PASSES : 8;
     float *ssp = a.ss_part + (size_t)tile * a.rows_pad;
-    const int c = (tid % LPR) * 4, col = tile * TN + c;
-    for (int r = tid / LPR; r < a.rows_pad; r += RPP) {
-      float ss = 0.f;
-      if (r < a.rows && col < a.n_total) {
-        float *xp = a.x_resid + (size_t)r * a.n_total + col;
-        const f32x4 v = *(const f32x4 *)xp + reduced4(r, c);
-        *(f32x4 *)xp = v;
-        ss = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
-        // operand of the next matmul: x * (next RMSNorm weight), as bf16 hi + lo
-        const bf16x4 nw = *(const bf16x4 *)((const bf16 *)a.next_norm_w + col);
-        bf16x4 hi, lo;
+    const int c = (tid % LPR) * 4, col = tile * TN + c, r0 = tid / LPR;
+    const bool col_ok = col < a.n_total;
+    const int colc = col_ok ? col : 0;
+    const bf16x4 nw = *(const bf16x4 *)((const bf16 *)a.next_norm_w + colc);
+#pragma unroll 1
+    for (int ub = 0; ub < PASSES; ub += UB) {
+      // the residual rows of UB passes first: one memory round trip instead of one per pass
+      f32x4 xv[UB];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float o = v[e] * (float)nw[e];
-          hi[e] = (bf16)o;
-          lo[e] = (bf16)(o - (float)hi[e]);
+      for (int u = 0; u < UB; ++u)
+        xv[u] = *(const f32x4 *)(a.x_resid + (size_t)min(r0 + (ub + u) * RPP, a.rows - 1) * a.n_total + colc);
+#pragma unroll
+      for (int u = 0; u < UB; ++u) {
+        const int r = r0 + (ub + u) * RPP;
+        float ss = 0.f;
+        if (r < a.rows && col_ok) {
+          const f32x4 v = xv[u] + reduced4(r, c);
+          *(f32x4 *)(a.x_resid + (size_t)r * a.n_total + col) = v;
+          ss = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+          // operand of the next matmul: x * (next RMSNorm weight), as bf16 hi + lo
+          bf16x4 hi, lo;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float o = v[e] * (float)nw[e];
+            hi[e] = (bf16)o;
+            lo[e] = (bf16)(o - (float)hi[e]);
+          }
+          bf16 *dst = (bf16 *)a.xw_out;   // operand layout of the next matmul (K = hidden)
+          *(bf16x4 *)(dst + ol_offset(r, col, 0, MB)) = hi;
+          *(bf16x4 *)(dst + ol_offset(r, col, 1, MB)) = lo;
         }
-        bf16 *dst = (bf16 *)a.xw_out + (size_t)r * a.n_total + col;
-        *(bf16x4 *)dst = hi;
-        *(bf16x4 *)(dst + a.out_panel) = lo;
-      }
 #pragma unroll
-      for (int o = LPR / 2; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
-      if (tid % LPR == 0 && r < a.rows) ssp[r] = ss;   // read by the next kernel
+        for (int o = LPR / 2; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+        if (tid % LPR == 0 && r < a.rows) ssp[r] = ss;   // read by the next kernel
+      }
     }
   }
 }

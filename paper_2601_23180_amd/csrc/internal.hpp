@@ -19,6 +19,7 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 constexpr int kMaxRows = TRISPEC_MAX_ROWS;
 constexpr int kMaxBatch = TRISPEC_MAX_BATCH;
 constexpr int kMaxNodes = TRISPEC_MAX_NODES;
+constexpr int kMaxGroup = 8;         // query heads per kv head (bf16 attention)
 constexpr int kMaxSplitK = 32;       // k-splits of one matmul
 constexpr int kMaxAttnSplits = 64;   // context splits of one attention call
 constexpr int kGemmTileN = 128;      // output columns per workgroup (4 waves x 32)
@@ -67,6 +68,7 @@ struct GemmArgs {
   int32_t k_per_split; // multiple of 64
   int32_t n_splits;
   int32_t n_tiles;
+  int32_t tile_n;      // output columns per workgroup (128)
   int32_t epi;
   float *out;          // fp32 path only
   float *part;         // [n_splits][n_tiles][rows_pad][128] split-K partial tiles
@@ -147,7 +149,7 @@ void launch_reduce_swiglu(hipStream_t st, int dtype, const float *part, int n_sp
 void launch_gemm_f32(hipStream_t st, const GemmArgs &a);
 size_t packed_weight_bytes(int n_rows, int k);
 void launch_pack_weights(hipStream_t st, const void *w, int n_rows, int k, void *out);
-void launch_gemm_bf16(hipStream_t st, const GemmArgs &a);
+void launch_gemm_bf16(hipStream_t st, const GemmArgs &a);   // 4 wavefronts, 128-column tiles
 void launch_stats_from_logits(hipStream_t st, const float *logits, int rows, int vocab,
                               const HeadStats &hs);
 void launch_attn_f32(hipStream_t st, const AttnArgs &a);

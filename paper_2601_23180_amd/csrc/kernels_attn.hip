@@ -307,87 +307,117 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
   }
 }
 
-// Combine the context splits of one (row, query head), ascending split order, with the draft-node
-// part: for every ancestor-or-self j of the node, score = q . k_j / sqrt(d) and value v_j, all
-// taken in fp32 from this pass's projections (a.qkv: [row][(nq + 2 nkv) * d], q and k already
-// rotated).  One thread per output feature.
+// Combine the context splits of one (row, kv head) — all `group` query heads that share the kv
+// head — in ascending split order, with the draft-node part: for every ancestor-or-self j of the
+// node, score = q . k_j / sqrt(d) and value v_j, all taken in fp32 from this pass's projections
+// (a.qkv: [row][(nq + 2 nkv) * d], q and k already rotated).
+// Memory round trips, not arithmetic, set this kernel's time, so every phase issues its loads as
+// one independent batch: the ancestor list (at most 64 nodes) is scored by 64 x 4 threads at once
+// (thread = ancestor slot x quarter of the features), and the value sum walks the list four
+// ancestors at a time.
+
 template <int D>
-__global__ __launch_bounds__(D) void k_attn_merge(AttnArgs a) {
-  __shared__ float sc[kMaxNodes];
-  __shared__ float red[2];
-  const int r = blockIdx.x, head = blockIdx.y, f = threadIdx.x;
+__global__ __launch_bounds__(256) void k_attn_merge(AttnArgs a) {
+  __shared__ float s_q[kMaxGroup][D];
+  __shared__ float s_sc[kMaxGroup][kMaxNodes];
+  __shared__ int s_anc[kMaxNodes];
+  const int r = blockIdx.x, kvh = blockIdx.y, tid = threadIdx.x;
   const int M = a.n_nodes, group = a.n_q_heads / a.n_kv_heads;
   const int b = r / M, node = r - b * M;
-  const int kvh = head / group, al = head - kvh * group;
-  const int p_rows = group * M, p = al * M + node;
+  const int p_rows = group * M;
   const size_t base = ((size_t)b * a.n_kv_heads + kvh) * a.n_splits;
   const int n_total = (a.n_q_heads + 2 * a.n_kv_heads) * D;
-  const uint64_t mask = a.anc[r];
+  const uint64_t mask = a.anc[r];          // bit j: node j is on the root path of this node (self included)
+  const int n_anc = __popcll(mask);        // >= 1
   const float scale = 1.0f / sqrtf((float)D);
-  const float qf = a.qkv[(size_t)r * n_total + head * D + f];
-  float m_tot = -INFINITY;
-  for (int j = 0; j <= node; ++j) {       // ancestors have lower node ids
-    if (!((mask >> j) & 1ull)) continue;  // uniform over the workgroup
-    const float kf = a.qkv[(size_t)(b * M + j) * n_total + (a.n_q_heads + kvh) * D + f];
-    float v = wave_sum(qf * kf);
-    if (D > 64) {
-      __syncthreads();
-      if ((f & 63) == 0) red[f >> 6] = v;
-      __syncthreads();
-      v = red[0] + red[1];
+  if (tid < kMaxNodes && ((mask >> tid) & 1ull)) s_anc[__popcll(mask & ((1ull << tid) - 1ull))] = tid;
+  for (int i = tid; i < group * D; i += 256)
+    s_q[i / D][i % D] = a.qkv[(size_t)r * n_total + (size_t)kvh * group * D + i];
+  __syncthreads();
+
+  // ---- scores of the ancestor list
+  {
+    const int slot = tid >> 2, qq = tid & 3;
+    const int j = s_anc[min(slot, n_anc - 1)];
+    const float *kp = a.qkv + (size_t)(b * M + j) * n_total + (size_t)(a.n_q_heads + kvh) * D + qq * (D / 4);
+    f32x4 kv4[D / 16];
+#pragma unroll
+    for (int i = 0; i < D / 16; ++i) kv4[i] = *(const f32x4 *)(kp + 4 * i);
+    for (int al = 0; al < group; ++al) {
+      float acc = 0.f;
+#pragma unroll
+      for (int i = 0; i < D / 16; ++i)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc += kv4[i][e] * s_q[al][qq * (D / 4) + 4 * i + e];
+      acc += __shfl_xor(acc, 1, 64);
+      acc += __shfl_xor(acc, 2, 64);
+      if (qq == 0 && slot < n_anc) s_sc[al][slot] = acc * scale;
     }
-    v *= scale;
-    if (f == 0) sc[j] = v;
-    m_tot = fmaxf(m_tot, v);
   }
   __syncthreads();
-  // context splits, 16 at a time so that the loads of a group are independent and in flight
-  // together; combined in ascending split order
-  for (int s0 = 0; s0 < a.n_splits; s0 += 16) {
-    float pm[16];
+
+  // ---- one output feature of one query head at a time
+  for (int o_idx = tid; o_idx < group * D; o_idx += 256) {
+    const int al = o_idx / D, f = o_idx - al * D;
+    const int p = al * M + node;
+    float m_tot = -INFINITY;
+    for (int i = 0; i < n_anc; ++i) m_tot = fmaxf(m_tot, s_sc[al][i]);
+    // context splits, 16 at a time so that the loads of a group are in flight together
+    for (int s0 = 0; s0 < a.n_splits; s0 += 16) {
+      float pm[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i)
-      pm[i] = (s0 + i < a.n_splits) ? a.part_m[(base + s0 + i) * p_rows + p] : -INFINITY;
+      for (int i = 0; i < 16; ++i)
+        pm[i] = (s0 + i < a.n_splits) ? a.part_m[(base + s0 + i) * p_rows + p] : -INFINITY;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) m_tot = fmaxf(m_tot, pm[i]);
-  }
-  float num = 0.f, den = 0.f;
-  for (int s0 = 0; s0 < a.n_splits; s0 += 16) {
-    float pm[16], pl[16], po[16];
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const bool ok = s0 + i < a.n_splits;
-      const size_t idx = (base + (ok ? s0 + i : 0)) * p_rows + p;
-      pm[i] = ok ? a.part_m[idx] : -INFINITY;
-      pl[i] = a.part_l[idx];
-      po[i] = a.part_o[idx * D + f];
+      for (int i = 0; i < 16; ++i) m_tot = fmaxf(m_tot, pm[i]);
     }
+    float num = 0.f, den = 0.f;
+    for (int s0 = 0; s0 < a.n_splits; s0 += 16) {
+      float pm[16], pl[16], po[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      if (pm[i] == -INFINITY) continue;   // empty split: its o / l were never written
-      const float w = expf(pm[i] - m_tot);
-      num += po[i] * w;
-      den += pl[i] * w;
+      for (int i = 0; i < 16; ++i) {
+        const bool ok = s0 + i < a.n_splits;
+        const size_t idx = (base + (ok ? s0 + i : 0)) * p_rows + p;
+        pm[i] = ok ? a.part_m[idx] : -INFINITY;
+        pl[i] = a.part_l[idx];
+        po[i] = a.part_o[idx * D + f];
+      }
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        if (pm[i] == -INFINITY) continue;   // empty split: its o / l were never written
+        const float w = expf(pm[i] - m_tot);
+        num += po[i] * w;
+        den += pl[i] * w;
+      }
     }
+    const float *vbase = a.qkv + (size_t)(a.n_q_heads + a.n_kv_heads + kvh) * D + f;
+    for (int i0 = 0; i0 < n_anc; i0 += 4) {
+      float vv[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        vv[i] = vbase[(size_t)(b * M + s_anc[min(i0 + i, n_anc - 1)]) * n_total];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (i0 + i < n_anc) {
+          const float w = expf(s_sc[al][i0 + i] - m_tot);
+          num += w * vv[i];
+          den += w;
+        }
+    }
+    const float o = num / den;
+    const bf16 hi = (bf16)o;
+    bf16 *dst = (bf16 *)a.out;   // operand layout of the O projection; out_panel = number of 32-row blocks
+    const int kk = (kvh * group + al) * D + f;
+    dst[ol_offset(r, kk, 0, (int)a.out_panel)] = hi;
+    dst[ol_offset(r, kk, 1, (int)a.out_panel)] = (bf16)(o - (float)hi);
   }
-  for (int j = 0; j <= node; ++j) {
-    if (!((mask >> j) & 1ull)) continue;
-    const float w = expf(sc[j] - m_tot);
-    num += w * a.qkv[(size_t)(b * M + j) * n_total + (a.n_q_heads + a.n_kv_heads + kvh) * D + f];
-    den += w;
-  }
-  const float o = num / den;
-  const bf16 hi = (bf16)o;
-  bf16 *dst = (bf16 *)a.out + (size_t)r * a.n_q_heads * D + (size_t)head * D + f;
-  dst[0] = hi;
-  dst[a.out_panel] = (bf16)(o - (float)hi);
 }
 
 template <int D>
 static void launch_attn_bf16_d(hipStream_t st, const AttnArgs &a) {
   dim3 grid(a.n_splits, a.n_kv_heads, a.batch * a.n_row_groups);
   hipLaunchKernelGGL((k_attn_bf16<D, 1>), grid, dim3(256), 0, st, a);
-  hipLaunchKernelGGL(k_attn_merge<D>, dim3(a.batch * a.n_nodes, a.n_q_heads), dim3(D), 0, st, a);
+  hipLaunchKernelGGL(k_attn_merge<D>, dim3(a.batch * a.n_nodes, a.n_kv_heads), dim3(256), 0, st, a);
 }
 
 void launch_attn_bf16(hipStream_t st, const AttnArgs &a) {

@@ -18,8 +18,9 @@
 // conversion in every one of the hundreds of workgroups and costs more issue slots than the
 // MFMAs).  Each W fragment is multiplied by both parts, so the activations keep ~16 significant
 // bits, the pass is a smooth function of its inputs, and W is still read exactly once.  X is
-// staged through LDS in chunks of KC reduction elements, double buffered, rows padded by 16
-// bytes so that the 16-byte operand reads are conflict free.
+// stored in the operand layout (device_util.hpp: 1 KB fragments in consumption order), staged
+// through LDS in chunks of KC reduction elements, double buffered, by plain contiguous copies;
+// the 16-byte operand reads are conflict free.
 // RMSNorm is fused around the matmul: the producer stores x * w_norm (the per-column weight) as
 // the operand panels, and the per-row 1/rms multiplies the reduced sums in the epilogue here.
 //
@@ -39,8 +40,6 @@
 //          up columns)
 //   HEAD   (LM head, no k split) per-row (largest logit, its column, second largest, sum of exp)
 //          of the tile's 128 logits — the probabilities are never materialised.
-#include <stdlib.h>
-
 #include "gemm_epilogue.hpp"
 
 namespace ts {
@@ -48,14 +47,15 @@ namespace ts {
 template <int MB, int KC, int EPI, bool RAGGED, int DEPTH>
 __global__ __launch_bounds__(256) void k_gemm_bf16(GemmArgs a) {
   constexpr int KB = KC / 64;                 // 64-deep k blocks per chunk
-  constexpr int STRIDE = KC * 2 + 16;         // LDS bytes per activation row (one panel)
-  constexpr int PANEL = MB * 32 * STRIDE;     // one operand panel (hi or lo) of one stage
-  constexpr int BUF = 2 * PANEL;
-  constexpr int XV = MB * 32 * (KC / 8) / 256;  // 16-byte vectors per thread per chunk, per panel
-  constexpr int ROWS_PER_PASS = 256 / (KC / 8); // rows covered by one vector index step
-  __shared__ __attribute__((aligned(16))) unsigned char lds[2 * BUF];
+  constexpr int FRAGS = KB * 4 * MB * 2;      // 1 KB operand fragments per chunk (operand layout)
+  constexpr int BUF = FRAGS * 1024;           // one LDS stage
+  constexpr int XV = FRAGS / 4;               // fragments (16 bytes per lane) per wavefront per chunk
+  constexpr int EPI_BYTES = MB * 32 * (kGemmTileN + 4) * 4;   // the epilogue's fp32 tile reuses the stages
+  constexpr int LDS_BYTES = 2 * BUF > EPI_BYTES ? 2 * BUF : EPI_BYTES;
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[LDS_BYTES];
   __shared__ int s_last;
   __shared__ float s_rs[kMaxRows];   // 1/rms of the rows of the matmul's input
+  __shared__ float s_rsp[4 * kMaxRows];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ln = lane & 31, g = lane >> 5;
@@ -86,19 +86,14 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(GemmArgs a) {
   sub = min(max(sub, 0), ((seg_rows + 31) >> 5) - 1);
   const bf16 *wrow = wseg + ((size_t)sub * (a.k >> 6) + (k_begin >> 6)) * 2048 + lane * 8;
 
-  // ---- X staging: thread copies 16-byte column c8 of rows r0 + ROWS_PER_PASS * i, both panels
-  const int c8 = tid % (KC / 8), r0 = tid / (KC / 8);
-  const bf16 *xg = (const bf16 *)a.x + (size_t)r0 * a.k + k_begin + c8 * 8;
+  // ---- X staging: the chunk is a contiguous run of FRAGS fragments in operand layout; this
+  // wavefront copies fragments wave*XV .. wave*XV + XV-1, 16 bytes per lane each
+  const bf16 *xg = (const bf16 *)a.x + ((size_t)(k_begin >> 6) * 4 * MB * 2 + wave * XV) * 512 + lane * 8;
 
-  // 1/rms of every row of the matmul's INPUT, from the per-tile sums of squares its producer left
-  // (ascending tile order); used by the epilogue, loaded here so that it overlaps the stream.
-  if (a.ss_in != nullptr) {
-    for (int r = tid; r < a.rows; r += 256) {
-      float ss = 0.f;
-      for (int t = 0; t < a.ss_tiles; ++t) ss += a.ss_in[(size_t)t * a.rows_pad + r];
-      s_rs[r] = 1.0f / sqrtf(ss / (float)a.k + a.eps);
-    }
-  }
+  // 1/rms of every row of the matmul's INPUT (used by the epilogue): the loads go out here, ahead
+  // of the stream, and are consumed after it.
+  float rs_in[(MB + 1) / 2][8];
+  rstd_load<256, MB>(a, rs_in);
 
   f32x16 acc[MB];
 #pragma unroll
@@ -121,7 +116,7 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(GemmArgs a) {
   // sched_barrier pins the load issue points; the compiler would otherwise sink every load to
   // just before its first use and expose the whole memory latency once per chunk.
   bf16x8 w[DEPTH][KB][4];
-  uint4 xr[2][XV];
+  uint4 xr[XV];
 
   auto load_w_block = [&](int set, int c, int kb) {
     const int k = c * KC + kb * 64;
@@ -130,25 +125,23 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(GemmArgs a) {
     for (int j = 0; j < 4; ++j) w[set][kb][j] = *(const bf16x8 *)(p + 512 * j);
   };
   auto load_x = [&](int c) {
-    const bool ok = !RAGGED || (c * KC + c8 * 8 < klen);
-    const int off = ok ? c * KC : 0;
+    const bool ok = !RAGGED || (c * KC < klen);
+    const bf16 *src = xg + (size_t)(ok ? c : 0) * FRAGS * 512;
 #pragma unroll
     for (int i = 0; i < XV; ++i) {
-      const bf16 *src = xg + (size_t)(ROWS_PER_PASS * i) * a.k + off;
-      uint4 hi = *(const uint4 *)src;
-      uint4 lo = *(const uint4 *)(src + a.x_panel);
-      if (RAGGED && !ok) { hi = make_uint4(0, 0, 0, 0); lo = make_uint4(0, 0, 0, 0); }
-      xr[0][i] = hi;
-      xr[1][i] = lo;
+      uint4 v = *(const uint4 *)(src + i * 512);
+      if (RAGGED) {
+        // fragment (wave*XV + i) belongs to k block kb of the chunk; blocks past the split are zero
+        const int kb = (wave * XV + i) / (4 * MB * 2);
+        if (!ok || c * KC + kb * 64 >= klen) v = make_uint4(0, 0, 0, 0);
+      }
+      xr[i] = v;
     }
   };
   auto store_x = [&](int buf) {
+    unsigned char *dst = lds + buf * BUF + (wave * XV) * 1024 + lane * 16;
 #pragma unroll
-    for (int i = 0; i < XV; ++i) {
-      unsigned char *dst = lds + buf * BUF + (r0 + ROWS_PER_PASS * i) * STRIDE + c8 * 16;
-      *(uint4 *)dst = xr[0][i];
-      *(uint4 *)(dst + PANEL) = xr[1][i];
-    }
+    for (int i = 0; i < XV; ++i) *(uint4 *)(dst + i * 1024) = xr[i];
   };
   // One chunk of MFMAs, software pipelined: step t = (k block, j) needs four A fragments
   // (row block 0/1 x hi/lo); they are read from LDS two steps ahead into a 2-slot register ring,
@@ -156,12 +149,11 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(GemmArgs a) {
   // block, that block of the W set is refilled from chunk `c_next` (if LOADW).
   bf16x8 xf[2][2 * MB];
   auto read_frags = [&](int slot, int t, int buf) {
-    const int kb = t >> 2, j = t & 3;
-    const unsigned char *xp = lds + buf * BUF + ln * STRIDE + 64 * g + kb * 128 + j * 16;
+    const unsigned char *xp = lds + buf * BUF + (size_t)(t * MB * 2) * 1024 + lane * 16;   // t = kb*4 + j
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
-      xf[slot][2 * mb] = *(const bf16x8 *)(xp + mb * 32 * STRIDE);
-      xf[slot][2 * mb + 1] = *(const bf16x8 *)(xp + mb * 32 * STRIDE + PANEL);
+      xf[slot][2 * mb] = *(const bf16x8 *)(xp + (mb * 2) * 1024);
+      xf[slot][2 * mb + 1] = *(const bf16x8 *)(xp + (mb * 2 + 1) * 1024);
     }
   };
   auto compute_chunk = [&](int set, int buf, int c_next, bool loadw) {
@@ -235,6 +227,7 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(GemmArgs a) {
     }
   }
 
+  rstd_finish<256, MB>(a, rs_in, s_rsp, s_rs);
   __syncthreads();   // every wavefront is done reading the last X stage
   gemm_epilogue<MB, EPI, 4>(a, acc, lds, &s_last, s_rs, tile, split);
 }
@@ -268,10 +261,9 @@ void launch_pack_weights(hipStream_t st, const void *w, int n_rows, int k, void 
 template <int EPI>
 static void dispatch(hipStream_t st, const GemmArgs &a) {
   dim3 grid(a.n_tiles, a.n_splits), block(256);
-  static const bool depth4 = !(getenv("TRISPEC_DEPTH2"));
 #define TS_LAUNCH(MB_, KC_)                                                                   \
   do {                                                                                        \
-    if (a.k_per_split % (4 * KC_) == 0 && a.k % (4 * KC_) == 0 && depth4)                     \
+    if (a.k_per_split % (4 * KC_) == 0 && a.k % (4 * KC_) == 0)                               \
       hipLaunchKernelGGL((k_gemm_bf16<MB_, KC_, EPI, false, 4>), grid, block, 0, st, a);      \
     else if (a.k_per_split % (2 * KC_) == 0 && a.k % (2 * KC_) == 0)                          \
       hipLaunchKernelGGL((k_gemm_bf16<MB_, KC_, EPI, false, 2>), grid, block, 0, st, a);      \

@@ -68,12 +68,12 @@ __global__ __launch_bounds__(256) void k_embed_norm(const int32_t *tokens, const
   const float rstd = 1.0f / sqrtf(ss / (float)hidden + eps);
   if (ss_out != nullptr) {
     if (threadIdx.x == 0) ss_out[r] = ss;
-    bf16 *hp = (bf16 *)h + (size_t)r * hidden;
+    bf16 *hp = (bf16 *)h;   // operand layout; h_panel carries the number of 32-row blocks
     for (int i = threadIdx.x; i < hidden; i += 256) {
       const float v = to_f32(e[i]) * to_f32(norm_w[i]);
       const bf16 hi = (bf16)v;
-      hp[i] = hi;
-      hp[h_panel + i] = (bf16)(v - (float)hi);
+      hp[ol_offset(r, i, 0, (int)h_panel)] = hi;
+      hp[ol_offset(r, i, 1, (int)h_panel)] = (bf16)(v - (float)hi);
     }
   } else {
     float *hp = (float *)h + (size_t)r * hidden;
