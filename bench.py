@@ -60,8 +60,8 @@ def build_inputs(shape, batch, ctx, n_nodes, kind, seed):
 
 def cpu_baseline(shape, batch, ctx, n_nodes, kind, seed):
     """The oracle as it stands, timed on the host cores on a bounded sample of the workload:
-    the full-width model cut to 1 and to 2 layers (full LM head both times), sequence 0 only;
-    the per-layer time is the difference and the whole pass is extrapolated from it."""
+    the full-width model cut to 1 and to 4 layers (full LM head both times), sequence 0 only;
+    the per-layer time is the difference / 3 and the whole pass is extrapolated from it."""
     from oracle import OracleWeights, verify_forward
     from workloads import WeightSource, gen_chain, gen_draft_tokens, gen_kv_cache, gen_tree, tree_depths
 
@@ -73,21 +73,22 @@ def cpu_baseline(shape, batch, ctx, n_nodes, kind, seed):
 
     for name in ("embed", "lm_head", "final_norm"):
         cache[(name, 0)] = ws.get(name, 0)
-    for l in range(2):
+    cuts = (1, 4)
+    for l in range(cuts[1]):
         for name in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "norm_attn", "norm_ffn"):
             cache[(name, l)] = ws.get(name, l)
-    kvs = [tuple(a[0] for a in gen_kv_cache(shape, 1, ctx, seed, l)) for l in range(2)]
+    kvs = [tuple(a[0] for a in gen_kv_cache(shape, 1, ctx, seed, l)) for l in range(cuts[1])]
     parents = gen_chain(n_nodes) if kind == "chain" else gen_tree(n_nodes, 8, 4, seed)
     tokens = gen_draft_tokens(parents, shape.vocab, seed)
     positions = ctx + tree_depths(parents)
     W = OracleWeights(get)
     times = []
-    for nl in (1, 2):
+    for nl in cuts:
         sh = shape.with_(n_layers=nl)
         t0 = time.perf_counter()
         verify_forward(W, sh, lambda l: kvs[l][0], lambda l: kvs[l][1], tokens, parents, positions)
         times.append(time.perf_counter() - t0)
-    per_layer = max(times[1] - times[0], 1e-9)
+    per_layer = max((times[1] - times[0]) / (cuts[1] - cuts[0]), 1e-9)
     full = (times[0] + (shape.n_layers - 1) * per_layer) * batch
     try:
         from threadpoolctl import threadpool_info
@@ -96,8 +97,9 @@ def cpu_baseline(shape, batch, ctx, n_nodes, kind, seed):
         cores = os.cpu_count() or 1
     return {"value": batch * (n_nodes - 1) / full, "unit": "draft tokens/s", "cores": int(cores),
             "kind": "oracle", "seconds_per_pass_extrapolated": full,
-            "sample": f"numpy fp64 oracle, sequence 0, model cut to 1 and 2 layers at full width + full LM head "
-                      f"({times[0]:.2f}s, {times[1]:.2f}s); pass = t1 + (L-1)*(t2-t1), times batch"}
+            "sample": f"numpy fp64 oracle, sequence 0, model cut to {cuts[0]} and {cuts[1]} layers at full width + "
+                      f"full LM head ({times[0]:.2f}s, {times[1]:.2f}s); per layer = (t{cuts[1]}-t{cuts[0]})/{cuts[1] - cuts[0]}, "
+                      f"pass = t{cuts[0]} + (L-{cuts[0]})*per layer, times batch"}
 
 
 def main():
@@ -153,10 +155,33 @@ def main():
         ver.timer = None
         kernels[name] = {"launches": n, "avg_us": tms / n * 1e3, "bytes_per_launch": by / n,
                          "achieved_GBs": by / (tms * 1e-3) / 1e9, "ms_per_pass": tms / args.steps}
+    # measured streaming ceiling of this card: a plain copy of 1 GiB (read + write counted)
+    from paper_2601_23180_amd import copy_probe
+    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+    dst = torch.empty_like(src)
+    copy_probe(dst, src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        copy_probe(dst, src)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 5 * 2 * src.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del src, dst
+
+    # HBM traffic of the dominant kernel from the committed counter summary of the same command
+    # (two rocprofv3 --pmc runs, scaled by the copy kernel of known size; see profiles/)
+    traffic, traffic_note = None, None
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{args.workload}.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            tj = json.load(f)
+        traffic, traffic_note = tj.get("gemm_bytes_per_launch"), tj.get("source")
+
     g = kernels["gemm"]
     roofline = {"bound": "hbm", "kernel": "k_gemm_bf16 (weight-streaming projection / FFN matmul)",
                 "achieved": g["achieved_GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": g["achieved_GBs"] / HBM_PEAK_GBS, "traffic": None,
+                "frac": g["achieved_GBs"] / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_note,
                 "avg_launch_us": g["avg_us"], "bytes_per_launch": g["bytes_per_launch"]}
 
     out = {
@@ -171,6 +196,7 @@ def main():
         "pass_achieved_GBs": pass_bytes / (ms * 1e-3) / 1e9,
         "pass_frac_of_hbm_peak": pass_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "roofline": roofline,
+        "copy_ceiling_GBs": copy_gbs,
         "kernels": kernels,
         "accepted_len": ver.out["accepted_len"].cpu().tolist(),
         "escalate": ver.out["escalate"].cpu().tolist(),

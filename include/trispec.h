@@ -219,8 +219,9 @@ int trispec_timer_read(trispec_timer *t, int32_t *n_launches, double *total_ms, 
 int trispec_timer_destroy(trispec_timer *t);
 
 /* Test hook: byte offset and size, inside the workspace of a verify call with these
- * (batch, n_nodes), of a named intermediate of the LAST layer ("x" residual stream fp32,
- * "h" normalised operand, "q", "attn_out", "act", "node_l1", "node_l2", "node_sum",
+ * (batch, n_nodes), of a named intermediate of the LAST layer ("x" residual stream fp32;
+ * "attn_out" and "act", the O- and down-projection operands in the kernels' fragment order)
+ * or of the per-node statistics behind the decision ("node_l1", "node_l2", "node_sum",
  * "node_idx").  Errors: TRISPEC_ENULL, TRISPEC_ENODES, TRISPEC_EARG (unknown name). */
 int trispec_workspace_region(const trispec_model *m, int32_t batch, int32_t n_nodes,
                              const char *name, size_t *offset, size_t *bytes);
@@ -229,6 +230,13 @@ int trispec_workspace_region(const trispec_model *m, int32_t batch, int32_t n_no
  * once + context K/V once + draft K/V written (the figure the roofline is priced on). */
 int trispec_pass_bytes(const trispec_model *m, int32_t batch, int32_t n_nodes,
                        const int32_t *ctx_len_host, double *bytes);
+
+/* Plain device-to-device copy of `bytes` bytes (a multiple of 16; both pointers 16-byte
+ * aligned, regions must not overlap) on `stream`, by one streaming kernel.  Not part of the
+ * method: it is the measured streaming ceiling quoted next to the roofline, and the kernel of
+ * known traffic (bytes read + bytes written) that memory counters are calibrated against.
+ * Errors: TRISPEC_ENULL, TRISPEC_EARG (size or alignment), TRISPEC_ELAUNCH. */
+int trispec_copy_probe(void *dst_dev, const void *src_dev, size_t bytes, void *stream);
 
 const char *trispec_strerror(int code);
 

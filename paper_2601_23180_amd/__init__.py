@@ -4,5 +4,5 @@
 host arrays into device tensors; `build` compiles the HIP sources for gfx950.
 """
 from .binding import (CRIT_MARGIN, CRIT_TOP1, K_ATTN, K_GEMM, K_HEAD, TRISPEC_BF16, TRISPEC_F32,  # noqa: F401
-                      KernelTimer, KVCache, Model, TriSpecError, Verifier, lib)
+                      KernelTimer, KVCache, Model, TriSpecError, Verifier, copy_probe, lib)
 from .loader import fill_kv_layer, model_from_arrays  # noqa: F401

@@ -26,7 +26,7 @@ EXPORTS = [
     "trispec_kv_set_len", "trispec_kv_destroy", "trispec_workspace_bytes",
     "trispec_workspace_region", "trispec_pass_bytes", "trispec_verify", "trispec_decide",
     "trispec_strerror", "trispec_timer_create", "trispec_timer_reset", "trispec_timer_read",
-    "trispec_timer_destroy", "trispec_model_pack_bytes", "trispec_model_pack",
+    "trispec_timer_destroy", "trispec_model_pack_bytes", "trispec_model_pack", "trispec_copy_probe",
 ]
 K_GEMM, K_HEAD, K_ATTN = 0, 1, 2
 
@@ -91,6 +91,7 @@ def lib() -> C.CDLL:
         l.trispec_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
         l.trispec_workspace_region.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_char_p,
                                                C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
+        l.trispec_copy_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         l.trispec_pass_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_int32),
                                          C.POINTER(C.c_double)]
         l.trispec_verify.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_int32), C.c_void_p,
@@ -252,6 +253,16 @@ class KernelTimer:
                 self.handle = C.c_void_p()
         except Exception:
             pass
+
+
+def copy_probe(dst, src, stream=None) -> None:
+    """trispec_copy_probe on two device tensors of equal byte size (argument marshalling only)."""
+    import torch
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("copy_probe: sizes differ")
+    st = stream if stream is not None else torch.cuda.current_stream().cuda_stream
+    check(lib().trispec_copy_probe(dst.data_ptr(), src.data_ptr(), nbytes, st))
 
 
 class Verifier:

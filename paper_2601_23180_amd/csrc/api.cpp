@@ -730,6 +730,14 @@ int trispec_timer_destroy(trispec_timer *t) {
   return TRISPEC_OK;
 }
 
+int trispec_copy_probe(void *dst_dev, const void *src_dev, size_t bytes, void *stream) {
+  if (!dst_dev || !src_dev) return TRISPEC_ENULL;
+  if (bytes == 0 || bytes % 16 || ((((uintptr_t)dst_dev) | ((uintptr_t)src_dev)) & 15)) return TRISPEC_EARG;
+  (void)hipGetLastError();
+  launch_copy_probe((hipStream_t)stream, dst_dev, src_dev, bytes);
+  return hipGetLastError() == hipSuccess ? TRISPEC_OK : TRISPEC_ELAUNCH;
+}
+
 const char *trispec_strerror(int code) {
   switch (code) {
     case TRISPEC_OK: return "ok";

@@ -136,6 +136,7 @@ void launch_rope_table(hipStream_t st, const int32_t *positions, int rows, int h
 void launch_embed_norm(hipStream_t st, int dtype, const int32_t *tokens, const void *embed,
                        const void *norm_w, int rows, int hidden, int vocab, float eps, float *x,
                        void *h, size_t h_panel, float *ss_out, int32_t *status);
+void launch_copy_probe(hipStream_t st, void *dst, const void *src, size_t bytes);
 void launch_zero_counters(hipStream_t st, int32_t *counters, int n_counters);
 void launch_qkv_epilogue(hipStream_t st, int dtype, const float *part, int n_splits, int rows,
                          int rows_pad, int n_q_heads, int n_kv_heads, int head_dim,

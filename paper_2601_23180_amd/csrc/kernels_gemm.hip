@@ -63,6 +63,11 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(GemmArgs a) {
   const int k_begin = split * a.k_per_split;
   const int klen = min(a.k, k_begin + a.k_per_split) - k_begin;
   const int n_chunks = (klen + KC - 1) / KC;
+  // Workgroups that run side by side start at different depths of their k range (and wrap
+  // around), so that they do not all walk the memory channels in lockstep.  The order of the
+  // additions is still a fixed function of (tile, split).
+  const int rot = RAGGED ? 0 : (int)((blockIdx.x * 11u + blockIdx.y * 5u) % (unsigned)n_chunks);
+  auto rc = [&](int c) { const int cc = c + rot; return cc >= n_chunks ? cc - n_chunks : cc; };
 
   // ---- this wavefront's packed sub-tile.  Plain tiles: 4 consecutive sub-tiles of the
   // concatenated segments.  SWIGLU tiles: waves 0,1 -> gate sub-tiles 2t, 2t+1; waves 2,3 -> the
@@ -119,14 +124,14 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(GemmArgs a) {
   uint4 xr[XV];
 
   auto load_w_block = [&](int set, int c, int kb) {
-    const int k = c * KC + kb * 64;
+    const int k = rc(c) * KC + kb * 64;
     const bf16 *p = wrow + (size_t)((!RAGGED || k < klen) ? (k >> 6) : 0) * 2048;
 #pragma unroll
     for (int j = 0; j < 4; ++j) w[set][kb][j] = *(const bf16x8 *)(p + 512 * j);
   };
   auto load_x = [&](int c) {
     const bool ok = !RAGGED || (c * KC < klen);
-    const bf16 *src = xg + (size_t)(ok ? c : 0) * FRAGS * 512;
+    const bf16 *src = xg + (size_t)(ok ? rc(c) : 0) * FRAGS * 512;
 #pragma unroll
     for (int i = 0; i < XV; ++i) {
       uint4 v = *(const uint4 *)(src + i * 512);

@@ -339,4 +339,18 @@ void launch_decide(hipStream_t st, const DecideArgs &a) {
   hipLaunchKernelGGL(k_decide, dim3(a.batch), dim3(64), 0, st, a);
 }
 
+// Plain streaming copy, 16 bytes per thread per step, grid-stride.
+__global__ __launch_bounds__(256) void k_copy_probe(uint4 *dst, const uint4 *src, size_t n) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+}
+
+void launch_copy_probe(hipStream_t st, void *dst, const void *src, size_t bytes) {
+  const size_t n = bytes / 16;
+  size_t blocks = (n + 255) / 256;
+  if (blocks > 256 * 32) blocks = 256 * 32;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(k_copy_probe, dim3((unsigned)blocks), dim3(256), 0, st, (uint4 *)dst, (const uint4 *)src, n);
+}
+
 }  // namespace ts
