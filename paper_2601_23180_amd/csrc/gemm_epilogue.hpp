@@ -100,10 +100,38 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, f32x16 (&acc)[M
   // counter per tile; only the last workgroup to arrive goes on.
   constexpr int EPI_LD = TN + 4;       // floats per row of the LDS tile
   float *tl = (float *)lds;
+  // Loads of the epilogue that do not depend on the reduced tile (rotary tables; residual rows and
+  // the next norm weight).  Issued together with the loads of the partial tiles: a memory round
+  // trip costs more than everything else the epilogue does, so they must not follow each other.
+  constexpr int QKV_PASSES = MB * 32 * (TN / 8) / NT;
+  constexpr int RES_LPR = TN / 4, RES_RPP = NT / RES_LPR, RES_PASSES = MB * 32 / RES_RPP;
+  constexpr int RES_UB = RES_PASSES < 8 ? RES_PASSES : 8;
+  f32x4 pre_a[EPI == EPI_QKV ? QKV_PASSES : (EPI == EPI_RESID ? RES_UB : 1)];
+  f32x4 pre_b[EPI == EPI_QKV ? QKV_PASSES : 1];
+  bf16x4 pre_nw;
+  auto preload = [&]() {
+    if constexpr (EPI == EPI_QKV) {
+      const int half = a.head_dim >> 1;
+#pragma unroll
+      for (int u = 0; u < QKV_PASSES; ++u) {
+        const int t = tid + u * NT, r = min(t / (TN / 8), a.rows - 1), qi = t % (TN / 8);
+        const int j = qi * 4 - ((qi * 4) / half) * half;
+        pre_a[u] = *(const f32x4 *)(a.cos_t + r * half + j);
+        pre_b[u] = *(const f32x4 *)(a.sin_t + r * half + j);
+      }
+    } else if constexpr (EPI == EPI_RESID) {
+      const int col = tile * TN + (tid % RES_LPR) * 4, colc = col < a.n_total ? col : 0;
+      pre_nw = *(const bf16x4 *)((const bf16 *)a.next_norm_w + colc);
+#pragma unroll
+      for (int u = 0; u < RES_UB; ++u)
+        pre_a[u] = *(const f32x4 *)(a.x_resid + (size_t)min(tid / RES_LPR + u * RES_RPP, a.rows - 1) * a.n_total + colc);
+    }
+  };
   const bool single = a.n_splits == 1;
   const size_t tile_elems = (size_t)a.rows_pad * TN;
   __syncthreads();   // every wavefront is done reading the last X stage
   if (single) {
+    preload();
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
@@ -120,6 +148,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, f32x16 (&acc)[M
         if (r < a.rows) st_agent(o + (size_t)r * TN, acc[mb][e]);
       }
     if (!publish_then_count(&a.counters[tile], a.n_splits, s_last)) return;
+    preload();
     // Last workgroup of the tile: sum the splits, in ascending order, into the LDS tile.  The
     // partial tiles were written through to memory (st_agent) and nobody on this chip has read
     // these lines before, so plain vector loads see them.  A memory round trip costs far more
@@ -164,16 +193,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, f32x16 (&acc)[M
     const int d = a.head_dim, half = d >> 1;
     const int n_q = a.n_q_heads, n_kv = a.n_kv_heads;
     constexpr int quads = TN / 8;                           // 4-pair groups per row
-    constexpr int PASSES = MB * 32 * quads / NT;
-    // the rotation tables of every pass first: one memory round trip instead of one per pass
-    f32x4 cs[PASSES], sn[PASSES];
-#pragma unroll
-    for (int u = 0; u < PASSES; ++u) {
-      const int t = tid + u * NT, r = min(t / quads, a.rows - 1), qi = t % quads;
-      const int j = qi * 4 - ((qi * 4) / half) * half;
-      cs[u] = *(const f32x4 *)(a.cos_t + r * half + j);
-      sn[u] = *(const f32x4 *)(a.sin_t + r * half + j);
-    }
+    constexpr int PASSES = QKV_PASSES;
 #pragma unroll
     for (int u = 0; u < PASSES; ++u) {
       const int t = tid + u * NT;
@@ -189,17 +209,21 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, f32x16 (&acc)[M
       const int b = r / a.n_nodes, node = r - b * a.n_nodes;
       const int slot = a.ctx.v[b] + node;
       if (hh < n_q + n_kv) {
-        const f32x4 rl = lo * cs[u] - hi * sn[u], rh = hi * cs[u] + lo * sn[u];
+        const f32x4 rl = lo * pre_a[u] - hi * pre_b[u], rh = hi * pre_a[u] + lo * pre_b[u];
         lo = rl; hi = rh;
       }
       *(f32x4 *)(a.qkv_f32 + (size_t)r * a.n_total + col) = lo;
       *(f32x4 *)(a.qkv_f32 + (size_t)r * a.n_total + col + half) = hi;
-      if (hh < n_q) {   // matrix-core operand of the context attention: bf16 hi + lo
+      if (hh < n_q) {
+        // matrix-core operand of the context attention: q * log2(e) / sqrt(d) as bf16 hi + lo, so
+        // that the scores come out of the MFMA ready for exp2
+        const float qs = 1.44269504088896f / sqrtf((float)d);
         bf16x4 lh, ll, hh4, hl4;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          lh[e] = (bf16)lo[e]; ll[e] = (bf16)(lo[e] - (float)lh[e]);
-          hh4[e] = (bf16)hi[e]; hl4[e] = (bf16)(hi[e] - (float)hh4[e]);
+          const float ql_ = lo[e] * qs, qh_ = hi[e] * qs;
+          lh[e] = (bf16)ql_; ll[e] = (bf16)(ql_ - (float)lh[e]);
+          hh4[e] = (bf16)qh_; hl4[e] = (bf16)(qh_ - (float)hh4[e]);
         }
         bf16 *qo = (bf16 *)a.q_out + (size_t)r * n_q * d + col;
         *(bf16x4 *)qo = lh;
@@ -252,20 +276,24 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, f32x16 (&acc)[M
   // ---- EPI_RESID: x += y; per-row sum of squares of the new x over this tile's columns.
   // TN/4 consecutive lanes (4 columns each) cover one row of the tile.
   {
-    constexpr int LPR = TN / 4, RPP = NT / LPR;   // lanes per row, rows per pass
-    constexpr int PASSES = MB * 32 / RPP, UB = PASSES < 8 ? PASSES : 8;
+    constexpr int LPR = RES_LPR, RPP = RES_RPP;   // lanes per row, rows per pass
+    constexpr int PASSES = RES_PASSES, UB = RES_UB;
     float *ssp = a.ss_part + (size_t)tile * a.rows_pad;
     const int c = (tid % LPR) * 4, col = tile * TN + c, r0 = tid / LPR;
     const bool col_ok = col < a.n_total;
     const int colc = col_ok ? col : 0;
-    const bf16x4 nw = *(const bf16x4 *)((const bf16 *)a.next_norm_w + colc);
+    const bf16x4 nw = pre_nw;
 #pragma unroll 1
     for (int ub = 0; ub < PASSES; ub += UB) {
-      // the residual rows of UB passes first: one memory round trip instead of one per pass
+      // the residual rows of UB passes at once (the first UB were fetched before the reduction)
       f32x4 xv[UB];
 #pragma unroll
-      for (int u = 0; u < UB; ++u)
-        xv[u] = *(const f32x4 *)(a.x_resid + (size_t)min(r0 + (ub + u) * RPP, a.rows - 1) * a.n_total + colc);
+      for (int u = 0; u < UB; ++u) xv[u] = pre_a[u];
+      if (ub > 0) {
+#pragma unroll
+        for (int u = 0; u < UB; ++u)
+          xv[u] = *(const f32x4 *)(a.x_resid + (size_t)min(r0 + (ub + u) * RPP, a.rows - 1) * a.n_total + colc);
+      }
 #pragma unroll
       for (int u = 0; u < UB; ++u) {
         const int r = r0 + (ub + u) * RPP;

@@ -10,14 +10,6 @@
 // evaluates them in fp32 straight from this pass's unrounded q/k/v projections (the cache gets
 // bf16 copies for later rounds, but the pass itself never reads them back) and folds them in as
 // one more softmax partial.
-// Context kernel:  The `group` query heads that
-// share the kv head, times the M nodes, form one panel of query rows; four wavefronts each own
-// up to two 32-row blocks of it.  Per 64-key tile, K and V^T are staged in LDS (double buffered),
-// S^T = K Q^T and O^T += V^T P^T run on the matrix cores in the transposed form, which puts one
-// query row per lane: the online-softmax max / sum are per-lane scalars plus one exchange between
-// the two lane halves.  Q and P are fed as a bf16 high part plus a bf16 low part (two MFMAs each),
-// so both products carry ~16 bits of the activation and the result is reproducible against an
-// unrounded reference; K and V are the bf16 values the cache stores.
 // A merge kernel combines the splits in ascending order.
 #include "device_util.hpp"
 
@@ -95,7 +87,8 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
   __shared__ __attribute__((aligned(16))) unsigned char lds[2 * L::kBuf];
   const int split = blockIdx.x, kvh = blockIdx.y;
   const int b = blockIdx.z / a.n_row_groups, rg = blockIdx.z - b * a.n_row_groups;   // sequence, group of 128 query rows
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: branches on it are wave-uniform
   const int ln = lane & 31, g = lane >> 5;
   const int M = a.n_nodes, group = a.n_q_heads / a.n_kv_heads;
   const int p_rows = group * M;
@@ -142,7 +135,6 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
 
   const bf16 *kc = (const bf16 *)a.k_cache + ((size_t)b * a.n_kv_heads + kvh) * a.capacity * D;
   const bf16 *vc = (const bf16 *)a.v_cache + ((size_t)b * a.n_kv_heads + kvh) * D * a.capacity;
-  const float scale = 1.0f / sqrtf((float)D);
 
   // ---- tile staging: K tile = KT rows of D*2 bytes (16-byte vectors), V^T tile = D rows of KT*2 bytes
   constexpr int KV_PER_T = KT * D * 2 / 16 / 256;   // 16-byte vectors per thread, each of K and V^T
@@ -161,11 +153,12 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
         uint4 t = *(const uint4 *)(vc + (size_t)f * a.capacity + k0 + c * 8);
         const int kfirst = k0 + c * 8;
         if (kfirst + 8 > n_keys) {   // zero the values of slots that hold no token
-          uint32_t w[4] = {t.x, t.y, t.z, t.w};
-#pragma unroll
-          for (int e = 0; e < 8; ++e)
-            if (kfirst + e >= n_keys) w[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
-          t = make_uint4(w[0], w[1], w[2], w[3]);
+          auto keep = [&](uint32_t x, int e0) {   // x holds keys kfirst + e0 (low half) and kfirst + e0 + 1
+            if (kfirst + e0 >= n_keys) x &= 0xffff0000u;
+            if (kfirst + e0 + 1 >= n_keys) x &= 0x0000ffffu;
+            return x;
+          };
+          t = make_uint4(keep(t.x, 0), keep(t.y, 2), keep(t.z, 4), keep(t.w, 6));
         }
         vreg[i] = t;
       }
@@ -238,7 +231,7 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
           const int key = k0 + ks * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
-          float v = s[ks][e] * scale;
+          float v = s[ks][e];   // q arrives pre-multiplied by log2(e) / sqrt(d)
           if (need_mask) v = (key < n_keys) ? v : -INFINITY;
           s[ks][e] = v;
           tmax = fmaxf(tmax, v);
@@ -246,7 +239,7 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
       tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
       const float m_new = fmaxf(m_run[i], tmax);
       const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = __expf(m_run[i] - m_safe);   // exp(-inf) = 0 on the first tile
+      const float alpha = __builtin_amdgcn_exp2f(m_run[i] - m_safe);   // exp2(-inf) = 0 on the first tile
       m_run[i] = m_new;
       float psum = 0.f;
       bf16x8 phi[KT / 16], plo[KT / 16];
@@ -254,7 +247,7 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
       for (int ks = 0; ks < KT / 32; ++ks)
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          const float p = __expf(s[ks][e] - m_safe);   // exp(-inf) = 0 for masked keys
+          const float p = __builtin_amdgcn_exp2f(s[ks][e] - m_safe);   // exp2(-inf) = 0 for masked keys
           psum += p;
           const bf16 hi = (bf16)p;
           const bf16 lo = (bf16)(p - (float)hi);
@@ -291,7 +284,7 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
     if (p >= p_rows) continue;
     const float l_tot = l_run[i] + __shfl_xor(l_run[i], 32, 64);
     if (g == 0) {
-      a.part_m[part_base * p_rows + p] = m_run[i];
+      a.part_m[part_base * p_rows + p] = m_run[i] * 0.693147180559945f;   // back to natural-log units
       a.part_l[part_base * p_rows + p] = l_tot;
     }
     float *o = a.part_o + (part_base * p_rows + p) * D;
@@ -311,113 +304,142 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
 // head — in ascending split order, with the draft-node part: for every ancestor-or-self j of the
 // node, score = q . k_j / sqrt(d) and value v_j, all taken in fp32 from this pass's projections
 // (a.qkv: [row][(nq + 2 nkv) * d], q and k already rotated).
-// Memory round trips, not arithmetic, set this kernel's time, so every phase issues its loads as
-// one independent batch: the ancestor list (at most 64 nodes) is scored by 64 x 4 threads at once
-// (thread = ancestor slot x quarter of the features), and the value sum walks the list four
-// ancestors at a time.
+// Memory round trips, not arithmetic, set this kernel's time, so there are only two of them:
+// (1) the ancestor mask, the query rows and the first 16 split partials of this thread's outputs;
+// (2) the keys and values of the ancestors.  Block = group * d / 2 threads, two adjacent output
+// features each; the ancestor list (at most 64 nodes) is scored by (slot x quarter of the
+// features) threads.
+constexpr int kMergePreV = 8;    // ancestors whose values are fetched ahead of the scores
 
 template <int D>
-__global__ __launch_bounds__(256) void k_attn_merge(AttnArgs a) {
+__global__ __launch_bounds__(512) void k_attn_merge(AttnArgs a) {
   __shared__ float s_q[kMaxGroup][D];
   __shared__ float s_sc[kMaxGroup][kMaxNodes];
   __shared__ int s_anc[kMaxNodes];
-  const int r = blockIdx.x, kvh = blockIdx.y, tid = threadIdx.x;
+  const int r = blockIdx.x, kvh = blockIdx.y, tid = threadIdx.x, nt = blockDim.x;
   const int M = a.n_nodes, group = a.n_q_heads / a.n_kv_heads;
   const int b = r / M, node = r - b * M;
   const int p_rows = group * M;
   const size_t base = ((size_t)b * a.n_kv_heads + kvh) * a.n_splits;
   const int n_total = (a.n_q_heads + 2 * a.n_kv_heads) * D;
+  const bool active = tid < group * D / 2;
+  const int al = active ? tid / (D / 2) : 0, f = active ? (tid - al * (D / 2)) * 2 : 0;   // head, first feature
+  const int p = al * M + node;
+
+  // ---- round trip 1
   const uint64_t mask = a.anc[r];          // bit j: node j is on the root path of this node (self included)
+  const float2 q2 = *(const float2 *)(a.qkv + (size_t)r * n_total + (size_t)(kvh * group + al) * D + f);
+  float pm[16], pl[16];
+  float2 po[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const size_t idx = (base + min(i, a.n_splits - 1)) * p_rows + p;
+    pm[i] = a.part_m[idx];
+    pl[i] = a.part_l[idx];
+    po[i] = *(const float2 *)(a.part_o + idx * D + f);
+  }
   const int n_anc = __popcll(mask);        // >= 1
-  const float scale = 1.0f / sqrtf((float)D);
   if (tid < kMaxNodes && ((mask >> tid) & 1ull)) s_anc[__popcll(mask & ((1ull << tid) - 1ull))] = tid;
-  for (int i = tid; i < group * D; i += 256)
-    s_q[i / D][i % D] = a.qkv[(size_t)r * n_total + (size_t)kvh * group * D + i];
+  if (active) { s_q[al][f] = q2.x; s_q[al][f + 1] = q2.y; }
   __syncthreads();
 
-  // ---- scores of the ancestor list
-  {
-    const int slot = tid >> 2, qq = tid & 3;
+  // ---- round trip 2: values of the first ancestors, keys of all of them
+  const float *vbase = a.qkv + (size_t)(a.n_q_heads + a.n_kv_heads + kvh) * D + f;
+  float2 vpre[kMergePreV];
+#pragma unroll
+  for (int i = 0; i < kMergePreV; ++i)
+    vpre[i] = *(const float2 *)(vbase + (size_t)(b * M + s_anc[min(i, n_anc - 1)]) * n_total);
+  const float scale = 1.0f / sqrtf((float)D);
+  for (int s0 = 0; s0 < n_anc; s0 += nt / 4) {
+    const int slot = s0 + (tid >> 2), qq = tid & 3;
     const int j = s_anc[min(slot, n_anc - 1)];
     const float *kp = a.qkv + (size_t)(b * M + j) * n_total + (size_t)(a.n_q_heads + kvh) * D + qq * (D / 4);
     f32x4 kv4[D / 16];
 #pragma unroll
     for (int i = 0; i < D / 16; ++i) kv4[i] = *(const f32x4 *)(kp + 4 * i);
-    for (int al = 0; al < group; ++al) {
+    for (int h = 0; h < group; ++h) {
       float acc = 0.f;
 #pragma unroll
       for (int i = 0; i < D / 16; ++i)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) acc += kv4[i][e] * s_q[al][qq * (D / 4) + 4 * i + e];
+        for (int e = 0; e < 4; ++e) acc += kv4[i][e] * s_q[h][qq * (D / 4) + 4 * i + e];
       acc += __shfl_xor(acc, 1, 64);
       acc += __shfl_xor(acc, 2, 64);
-      if (qq == 0 && slot < n_anc) s_sc[al][slot] = acc * scale;
+      if (qq == 0 && slot < n_anc) s_sc[h][slot] = acc * scale;
     }
   }
   __syncthreads();
+  if (!active) return;
 
-  // ---- one output feature of one query head at a time
-  for (int o_idx = tid; o_idx < group * D; o_idx += 256) {
-    const int al = o_idx / D, f = o_idx - al * D;
-    const int p = al * M + node;
-    float m_tot = -INFINITY;
-    for (int i = 0; i < n_anc; ++i) m_tot = fmaxf(m_tot, s_sc[al][i]);
-    // context splits, 16 at a time so that the loads of a group are in flight together
-    for (int s0 = 0; s0 < a.n_splits; s0 += 16) {
-      float pm[16];
+  float m_tot = -INFINITY;
+  for (int i = 0; i < n_anc; ++i) m_tot = fmaxf(m_tot, s_sc[al][i]);
 #pragma unroll
-      for (int i = 0; i < 16; ++i)
-        pm[i] = (s0 + i < a.n_splits) ? a.part_m[(base + s0 + i) * p_rows + p] : -INFINITY;
+  for (int i = 0; i < 16; ++i) m_tot = fmaxf(m_tot, (i < a.n_splits) ? pm[i] : -INFINITY);
+  for (int s0 = 16; s0 < a.n_splits; s0 += 16) {   // long contexts only
+    float t[16];
 #pragma unroll
-      for (int i = 0; i < 16; ++i) m_tot = fmaxf(m_tot, pm[i]);
-    }
-    float num = 0.f, den = 0.f;
-    for (int s0 = 0; s0 < a.n_splits; s0 += 16) {
-      float pm[16], pl[16], po[16];
+    for (int i = 0; i < 16; ++i) t[i] = (s0 + i < a.n_splits) ? a.part_m[(base + s0 + i) * p_rows + p] : -INFINITY;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const bool ok = s0 + i < a.n_splits;
-        const size_t idx = (base + (ok ? s0 + i : 0)) * p_rows + p;
-        pm[i] = ok ? a.part_m[idx] : -INFINITY;
-        pl[i] = a.part_l[idx];
-        po[i] = a.part_o[idx * D + f];
-      }
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        if (pm[i] == -INFINITY) continue;   // empty split: its o / l were never written
-        const float w = expf(pm[i] - m_tot);
-        num += po[i] * w;
-        den += pl[i] * w;
-      }
-    }
-    const float *vbase = a.qkv + (size_t)(a.n_q_heads + a.n_kv_heads + kvh) * D + f;
-    for (int i0 = 0; i0 < n_anc; i0 += 4) {
-      float vv[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        vv[i] = vbase[(size_t)(b * M + s_anc[min(i0 + i, n_anc - 1)]) * n_total];
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        if (i0 + i < n_anc) {
-          const float w = expf(s_sc[al][i0 + i] - m_tot);
-          num += w * vv[i];
-          den += w;
-        }
-    }
-    const float o = num / den;
-    const bf16 hi = (bf16)o;
-    bf16 *dst = (bf16 *)a.out;   // operand layout of the O projection; out_panel = number of 32-row blocks
-    const int kk = (kvh * group + al) * D + f;
-    dst[ol_offset(r, kk, 0, (int)a.out_panel)] = hi;
-    dst[ol_offset(r, kk, 1, (int)a.out_panel)] = (bf16)(o - (float)hi);
+    for (int i = 0; i < 16; ++i) m_tot = fmaxf(m_tot, t[i]);
   }
+  float num0 = 0.f, num1 = 0.f, den = 0.f;
+  for (int s0 = 0; s0 < a.n_splits; s0 += 16) {    // ascending split order
+    if (s0 > 0) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const size_t idx = (base + min(s0 + i, a.n_splits - 1)) * p_rows + p;
+        pm[i] = a.part_m[idx];
+        pl[i] = a.part_l[idx];
+        po[i] = *(const float2 *)(a.part_o + idx * D + f);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      if (s0 + i >= a.n_splits || pm[i] == -INFINITY) continue;   // empty split: its o / l were never written
+      const float w = expf(pm[i] - m_tot);
+      num0 += po[i].x * w;
+      num1 += po[i].y * w;
+      den += pl[i] * w;
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < kMergePreV; ++i)
+    if (i < n_anc) {
+      const float w = expf(s_sc[al][i] - m_tot);
+      num0 += w * vpre[i].x;
+      num1 += w * vpre[i].y;
+      den += w;
+    }
+  for (int i0 = kMergePreV; i0 < n_anc; i0 += 4) {
+    float2 vv[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      vv[i] = *(const float2 *)(vbase + (size_t)(b * M + s_anc[min(i0 + i, n_anc - 1)]) * n_total);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (i0 + i < n_anc) {
+        const float w = expf(s_sc[al][i0 + i] - m_tot);
+        num0 += w * vv[i].x;
+        num1 += w * vv[i].y;
+        den += w;
+      }
+  }
+  const float o0 = num0 / den, o1 = num1 / den;
+  const bf16 h0 = (bf16)o0, h1 = (bf16)o1;
+  bf16 *dst = (bf16 *)a.out;   // operand layout of the O projection; out_panel = number of 32-row blocks
+  const int kk = (kvh * group + al) * D + f;   // even: both features sit in the same 8-element run
+  bf16 *d0 = dst + ol_offset(r, kk, 0, (int)a.out_panel), *d1 = dst + ol_offset(r, kk, 1, (int)a.out_panel);
+  d0[0] = h0; d0[1] = h1;
+  d1[0] = (bf16)(o0 - (float)h0); d1[1] = (bf16)(o1 - (float)h1);
 }
 
 template <int D>
 static void launch_attn_bf16_d(hipStream_t st, const AttnArgs &a) {
   dim3 grid(a.n_splits, a.n_kv_heads, a.batch * a.n_row_groups);
   hipLaunchKernelGGL((k_attn_bf16<D, 1>), grid, dim3(256), 0, st, a);
-  hipLaunchKernelGGL(k_attn_merge<D>, dim3(a.batch * a.n_nodes, a.n_kv_heads), dim3(256), 0, st, a);
+  const int group = a.n_q_heads / a.n_kv_heads;
+  const int merge_threads = group * D / 2 < 64 ? 64 : group * D / 2;   // <= 512 (group <= 8, d <= 128)
+  hipLaunchKernelGGL(k_attn_merge<D>, dim3(a.batch * a.n_nodes, a.n_kv_heads), dim3(merge_threads), 0, st, a);
 }
 
 void launch_attn_bf16(hipStream_t st, const AttnArgs &a) {

@@ -127,7 +127,7 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(GemmArgs a) {
     const int k = rc(c) * KC + kb * 64;
     const bf16 *p = wrow + (size_t)((!RAGGED || k < klen) ? (k >> 6) : 0) * 2048;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) w[set][kb][j] = *(const bf16x8 *)(p + 512 * j);
+    for (int j = 0; j < 4; ++j) w[set][kb][j] = __builtin_nontemporal_load((const bf16x8 *)(p + 512 * j));
   };
   auto load_x = [&](int c) {
     const bool ok = !RAGGED || (c * KC < klen);
