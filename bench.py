@@ -111,6 +111,8 @@ def main():
     ap.add_argument("--seed", type=int, default=1003)
     ap.add_argument("--threshold", type=float, default=0.5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--launch", choices=("eager", "graph"), default="eager",
+                    help="graph: the pass is captured once into a HIP graph and the timed steps replay it")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs the verification pass on ONE GPU (no sharding, no collectives); "
@@ -130,12 +132,26 @@ def main():
     def step():
         ver.verify(kv, tok, parents, pos, args.threshold, want_logits=False)
 
+    timed_step = step
+    if args.launch == "graph":
+        # the library only launches kernels on the caller's stream (no allocation, no memset, no
+        # host synchronisation), so a pass can be captured as it is
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        timed_step = graph.replay
     for _ in range(args.warmup):
-        step()
+        timed_step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        timed_step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms = dt / args.steps * 1e3
@@ -190,7 +206,7 @@ def main():
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if shape.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "batch": batch, "ctx_len": ctx, "n_nodes": n_nodes,
-                   "tree": kind, "threshold": args.threshold},
+                   "tree": kind, "threshold": args.threshold, "launch": args.launch},
         "verify_latency_ms": ms,
         "pass_bytes": pass_bytes,
         "pass_achieved_GBs": pass_bytes / (ms * 1e-3) / 1e9,

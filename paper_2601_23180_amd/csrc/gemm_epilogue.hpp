@@ -294,14 +294,15 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, f32x16 (&acc)[M
         for (int u = 0; u < UB; ++u)
           xv[u] = *(const f32x4 *)(a.x_resid + (size_t)min(r0 + (ub + u) * RPP, a.rows - 1) * a.n_total + colc);
       }
+      float ss[UB];
 #pragma unroll
       for (int u = 0; u < UB; ++u) {
         const int r = r0 + (ub + u) * RPP;
-        float ss = 0.f;
+        ss[u] = 0.f;
         if (r < a.rows && col_ok) {
           const f32x4 v = xv[u] + reduced4(r, c);
           *(f32x4 *)(a.x_resid + (size_t)r * a.n_total + col) = v;
-          ss = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+          ss[u] = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
           // operand of the next matmul: x * (next RMSNorm weight), as bf16 hi + lo
           bf16x4 hi, lo;
 #pragma unroll
@@ -314,9 +315,16 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, f32x16 (&acc)[M
           *(bf16x4 *)(dst + ol_offset(r, col, 0, MB)) = hi;
           *(bf16x4 *)(dst + ol_offset(r, col, 1, MB)) = lo;
         }
+      }
+      // the UB row sums are reduced side by side, so the exchanges of one hide behind the others'
 #pragma unroll
-        for (int o = LPR / 2; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
-        if (tid % LPR == 0 && r < a.rows) ssp[r] = ss;   // read by the next kernel
+      for (int o = LPR / 2; o > 0; o >>= 1)
+#pragma unroll
+        for (int u = 0; u < UB; ++u) ss[u] += __shfl_xor(ss[u], o, 64);
+#pragma unroll
+      for (int u = 0; u < UB; ++u) {
+        const int r = r0 + (ub + u) * RPP;
+        if (tid % LPR == 0 && r < a.rows) ssp[r] = ss[u];   // read by the next kernel
       }
     }
   }
