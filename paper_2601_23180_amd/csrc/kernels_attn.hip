@@ -71,7 +71,7 @@ void launch_attn_f32(hipStream_t st, const AttnArgs &a) {
 }
 
 // ------------------------------------------------------------------ bf16 path
-constexpr int KT = 64;                      // keys per tile
+constexpr int KT = 128;                     // keys per tile
 template <int D>
 struct AttnLds {
   static constexpr int kStrideK = D * 2 + 16;     // bytes per key row of the K tile
@@ -145,13 +145,13 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
       const int v = tid + 256 * i;
       {  // K: vector v -> key v / (D/8), 16-byte column v % (D/8)
         const int key = v / (D / 8), c = v % (D / 8);
-        // slots past n_keys are never written; they stay in bounds (capacity is a multiple of KT)
-        kreg[i] = *(const uint4 *)(kc + (size_t)(k0 + key) * D + c * 8);
+        // rows past the context hold no token (their scores are masked); clamped into the cache
+        kreg[i] = *(const uint4 *)(kc + (size_t)min(k0 + key, a.capacity - 1) * D + c * 8);
       }
       {  // V^T: vector v -> feature v / (KT/8), 8 keys starting at (v % (KT/8)) * 8
         const int f = v / (KT / 8), c = v % (KT / 8);
-        uint4 t = *(const uint4 *)(vc + (size_t)f * a.capacity + k0 + c * 8);
         const int kfirst = k0 + c * 8;
+        uint4 t = *(const uint4 *)(vc + (size_t)f * a.capacity + min(kfirst, a.capacity - 8));
         if (kfirst + 8 > n_keys) {   // zero the values of slots that hold no token
           auto keep = [&](uint32_t x, int e0) {   // x holds keys kfirst + e0 (low half) and kfirst + e0 + 1
             if (kfirst + e0 >= n_keys) x &= 0xffff0000u;
@@ -206,7 +206,7 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
     if (t + 1 < n_tiles) load_tile(k0 + KT);
     const unsigned char *kb = lds + buf * L::kBuf;
     const unsigned char *vb = kb + L::kBytesK;
-    const bool need_mask = (k0 + KT > n_keys);
+    const bool need_mask = (k0 + KT > k_end);   // ragged end of the context or of this split
 
 #pragma unroll
     for (int i = 0; i < RBW; ++i) {
@@ -232,7 +232,7 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
         for (int e = 0; e < 16; ++e) {
           const int key = k0 + ks * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
           float v = s[ks][e];   // q arrives pre-multiplied by log2(e) / sqrt(d)
-          if (need_mask) v = (key < n_keys) ? v : -INFINITY;
+          if (need_mask) v = (key < k_end) ? v : -INFINITY;
           s[ks][e] = v;
           tmax = fmaxf(tmax, v);
         }

@@ -339,16 +339,29 @@ void launch_decide(hipStream_t st, const DecideArgs &a) {
   hipLaunchKernelGGL(k_decide, dim3(a.batch), dim3(64), 0, st, a);
 }
 
-// Plain streaming copy, 16 bytes per thread per step, grid-stride.
-__global__ __launch_bounds__(256) void k_copy_probe(uint4 *dst, const uint4 *src, size_t n) {
-  const size_t stride = (size_t)gridDim.x * 256;
-  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+// Plain streaming copy: grid-stride over blocks of 4 x 256 16-byte vectors, four independent
+// loads in flight per thread before the stores.
+__global__ __launch_bounds__(256) void k_copy_probe(uint4 *dst_, const uint4 *src_, size_t n) {
+  typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+  u32x4 *dst = (u32x4 *)dst_;
+  const u32x4 *src = (const u32x4 *)src_;
+  const size_t stride = (size_t)gridDim.x * 1024;
+  size_t i = (size_t)blockIdx.x * 1024 + threadIdx.x;
+  for (; i + 768 < n; i += stride) {
+    const u32x4 a = __builtin_nontemporal_load(src + i), b = __builtin_nontemporal_load(src + i + 256);
+    const u32x4 c = __builtin_nontemporal_load(src + i + 512), d = __builtin_nontemporal_load(src + i + 768);
+    __builtin_nontemporal_store(a, dst + i);
+    __builtin_nontemporal_store(b, dst + i + 256);
+    __builtin_nontemporal_store(c, dst + i + 512);
+    __builtin_nontemporal_store(d, dst + i + 768);
+  }
+  for (; i < n; i += 256) dst[i] = src[i];   // ragged end of the last block
 }
 
 void launch_copy_probe(hipStream_t st, void *dst, const void *src, size_t bytes) {
   const size_t n = bytes / 16;
-  size_t blocks = (n + 255) / 256;
-  if (blocks > 256 * 32) blocks = 256 * 32;
+  size_t blocks = (n + 1023) / 1024;
+  if (blocks > 256 * 16) blocks = 256 * 16;
   if (blocks < 1) blocks = 1;
   hipLaunchKernelGGL(k_copy_probe, dim3((unsigned)blocks), dim3(256), 0, st, (uint4 *)dst, (const uint4 *)src, n);
 }

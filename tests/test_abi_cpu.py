@@ -128,3 +128,13 @@ def test_verify_rejects_bad_arguments_before_any_launch():
     lib.trispec_kv_destroy(kv)
     lib.trispec_model_destroy(m)
     lib.trispec_model_destroy(m2)
+
+
+def test_copy_probe_rejects_bad_arguments_before_any_launch():
+    lib = B.lib()
+    assert lib.trispec_copy_probe(None, 0x1000, 1024, None) == lib.trispec_copy_probe(0x1000, None, 1024, None) < 0
+    bad_size = lib.trispec_copy_probe(0x1000, 0x2000, 1000, None)       # not a multiple of 16
+    bad_align = lib.trispec_copy_probe(0x1008, 0x2000, 1024, None)      # misaligned pointer
+    zero = lib.trispec_copy_probe(0x1000, 0x2000, 0, None)
+    assert bad_size == bad_align == zero < 0
+    assert b"argument" in lib.trispec_strerror(bad_size)

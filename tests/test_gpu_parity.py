@@ -220,3 +220,14 @@ def test_case2_prune_and_reroot_target_pass():
     assert want["accepted_len"] >= 3 and want["escalate"] == 0          # the rest of the planted path
     assert gpu["accepted_len"][0] == want["accepted_len"] and gpu["token"][0] == want["token"]
     assert [int(v) for v in gpu["path"][0] if v >= 0][0] == pr["n_forced"] - 1
+
+
+def test_copy_probe_copies_exactly():
+    """The calibration copy moves every byte, including a ragged last block."""
+    from paper_2601_23180_amd import copy_probe
+    for n_vec in (1, 255, 1024, 5 * 1024 + 3, (1 << 20) + 777):
+        src = torch.randint(-2 ** 31, 2 ** 31 - 1, (n_vec * 4,), dtype=torch.int32, device="cuda")
+        dst = torch.zeros_like(src)
+        copy_probe(dst, src)
+        torch.cuda.synchronize()
+        assert torch.equal(dst, src), n_vec
