@@ -120,8 +120,11 @@ def case_cfg3(log):
 
 def case_cfg4(log):
     """Proxy pass on the full tree; for every (criterion, threshold) of the sweep the oracle's
-    decision; for every distinct escalation the pruned / re-rooted target pass (Eq. 10)."""
-    pshape, tshape, seed, tseed, ctx = SHAPES["qwen3_1p7b"], SHAPES["qwen3_8b"], 1004, 1014, 8192
+    decision; for every distinct escalation the pruned / re-rooted target pass (Eq. 10).
+    Seed 2004 rather than 1004: with it the oracle's proxy is confident at the root (top-1
+    probability 0.905), so the sweep escalates part-way down the planted path and the target pass
+    sees a pruned tree with a forced chain, not only the whole tree."""
+    pshape, tshape, seed, tseed, ctx = SHAPES["qwen3_1p7b"], SHAPES["qwen3_8b"], 2004, 2014, 8192
     parents = gen_tree(60, 8, 4, seed)
     tokens = gen_draft_tokens(parents, pshape.vocab, seed)
     positions = (ctx + tree_depths(parents)).astype(np.int32)
