@@ -134,6 +134,22 @@ int trispec_kv_create(const trispec_model *m, void *k_dev, void *v_dev, int32_t 
 int trispec_kv_set_len(trispec_kv *kv, const int32_t *ctx_len_host);
 int trispec_kv_destroy(trispec_kv *kv);
 
+/* Makes a verified path part of the context (Sec. 2.1 / Alg. 1: after a round the accepted
+ * prefix is appended to the sequence; the token the verifier adds on top becomes the root of
+ * the next round and is not cached yet).  For every sequence b the K/V rows that the last
+ * trispec_verify wrote at slots ctx_len[b] + nodes[b][i], i < n_commit[b], are moved to slots
+ * ctx_len[b] + i in every layer, and ctx_len[b] grows by n_commit[b] (on return, on the host;
+ * the move itself is queued on `stream`, so later calls on that stream see it).
+ *   nodes_host     HOST [batch][TRISPEC_PATH_STRIDE]: node ids in path order, strictly
+ *                  increasing (root first: the forced chain, then the approved drafts — the
+ *                  `path` output of trispec_verify, preceded by nodes 0..n_forced-2)
+ *   n_commit_host  HOST [batch]: 0 .. TRISPEC_MAX_NODES
+ * Errors: TRISPEC_ENULL, TRISPEC_ENODES (count out of range), TRISPEC_ETREE (ids not strictly
+ * increasing or not below TRISPEC_MAX_NODES), TRISPEC_ECAPACITY, TRISPEC_ELAUNCH.  On error
+ * nothing is changed. */
+int trispec_kv_commit(trispec_kv *kv, const int32_t *nodes_host, const int32_t *n_commit_host,
+                      void *stream);
+
 /* Device scratch needed by trispec_verify for up to `batch` sequences of up to
  * `max_nodes` nodes (256-byte aligned buffer).  Errors: TRISPEC_ENULL, TRISPEC_ENODES. */
 int trispec_workspace_bytes(const trispec_model *m, int32_t batch, int32_t max_nodes,

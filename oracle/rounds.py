@@ -1,0 +1,74 @@
+"""Oracle: committing a verified path to the cache and running several rounds.  Test infrastructure.
+
+Standard speculative decoding (paper Sec. 2.1; Alg. 1 in the appendix) appends, after every
+round, the accepted draft prefix and one more token from the verifier (the correction at the
+first mismatch, or the bonus token after a fully accepted draft) to the output sequence.  In
+cache terms: the root of the round (the last emitted token, whose keys / values were not cached
+yet) and the accepted drafts become context; the extra token is the next round's root.
+"""
+from __future__ import annotations
+
+from typing import Callable, Dict, List, Sequence, Tuple
+
+import numpy as np
+
+from .decision import CRIT_MARGIN, decide, node_stats
+from .forward import OracleWeights, causal_forward, verify_forward
+
+
+def commit(k_ctx: np.ndarray, v_ctx: np.ndarray, k_new: np.ndarray, v_new: np.ndarray,
+           nodes: Sequence[int]) -> Tuple[np.ndarray, np.ndarray]:
+    """Cache after a round.  k_ctx, v_ctx: [L, n_kv, C, d]; k_new, v_new: [L, n_kv, M, d] as the
+    verification pass appends them (rounded to the storage type); nodes: the root and the
+    approved drafts in path order.  Returns caches of length C + len(nodes)."""
+    idx = np.asarray(list(nodes), dtype=np.int64)
+    return (np.concatenate([k_ctx, k_new[:, :, idx, :]], axis=2),
+            np.concatenate([v_ctx, v_new[:, :, idx, :]], axis=2))
+
+
+def greedy_decode(W: OracleWeights, shape, prompt: Sequence[int], n_new: int) -> List[int]:
+    """Plain autoregressive greedy decoding, no cache: the textbook definition the rounds are
+    pinned to.  (For bf16 storage every earlier token counts as cached when the next is computed.)"""
+    seq = [int(t) for t in prompt]
+    for _ in range(n_new):
+        lg = causal_forward(W, shape, seq, last_only=True, n_cached=len(seq) - 1)["logits"][0]
+        seq.append(int(np.argmax(lg)))
+    return seq
+
+
+def verify_rounds(W: OracleWeights, shape, prompt: Sequence[int],
+                  draft_fn: Callable[[int, List[int]], Tuple[np.ndarray, np.ndarray]],
+                  n_rounds: int, lam: float = 0.0, criterion: int = CRIT_MARGIN) -> Dict[str, list]:
+    """Rounds of draft -> verify -> commit with ONE verifier.
+
+    draft_fn(round, sequence so far) -> (parents [M], tokens [M]); tokens[0] is overwritten with
+    the round's root (the last emitted token).  With lam = 0 the margin test never fires and every
+    round is standard greedy acceptance, so the emitted sequence equals greedy_decode's.
+    If a round escalates (lam > 0) the loop stops there: what follows needs the target.
+    Returns the sequence, and per round the decision and the cache length before it."""
+    seq = [int(t) for t in prompt]
+    pre = causal_forward(W, shape, seq[:-1]) if len(seq) > 1 else None
+    L, nkv, d = shape.n_layers, shape.n_kv_heads, shape.head_dim
+    k_ctx = pre["K"] if pre is not None else np.zeros((L, nkv, 0, d))
+    v_ctx = pre["V"] if pre is not None else np.zeros((L, nkv, 0, d))
+    rounds = []
+    for r in range(n_rounds):
+        parents, tokens = draft_fn(r, seq)
+        parents = np.asarray(parents, dtype=np.int32)
+        tokens = np.asarray(tokens, dtype=np.int32).copy()
+        tokens[0] = seq[-1]
+        depth = np.zeros(len(parents), dtype=np.int64)
+        for i in range(1, len(parents)):
+            depth[i] = depth[parents[i]] + 1
+        C = k_ctx.shape[2]
+        out = verify_forward(W, shape, k_ctx, v_ctx, tokens, parents, C + depth)
+        st = node_stats(out["logits"])
+        dec = decide(tokens, parents, st["argmax"], st["conf"], st["margin"], lam, criterion, 1)
+        rounds.append({"ctx_len": C, "tokens": tokens, "parents": parents, "decision": dec, "stats": st})
+        path = [int(v) for v in dec["path"]]
+        k_ctx, v_ctx = commit(k_ctx, v_ctx, out["k_new"], out["v_new"], path)
+        seq += [int(tokens[i]) for i in path[1:]]
+        if dec["escalate"]:
+            break
+        seq.append(int(dec["token"]))
+    return {"sequence": seq, "rounds": rounds, "k_ctx": k_ctx, "v_ctx": v_ctx}

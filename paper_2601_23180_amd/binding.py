@@ -27,6 +27,7 @@ EXPORTS = [
     "trispec_workspace_region", "trispec_pass_bytes", "trispec_verify", "trispec_decide",
     "trispec_strerror", "trispec_timer_create", "trispec_timer_reset", "trispec_timer_read",
     "trispec_timer_destroy", "trispec_model_pack_bytes", "trispec_model_pack", "trispec_copy_probe",
+    "trispec_kv_commit",
 ]
 K_GEMM, K_HEAD, K_ATTN = 0, 1, 2
 
@@ -91,6 +92,7 @@ def lib() -> C.CDLL:
         l.trispec_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
         l.trispec_workspace_region.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_char_p,
                                                C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
+        l.trispec_kv_commit.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_void_p]
         l.trispec_copy_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         l.trispec_pass_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_int32),
                                          C.POINTER(C.c_double)]
@@ -217,6 +219,18 @@ class KVCache:
         arr = (C.c_int32 * self.batch)(*ctx_len)
         check(lib().trispec_kv_set_len(self.handle, arr))
         self.ctx_len = list(ctx_len)
+
+    def commit(self, nodes: Sequence[Sequence[int]], stream=None) -> None:
+        """trispec_kv_commit: nodes[b] = node ids of sequence b's verified path, root first."""
+        arr = (C.c_int32 * (self.batch * PATH_STRIDE))()
+        cnt = (C.c_int32 * self.batch)()
+        for b, p in enumerate(nodes):
+            cnt[b] = len(p)
+            for i, v in enumerate(p):
+                arr[b * PATH_STRIDE + i] = int(v)
+        st = (stream if stream is not None else torch.cuda.current_stream()).cuda_stream
+        check(lib().trispec_kv_commit(self.handle, arr, cnt, st))
+        self.ctx_len = [c + len(p) for c, p in zip(self.ctx_len, nodes)]
 
     def close(self):
         if self.handle:

@@ -737,6 +737,35 @@ int trispec_timer_destroy(trispec_timer *t) {
   return TRISPEC_OK;
 }
 
+int trispec_kv_commit(trispec_kv *kv, const int32_t *nodes_host, const int32_t *n_commit_host, void *stream) {
+  if (!kv || !nodes_host || !n_commit_host) return TRISPEC_ENULL;
+  const trispec_model_config &c = kv->model->cfg;
+  CommitTable t;
+  memset(&t, 0, sizeof(t));
+  int any = 0;
+  for (int b = 0; b < kv->batch; ++b) {
+    const int n = n_commit_host[b];
+    if (n < 0 || n > kMaxNodes) return TRISPEC_ENODES;
+    const int32_t *p = nodes_host + (size_t)b * TRISPEC_PATH_STRIDE;
+    for (int i = 0; i < n; ++i) {
+      if (p[i] < 0 || p[i] >= kMaxNodes || (i > 0 && p[i] <= p[i - 1])) return TRISPEC_ETREE;
+      t.node[b][i] = (uint8_t)p[i];
+    }
+    if (n > 0 && kv->ctx_len[b] + p[n - 1] >= kv->capacity) return TRISPEC_ECAPACITY;
+    t.n[b] = n;
+    t.ctx[b] = kv->ctx_len[b];
+    any |= n;
+  }
+  if (any) {
+    (void)hipGetLastError();
+    launch_kv_commit((hipStream_t)stream, c.dtype, kv->k, kv->v, c.n_layers, kv->batch, c.n_kv_heads, c.head_dim,
+                     kv->capacity, t);
+    if (hipGetLastError() != hipSuccess) return TRISPEC_ELAUNCH;
+  }
+  for (int b = 0; b < kv->batch; ++b) kv->ctx_len[b] += t.n[b];
+  return TRISPEC_OK;
+}
+
 int trispec_copy_probe(void *dst_dev, const void *src_dev, size_t bytes, void *stream) {
   if (!dst_dev || !src_dev) return TRISPEC_ENULL;
   if (bytes == 0 || bytes % 16 || ((((uintptr_t)dst_dev) | ((uintptr_t)src_dev)) & 15)) return TRISPEC_EARG;

@@ -136,6 +136,14 @@ void launch_rope_table(hipStream_t st, const int32_t *positions, int rows, int h
 void launch_embed_norm(hipStream_t st, int dtype, const int32_t *tokens, const void *embed,
                        const void *norm_w, int rows, int hidden, int vocab, float eps, float *x,
                        void *h, size_t h_panel, float *ss_out, int32_t *status);
+// nodes / counts of a commit, by value
+struct CommitTable {
+  uint8_t node[kMaxBatch][kMaxNodes];
+  int32_t n[kMaxBatch];
+  int32_t ctx[kMaxBatch];
+};
+void launch_kv_commit(hipStream_t st, int dtype, void *k_cache, void *v_cache, int n_layers, int batch,
+                      int n_kv_heads, int head_dim, int capacity, const CommitTable &t);
 void launch_copy_probe(hipStream_t st, void *dst, const void *src, size_t bytes);
 void launch_zero_counters(hipStream_t st, int32_t *counters, int n_counters);
 void launch_qkv_epilogue(hipStream_t st, int dtype, const float *part, int n_splits, int rows,

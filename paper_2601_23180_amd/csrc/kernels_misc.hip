@@ -366,4 +366,55 @@ void launch_copy_probe(hipStream_t st, void *dst, const void *src, size_t bytes)
   hipLaunchKernelGGL(k_copy_probe, dim3((unsigned)blocks), dim3(256), 0, st, (uint4 *)dst, (const uint4 *)src, n);
 }
 
+// Commit of a verified path: per (kv head, sequence, layer) the K rows and the V^T columns of the
+// path's nodes move from slot ctx + node[i] to slot ctx + i.  node[i] >= i, so a destination may
+// be another row's source: everything is read into registers, then a barrier, then written.
+template <typename T>
+__global__ __launch_bounds__(256) void k_kv_commit(T *k_cache, T *v_cache, int batch, int n_kv_heads, int d,
+                                                    int capacity, CommitTable t) {
+  const int h = blockIdx.x, b = blockIdx.y, l = blockIdx.z, tid = threadIdx.x;
+  const int n = t.n[b], ctx = t.ctx[b];
+  if (n == 0) return;   // uniform over the workgroup
+  T *kc = k_cache + (((size_t)l * batch + b) * n_kv_heads + h) * (size_t)capacity * d;
+  T *vc = v_cache + (((size_t)l * batch + b) * n_kv_heads + h) * (size_t)d * capacity;
+  constexpr int VEC = 16 / sizeof(T);                       // elements per 16-byte vector
+  constexpr int MAXV = kMaxNodes * 128 / VEC / 256;         // vectors per thread at d = 128
+  constexpr int MAXE = kMaxNodes * 128 / 256;               // V^T elements per thread at d = 128
+  const int vec_per_row = d / VEC;
+  uint4 kv[MAXV];
+  T ve[MAXE];
+#pragma unroll
+  for (int u = 0; u < MAXV; ++u) {
+    const int idx = tid + 256 * u, i = idx / vec_per_row, c = idx - i * vec_per_row;
+    if (i < n) kv[u] = *(const uint4 *)(kc + (size_t)(ctx + t.node[b][i]) * d + c * VEC);
+  }
+#pragma unroll
+  for (int u = 0; u < MAXE; ++u) {
+    const int idx = tid + 256 * u, f = idx / kMaxNodes, i = idx - f * kMaxNodes;   // 64 consecutive threads: one feature
+    if (f < d && i < n) ve[u] = vc[(size_t)f * capacity + ctx + t.node[b][i]];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int u = 0; u < MAXV; ++u) {
+    const int idx = tid + 256 * u, i = idx / vec_per_row, c = idx - i * vec_per_row;
+    if (i < n) *(uint4 *)(kc + (size_t)(ctx + i) * d + c * VEC) = kv[u];
+  }
+#pragma unroll
+  for (int u = 0; u < MAXE; ++u) {
+    const int idx = tid + 256 * u, f = idx / kMaxNodes, i = idx - f * kMaxNodes;
+    if (f < d && i < n) vc[(size_t)f * capacity + ctx + i] = ve[u];
+  }
+}
+
+void launch_kv_commit(hipStream_t st, int dtype, void *k_cache, void *v_cache, int n_layers, int batch,
+                      int n_kv_heads, int head_dim, int capacity, const CommitTable &t) {
+  dim3 grid(n_kv_heads, batch, n_layers);
+  if (dtype == TRISPEC_F32)
+    hipLaunchKernelGGL(k_kv_commit<float>, grid, dim3(256), 0, st, (float *)k_cache, (float *)v_cache, batch,
+                       n_kv_heads, head_dim, capacity, t);
+  else
+    hipLaunchKernelGGL(k_kv_commit<bf16>, grid, dim3(256), 0, st, (bf16 *)k_cache, (bf16 *)v_cache, batch,
+                       n_kv_heads, head_dim, capacity, t);
+}
+
 }  // namespace ts

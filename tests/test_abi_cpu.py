@@ -138,3 +138,27 @@ def test_copy_probe_rejects_bad_arguments_before_any_launch():
     zero = lib.trispec_copy_probe(0x1000, 0x2000, 0, None)
     assert bad_size == bad_align == zero < 0
     assert b"argument" in lib.trispec_strerror(bad_size)
+
+
+def test_kv_commit_rejects_bad_arguments_before_any_launch():
+    lib = B.lib()
+    rc, m, keep = _model()
+    kv = C.c_void_p()
+    assert lib.trispec_kv_create(m, 0x4000, 0x8000, 1, 256, C.byref(kv)) == 0
+    assert lib.trispec_kv_set_len(kv, (C.c_int32 * 1)(250)) == 0
+
+    def commit(nodes, n):
+        arr = (C.c_int32 * B.PATH_STRIDE)(*nodes)
+        return lib.trispec_kv_commit(kv, arr, (C.c_int32 * 1)(n), None)
+
+    assert lib.trispec_kv_commit(kv, None, (C.c_int32 * 1)(0), None) == -1
+    assert commit([0, 1], 65) == -3                     # count out of range
+    assert commit([0, 1], -1) == -3
+    assert commit([0, 2, 2], 3) == -4                   # not strictly increasing
+    assert commit([1, 0], 2) == -4
+    assert commit([0, 64], 2) == -4                     # node id out of range
+    assert commit([0, 3, 6], 3) == -6                   # 250 + 6 >= 256
+    assert commit([], 0) == 0                           # nothing to move: no launch, length unchanged
+    assert _verify_rc(m, kv, list(range(-1, 6)), 7) == -6   # still 250 cached: 250 + 7 > 256
+    lib.trispec_kv_destroy(kv)
+    lib.trispec_model_destroy(m)

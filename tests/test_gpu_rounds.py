@@ -1,0 +1,121 @@
+"""GPU: committing a verified path (trispec_kv_commit) and several rounds of
+draft -> verify -> commit through the C ABI, against the oracle's rounds (Sec. 2.1, Alg. 1)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import CRIT_MARGIN, greedy_decode, tie_flags, verify_rounds
+from paper_2601_23180_amd import KVCache, Verifier
+from workloads import SHAPES, gen_chain, gen_context_tokens, gen_draft_tokens, gen_tree, tree_depths
+
+from gpu_helpers import capacity_for, device_model
+from helpers import oracle_weights, prefill
+
+pytestmark = pytest.mark.gpu
+
+
+def mixed_drafts(W, shape, seed, n_nodes):
+    """Seeded trees; along the path to the deepest leaf the first r drafts are the oracle's own
+    greedy continuation (r varies per round), so accepted lengths cover 0 .. depth."""
+    def fn(r, seq):
+        parents = gen_tree(n_nodes, 5, 3, seed + r)
+        tokens = gen_draft_tokens(parents, shape.vocab, seed + 17 * r)
+        depth = tree_depths(parents)
+        leaf = int(np.argmax(depth))
+        path = [leaf]
+        while parents[path[-1]] >= 0:
+            path.append(int(parents[path[-1]]))
+        path = path[::-1]
+        n_right = (r * 2) % len(path)
+        cont = greedy_decode(W, shape, seq, n_right)[len(seq):]
+        for node, tok in zip(path[1:], cont):
+            tokens[node] = tok
+            # keep siblings distinct
+            for s in np.nonzero(parents == parents[node])[0]:
+                if s != node and tokens[s] == tok:
+                    tokens[s] = (tok + 1) % shape.vocab
+        return parents, tokens
+    return fn
+
+
+def gpu_rounds(shape, seed, prompt, draft_fn, n_rounds, n_nodes):
+    model = device_model(shape, seed)
+    K, V = prefill(shape, seed, prompt[:-1])
+    C0 = len(prompt) - 1
+    kv = KVCache(model, 1, capacity_for(C0 + n_rounds * n_nodes + n_nodes))
+    kv.k.fill_(float("nan")); kv.v.fill_(float("nan"))
+    kv.k[:, 0, :, :C0, :] = torch.from_numpy(np.asarray(K, dtype=np.float32)).cuda().to(kv.k.dtype)
+    kv.v[:, 0, :, :, :C0] = torch.from_numpy(np.asarray(V, dtype=np.float32)).cuda().to(kv.v.dtype).transpose(-1, -2)
+    kv.set_len([C0])
+    ver = Verifier(model, 1, n_nodes)
+    seq = [int(t) for t in prompt]
+    rounds = []
+    for r in range(n_rounds):
+        parents, tokens = draft_fn(r, seq)
+        tokens = np.asarray(tokens, dtype=np.int32).copy()
+        tokens[0] = seq[-1]
+        C = kv.ctx_len[0]
+        pos = (C + tree_depths(parents)).astype(np.int32)
+        out = ver.verify(kv, torch.from_numpy(tokens[None]).cuda(), parents[None], torch.from_numpy(pos[None]).cuda(),
+                         0.0, CRIT_MARGIN, 1, want_logits=False)
+        torch.cuda.synchronize()
+        path = [int(v) for v in out["path"][0].cpu().numpy() if v >= 0]
+        rounds.append({"ctx_len": C, "accepted_len": int(out["accepted_len"][0]), "token": int(out["token"][0]),
+                       "escalate": int(out["escalate"][0]), "path": path})
+        kv.commit([path])
+        seq += [int(tokens[i]) for i in path[1:]] + [int(out["token"][0])]
+    torch.cuda.synchronize()
+    return seq, rounds, kv
+
+
+@pytest.mark.parametrize("shape_name,seed", [("tiny", 3), ("tiny_bf16", 4)])
+def test_rounds_match_the_oracle_and_greedy_decoding(shape_name, seed):
+    shape, n_nodes, n_rounds = SHAPES[shape_name], 12, 5
+    W = oracle_weights(shape, seed)
+    prompt = gen_context_tokens(shape.vocab, 20, seed).tolist()
+    fn = mixed_drafts(W, shape, seed, n_nodes)
+    want = verify_rounds(W, shape, prompt, fn, n_rounds)
+    seq, rounds, kv = gpu_rounds(shape, seed, prompt, fn, n_rounds, n_nodes)
+    # a tie inside 1e-3 on a node the walk touches may change a round (and everything after it)
+    for r, (g, w) in enumerate(zip(rounds, want["rounds"])):
+        d = w["decision"]
+        same = (g["accepted_len"] == d["accepted_len"] and g["token"] == d["token"] and g["path"] == [int(v) for v in d["path"]])
+        if not same:
+            flags = tie_flags(w["stats"], 0.0, CRIT_MARGIN)
+            assert any(flags[i] for i in set(g["path"]) | set(int(v) for v in d["path"])), (r, g, d)
+            pytest.skip("tie inside the tolerance changed a round")
+        assert g["ctx_len"] == w["ctx_len"] and g["escalate"] == 0
+    assert seq == want["sequence"]
+    assert max(g["accepted_len"] for g in rounds) >= 3            # the planted prefixes were accepted and committed
+    if shape.dtype == "f32":
+        assert seq == greedy_decode(W, shape, prompt, len(seq) - len(prompt))
+    # the committed cache is the oracle's committed cache (bf16: half an ulp where a value sits on a boundary)
+    Cn = kv.ctx_len[0]
+    assert Cn == want["k_ctx"].shape[2]
+    kg = kv.k[:, 0, :, :Cn, :].float().cpu().numpy()
+    vg = kv.v[:, 0, :, :, :Cn].float().cpu().numpy().transpose(0, 1, 3, 2)
+    tol = (lambda w: 1e-4) if shape.dtype == "f32" else (lambda w: np.abs(w) * 2 ** -7 + 1e-4)
+    assert np.all(np.abs(kg - want["k_ctx"]) <= tol(want["k_ctx"]))
+    assert np.all(np.abs(vg - want["v_ctx"]) <= tol(want["v_ctx"]))
+
+
+def test_commit_moves_exactly_the_path_rows():
+    shape, seed, n_nodes = SHAPES["tiny_bf16"], 9, 20
+    model = device_model(shape, seed)
+    kv = KVCache(model, 2, 128)
+    g = torch.Generator(device="cuda").manual_seed(1)
+    kv.k.copy_(torch.randn(kv.k.shape, device="cuda", generator=g).to(kv.k.dtype))
+    kv.v.copy_(torch.randn(kv.v.shape, device="cuda", generator=g).to(kv.v.dtype))
+    k0, v0 = kv.k.clone(), kv.v.clone()
+    kv.set_len([40, 17])
+    paths = [[0, 3, 4, 11, 19], [2]]
+    kv.commit(paths)
+    torch.cuda.synchronize()
+    assert kv.ctx_len == [45, 18]
+    for b, (C, p) in enumerate(zip([40, 17], paths)):
+        for i, n in enumerate(p):
+            assert torch.equal(kv.k[:, b, :, C + i, :], k0[:, b, :, C + n, :])
+            assert torch.equal(kv.v[:, b, :, :, C + i], v0[:, b, :, :, C + n])
+        untouched = [s for s in range(128) if not (C <= s < C + len(p))]
+        assert torch.equal(kv.k[:, b, :, untouched, :], k0[:, b, :, untouched, :])
+        assert torch.equal(kv.v[:, b, :, :, untouched], v0[:, b, :, :, untouched])
