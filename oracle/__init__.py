@@ -32,4 +32,4 @@ from .decision import (  # noqa: F401
     tie_flags,
     prune_reroot,
 )
-from .rounds import commit, greedy_decode, verify_rounds  # noqa: F401
+from .rounds import commit, greedy_decode, trispec_rounds, verify_rounds  # noqa: F401

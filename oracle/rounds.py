@@ -72,3 +72,82 @@ def verify_rounds(W: OracleWeights, shape, prompt: Sequence[int],
             break
         seq.append(int(dec["token"]))
     return {"sequence": seq, "rounds": rounds, "k_ctx": k_ctx, "v_ctx": v_ctx}
+
+
+def trispec_rounds(Wp: OracleWeights, shape_p, Wt: OracleWeights, shape_t, prompt: Sequence[int],
+                   draft_fn: Callable[[int, List[int]], Tuple[np.ndarray, np.ndarray]], n_rounds: int,
+                   lam: float, criterion: int = CRIT_MARGIN, max_nodes: int = 64) -> Dict[str, list]:
+    """Rounds of the ternary scheme (Alg. 1, greedy): draft -> proxy pre-verification ->
+    Case I (tau_a < tau_m: the proxy's own correction / bonus token ends the round) or
+    Case II (tau_a >= tau_m: the target re-verifies what the proxy did not vouch for, Eq. 10).
+
+    Each model keeps its own cache.  The proxy sees every token.  The target only runs in
+    Case II, so its cache lags: the committed tokens it has not seen yet are prepended to its
+    input as part of the forced chain (they are certain, the pass only has to produce their
+    keys / values), followed by the proxy-approved path v_0..v_tau_m and the subtree under
+    v_tau_m.  If that exceeds max_nodes, the unseen tokens go in by plain catch-up passes
+    first.  Returns the emitted sequence and one record per round."""
+    from .decision import prune_reroot
+
+    seq = [int(t) for t in prompt]
+
+    def prefill(W, shape):
+        if len(seq) > 1:
+            o = causal_forward(W, shape, seq[:-1])
+            return o["K"], o["V"]
+        z = np.zeros((shape.n_layers, shape.n_kv_heads, 0, shape.head_dim))
+        return z, z.copy()
+
+    kp, vp = prefill(Wp, shape_p)
+    kt, vt = prefill(Wt, shape_t)
+    records = []
+    for r in range(n_rounds):
+        parents, tokens = draft_fn(r, seq)
+        parents = np.asarray(parents, dtype=np.int32)
+        tokens = np.asarray(tokens, dtype=np.int32).copy()
+        tokens[0] = seq[-1]
+        depth = np.zeros(len(parents), dtype=np.int64)
+        for i in range(1, len(parents)):
+            depth[i] = depth[parents[i]] + 1
+        Cp = kp.shape[2]
+        positions = Cp + depth
+        out = verify_forward(Wp, shape_p, kp, vp, tokens, parents, positions)
+        st = node_stats(out["logits"])
+        dec = decide(tokens, parents, st["argmax"], st["conf"], st["margin"], lam, criterion, 1)
+        path = [int(v) for v in dec["path"]]
+        rec = {"proxy": dec, "proxy_stats": st, "escalate": int(dec["escalate"]), "catch_up": 0}
+        if not dec["escalate"]:                                   # Case I
+            kp, vp = commit(kp, vp, out["k_new"], out["v_new"], path)
+            seq += [int(tokens[i]) for i in path[1:]] + [int(dec["token"])]
+            records.append(rec)
+            continue
+        # Case II
+        pr = prune_reroot(tokens, parents, positions, path)
+        t_len = kt.shape[2]
+        unseen = seq[t_len:-1]                                     # committed, not yet cached by the target
+        fits = len(unseen) + len(pr["tokens"]) <= max_nodes
+        while unseen and not fits:                                 # plain catch-up passes over all of them
+            take = min(len(unseen), max_nodes)
+            chunk = np.asarray(unseen[:take], dtype=np.int32)
+            o = verify_forward(Wt, shape_t, kt, vt, chunk, np.arange(-1, take - 1), t_len + np.arange(take))
+            kt, vt = commit(kt, vt, o["k_new"], o["v_new"], list(range(take)))
+            t_len += take
+            unseen = unseen[take:]
+            rec["catch_up"] += 1
+        u = len(unseen)
+        tok_t = np.concatenate([np.asarray(unseen, dtype=np.int32), pr["tokens"]])
+        par_t = np.concatenate([np.arange(-1, u - 1, dtype=np.int32),
+                                np.where(pr["parents"] < 0, u - 1, pr["parents"] + u).astype(np.int32)])
+        pos_t = np.concatenate([t_len + np.arange(u), pr["positions"]])
+        n_forced_t = u + pr["n_forced"]
+        out_t = verify_forward(Wt, shape_t, kt, vt, tok_t, par_t, pos_t)
+        st_t = node_stats(out_t["logits"])
+        dec_t = decide(tok_t, par_t, st_t["argmax"], st_t["conf"], st_t["margin"], 0.0, CRIT_MARGIN, n_forced_t)
+        path_t = [int(v) for v in dec_t["path"]]                  # starts at v_tau_m (node n_forced_t - 1)
+        kt, vt = commit(kt, vt, out_t["k_new"], out_t["v_new"], list(range(n_forced_t - 1)) + path_t)
+        extra = [int(pr["old_id"][n - u]) for n in path_t[1:]]    # the drafts the target accepted, old ids
+        kp, vp = commit(kp, vp, out["k_new"], out["v_new"], path + extra)
+        seq += [int(tokens[i]) for i in path[1:] + extra] + [int(dec_t["token"])]
+        rec.update({"target": dec_t, "target_stats": st_t, "target_nodes": len(tok_t), "n_forced_t": n_forced_t})
+        records.append(rec)
+    return {"sequence": seq, "rounds": records, "kp": kp, "vp": vp, "kt": kt, "vt": vt}

@@ -1,0 +1,127 @@
+"""Round driver of the ternary scheme on top of the C ABI (Alg. 1 of the paper, greedy).
+
+Host control flow only — a few dozen integers per round; every model pass is one
+trispec_verify call and every cache update one trispec_kv_commit call.  One sequence (batch 1).
+
+  round:  draft tree -> proxy pass (threshold lambda)
+          Case I  (no escalation): commit the approved path to the proxy cache; the proxy's
+                  correction / bonus token is the next root.  The target is not run.
+          Case II (escalation): the target verifies [tokens it has not cached yet] + [approved
+                  path v_0..v_tau_m] as a forced chain, plus the subtree under v_tau_m
+                  (Eq. 10), with lambda = 0; both caches commit what was accepted; the target's
+                  token is the next root.
+The target's cache lags behind while rounds end at the proxy; tokens it has not seen ride along
+as the head of the forced chain, or go in by plain catch-up passes when they do not fit.
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Sequence
+
+import numpy as np
+import torch
+
+from .binding import CRIT_MARGIN, MAX_NODES, KVCache, Model, Verifier
+
+
+def _depths(parents: Sequence[int]) -> np.ndarray:
+    d = np.zeros(len(parents), dtype=np.int32)
+    for i in range(1, len(parents)):
+        d[i] = d[parents[i]] + 1
+    return d
+
+
+def _subtree_below(parents: Sequence[int], path: Sequence[int]):
+    """Nodes kept for the target pass: the path, then every descendant of its last node, in
+    ascending id order; and their parents in the new numbering."""
+    last = path[-1]
+    keep = [int(v) for v in path]
+    inside = {last}
+    for i in range(last + 1, len(parents)):
+        if int(parents[i]) in inside:
+            inside.add(i)
+            keep.append(i)
+    renum = {old: new for new, old in enumerate(keep)}
+    new_parents = [-1] + [renum[int(parents[old])] for old in keep[1:]]
+    return keep, new_parents
+
+
+class TernaryDecoder:
+    def __init__(self, proxy: Model, target: Model, capacity: int, criterion: int = CRIT_MARGIN,
+                 max_nodes: int = MAX_NODES):
+        self.proxy, self.target = proxy, target
+        self.kv_p, self.kv_t = KVCache(proxy, 1, capacity), KVCache(target, 1, capacity)
+        self.criterion, self.max_nodes = criterion, max_nodes
+        self._ver: Dict[tuple, Verifier] = {}
+        self.seq: List[int] = []
+        self.target_passes = 0          # passes of the target that verified drafts (not catch-up)
+
+    # -- one pass --------------------------------------------------------------------------
+    def _pass(self, which: str, tokens, parents, positions, lam: float, criterion: int, n_forced: int):
+        model, kv = (self.proxy, self.kv_p) if which == "p" else (self.target, self.kv_t)
+        n = len(tokens)
+        ver = self._ver.get((which, n))
+        if ver is None:
+            ver = self._ver[(which, n)] = Verifier(model, 1, n)
+        tok = torch.tensor([list(map(int, tokens))], dtype=torch.int32, device="cuda")
+        pos = torch.tensor([list(map(int, positions))], dtype=torch.int32, device="cuda")
+        par = np.asarray([list(map(int, parents))], dtype=np.int32)
+        out = ver.verify(kv, tok, par, pos, lam, criterion, n_forced, want_logits=False)
+        torch.cuda.synchronize()
+        return {"accepted_len": int(out["accepted_len"][0]), "token": int(out["token"][0]),
+                "escalate": int(out["escalate"][0]),
+                "path": [int(v) for v in out["path"][0].cpu().numpy() if v >= 0]}
+
+    def _ingest(self, which: str, tokens: Sequence[int]) -> None:
+        """Plain passes over certain tokens: a forced chain, everything committed."""
+        kv = self.kv_p if which == "p" else self.kv_t
+        tokens = list(tokens)
+        while tokens:
+            chunk, tokens = tokens[: self.max_nodes], tokens[self.max_nodes:]
+            n, c = len(chunk), kv.ctx_len[0]
+            self._pass(which, chunk, range(-1, n - 1), range(c, c + n), 0.0, CRIT_MARGIN, n)
+            kv.commit([list(range(n))])
+
+    # -- API -------------------------------------------------------------------------------
+    def start(self, prompt: Sequence[int]) -> None:
+        """Caches of both models over the prompt but its last token (the first root)."""
+        self.seq = [int(t) for t in prompt]
+        self.kv_p.set_len([0]); self.kv_t.set_len([0])
+        self._ingest("p", self.seq[:-1])
+        self._ingest("t", self.seq[:-1])
+
+    def round(self, parents: Sequence[int], tokens: Sequence[int], lam: float) -> Dict[str, object]:
+        """One round on a draft tree (tokens[0] is replaced by the current root).  Returns what
+        happened; self.seq has grown by the accepted drafts and one verifier token."""
+        parents = [int(p) for p in parents]
+        tokens = [int(t) for t in tokens]
+        tokens[0] = self.seq[-1]
+        cp = self.kv_p.ctx_len[0]
+        positions = cp + _depths(parents)
+        pr = self._pass("p", tokens, parents, positions, lam, self.criterion, 1)
+        rec = {"proxy": pr, "escalate": pr["escalate"], "catch_up": 0}
+        path = pr["path"]
+        if not pr["escalate"]:                                               # Case I
+            self.kv_p.commit([path])
+            self.seq += [tokens[i] for i in path[1:]] + [pr["token"]]
+            return rec
+        keep, sub_parents = _subtree_below(parents, path)                    # Case II
+        t_len = self.kv_t.ctx_len[0]
+        unseen = self.seq[t_len:-1]
+        if len(unseen) + len(keep) > self.max_nodes:
+            before = self.kv_t.ctx_len[0]
+            self._ingest("t", unseen)
+            rec["catch_up"] = (self.kv_t.ctx_len[0] - before + self.max_nodes - 1) // self.max_nodes
+            t_len, unseen = self.kv_t.ctx_len[0], []
+        u = len(unseen)
+        tok_t = unseen + [tokens[i] for i in keep]
+        par_t = list(range(-1, u - 1)) + [u - 1 if p < 0 else p + u for p in sub_parents]
+        pos_t = list(range(t_len, t_len + u)) + [int(positions[i]) for i in keep]
+        n_forced = u + len(path)
+        tr = self._pass("t", tok_t, par_t, pos_t, 0.0, CRIT_MARGIN, n_forced)
+        self.target_passes += 1
+        self.kv_t.commit([list(range(n_forced - 1)) + tr["path"]])
+        extra = [keep[n - u] for n in tr["path"][1:]]                        # drafts the target accepted, old ids
+        self.kv_p.commit([path + extra])
+        self.seq += [tokens[i] for i in path[1:] + extra] + [tr["token"]]
+        rec.update({"target": tr, "target_nodes": len(tok_t), "n_forced_t": n_forced})
+        return rec

@@ -71,3 +71,84 @@ def test_commit_is_a_gather_of_the_path_rows():
             for i, n in enumerate([0, 2, 7]):
                 assert np.array_equal(k[l, h, 5 + i], k_new[l, h, n]) and np.array_equal(v[l, h, 5 + i], v_new[l, h, n])
             assert np.array_equal(k[l, h, :5], k_ctx[l, h]) and np.array_equal(v[l, h, :5], v_ctx[l, h])
+
+
+# ---- the ternary scheme (Alg. 1) with two models
+
+def _two_models(seed_p, seed_t):
+    return oracle_weights(MICRO, seed_p), oracle_weights(MICRO, seed_t)
+
+
+def _mixed_drafts(Wref, shape, seed, n_nodes):
+    """Seeded trees whose path to the deepest leaf starts with r tokens of Wref's greedy continuation."""
+    from workloads import tree_depths
+
+    def fn(r, seq):
+        parents = gen_tree(n_nodes, 5, 3, seed + r)
+        tokens = gen_draft_tokens(parents, shape.vocab, seed + 13 * r)
+        leaf = int(np.argmax(tree_depths(parents)))
+        path = [leaf]
+        while parents[path[-1]] >= 0:
+            path.append(int(parents[path[-1]]))
+        path = path[::-1]
+        cont = greedy_decode(Wref, shape, seq, (2 * r + 1) % len(path))[len(seq):]
+        for node, tok in zip(path[1:], cont):
+            tokens[node] = tok
+            for s in np.nonzero(parents == parents[node])[0]:
+                if s != node and tokens[s] == tok:
+                    tokens[s] = (tok + 1) % shape.vocab
+        return parents, tokens
+    return fn
+
+
+@pytest.mark.parametrize("lam", [0.0, 0.3, 2.0])
+def test_same_model_as_proxy_and_target_is_greedy_decoding_at_any_threshold(lam):
+    from oracle import trispec_rounds
+    W = oracle_weights(MICRO, 11)
+    prompt = gen_context_tokens(MICRO.vocab, 6, 11).tolist()
+    res = trispec_rounds(W, MICRO, W, MICRO, prompt, _mixed_drafts(W, MICRO, 11, 10), 6, lam)
+    seq = res["sequence"]
+    assert seq == greedy_decode(W, MICRO, prompt, len(seq) - len(prompt))
+    n_esc = sum(r["escalate"] for r in res["rounds"])
+    assert (lam == 0.0 and n_esc == 0) or (lam == 2.0 and n_esc == 6) or lam == 0.3
+
+
+def test_never_trusted_proxy_gives_the_targets_sequence_and_always_trusted_the_proxys():
+    from oracle import trispec_rounds
+    Wp, Wt = _two_models(21, 22)
+    prompt = gen_context_tokens(MICRO.vocab, 6, 21).tolist()
+    drafts = _mixed_drafts(Wt, MICRO, 21, 10)
+    lossless = trispec_rounds(Wp, MICRO, Wt, MICRO, prompt, drafts, 6, 2.0)        # margin <= 1 < lambda
+    seq = lossless["sequence"]
+    assert seq == greedy_decode(Wt, MICRO, prompt, len(seq) - len(prompt))
+    assert all(r["escalate"] for r in lossless["rounds"])
+    assert max(r["target"]["accepted_len"] for r in lossless["rounds"]) >= 2        # planted drafts accepted by the target
+    trusting = trispec_rounds(Wp, MICRO, Wt, MICRO, prompt, _mixed_drafts(Wp, MICRO, 21, 10), 6, 0.0)
+    seq = trusting["sequence"]
+    assert seq == greedy_decode(Wp, MICRO, prompt, len(seq) - len(prompt))
+    assert not any(r["escalate"] for r in trusting["rounds"])
+
+
+@pytest.mark.parametrize("lam,max_nodes,want_catch_up", [(0.25, 16, False), (0.1, 12, True)])
+def test_target_catches_up_on_tokens_it_never_saw(lam, max_nodes, want_catch_up):
+    """Rounds that end at the proxy leave the target's cache behind; the next escalation carries
+    the unseen tokens as a forced chain (plain catch-up passes first if they do not fit), and
+    afterwards both caches are the textbook caches of the emitted sequence."""
+    from oracle import trispec_rounds
+    Wp, Wt = _two_models(31, 32)
+    prompt = gen_context_tokens(MICRO.vocab, 5, 31).tolist()
+    drafts = _mixed_drafts(Wp, MICRO, 31, 10)
+    # a threshold in the middle of the proxy's margins: some rounds end at the proxy, some escalate
+    res = trispec_rounds(Wp, MICRO, Wt, MICRO, prompt, drafts, 14, lam, max_nodes=max_nodes)
+    esc = [r["escalate"] for r in res["rounds"]]
+    assert 0 < sum(esc) < len(esc)
+    carried = any(r["escalate"] and r["n_forced_t"] > len(r["proxy"]["path"]) for r in res["rounds"])
+    caught_up = any(r["catch_up"] > 0 for r in res["rounds"])
+    assert caught_up == want_catch_up and (carried or caught_up)      # the lag went in one way or the other
+    assert all(r["target_nodes"] <= max_nodes for r in res["rounds"] if r["escalate"])
+    seq = res["sequence"]
+    refp = causal_forward(Wp, MICRO, seq[:-1])
+    assert np.max(np.abs(res["kp"] - refp["K"])) < 1e-9 and np.max(np.abs(res["vp"] - refp["V"])) < 1e-9
+    t_len = res["kt"].shape[2]
+    reft = causal_forward(Wt, MICRO, seq[:t_len])
+    assert np.max(np.abs(res["kt"] - reft["K"])) < 1e-9 and np.max(np.abs(res["vt"] - reft["V"])) < 1e-9
