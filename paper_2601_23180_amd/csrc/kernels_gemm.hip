@@ -234,7 +234,7 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(GemmArgs a) {
 
   rstd_finish<256, MB>(a, rs_in, s_rsp, s_rs);
   __syncthreads();   // every wavefront is done reading the last X stage
-  gemm_epilogue<MB, EPI, 4>(a, acc, lds, &s_last, s_rs, tile, split);
+  gemm_epilogue<MB, EPI, 4>(a, reinterpret_cast<f32x16(&)[1][MB]>(acc), lds, &s_last, s_rs, tile, split);
 }
 
 // One-time repack of a row-major [n_rows, k] bf16 matrix into the layout above.  One thread per
@@ -266,9 +266,10 @@ void launch_pack_weights(hipStream_t st, const void *w, int n_rows, int k, void 
 template <int EPI>
 static void dispatch(hipStream_t st, const GemmArgs &a) {
   dim3 grid(a.n_tiles, a.n_splits), block(256);
+  // (the 4-deep W ring does not fit the register file next to the accumulators of 256 rows)
 #define TS_LAUNCH(MB_, KC_)                                                                   \
   do {                                                                                        \
-    if (a.k_per_split % (4 * KC_) == 0 && a.k % (4 * KC_) == 0)                               \
+    if (MB_ < 8 && a.k_per_split % (4 * KC_) == 0 && a.k % (4 * KC_) == 0)                    \
       hipLaunchKernelGGL((k_gemm_bf16<MB_, KC_, EPI, false, 4>), grid, block, 0, st, a);      \
     else if (a.k_per_split % (2 * KC_) == 0 && a.k % (2 * KC_) == 0)                          \
       hipLaunchKernelGGL((k_gemm_bf16<MB_, KC_, EPI, false, 2>), grid, block, 0, st, a);      \
