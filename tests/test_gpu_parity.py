@@ -133,11 +133,16 @@ BF16_CASES = [
     ("batch3_ragged_ctx", TB, [10, 131, 64], lambda s: gen_tree(30, 6, 4, s)),
     ("batch4_rows240", TB.with_(n_layers=1), [40, 0, 129, 77], lambda s: gen_tree(60, 8, 4, s)),
     ("batch2_rows128", TB.with_(n_layers=1), [70, 33], lambda s: gen_tree(50, 8, 4, s)),
-    # reductions of 1024: the 8-wavefront kernel's steady-state loop (LM head: one split, 8 chunks)
+    # reductions of 1024: the steady-state loop of the streaming matmul (LM head: one split, 8 chunks)
     ("wide_hidden1024", TB.with_(n_layers=1, hidden=1024, ffn=1024, lm_head_std=6.5 / 32), [96],
      lambda s: gen_tree(60, 8, 4, s)),
     ("wide_chain9_rows32", TB.with_(n_layers=2, hidden=512, ffn=1536, lm_head_std=6.5 / 22.6), [40],
      lambda s: gen_chain(9)),
+    # many rows and reductions long enough for k splits (partial tiles of 128 and 256 rows)
+    ("rows100_hidden1024_splits", TB.with_(n_layers=2, hidden=1024, ffn=1536, lm_head_std=6.5 / 32), [70, 33],
+     lambda s: gen_tree(50, 8, 4, s)),
+    ("rows240_hidden1024_splits", TB.with_(n_layers=1, hidden=1024, ffn=1024, vocab=4001, lm_head_std=6.5 / 32),
+     [40, 0, 129, 77], lambda s: gen_tree(60, 8, 4, s)),
 ]
 
 
