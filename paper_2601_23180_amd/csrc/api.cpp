@@ -68,7 +68,7 @@ int rows_pad_for(int rows) {
 
 // Workspace regions, in order.  Offsets are a pure function of (model, batch, n_nodes).
 struct Layout {
-  size_t anc, parent, status, cos_t, sin_t, x, rstd, h, q, qkv_f32, attn_out, act, part, counters, ss_part, attn_o, attn_m, attn_l, head_l1, head_l2, head_sum, head_idx, node_l1, node_l2, node_sum,
+  size_t anc, parent, status, cos_t, sin_t, x, h, q, qkv_f32, attn_out, act, part, counters, ss_part, attn_o, attn_m, attn_l, head_l1, head_l2, head_sum, head_idx, node_l1, node_l2, node_sum,
       node_idx, logits, total;
   int rows_max, rows_pad_max, head_tiles, max_tiles;
 };
@@ -123,7 +123,6 @@ Layout make_layout(const trispec_model_config &c, int batch, int max_nodes) {
   L.cos_t = take(sizeof(float) * rows * (c.head_dim / 2));
   L.sin_t = take(sizeof(float) * rows * (c.head_dim / 2));
   L.x = take(sizeof(float) * (size_t)rp * c.hidden);
-  L.rstd = take(sizeof(float) * rp);
   // matmul operands: fp32 models one fp32 panel; bf16 models a bf16 hi panel + a bf16 lo panel
   L.h = take(sizeof(float) * (size_t)rp * c.hidden);
   L.q = take(sizeof(float) * (size_t)rp * qd);

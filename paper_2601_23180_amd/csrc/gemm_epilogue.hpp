@@ -1,5 +1,5 @@
-// Epilogue of the weight-streaming matmul kernels (see kernels_gemm.hip): shared by the
-// 4-wavefront / 128-column and the 8-wavefront / 256-column variants.
+// Epilogue of the weight-streaming matmul kernel (see kernels_gemm.hip), written for any number
+// of wavefronts per workgroup and of 32-column sub-tiles per wavefront.
 #pragma once
 
 #include "device_util.hpp"

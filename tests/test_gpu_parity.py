@@ -236,3 +236,34 @@ def test_copy_probe_copies_exactly():
         copy_probe(dst, src)
         torch.cuda.synchronize()
         assert torch.equal(dst, src), n_vec
+
+
+def test_pass_replayed_from_a_captured_graph_equals_eager():
+    """The library only launches kernels on the caller's stream (no allocation, no memset, no host
+    synchronisation), so a pass can be captured into a HIP graph.  Replays — with eager work and
+    synchronisations between them — must reproduce the eager outputs bit for bit."""
+    shape, seed = TB, 21
+    parents = gen_tree(40, 7, 3, seed)
+    case = make_case(shape, seed, [150], [parents])
+    eager = case.run_gpu(0.5, CRIT_MARGIN)
+    ver, kv, tok = eager["_ver"], eager["_kv"], eager["_tok"]
+    pos = torch.from_numpy(case.positions).cuda()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        ver.verify(kv, tok, case.parents, pos, 0.5, CRIT_MARGIN, 1)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        ver.verify(kv, tok, case.parents, pos, 0.5, CRIT_MARGIN, 1)
+    for rep in range(3):
+        for name in ("accepted_len", "token", "escalate", "path", "argmax", "confidence", "margin"):
+            ver.out[name].fill_(-7)            # eager work between replays; also proves the replay wrote them
+        ver.logits.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name in ("accepted_len", "token", "escalate", "path", "argmax", "confidence", "margin"):
+            assert np.array_equal(ver.out[name].cpu().numpy(), eager[name]), (rep, name)
+        assert np.array_equal(ver.logits.cpu().numpy(), eager["logits"]), rep
