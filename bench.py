@@ -60,8 +60,9 @@ def build_inputs(shape, batch, ctx, n_nodes, kind, seed):
 
 def cpu_baseline(shape, batch, ctx, n_nodes, kind, seed):
     """The oracle as it stands, timed on the host cores on a bounded sample of the workload:
-    the full-width model cut to 1 and to 4 layers (full LM head both times), sequence 0 only;
-    the per-layer time is the difference / 3 and the whole pass is extrapolated from it."""
+    the full-width model cut to 2 and to 10 layers (full LM head both times), sequence 0 only,
+    about 10 s of oracle time; the per-layer time is the difference / 8 and the whole pass is
+    extrapolated from it."""
     from oracle import OracleWeights, verify_forward
     from workloads import WeightSource, gen_chain, gen_draft_tokens, gen_kv_cache, gen_tree, tree_depths
 
@@ -73,7 +74,7 @@ def cpu_baseline(shape, batch, ctx, n_nodes, kind, seed):
 
     for name in ("embed", "lm_head", "final_norm"):
         cache[(name, 0)] = ws.get(name, 0)
-    cuts = (1, 4)
+    cuts = (2, 10) if shape.n_layers >= 10 else (1, min(4, shape.n_layers))
     for l in range(cuts[1]):
         for name in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "norm_attn", "norm_ffn"):
             cache[(name, l)] = ws.get(name, l)

@@ -478,13 +478,13 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
   at.batch = B; at.n_nodes = n_nodes; at.n_q_heads = c.n_q_heads; at.n_kv_heads = c.n_kv_heads;
   at.head_dim = c.head_dim; at.capacity = kv->capacity;
   {
-    // context split: aim at about two workgroups per CU over (sequence, kv head, row group, split),
+    // context split: aim at one workgroup per CU (its LDS tiles allow no more) over (sequence, kv head, row group, split),
     // at least 256 keys (four LDS tiles) per workgroup, at most kMaxAttnSplits splits.  Long
     // contexts and batches then take few, long splits — the fp32 partial outputs a split writes
     // (rows x head_dim) would otherwise outweigh the K/V it reads.
     const int group = c.n_q_heads / c.n_kv_heads;
     const int per_split = B * c.n_kv_heads * ((group * n_nodes + 127) / 128);
-    int want = (512 + per_split - 1) / per_split;
+    int want = (256 + per_split - 1) / per_split;
     if (want > kMaxAttnSplits) want = kMaxAttnSplits;
     int kps = (int)align_up((size_t)((max_keys + want - 1) / want), 64);
     if (kps < 256) kps = 256;
