@@ -267,3 +267,17 @@ def test_pass_replayed_from_a_captured_graph_equals_eager():
         for name in ("accepted_len", "token", "escalate", "path", "argmax", "confidence", "margin"):
             assert np.array_equal(ver.out[name].cpu().numpy(), eager[name]), (rep, name)
         assert np.array_equal(ver.logits.cpu().numpy(), eager["logits"]), rep
+
+
+@pytest.mark.parametrize("ctx", [40000, 1000])
+def test_long_context_with_synthetic_cache(ctx):
+    """Contexts beyond what the oracle can prefill: N(0,1) caches as in the full-size workloads.
+    40000 keys: 63 key splits of 640 keys (the merge walks more than one batch of splits, a split
+    ends inside a 128-key tile); 1000 keys: splits shorter than a tile pair."""
+    from workloads import gen_kv_cache
+    shape, seed = TB.with_(n_layers=1), 33
+    parents = gen_tree(33, 8, 4, seed)
+    k, v = gen_kv_cache(shape, 1, ctx, seed, 0)
+    case = Case(shape, seed, [k[0][None].astype(np.float64)], [v[0][None].astype(np.float64)],
+                gen_draft_tokens(parents, shape.vocab, seed), parents, ctx + tree_depths(parents))
+    full_check(case, thresholds=(0.0, 0.5))
