@@ -120,6 +120,10 @@ def main():
                  "use --gpus 1")
 
     import torch
+    from paper_2601_23180_amd.binding import LIB_PATH
+    if not os.path.exists(LIB_PATH):     # load what is built; build only if nothing is
+        from paper_2601_23180_amd.build import build
+        build()
     from paper_2601_23180_amd import K_ATTN, K_GEMM, K_HEAD, KernelTimer
     from workloads import SHAPES
 

@@ -10,6 +10,11 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # the tests load the library that is built; only if nothing is built do they build it
+    from paper_2601_23180_amd.binding import LIB_PATH
+    if not os.path.exists(LIB_PATH):
+        from paper_2601_23180_amd.build import build
+        build()
 
 
 def _have_gpu() -> bool:
