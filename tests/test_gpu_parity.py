@@ -133,6 +133,7 @@ BF16_CASES = [
     ("batch3_ragged_ctx", TB, [10, 131, 64], lambda s: gen_tree(30, 6, 4, s)),
     ("batch4_rows240", TB.with_(n_layers=1), [40, 0, 129, 77], lambda s: gen_tree(60, 8, 4, s)),
     ("batch2_rows128", TB.with_(n_layers=1), [70, 33], lambda s: gen_tree(50, 8, 4, s)),
+    ("batch8_rows240", TB.with_(n_layers=1), [5, 64, 0, 33, 129, 17, 80, 250], lambda s: gen_tree(30, 6, 4, s)),
     # reductions of 1024: the steady-state loop of the streaming matmul (LM head: one split, 8 chunks)
     ("wide_hidden1024", TB.with_(n_layers=1, hidden=1024, ffn=1024, lm_head_std=6.5 / 32), [96],
      lambda s: gen_tree(60, 8, 4, s)),
