@@ -62,7 +62,9 @@ enum {
 
 typedef struct {             /* plain data, copied by trispec_model_create */
   int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
-  int32_t dtype;             /* TRISPEC_F32 | TRISPEC_BF16: weights, KV cache, matmul operands */
+  int32_t dtype;             /* TRISPEC_F32 | TRISPEC_BF16: what the model STORES (weights, KV cache).
+                                bf16 models round nothing else: activations reach the matrix cores
+                                as bf16 high + low pairs (~16 bits), accumulation is fp32 */
   float rms_eps;
   float rope_base;
 } trispec_model_config;
@@ -94,8 +96,8 @@ typedef struct trispec_timer trispec_timer;
  * Copies the config and the pointer tables (not the weights); the weights must
  * outlive the model.  Makes no HIP call.
  * Supported: head_dim in {64, 128}; n_q_heads a multiple of n_kv_heads;
- * bf16 additionally needs hidden, ffn and n_q_heads*head_dim multiples of 64 and
- * n_kv_heads*head_dim a multiple of 32.
+ * bf16 additionally needs hidden, ffn and n_q_heads*head_dim multiples of 64,
+ * n_kv_heads*head_dim a multiple of 32 and at most 8 query heads per kv head.
  * Errors: TRISPEC_ENULL, TRISPEC_ESHAPE.
  */
 int trispec_model_create(const trispec_model_config *cfg, const trispec_weights *w,
@@ -221,7 +223,7 @@ int trispec_decide(trispec_model *m, int32_t batch, const int32_t *draft_tokens,
  * kernel class, so a benchmark can price that kernel against the HBM roofline.
  *   TRISPEC_K_GEMM  the weight-streaming projection / FFN matmul (4 launches per layer)
  *   TRISPEC_K_HEAD  the fused LM-head + softmax-statistics kernel (1 launch per pass)
- *   TRISPEC_K_ATTN  the tree-masked attention kernel (1 launch per layer)
+ *   TRISPEC_K_ATTN  the tree-masked attention of a layer (context kernel + merge kernel, one bracket)
  * create/destroy make HIP event calls (not for the hot path).  read() needs the stream to be
  * idle (caller synchronises); it returns the number of timed launches since the last reset,
  * their summed duration and the summed algorithmic HBM bytes of those launches (weights or
