@@ -3,7 +3,7 @@
 
 A step = one trispec_verify() call: the whole hot path (embedding, every layer's projections,
 tree-masked attention and FFN, fused LM head, decision) over one batch of synthetic input that
-is already resident in HBM.  Prints ONE JSON line (see DESIGN.md "Measurement").
+is already resident in HBM.  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -22,11 +22,11 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E vendor peak
 
 # name -> (shape key, batch, ctx_len, n_nodes, tree kind)
 WORKLOADS = {
-    "qwen3_8b_tree60_ctx4096": ("qwen3_8b", 1, 4096, 60, "tree"),        # BASELINE config 3 (headline)
-    "qwen3_0p6b_chain8_ctx2048": ("qwen3_0p6b", 1, 2048, 9, "chain"),    # BASELINE config 2
-    "qwen3_1p7b_tree60_ctx8192": ("qwen3_1p7b", 1, 8192, 60, "tree"),    # BASELINE config 4, proxy
-    "qwen3_8b_tree60_ctx8192": ("qwen3_8b", 1, 8192, 60, "tree"),        # BASELINE config 4, target
-    "llama3_8b_b4_tree60_ctx16384": ("llama3_8b", 4, 16384, 60, "tree"),  # BASELINE config 5
+    "qwen3_8b_tree60_ctx4096": ("qwen3_8b", 1, 4096, 60, "tree"),        # workload 3 (headline)
+    "qwen3_0p6b_chain8_ctx2048": ("qwen3_0p6b", 1, 2048, 9, "chain"),    # workload 2
+    "qwen3_1p7b_tree60_ctx8192": ("qwen3_1p7b", 1, 8192, 60, "tree"),    # workload 4, proxy
+    "qwen3_8b_tree60_ctx8192": ("qwen3_8b", 1, 8192, 60, "tree"),        # workload 4, target
+    "llama3_8b_b4_tree60_ctx16384": ("llama3_8b", 4, 16384, 60, "tree"),  # workload 5
     "tiny_bf16_tree60_ctx256": ("tiny_bf16", 1, 256, 60, "tree"),        # plumbing check only
     "qwen3_8b_4layers_tree60_ctx4096": ("qwen3_8b_L4", 1, 4096, 60, "tree"),  # kernel tuning aid (not a result)
 }

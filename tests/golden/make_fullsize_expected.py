@@ -1,6 +1,6 @@
 #!/usr/bin/env python3
 """Writes tests/golden/fullsize_<case>.json: what the ORACLE computes for the full-size workloads
-(BASELINE configs 2-5), so that the GPU parity tests at those sizes need no minutes-long CPU run.
+(workloads 2-5 of bench.py), so that the GPU parity tests at those sizes need no minutes-long CPU run.
 
 Calls only `oracle/` and the seeded generators in `workloads/`; nothing here touches the GPU path.
 The paper prints no worked numbers for a verification pass, so these are oracle values, not paper

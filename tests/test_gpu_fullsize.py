@@ -1,4 +1,4 @@
-"""GPU parity at the full sizes of BASELINE configs 2-5, in the launch configuration bench.py
+"""GPU parity at the full sizes of workloads 2-5 (see bench.py), in the launch configuration bench.py
 times (same shapes, context lengths, trees, seeds and generators).
 
 The oracle's answers for these workloads take minutes of CPU time, so they are stored:

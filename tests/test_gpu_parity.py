@@ -85,7 +85,7 @@ def full_check(case, thresholds=(0.0, 0.3, 0.5, 0.9, 1.5), n_forced=1):
     return gpu, oracle_out, excused
 
 
-# ------------------------------------------------------------------ BASELINE config 1
+# ------------------------------------------------------------------ workload 1 (tiny fp32 decoder)
 
 
 def test_config1_tiny_fp32_chain_threshold_half():

@@ -69,22 +69,22 @@ class ModelShape:
 # top-1 probability covers roughly 0.05..0.99 over seeds (s = 6.5 at V = 4096,
 # s = 9.5 at V ~ 1.5e5: median top-1 about 0.5, 10%..90% quantiles about 0.25..0.9).
 SHAPES: Dict[str, ModelShape] = {
-    # BASELINE config 1: tiny fp32 decoder
+    # workload 1: tiny fp32 decoder
     "tiny": ModelShape("tiny", 2, 256, 4, 2, 64, 512, 4096, "f32",
                        rope_base=1e4, lm_head_std=6.5 / 16.0),
     # same shape in bf16 storage (exercises the MFMA path at oracle-friendly size)
     "tiny_bf16": ModelShape("tiny_bf16", 2, 256, 4, 2, 128, 512, 4096, "bf16",
                             rope_base=1e4, lm_head_std=6.5 / 16.0),
-    # BASELINE config 2: Qwen3-0.6B-shaped proxy
+    # workload 2: Qwen3-0.6B-shaped proxy
     "qwen3_0p6b": ModelShape("qwen3_0p6b", 28, 1024, 16, 8, 128, 3072, 151936, "bf16",
                              rope_base=1e6, lm_head_std=9.5 / 32.0),
-    # BASELINE config 4 proxy: Qwen3-1.7B-shaped
+    # workload 4, proxy: Qwen3-1.7B-shaped
     "qwen3_1p7b": ModelShape("qwen3_1p7b", 28, 2048, 16, 8, 128, 6144, 151936, "bf16",
                              rope_base=1e6, lm_head_std=9.5 / 45.254833995939045),
-    # BASELINE config 3 / 4 target: Qwen3-8B-shaped
+    # workload 3 and workload 4's target: Qwen3-8B-shaped
     "qwen3_8b": ModelShape("qwen3_8b", 36, 4096, 32, 8, 128, 12288, 151936, "bf16",
                            rope_base=1e6, lm_head_std=9.5 / 64.0),
-    # BASELINE config 5: LLaMA-3-8B-shaped
+    # workload 5: LLaMA-3-8B-shaped
     "llama3_8b": ModelShape("llama3_8b", 32, 4096, 32, 8, 128, 14336, 128256, "bf16",
                             rope_base=5e5, lm_head_std=9.5 / 64.0),
 }
