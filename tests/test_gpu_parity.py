@@ -282,3 +282,19 @@ def test_long_context_with_synthetic_cache(ctx):
     case = Case(shape, seed, [k[0][None].astype(np.float64)], [v[0][None].astype(np.float64)],
                 gen_draft_tokens(parents, shape.vocab, seed), parents, ctx + tree_depths(parents))
     full_check(case, thresholds=(0.0, 0.5))
+
+
+@pytest.mark.parametrize("seed", list(range(100, 116)))
+def test_seed_sweep_random_shapes(seed):
+    """Random small problems: batch, context lengths, tree size and shape all drawn from the seed."""
+    rng = np.random.default_rng(seed)
+    batch = int(rng.integers(1, 4))
+    max_depth, max_children = int(rng.integers(2, 9)), int(rng.integers(1, 5))
+    room = sum(max_children ** i for i in range(max_depth + 1))        # nodes a tree of that shape can hold
+    n_nodes = int(rng.integers(max_depth + 1, min(40, room) + 1))
+    shape = TB.with_(n_layers=int(rng.integers(1, 3)), n_q_heads=int(rng.choice([2, 4, 8])), n_kv_heads=2)
+    ctx_lens = [int(rng.integers(0, 140)) for _ in range(batch)]
+    parents = [gen_tree(n_nodes, max_depth, max_children, seed + b) for b in range(batch)]
+    plant = [(int(np.argmax(tree_depths(p))), int(rng.integers(0, 5))) for p in parents]
+    case = make_case(shape, seed, ctx_lens, parents, plant=plant)
+    full_check(case, thresholds=(0.0, float(rng.uniform(0.1, 0.9)), 1.5))
