@@ -478,12 +478,18 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
   at.batch = B; at.n_nodes = n_nodes; at.n_q_heads = c.n_q_heads; at.n_kv_heads = c.n_kv_heads;
   at.head_dim = c.head_dim; at.capacity = kv->capacity;
   {
-    // context split: aim at one workgroup per CU (its LDS tiles allow no more) over (sequence, kv head, row group, split),
-    // at least 256 keys (four LDS tiles) per workgroup, at most kMaxAttnSplits splits.  Long
-    // contexts and batches then take few, long splits — the fp32 partial outputs a split writes
-    // (rows x head_dim) would otherwise outweigh the K/V it reads.
+    // context split: aim at one workgroup per CU over (sequence, kv head, row group, split), at
+    // least 256 keys per workgroup, at most kMaxAttnSplits splits.  Long contexts and batches then
+    // take few, long splits — the fp32 partial outputs a split writes (rows x head_dim) would
+    // otherwise outweigh the K/V it reads.  A tree of more than 128 query rows per kv head over a
+    // long context takes 256-row workgroups (eight waves, 64-key tiles), which stage every K/V
+    // tile once instead of once per 128-row group; on shorter contexts the two 128-row groups,
+    // each with its own CU, finish sooner.
     const int group = c.n_q_heads / c.n_kv_heads;
-    const int per_split = B * c.n_kv_heads * ((group * n_nodes + 127) / 128);
+    const int p_rows = group * n_nodes;
+    at.rows_per_wg = (p_rows > 128 && max_keys >= kAttnWideMinKeys) ? 256 : 128;
+    at.n_row_groups = (p_rows + at.rows_per_wg - 1) / at.rows_per_wg;
+    const int per_split = B * c.n_kv_heads * at.n_row_groups;
     int want = (256 + per_split - 1) / per_split;
     if (want > kMaxAttnSplits) want = kMaxAttnSplits;
     int kps = (int)align_up((size_t)((max_keys + want - 1) / want), 64);
@@ -562,7 +568,6 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
     at.qkv = qkv_f32;
     at.q = ws + L.q;
     at.q_panel = pan_q;
-    at.n_row_groups = (group * n_nodes + 127) / 128;
     launch_zero_counters(st, counters, L.max_tiles + 1);
     // ss[0]: written by the embedding (1 tile) and by every down projection; ss[1]: by every O projection
     float *ss0 = (float *)(ws + L.ss_part), *ss1 = ss0 + (size_t)tiles_of(c.hidden) * rp;

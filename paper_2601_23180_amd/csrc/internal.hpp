@@ -22,6 +22,7 @@ constexpr int kMaxNodes = TRISPEC_MAX_NODES;
 constexpr int kMaxGroup = 8;         // query heads per kv head (bf16 attention)
 constexpr int kMaxSplitK = 32;       // k-splits of one matmul
 constexpr int kMaxAttnSplits = 64;   // context splits of one attention call
+constexpr int kAttnWideMinKeys = 6144;   // longest context from which trees of > 128 rows take 256-row workgroups
 constexpr int kGemmTileN = 128;      // output columns per workgroup (4 waves x 32)
 
 // Per-call node table, passed to the set-up kernel by value (3 KB < 4 KB kernarg limit).
@@ -99,7 +100,8 @@ struct GemmArgs {
 struct AttnArgs {
   const void *q;        // fp32 path: [rows_pad, nq*d] fp32 queries; bf16 path: bf16 hi panel, lo q_panel later
   size_t q_panel;
-  int32_t n_row_groups; // ceil(group * n_nodes / 128): query rows per workgroup = 128
+  int32_t rows_per_wg;  // query rows (group * n_nodes of them per kv head) one workgroup covers: 128 or 256
+  int32_t n_row_groups; // ceil(group * n_nodes / rows_per_wg)
   const void *k_cache;  // this layer: [B][nkv][cap][d]
   const void *v_cache;  // this layer: [B][nkv][d][cap]
   const uint64_t *anc;  // [B*M]

@@ -71,8 +71,8 @@ void launch_attn_f32(hipStream_t st, const AttnArgs &a) {
 }
 
 // ------------------------------------------------------------------ bf16 path
-constexpr int KT = 128;                     // keys per tile
-template <int D>
+// KT = keys per LDS tile
+template <int D, int KT>
 struct AttnLds {
   static constexpr int kStrideK = D * 2 + 16;     // bytes per key row of the K tile
   static constexpr int kStrideV = KT * 2 + 8;     // bytes per feature row of the V^T tile
@@ -81,12 +81,17 @@ struct AttnLds {
   static constexpr int kBuf = kBytesK + kBytesV;  // one stage
 };
 
-template <int D, int RBW>
-__global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
-  using L = AttnLds<D>;
+// NW waves, each owning RBW blocks of 32 query rows: a workgroup covers 32 * NW * RBW rows.
+// <KT 128, NW 4>: one workgroup per CU.  <KT 64, NW 8>: 256 rows share every staged K/V tile
+// (trees of more than 128 rows read the cache once, not twice) and two waves per SIMD overlap
+// one another's softmax arithmetic and matrix work.
+template <int D, int RBW, int KT, int NW>
+__global__ __launch_bounds__(64 * NW) void k_attn_bf16(AttnArgs a) {
+  using L = AttnLds<D, KT>;
+  constexpr int NT = 64 * NW;
   __shared__ __attribute__((aligned(16))) unsigned char lds[2 * L::kBuf];
   const int split = blockIdx.x, kvh = blockIdx.y;
-  const int b = blockIdx.z / a.n_row_groups, rg = blockIdx.z - b * a.n_row_groups;   // sequence, group of 128 query rows
+  const int b = blockIdx.z / a.n_row_groups, rg = blockIdx.z - b * a.n_row_groups;   // sequence, group of query rows
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: branches on it are wave-uniform
   const int ln = lane & 31, g = lane >> 5;
@@ -103,7 +108,7 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
   bf16x8 qf[RBW][D / 16], ql[RBW][D / 16];
 #pragma unroll
   for (int i = 0; i < RBW; ++i) {
-    const int rb = rg * 4 * RBW + wave + 4 * i;
+    const int rb = rg * NW * RBW + wave + NW * i;
     const int p = rb * 32 + ln;
     prow[i] = p;
 #pragma unroll
@@ -137,12 +142,12 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
   const bf16 *vc = (const bf16 *)a.v_cache + ((size_t)b * a.n_kv_heads + kvh) * D * a.capacity;
 
   // ---- tile staging: K tile = KT rows of D*2 bytes (16-byte vectors), V^T tile = D rows of KT*2 bytes
-  constexpr int KV_PER_T = KT * D * 2 / 16 / 256;   // 16-byte vectors per thread, each of K and V^T
+  constexpr int KV_PER_T = KT * D * 2 / 16 / NT;   // 16-byte vectors per thread, each of K and V^T
   uint4 kreg[KV_PER_T], vreg[KV_PER_T];
   auto load_tile = [&](int k0) {
 #pragma unroll
     for (int i = 0; i < KV_PER_T; ++i) {
-      const int v = tid + 256 * i;
+      const int v = tid + NT * i;
       {  // K: vector v -> key v / (D/8), 16-byte column v % (D/8)
         const int key = v / (D / 8), c = v % (D / 8);
         // rows past the context hold no token (their scores are masked); clamped into the cache
@@ -168,7 +173,7 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
     unsigned char *base = lds + buf * L::kBuf;
 #pragma unroll
     for (int i = 0; i < KV_PER_T; ++i) {
-      const int v = tid + 256 * i;
+      const int v = tid + NT * i;
       {
         const int key = v / (D / 8), c = v % (D / 8);
         *(uint4 *)(base + key * L::kStrideK + c * 16) = kreg[i];
@@ -210,7 +215,7 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
 
 #pragma unroll
     for (int i = 0; i < RBW; ++i) {
-      if ((rg * 4 * RBW + wave + 4 * i) * 32 >= p_rows) continue;   // wave-uniform
+      if ((rg * NW * RBW + wave + NW * i) * 32 >= p_rows) continue;   // wave-uniform
       // S^T[key][row] for the two 32-key sub-tiles
       f32x16 s[KT / 32];
 #pragma unroll
@@ -436,7 +441,8 @@ __global__ __launch_bounds__(512) void k_attn_merge(AttnArgs a) {
 template <int D>
 static void launch_attn_bf16_d(hipStream_t st, const AttnArgs &a) {
   dim3 grid(a.n_splits, a.n_kv_heads, a.batch * a.n_row_groups);
-  hipLaunchKernelGGL((k_attn_bf16<D, 1>), grid, dim3(256), 0, st, a);
+  if (a.rows_per_wg == 256) hipLaunchKernelGGL((k_attn_bf16<D, 1, 64, 8>), grid, dim3(512), 0, st, a);
+  else hipLaunchKernelGGL((k_attn_bf16<D, 1, 128, 4>), grid, dim3(256), 0, st, a);
   const int group = a.n_q_heads / a.n_kv_heads;
   const int merge_threads = group * D / 2 < 64 ? 64 : group * D / 2;   // <= 512 (group <= 8, d <= 128)
   hipLaunchKernelGGL(k_attn_merge<D>, dim3(a.batch * a.n_nodes, a.n_kv_heads), dim3(merge_threads), 0, st, a);

@@ -270,17 +270,27 @@ def test_pass_replayed_from_a_captured_graph_equals_eager():
         assert np.array_equal(ver.logits.cpu().numpy(), eager["logits"]), rep
 
 
-@pytest.mark.parametrize("ctx", [40000, 1000])
-def test_long_context_with_synthetic_cache(ctx):
+@pytest.mark.parametrize("ctx_lens,n_nodes,n_q_heads", [
+    ((40000,), 33, 4), ((1000,), 33, 4),
+    ((7000,), 60, 8), ((6144,), 40, 8), ((6500, 300), 60, 8), ((6100,), 60, 8),
+], ids=["ctx40000", "ctx1000", "ctx7000_rows240", "ctx6144_rows160", "ctx6500_300_rows240", "ctx6100_rows240"])
+def test_long_context_with_synthetic_cache(ctx_lens, n_nodes, n_q_heads):
     """Contexts beyond what the oracle can prefill: N(0,1) caches as in the full-size workloads.
     40000 keys: 63 key splits of 640 keys (the merge walks more than one batch of splits, a split
-    ends inside a 128-key tile); 1000 keys: splits shorter than a tile pair."""
+    ends inside a 128-key tile); 1000 keys: splits shorter than a tile pair.  The cases with more
+    than 128 query rows per kv head and 6144 keys or more take the 256-row workgroups with 64-key
+    tiles (a ragged last tile, a second sequence whose splits are mostly empty); 6100 keys stays
+    just below that switch, on two 128-row groups."""
     from workloads import gen_kv_cache
-    shape, seed = TB.with_(n_layers=1), 33
-    parents = gen_tree(33, 8, 4, seed)
-    k, v = gen_kv_cache(shape, 1, ctx, seed, 0)
-    case = Case(shape, seed, [k[0][None].astype(np.float64)], [v[0][None].astype(np.float64)],
-                gen_draft_tokens(parents, shape.vocab, seed), parents, ctx + tree_depths(parents))
+    shape, seed = TB.with_(n_layers=1, n_q_heads=n_q_heads), 33
+    batch = len(ctx_lens)
+    parents = [gen_tree(n_nodes, 8, 4, seed + b) for b in range(batch)]
+    k, v = gen_kv_cache(shape, batch, max(ctx_lens), seed, 0)
+    case = Case(shape, seed,
+                [k[b][None, :, :n].astype(np.float64) for b, n in enumerate(ctx_lens)],
+                [v[b][None, :, :n].astype(np.float64) for b, n in enumerate(ctx_lens)],
+                np.stack([gen_draft_tokens(p_, shape.vocab, seed + b) for b, p_ in enumerate(parents)]),
+                np.stack(parents), np.stack([n + tree_depths(p_) for n, p_ in zip(ctx_lens, parents)]))
     full_check(case, thresholds=(0.0, 0.5))
 
 
