@@ -8,7 +8,9 @@ library and its Python binding) never does, and shares no code with it.
 Pins (tests/test_oracle_*.py): brute-force sequential autoregressive forwards,
 an independent torch-CPU forward, closed forms for RMSNorm / RoPE / softmax
 statistics, the set-min definitions of tau_a and tau_m (paper Eq. 7, Eq. 9)
-enumerated exhaustively, and the invariants at lambda = 0 and lambda > 1.
+enumerated exhaustively, and the invariants at lambda = 0 and lambda > 1; for the
+sampling form (Sec. 2.1, Eq. 6) the exactness of speculative sampling by enumeration
+and by Monte Carlo, its greedy limit, and exact interval counts of the inverse CDF.
 No function here is "parity unpinned".
 """
 from .forward import (  # noqa: F401
@@ -33,3 +35,13 @@ from .decision import (  # noqa: F401
     prune_reroot,
 )
 from .rounds import commit, greedy_decode, trispec_rounds, verify_rounds  # noqa: F401
+from .sampling import (  # noqa: F401
+    RESAMPLE_DIRECT,
+    RESAMPLE_RESIDUAL,
+    accept_probability,
+    inverse_cdf,
+    residual_distribution,
+    residual_mass,
+    sample_decide,
+    tempered_softmax,
+)
