@@ -219,6 +219,60 @@ int trispec_decide(trispec_model *m, int32_t batch, const int32_t *draft_tokens,
                    const trispec_verify_opts *opts, const trispec_verify_out *out);
 
 /*
+ * Sampling form of the decision (temperature > 0) for a draft CHAIN of n_nodes = k + 1 nodes
+ * (node 0 = last committed token, node i = i-th draft token; parents are implied).
+ * Sec. 2.1: draft token x_i is accepted with probability min(1, p_v,i(x_i) / p_d,i(x_i)); at the
+ * first rejection the replacement is drawn from norm(max(0, p_v,i - p_d,i)).  Sec. 3.2 Eq. 6 is
+ * the same Bernoulli variable for the proxy; tau_a, the trust predicate g and tau_m (Eq. 7 - 9)
+ * and the routing into Case I / Case II are those of trispec_verify, with p_v = softmax(logits / T)
+ * also inside g.  Algorithm 1 prints the token after the accepted prefix as a plain draw from the
+ * verifier's distribution; TRISPEC_RESAMPLE_DIRECT does that, TRISPEC_RESAMPLE_RESIDUAL follows
+ * Sec. 2.1 (the rule that keeps the verifier's output distribution).  When every draft token is
+ * accepted both draw the bonus token from p_v at the last node.  A residual without mass (the
+ * supplied draft row dominates the verifier's everywhere) falls back to the direct draw.
+ * Tree-shaped drafts need a multi-candidate rule the paper does not define: not provided.
+ *
+ * A pure function of its inputs; no model or cache is involved, no random numbers are drawn here:
+ *   logits        device [batch, n_nodes, vocab] fp32: the pass's logits (trispec_verify's
+ *                 debug_logits buffer)
+ *   draft_tokens  device [batch, n_nodes]
+ *   p_draft       device [batch, n_nodes - 1, vocab] fp32: row i is the drafter's distribution
+ *                 from which node i + 1's token was drawn (may be NULL when n_nodes = 1)
+ *   u_accept      device [batch, n_nodes] uniforms in [0, 1): entry i decides draft node i
+ *                 (entries below n_forced are not read): accepted iff u * p_d(x) < p_v(x)
+ *   u_sample      device [batch] uniforms in [0, 1): the token is the smallest v whose cumulative
+ *                 mass (ascending token id) exceeds u * total mass
+ *   scratch       device, 256-byte aligned, trispec_sample_scratch_bytes() bytes
+ * out: accepted_len, token (-1 in Case II), escalate, path, argmax, confidence and margin (of the
+ * tempered distribution), status (bit 0: a draft token id outside [0, vocab); such a token is
+ * never accepted).  Any out pointer may be NULL.  Enqueues three kernels on `stream`, allocates
+ * nothing, does not synchronise.
+ * Errors (host side, before any launch): TRISPEC_ENULL, TRISPEC_ENODES, TRISPEC_EFORCED,
+ * TRISPEC_EWORKSPACE (scratch), TRISPEC_EARG (temperature not finite and positive, threshold NaN,
+ * criterion, resample, vocab < 1); TRISPEC_ELAUNCH afterwards.
+ */
+#define TRISPEC_RESAMPLE_RESIDUAL 0
+#define TRISPEC_RESAMPLE_DIRECT 1
+
+typedef struct {
+  float temperature;         /* T > 0 */
+  int32_t resample;          /* TRISPEC_RESAMPLE_* */
+  int32_t criterion;         /* TRISPEC_CRIT_* */
+  int32_t n_forced;          /* >= 1: nodes 0..n_forced-1 are already approved (Case II hand-over) */
+  const float *p_draft;      /* device */
+  const float *u_accept;     /* device */
+  const float *u_sample;     /* device */
+  void *scratch;             /* device */
+  size_t scratch_bytes;
+  void *stream;              /* hipStream_t; NULL = the default stream */
+} trispec_sample_opts;
+
+int trispec_sample_scratch_bytes(int32_t batch, int32_t n_nodes, size_t *bytes);
+int trispec_sample_decide(const float *logits, const int32_t *draft_tokens, int32_t batch,
+                          int32_t n_nodes, int32_t vocab, float threshold,
+                          const trispec_sample_opts *opts, const trispec_verify_out *out);
+
+/*
  * Measurement aid: HIP events recorded on the pass's own stream around every launch of one
  * kernel class, so a benchmark can price that kernel against the HBM roofline.
  *   TRISPEC_K_GEMM  the weight-streaming projection / FFN matmul (4 launches per layer)

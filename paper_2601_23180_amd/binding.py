@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libtrispec.so")
 
 TRISPEC_F32, TRISPEC_BF16 = 0, 1
 CRIT_MARGIN, CRIT_TOP1 = 0, 1
+RESAMPLE_RESIDUAL, RESAMPLE_DIRECT = 0, 1
 MAX_NODES, MAX_BATCH, MAX_ROWS, PATH_STRIDE = 64, 8, 256, 64
 
 EXPORTS = [
@@ -27,7 +28,7 @@ EXPORTS = [
     "trispec_workspace_region", "trispec_pass_bytes", "trispec_verify", "trispec_decide",
     "trispec_strerror", "trispec_timer_create", "trispec_timer_reset", "trispec_timer_read",
     "trispec_timer_destroy", "trispec_model_pack_bytes", "trispec_model_pack", "trispec_copy_probe",
-    "trispec_kv_commit",
+    "trispec_kv_commit", "trispec_sample_scratch_bytes", "trispec_sample_decide",
 ]
 K_GEMM, K_HEAD, K_ATTN = 0, 1, 2
 
@@ -55,6 +56,13 @@ class VerifyOpts(C.Structure):
 class VerifyOut(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in
                 ("accepted_len", "token", "escalate", "path", "argmax", "confidence", "margin", "status")]
+
+
+class SampleOpts(C.Structure):
+    _fields_ = [("temperature", C.c_float), ("resample", C.c_int32), ("criterion", C.c_int32),
+                ("n_forced", C.c_int32), ("p_draft", C.c_void_p), ("u_accept", C.c_void_p),
+                ("u_sample", C.c_void_p), ("scratch", C.c_void_p), ("scratch_bytes", C.c_size_t),
+                ("stream", C.c_void_p)]
 
 
 class TriSpecError(RuntimeError):
@@ -100,6 +108,9 @@ def lib() -> C.CDLL:
                                      C.c_int32, C.c_float, C.POINTER(VerifyOpts), C.POINTER(VerifyOut)]
         l.trispec_decide.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.POINTER(C.c_int32), C.c_int32,
                                      C.c_float, C.POINTER(VerifyOpts), C.POINTER(VerifyOut)]
+        l.trispec_sample_scratch_bytes.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
+        l.trispec_sample_decide.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_float,
+                                            C.POINTER(SampleOpts), C.POINTER(VerifyOut)]
         l.trispec_timer_create.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]
         l.trispec_timer_reset.argtypes = [C.c_void_p]
         l.trispec_timer_read.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_double),
@@ -277,6 +288,44 @@ def copy_probe(dst, src, stream=None) -> None:
         raise ValueError("copy_probe: sizes differ")
     st = stream if stream is not None else torch.cuda.current_stream().cuda_stream
     check(lib().trispec_copy_probe(dst.data_ptr(), src.data_ptr(), nbytes, st))
+
+
+def sample_decide(logits, draft_tokens, p_draft, u_accept, u_sample, temperature: float, threshold: float,
+                  criterion: int = CRIT_MARGIN, n_forced: int = 1, resample: int = RESAMPLE_RESIDUAL,
+                  stream=None) -> Dict[str, "torch.Tensor"]:
+    """trispec_sample_decide on device tensors: logits [batch, n_nodes, vocab] fp32, draft_tokens
+    [batch, n_nodes] int32, p_draft [batch, n_nodes - 1, vocab] fp32, u_accept [batch, n_nodes] fp32,
+    u_sample [batch] fp32.  Allocates the scratch and output tensors, marshals, returns the outputs."""
+    import torch
+    batch, n_nodes, vocab = logits.shape
+    for t, dt, shape in ((logits, torch.float32, (batch, n_nodes, vocab)), (draft_tokens, torch.int32, (batch, n_nodes)),
+                         (u_accept, torch.float32, (batch, n_nodes)), (u_sample, torch.float32, (batch,))):
+        if t.dtype != dt or tuple(t.shape) != shape or not t.is_contiguous() or not t.is_cuda:
+            raise ValueError("sample_decide: tensor of the wrong dtype, shape, layout or device")
+    if n_nodes > 1 and (p_draft.dtype != torch.float32 or tuple(p_draft.shape) != (batch, n_nodes - 1, vocab)
+                        or not p_draft.is_contiguous() or not p_draft.is_cuda):
+        raise ValueError("sample_decide: p_draft of the wrong dtype, shape, layout or device")
+    n = C.c_size_t()
+    check(lib().trispec_sample_scratch_bytes(batch, n_nodes, C.byref(n)))
+    scratch = torch.empty(n.value + 256, dtype=torch.uint8, device=logits.device)
+    sptr = scratch.data_ptr() + (-scratch.data_ptr()) % 256
+    i32 = dict(dtype=torch.int32, device=logits.device)
+    f32 = dict(dtype=torch.float32, device=logits.device)
+    res = {
+        "accepted_len": torch.zeros(batch, **i32), "token": torch.zeros(batch, **i32),
+        "escalate": torch.zeros(batch, **i32), "path": torch.zeros((batch, PATH_STRIDE), **i32),
+        "argmax": torch.zeros((batch, n_nodes), **i32), "confidence": torch.zeros((batch, n_nodes), **f32),
+        "margin": torch.zeros((batch, n_nodes), **f32), "status": torch.zeros(1, **i32),
+    }
+    out = VerifyOut(*[res[k].data_ptr() for k, _ in VerifyOut._fields_])
+    st = stream if stream is not None else torch.cuda.current_stream().cuda_stream
+    opts = SampleOpts(float(temperature), int(resample), int(criterion), int(n_forced),
+                      p_draft.data_ptr() if n_nodes > 1 else None, u_accept.data_ptr(), u_sample.data_ptr(),
+                      sptr, n.value, st)
+    check(lib().trispec_sample_decide(logits.data_ptr(), draft_tokens.data_ptr(), batch, n_nodes, vocab,
+                                      float(threshold), C.byref(opts), C.byref(out)))
+    res["_scratch"] = scratch   # keeps the scratch alive until the caller drops the result
+    return res
 
 
 class Verifier:

@@ -1,6 +1,7 @@
 // Host side of the C ABI: validation, workspace carve-up, launch sequence of one pass.
 // No allocation, no synchronisation and no HIP call other than kernel launches on the hot path.
 #include <math.h>
+#include <cmath>
 #include <stdlib.h>
 #include <string.h>
 
@@ -686,6 +687,70 @@ int trispec_decide(trispec_model *m, int32_t batch, const int32_t *draft_tokens,
   (void)hipGetLastError();
   DecideArgs d = make_decide(L, ws, draft_tokens, batch, n_nodes, threshold, opts, out);
   launch_decide(st, d);
+  return hipGetLastError() == hipSuccess ? TRISPEC_OK : TRISPEC_ELAUNCH;
+}
+
+namespace {
+struct SampleLayout {
+  size_t z, l1, l2, idx, pv, q, sel_row, sel_mode, total;
+};
+SampleLayout sample_layout(int batch, int n_nodes) {
+  const size_t rows = (size_t)batch * n_nodes;
+  SampleLayout L;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { const size_t o = off; off = align_up(off + bytes, 256); return o; };
+  L.z = take(rows * sizeof(double));
+  L.l1 = take(rows * sizeof(float));
+  L.l2 = take(rows * sizeof(float));
+  L.idx = take(rows * sizeof(int32_t));
+  L.pv = take(rows * sizeof(float));
+  L.q = take(rows * sizeof(float));
+  L.sel_row = take((size_t)batch * sizeof(int32_t));
+  L.sel_mode = take((size_t)batch * sizeof(int32_t));
+  L.total = off;
+  return L;
+}
+bool sample_shape_ok(int batch, int n_nodes) {
+  return batch >= 1 && batch <= kMaxBatch && n_nodes >= 1 && n_nodes <= kMaxNodes && batch * n_nodes <= kMaxRows;
+}
+}  // namespace
+
+int trispec_sample_scratch_bytes(int32_t batch, int32_t n_nodes, size_t *bytes) {
+  if (!bytes) return TRISPEC_ENULL;
+  if (!sample_shape_ok(batch, n_nodes)) return TRISPEC_ENODES;
+  *bytes = sample_layout(batch, n_nodes).total;
+  return TRISPEC_OK;
+}
+
+int trispec_sample_decide(const float *logits, const int32_t *draft_tokens, int32_t batch, int32_t n_nodes,
+                          int32_t vocab, float threshold, const trispec_sample_opts *o,
+                          const trispec_verify_out *out) {
+  if (!logits || !draft_tokens || !o || !out || !o->u_accept || !o->u_sample) return TRISPEC_ENULL;
+  if (!sample_shape_ok(batch, n_nodes)) return TRISPEC_ENODES;
+  if (n_nodes > 1 && !o->p_draft) return TRISPEC_ENULL;
+  if (o->n_forced < 1 || o->n_forced > n_nodes) return TRISPEC_EFORCED;
+  if (!(o->temperature > 0.f) || !std::isfinite(o->temperature) || threshold != threshold || vocab < 1 ||
+      (o->criterion != TRISPEC_CRIT_MARGIN && o->criterion != TRISPEC_CRIT_TOP1) ||
+      (o->resample != TRISPEC_RESAMPLE_RESIDUAL && o->resample != TRISPEC_RESAMPLE_DIRECT))
+    return TRISPEC_EARG;
+  const SampleLayout L = sample_layout(batch, n_nodes);
+  if (!o->scratch || ((uintptr_t)o->scratch & 255) || o->scratch_bytes < L.total) return TRISPEC_EWORKSPACE;
+  char *ws = (char *)o->scratch;
+  SampleArgs a;
+  memset(&a, 0, sizeof(a));
+  a.logits = logits; a.tokens = draft_tokens; a.p_draft = o->p_draft;
+  a.u_accept = o->u_accept; a.u_sample = o->u_sample;
+  a.batch = batch; a.n_nodes = n_nodes; a.vocab = vocab; a.n_forced = o->n_forced;
+  a.criterion = o->criterion; a.resample = o->resample;
+  a.inv_temp = 1.0f / o->temperature; a.threshold = threshold;
+  a.row_z = (double *)(ws + L.z);
+  a.row_l1 = (float *)(ws + L.l1); a.row_l2 = (float *)(ws + L.l2);
+  a.row_idx = (int32_t *)(ws + L.idx);
+  a.row_pv = (float *)(ws + L.pv); a.row_q = (float *)(ws + L.q);
+  a.sel_row = (int32_t *)(ws + L.sel_row); a.sel_mode = (int32_t *)(ws + L.sel_mode);
+  a.out = *out;
+  (void)hipGetLastError();
+  launch_sample_decide((hipStream_t)o->stream, a);
   return hipGetLastError() == hipSuccess ? TRISPEC_OK : TRISPEC_ELAUNCH;
 }
 

@@ -117,6 +117,25 @@ struct AttnArgs {
   size_t out_panel;     // panel stride (elements) of out
 };
 
+// Sampling-mode decision on a chain (kernels_sample.hip).  rows = batch * n_nodes.
+struct SampleArgs {
+  const float *logits;      // [rows, vocab]
+  const int32_t *tokens;    // [rows]
+  const float *p_draft;     // [batch, n_nodes - 1, vocab]
+  const float *u_accept;    // [rows]
+  const float *u_sample;    // [batch]
+  int32_t batch, n_nodes, vocab, n_forced, criterion, resample;
+  float inv_temp, threshold;
+  // scratch
+  double *row_z;            // [rows] sum exp((l - max) / T)
+  float *row_l1, *row_l2;   // [rows] largest and second-largest logit
+  int32_t *row_idx;         // [rows] argmax
+  float *row_pv, *row_q;    // [rows] p_v and p_d of the next node's token (row_pv < 0: invalid token id)
+  int32_t *sel_row, *sel_mode;   // [batch] node whose distribution yields the token; 0 none, 1 direct, 2 residual
+  trispec_verify_out out;
+};
+void launch_sample_decide(hipStream_t st, const SampleArgs &a);
+
 struct DecideArgs {
   const int32_t *tokens;   // device [B*M]
   const int32_t *parent;   // device [B*M] (workspace copy)

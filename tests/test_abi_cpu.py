@@ -162,3 +162,28 @@ def test_kv_commit_rejects_bad_arguments_before_any_launch():
     assert _verify_rc(m, kv, list(range(-1, 6)), 7) == -6   # still 250 cached: 250 + 7 > 256
     lib.trispec_kv_destroy(kv)
     lib.trispec_model_destroy(m)
+
+
+def test_sample_decide_rejects_bad_arguments_before_any_launch():
+    lib = B.lib()
+    n = C.c_size_t()
+    assert lib.trispec_sample_scratch_bytes(2, 9, None) == -1
+    assert lib.trispec_sample_scratch_bytes(0, 9, C.byref(n)) == -3
+    assert lib.trispec_sample_scratch_bytes(2, 65, C.byref(n)) == -3
+    assert lib.trispec_sample_scratch_bytes(8, 64, C.byref(n)) == -3       # 512 rows
+    assert lib.trispec_sample_scratch_bytes(2, 9, C.byref(n)) == 0 and n.value >= 18 * 28 and n.value % 256 == 0
+    out = B.VerifyOut()
+
+    def rc(logits=0x1000, tokens=0x2000, batch=2, n_nodes=9, vocab=100, lam=0.1, T=1.0, resample=0, crit=0,
+           n_forced=1, p_draft=0x3000, ua=0x4000, us=0x5000, scratch=0x10000, scratch_bytes=None):
+        o = B.SampleOpts(T, resample, crit, n_forced, p_draft, ua, us, scratch,
+                         n.value if scratch_bytes is None else scratch_bytes, None)
+        return lib.trispec_sample_decide(logits, tokens, batch, n_nodes, vocab, lam, C.byref(o), C.byref(out))
+
+    assert rc(logits=None) == -1 and rc(tokens=None) == -1 and rc(ua=None) == -1 and rc(us=None) == -1
+    assert rc(p_draft=None) == -1
+    assert rc(batch=9) == -3 and rc(n_nodes=0) == -3
+    assert rc(n_forced=0) == -5 and rc(n_forced=10) == -5
+    assert rc(T=0.0) == -8 and rc(T=-1.0) == -8 and rc(T=float("inf")) == -8 and rc(T=float("nan")) == -8
+    assert rc(lam=float("nan")) == -8 and rc(vocab=0) == -8 and rc(resample=2) == -8 and rc(crit=5) == -8
+    assert rc(scratch=None) == -7 and rc(scratch=0x10010) == -7 and rc(scratch_bytes=64) == -7

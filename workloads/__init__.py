@@ -18,5 +18,7 @@ from .gen import (  # noqa: F401
     gen_tree,
     gen_eagle2_tree,
     gen_draft_tokens,
+    gen_draft_distributions,
+    gen_uniforms,
     tree_depths,
 )

@@ -330,3 +330,39 @@ def gen_draft_tokens(parents: np.ndarray, vocab: int, seed: int) -> np.ndarray:
         s.add(t)
         tok[i] = t
     return tok
+
+
+# ---------------------------------------------------------------- sampling-mode inputs
+def gen_draft_distributions(verifier_logits: np.ndarray, temperature: float, seed: int, noise: float = 0.7,
+                            keep: int = 0) -> Tuple[np.ndarray, np.ndarray]:
+    """A stand-in drafter for a chain of M nodes whose verifier logits are given ([M, V]): its
+    distribution at node i is softmax((l_i + noise * N(0,1)) / T) — close to the verifier's, so
+    acceptance is neither certain nor hopeless — optionally cut to its `keep` most probable
+    tokens and renormalised (a drafter with a reduced vocabulary gives zero mass elsewhere).
+    Node i + 1's token is drawn from row i; node 0's token is uniform.
+    Returns (p_draft [M-1, V] float32, tokens [M] int32)."""
+    g = _rng(seed, 404)
+    l = np.asarray(verifier_logits, dtype=np.float64)
+    M, V = l.shape
+    tokens = np.empty(M, dtype=np.int32)
+    tokens[0] = int(g.integers(0, V))
+    p_draft = np.zeros((max(M - 1, 0), V), dtype=np.float32)
+    for i in range(M - 1):
+        z = (l[i] + noise * g.standard_normal(V)) / temperature
+        e = np.exp(z - z.max())
+        if keep and keep < V:
+            e[np.argsort(e)[: V - keep]] = 0.0
+        q = (e / e.sum()).astype(np.float32)
+        p_draft[i] = q
+        c = np.cumsum(q.astype(np.float64))
+        tokens[i + 1] = min(int(np.searchsorted(c, g.random() * c[-1], side="right")), V - 1)
+    return p_draft, tokens
+
+
+def gen_uniforms(seed: int, batch: int, n_nodes: int) -> Tuple[np.ndarray, np.ndarray]:
+    """u_accept [batch, n_nodes] and u_sample [batch], float32 in [0, 1)."""
+    g = _rng(seed, 405)
+    top = np.float32(1.0) - np.float32(2.0 ** -24)
+    ua = np.minimum(g.random((batch, n_nodes), dtype=np.float32), top)
+    us = np.minimum(g.random(batch, dtype=np.float32), top)
+    return ua, us
