@@ -143,7 +143,9 @@ __global__ __launch_bounds__(64 * NW) void k_attn_bf16(AttnArgs a) {
 
   // ---- tile staging: K tile = KT rows of D*2 bytes (16-byte vectors), V^T tile = D rows of KT*2 bytes
   constexpr int KV_PER_T = KT * D * 2 / 16 / NT;   // 16-byte vectors per thread, each of K and V^T
-  uint4 kreg[KV_PER_T], vreg[KV_PER_T];
+  typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // native vector: stays in registers
+  typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+  u32x4 kreg[KV_PER_T], vreg[KV_PER_T];
   auto load_tile = [&](int k0) {
 #pragma unroll
     for (int i = 0; i < KV_PER_T; ++i) {
@@ -151,19 +153,19 @@ __global__ __launch_bounds__(64 * NW) void k_attn_bf16(AttnArgs a) {
       {  // K: vector v -> key v / (D/8), 16-byte column v % (D/8)
         const int key = v / (D / 8), c = v % (D / 8);
         // rows past the context hold no token (their scores are masked); clamped into the cache
-        kreg[i] = *(const uint4 *)(kc + (size_t)min(k0 + key, a.capacity - 1) * D + c * 8);
+        kreg[i] = *(const u32x4 *)(kc + (size_t)min(k0 + key, a.capacity - 1) * D + c * 8);
       }
       {  // V^T: vector v -> feature v / (KT/8), 8 keys starting at (v % (KT/8)) * 8
         const int f = v / (KT / 8), c = v % (KT / 8);
         const int kfirst = k0 + c * 8;
-        uint4 t = *(const uint4 *)(vc + (size_t)f * a.capacity + min(kfirst, a.capacity - 8));
+        u32x4 t = *(const u32x4 *)(vc + (size_t)f * a.capacity + min(kfirst, a.capacity - 8));
         if (kfirst + 8 > n_keys) {   // zero the values of slots that hold no token
           auto keep = [&](uint32_t x, int e0) {   // x holds keys kfirst + e0 (low half) and kfirst + e0 + 1
             if (kfirst + e0 >= n_keys) x &= 0xffff0000u;
             if (kfirst + e0 + 1 >= n_keys) x &= 0x0000ffffu;
             return x;
           };
-          t = make_uint4(keep(t.x, 0), keep(t.y, 2), keep(t.z, 4), keep(t.w, 6));
+          t = u32x4{keep(t.x, 0), keep(t.y, 2), keep(t.z, 4), keep(t.w, 6)};
         }
         vreg[i] = t;
       }
@@ -176,13 +178,13 @@ __global__ __launch_bounds__(64 * NW) void k_attn_bf16(AttnArgs a) {
       const int v = tid + NT * i;
       {
         const int key = v / (D / 8), c = v % (D / 8);
-        *(uint4 *)(base + key * L::kStrideK + c * 16) = kreg[i];
+        *(u32x4 *)(base + key * L::kStrideK + c * 16) = kreg[i];
       }
       {
         const int f = v / (KT / 8), c = v % (KT / 8);
-        uint2 *dst = (uint2 *)(base + L::kBytesK + f * L::kStrideV + c * 16);
-        dst[0] = make_uint2(vreg[i].x, vreg[i].y);
-        dst[1] = make_uint2(vreg[i].z, vreg[i].w);
+        u32x2 *dst = (u32x2 *)(base + L::kBytesK + f * L::kStrideV + c * 16);
+        dst[0] = u32x2{vreg[i].x, vreg[i].y};
+        dst[1] = u32x2{vreg[i].z, vreg[i].w};
       }
     }
   };

@@ -381,12 +381,13 @@ __global__ __launch_bounds__(256) void k_kv_commit(T *k_cache, T *v_cache, int b
   constexpr int MAXV = kMaxNodes * 128 / VEC / 256;         // vectors per thread at d = 128
   constexpr int MAXE = kMaxNodes * 128 / 256;               // V^T elements per thread at d = 128
   const int vec_per_row = d / VEC;
-  uint4 kv[MAXV];
+  typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // native vector: stays in registers
+  u32x4 kv[MAXV];
   T ve[MAXE];
 #pragma unroll
   for (int u = 0; u < MAXV; ++u) {
     const int idx = tid + 256 * u, i = idx / vec_per_row, c = idx - i * vec_per_row;
-    if (i < n) kv[u] = *(const uint4 *)(kc + (size_t)(ctx + t.node[b][i]) * d + c * VEC);
+    if (i < n) kv[u] = *(const u32x4 *)(kc + (size_t)(ctx + t.node[b][i]) * d + c * VEC);
   }
 #pragma unroll
   for (int u = 0; u < MAXE; ++u) {
@@ -397,7 +398,7 @@ __global__ __launch_bounds__(256) void k_kv_commit(T *k_cache, T *v_cache, int b
 #pragma unroll
   for (int u = 0; u < MAXV; ++u) {
     const int idx = tid + 256 * u, i = idx / vec_per_row, c = idx - i * vec_per_row;
-    if (i < n) *(uint4 *)(kc + (size_t)(ctx + i) * d + c * VEC) = kv[u];
+    if (i < n) *(u32x4 *)(kc + (size_t)(ctx + i) * d + c * VEC) = kv[u];
   }
 #pragma unroll
   for (int u = 0; u < MAXE; ++u) {
