@@ -167,6 +167,10 @@ typedef struct {
   float *debug_logits;       /* optional device [batch, n_nodes, vocab] fp32; NULL on the hot path */
   void *stream;              /* hipStream_t; NULL = the default stream */
   trispec_timer *timer;      /* optional per-kernel timer (measurement only); NULL on the hot path */
+  float *hidden_out;         /* optional device [batch, n_nodes, hidden] fp32: the verifier's feature at
+                                every node — the final-norm output the LM head reads — which the
+                                drafter is re-seeded with after the round (Sec. 3.2, "Drafter
+                                selection and adapter training"); NULL = not exported */
 } trispec_verify_opts;
 
 #define TRISPEC_PATH_STRIDE (TRISPEC_MAX_NODES)

@@ -50,7 +50,7 @@ class Weights(C.Structure):
 class VerifyOpts(C.Structure):
     _fields_ = [("criterion", C.c_int32), ("n_forced", C.c_int32), ("workspace", C.c_void_p),
                 ("workspace_bytes", C.c_size_t), ("debug_logits", C.c_void_p), ("stream", C.c_void_p),
-                ("timer", C.c_void_p)]
+                ("timer", C.c_void_p), ("hidden_out", C.c_void_p)]
 
 
 class VerifyOut(C.Structure):
@@ -331,7 +331,8 @@ def sample_decide(logits, draft_tokens, p_draft, u_accept, u_sample, temperature
 class Verifier:
     """Pre-allocated workspace and output buffers for repeated trispec_verify calls."""
 
-    def __init__(self, model: Model, batch: int, max_nodes: int, debug_logits: bool = False, device="cuda"):
+    def __init__(self, model: Model, batch: int, max_nodes: int, debug_logits: bool = False, device="cuda",
+                 export_hidden: bool = False):
         self.model, self.batch, self.max_nodes = model, batch, max_nodes
         self.ws_bytes = model.workspace_bytes(batch, max_nodes)
         self.workspace = torch.zeros(self.ws_bytes + 256, dtype=torch.uint8, device=device)
@@ -346,6 +347,7 @@ class Verifier:
             "margin": torch.zeros((batch, max_nodes), **f32), "status": torch.zeros(1, **i32),
         }
         self.logits = torch.zeros((batch, max_nodes, model.cfg.vocab), **f32) if debug_logits else None
+        self.hidden = torch.zeros((batch, max_nodes, model.cfg.hidden), **f32) if export_hidden else None
         self.timer = None   # optional KernelTimer attached to every verify call
 
     def _opts(self, criterion, n_forced, stream, want_logits):
@@ -356,6 +358,7 @@ class Verifier:
         s = stream if stream is not None else torch.cuda.current_stream()
         o.stream = s.cuda_stream
         o.timer = self.timer.handle if self.timer is not None else None
+        o.hidden_out = self.hidden.data_ptr() if self.hidden is not None else None
         return o
 
     def _out(self, n_nodes):

@@ -561,6 +561,8 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
       gemm(h, c.hidden, 1, m->lm_head, c.vocab, nullptr, 0, nullptr, 0, logits);
       launch_stats_from_logits(st, logits, rows, c.vocab, hs);
     }
+    if (opts->hidden_out)
+      launch_export_hidden(st, c.dtype, h, nullptr, nullptr, 0, rows, rp, c.hidden, c.rms_eps, opts->hidden_out);
   } else {
     // ---------------- bf16 models: per layer QKV, attention (+ merge), O, gate/up, down
     void *h = ws + L.h;
@@ -658,6 +660,9 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
       TimedLaunch tl(opts->timer, TRISPEC_K_HEAD, st, (double)c.vocab * c.hidden * es);
       launch_gemm(st, g);
     }
+    if (opts->hidden_out)   // x after the last layer, the final norm's weight, the sums of squares the last down projection left
+      launch_export_hidden(st, c.dtype, x, m->final_norm, ss0, ss0_tiles, rows, rp, c.hidden, c.rms_eps,
+                           opts->hidden_out);
   }
 
   launch_stats_reduce(st, hs, rows, (float *)(ws + L.node_l1), (float *)(ws + L.node_l2),

@@ -166,6 +166,10 @@ struct CommitTable {
 void launch_kv_commit(hipStream_t st, int dtype, void *k_cache, void *v_cache, int n_layers, int batch,
                       int n_kv_heads, int head_dim, int capacity, const CommitTable &t);
 void launch_copy_probe(hipStream_t st, void *dst, const void *src, size_t bytes);
+// out[r][c] = x[r][c] * rstd(r) * w[c]; rstd from the per-tile sums of squares ss[tile][rows_pad]
+// (ss == nullptr: x is already normalised and weighted, plain copy)
+void launch_export_hidden(hipStream_t st, int dtype, const float *x, const void *norm_w, const float *ss,
+                          int ss_tiles, int rows, int rows_pad, int hidden, float eps, float *out);
 void launch_zero_counters(hipStream_t st, int32_t *counters, int n_counters);
 void launch_qkv_epilogue(hipStream_t st, int dtype, const float *part, int n_splits, int rows,
                          int rows_pad, int n_q_heads, int n_kv_heads, int head_dim,

@@ -366,6 +366,33 @@ void launch_copy_probe(hipStream_t st, void *dst, const void *src, size_t bytes)
   hipLaunchKernelGGL(k_copy_probe, dim3((unsigned)blocks), dim3(256), 0, st, (uint4 *)dst, (const uint4 *)src, n);
 }
 
+// Feature export: the final-norm output of every row in fp32.  One workgroup per row.
+template <typename T>
+__global__ __launch_bounds__(256) void k_export_hidden(const float *x, const T *w, const float *ss, int ss_tiles,
+                                                        int rows_pad, int hidden, float eps, float *out) {
+  const int r = blockIdx.x;
+  float rstd = 1.f;
+  if (ss != nullptr) {
+    float s = 0.f;
+    for (int t = 0; t < ss_tiles; ++t) s += ss[(size_t)t * rows_pad + r];   // ascending tile order
+    rstd = 1.0f / sqrtf(s / (float)hidden + eps);
+  }
+  for (int c = threadIdx.x; c < hidden; c += 256) {
+    const float v = x[(size_t)r * hidden + c];
+    out[(size_t)r * hidden + c] = (ss != nullptr) ? v * rstd * to_f32(w[c]) : v;
+  }
+}
+
+void launch_export_hidden(hipStream_t st, int dtype, const float *x, const void *norm_w, const float *ss,
+                          int ss_tiles, int rows, int rows_pad, int hidden, float eps, float *out) {
+  if (dtype == TRISPEC_F32)
+    hipLaunchKernelGGL(k_export_hidden<float>, dim3(rows), dim3(256), 0, st, x, (const float *)norm_w, ss,
+                       ss_tiles, rows_pad, hidden, eps, out);
+  else
+    hipLaunchKernelGGL(k_export_hidden<bf16>, dim3(rows), dim3(256), 0, st, x, (const bf16 *)norm_w, ss,
+                       ss_tiles, rows_pad, hidden, eps, out);
+}
+
 // Commit of a verified path: per (kv head, sequence, layer) the K rows and the V^T columns of the
 // path's nodes move from slot ctx + node[i] to slot ctx + i.  node[i] >= i, so a destination may
 // be another row's source: everything is read into registers, then a barrier, then written.

@@ -42,7 +42,8 @@ class Case:
             outs.append(o)
         return outs
 
-    def run_gpu(self, threshold, criterion=CRIT_MARGIN, n_forced=1, model=None, want_logits=True):
+    def run_gpu(self, threshold, criterion=CRIT_MARGIN, n_forced=1, model=None, want_logits=True,
+                export_hidden=False):
         model = model or device_model(self.shape, self.seed)
         cap = capacity_for(max(self.ctx_len) + self.n_nodes)
         kv = KVCache(model, self.batch, cap)
@@ -56,7 +57,7 @@ class Case:
                 kv.k[l, b, :, :C, :] = kt
                 kv.v[l, b, :, :, :C] = vt.transpose(-1, -2)
         kv.set_len(self.ctx_len)
-        ver = Verifier(model, self.batch, self.n_nodes, debug_logits=want_logits)
+        ver = Verifier(model, self.batch, self.n_nodes, debug_logits=want_logits, export_hidden=export_hidden)
         tok = torch.from_numpy(self.tokens).cuda()
         pos = torch.from_numpy(self.positions).cuda()
         out = ver.verify(kv, tok, self.parents, pos, threshold, criterion, n_forced)
@@ -64,6 +65,8 @@ class Case:
         res = {k: v.cpu().numpy().copy() for k, v in out.items()}
         if want_logits:
             res["logits"] = ver.logits.cpu().numpy().copy()
+        if export_hidden:
+            res["hidden"] = ver.hidden.cpu().numpy().copy()
         res["_ver"], res["_kv"], res["_model"], res["_tok"] = ver, kv, model, tok
         return res
 

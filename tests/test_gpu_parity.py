@@ -308,3 +308,19 @@ def test_seed_sweep_random_shapes(seed):
     plant = [(int(np.argmax(tree_depths(p))), int(rng.integers(0, 5))) for p in parents]
     case = make_case(shape, seed, ctx_lens, parents, plant=plant)
     full_check(case, thresholds=(0.0, float(rng.uniform(0.1, 0.9)), 1.5))
+
+
+@pytest.mark.parametrize("key,tol", [("tiny", 2e-5), ("tiny_bf16", 3e-4)])
+def test_exported_features_equal_the_final_norm_output(key, tol):
+    """hidden_out = the LM head's input (final RMSNorm of the last residual stream) at every node,
+    two sequences with unequal contexts; tolerance relative to the largest feature of the row."""
+    shape = SHAPES[key]
+    parents = [gen_tree(24, 6, 3, 5), gen_tree(24, 6, 3, 6)]
+    case = make_case(shape, 77, [70, 33], parents)
+    want = case.run_oracle()
+    got = case.run_gpu(0.5, CRIT_MARGIN, export_hidden=True)
+    for b in range(2):
+        ref = want[b]["final_hidden"]
+        err = np.abs(got["hidden"][b] - ref).max(axis=1) / np.abs(ref).max(axis=1)
+        assert err.max() <= tol, (b, err.max())
+        logits_ok(shape, got["logits"][b], want[b]["logits"])      # the export does not disturb the pass

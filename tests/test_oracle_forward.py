@@ -145,3 +145,24 @@ def test_single_path_tree_equals_chain_and_position_shift():
     Ks, Vs = prefill(shape, seed, ctx, start_pos=1000)
     sh = verify_forward(W, shape, Ks, Vs, toks, parents, 1000 + C + tree_depths(parents))["logits"]
     assert np.max(np.abs(sh - full)) < 1e-8
+
+
+def test_final_hidden_is_what_the_lm_head_maps_to_the_logits():
+    """The exported feature is pinned through the logits (themselves pinned above): the vocabulary is
+    larger than the hidden size, so a least-squares solve of lm_head . h = logits (numpy's LAPACK
+    routine) has one solution, which must be final_hidden."""
+    from oracle import OracleWeights, verify_forward
+    from workloads import SHAPES, WeightSource, gen_draft_tokens, gen_tree, tree_depths
+    shape, seed = SHAPES["tiny"], 3
+    W = OracleWeights(WeightSource(shape, seed).get)
+    parents = gen_tree(12, 4, 3, seed)
+    d = shape.head_dim
+    rng = np.random.default_rng(0)
+    k = rng.standard_normal((shape.n_layers, shape.n_kv_heads, 20, d))
+    v = rng.standard_normal((shape.n_layers, shape.n_kv_heads, 20, d))
+    out = verify_forward(W, shape, k, v, gen_draft_tokens(parents, shape.vocab, seed), parents, 20 + tree_depths(parents))
+    head = np.asarray(W("lm_head"), dtype=np.float64)
+    assert head.shape[0] > head.shape[1]
+    sol, _, rank, _ = np.linalg.lstsq(head, out["logits"].T, rcond=None)
+    assert rank == shape.hidden
+    assert np.allclose(sol.T, out["final_hidden"], rtol=0, atol=1e-9)
