@@ -123,6 +123,8 @@ BF16_CASES = [
     ("tree60_group4_rb2", TB.with_(n_q_heads=8), [300], lambda s: gen_tree(60, 8, 4, s)),
     ("eagle2_tree", TB, [77], lambda s: gen_eagle2_tree(s)),
     ("max_nodes_64", TB, [130], lambda s: gen_tree(64, 8, 4, s)),
+    ("chain64_deepest_paths", TB.with_(n_layers=1), [100], lambda s: gen_chain(64)),
+    ("group4_nodes64_rows256", TB.with_(n_layers=1, n_q_heads=8), [150], lambda s: gen_tree(64, 12, 3, s)),
     ("single_node", TB, [64], lambda s: gen_chain(1)),
     ("empty_context", TB, [0], lambda s: gen_tree(20, 5, 3, s)),
     ("many_splits", TB.with_(n_layers=1), [1100], lambda s: gen_tree(33, 8, 4, s)),
