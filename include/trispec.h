@@ -249,11 +249,11 @@ int trispec_decide(trispec_model *m, int32_t batch, const int32_t *draft_tokens,
  *   scratch       device, 256-byte aligned, trispec_sample_scratch_bytes() bytes
  * out: accepted_len, token (-1 in Case II), escalate, path, argmax, confidence and margin (of the
  * tempered distribution), status (bit 0: a draft token id outside [0, vocab); such a token is
- * never accepted).  Any out pointer may be NULL.  Enqueues three kernels on `stream`, allocates
+ * never accepted).  Any out pointer may be NULL.  Enqueues four kernels on `stream`, allocates
  * nothing, does not synchronise.
  * Errors (host side, before any launch): TRISPEC_ENULL, TRISPEC_ENODES, TRISPEC_EFORCED,
  * TRISPEC_EWORKSPACE (scratch), TRISPEC_EARG (temperature not finite and positive, threshold NaN,
- * criterion, resample, vocab < 1); TRISPEC_ELAUNCH afterwards.
+ * criterion, resample, vocab outside [1, 4194304]); TRISPEC_ELAUNCH afterwards.
  */
 #define TRISPEC_RESAMPLE_RESIDUAL 0
 #define TRISPEC_RESAMPLE_DIRECT 1
@@ -271,7 +271,7 @@ typedef struct {
   void *stream;              /* hipStream_t; NULL = the default stream */
 } trispec_sample_opts;
 
-int trispec_sample_scratch_bytes(int32_t batch, int32_t n_nodes, size_t *bytes);
+int trispec_sample_scratch_bytes(int32_t batch, int32_t n_nodes, int32_t vocab, size_t *bytes);
 int trispec_sample_decide(const float *logits, const int32_t *draft_tokens, int32_t batch,
                           int32_t n_nodes, int32_t vocab, float threshold,
                           const trispec_sample_opts *opts, const trispec_verify_out *out);

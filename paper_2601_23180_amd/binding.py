@@ -108,7 +108,7 @@ def lib() -> C.CDLL:
                                      C.c_int32, C.c_float, C.POINTER(VerifyOpts), C.POINTER(VerifyOut)]
         l.trispec_decide.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.POINTER(C.c_int32), C.c_int32,
                                      C.c_float, C.POINTER(VerifyOpts), C.POINTER(VerifyOut)]
-        l.trispec_sample_scratch_bytes.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
+        l.trispec_sample_scratch_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
         l.trispec_sample_decide.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_float,
                                             C.POINTER(SampleOpts), C.POINTER(VerifyOut)]
         l.trispec_timer_create.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]
@@ -290,41 +290,60 @@ def copy_probe(dst, src, stream=None) -> None:
     check(lib().trispec_copy_probe(dst.data_ptr(), src.data_ptr(), nbytes, st))
 
 
+class SampleDecider:
+    """Pre-allocated scratch and output buffers for repeated trispec_sample_decide calls on
+    [batch, n_nodes, vocab] logits."""
+
+    def __init__(self, batch: int, n_nodes: int, vocab: int, device="cuda"):
+        self.batch, self.n_nodes, self.vocab = batch, n_nodes, vocab
+        n = C.c_size_t()
+        check(lib().trispec_sample_scratch_bytes(batch, n_nodes, vocab, C.byref(n)))
+        self.scratch_bytes = n.value
+        self.scratch = torch.empty(n.value + 256, dtype=torch.uint8, device=device)
+        self._sptr = self.scratch.data_ptr() + (-self.scratch.data_ptr()) % 256
+        i32 = dict(dtype=torch.int32, device=device)
+        f32 = dict(dtype=torch.float32, device=device)
+        self.out = {
+            "accepted_len": torch.zeros(batch, **i32), "token": torch.zeros(batch, **i32),
+            "escalate": torch.zeros(batch, **i32), "path": torch.zeros((batch, PATH_STRIDE), **i32),
+            "argmax": torch.zeros((batch, n_nodes), **i32), "confidence": torch.zeros((batch, n_nodes), **f32),
+            "margin": torch.zeros((batch, n_nodes), **f32), "status": torch.zeros(1, **i32),
+        }
+        self._out = VerifyOut(*[self.out[k].data_ptr() for k, _ in VerifyOut._fields_])
+
+    def decide(self, logits, draft_tokens, p_draft, u_accept, u_sample, temperature: float, threshold: float,
+               criterion: int = CRIT_MARGIN, n_forced: int = 1, resample: int = RESAMPLE_RESIDUAL,
+               stream=None) -> Dict[str, torch.Tensor]:
+        """logits [batch, n_nodes, vocab] fp32, draft_tokens [batch, n_nodes] int32, p_draft
+        [batch, n_nodes - 1, vocab] fp32, u_accept [batch, n_nodes] fp32, u_sample [batch] fp32,
+        all contiguous device tensors.  Marshals and returns the (reused) output tensors."""
+        batch, n_nodes, vocab = self.batch, self.n_nodes, self.vocab
+        for t, dt, shape in ((logits, torch.float32, (batch, n_nodes, vocab)),
+                             (draft_tokens, torch.int32, (batch, n_nodes)),
+                             (u_accept, torch.float32, (batch, n_nodes)), (u_sample, torch.float32, (batch,))):
+            if t.dtype != dt or tuple(t.shape) != shape or not t.is_contiguous() or not t.is_cuda:
+                raise ValueError("sample_decide: tensor of the wrong dtype, shape, layout or device")
+        if n_nodes > 1 and (p_draft.dtype != torch.float32 or tuple(p_draft.shape) != (batch, n_nodes - 1, vocab)
+                            or not p_draft.is_contiguous() or not p_draft.is_cuda):
+            raise ValueError("sample_decide: p_draft of the wrong dtype, shape, layout or device")
+        st = stream if stream is not None else torch.cuda.current_stream().cuda_stream
+        opts = SampleOpts(float(temperature), int(resample), int(criterion), int(n_forced),
+                          p_draft.data_ptr() if n_nodes > 1 else None, u_accept.data_ptr(), u_sample.data_ptr(),
+                          self._sptr, self.scratch_bytes, st)
+        check(lib().trispec_sample_decide(logits.data_ptr(), draft_tokens.data_ptr(), batch, n_nodes, vocab,
+                                          float(threshold), C.byref(opts), C.byref(self._out)))
+        return self.out
+
+
 def sample_decide(logits, draft_tokens, p_draft, u_accept, u_sample, temperature: float, threshold: float,
                   criterion: int = CRIT_MARGIN, n_forced: int = 1, resample: int = RESAMPLE_RESIDUAL,
-                  stream=None) -> Dict[str, "torch.Tensor"]:
-    """trispec_sample_decide on device tensors: logits [batch, n_nodes, vocab] fp32, draft_tokens
-    [batch, n_nodes] int32, p_draft [batch, n_nodes - 1, vocab] fp32, u_accept [batch, n_nodes] fp32,
-    u_sample [batch] fp32.  Allocates the scratch and output tensors, marshals, returns the outputs."""
-    import torch
+                  stream=None) -> Dict[str, torch.Tensor]:
+    """One-off form of SampleDecider.decide (allocates its buffers on every call)."""
     batch, n_nodes, vocab = logits.shape
-    for t, dt, shape in ((logits, torch.float32, (batch, n_nodes, vocab)), (draft_tokens, torch.int32, (batch, n_nodes)),
-                         (u_accept, torch.float32, (batch, n_nodes)), (u_sample, torch.float32, (batch,))):
-        if t.dtype != dt or tuple(t.shape) != shape or not t.is_contiguous() or not t.is_cuda:
-            raise ValueError("sample_decide: tensor of the wrong dtype, shape, layout or device")
-    if n_nodes > 1 and (p_draft.dtype != torch.float32 or tuple(p_draft.shape) != (batch, n_nodes - 1, vocab)
-                        or not p_draft.is_contiguous() or not p_draft.is_cuda):
-        raise ValueError("sample_decide: p_draft of the wrong dtype, shape, layout or device")
-    n = C.c_size_t()
-    check(lib().trispec_sample_scratch_bytes(batch, n_nodes, C.byref(n)))
-    scratch = torch.empty(n.value + 256, dtype=torch.uint8, device=logits.device)
-    sptr = scratch.data_ptr() + (-scratch.data_ptr()) % 256
-    i32 = dict(dtype=torch.int32, device=logits.device)
-    f32 = dict(dtype=torch.float32, device=logits.device)
-    res = {
-        "accepted_len": torch.zeros(batch, **i32), "token": torch.zeros(batch, **i32),
-        "escalate": torch.zeros(batch, **i32), "path": torch.zeros((batch, PATH_STRIDE), **i32),
-        "argmax": torch.zeros((batch, n_nodes), **i32), "confidence": torch.zeros((batch, n_nodes), **f32),
-        "margin": torch.zeros((batch, n_nodes), **f32), "status": torch.zeros(1, **i32),
-    }
-    out = VerifyOut(*[res[k].data_ptr() for k, _ in VerifyOut._fields_])
-    st = stream if stream is not None else torch.cuda.current_stream().cuda_stream
-    opts = SampleOpts(float(temperature), int(resample), int(criterion), int(n_forced),
-                      p_draft.data_ptr() if n_nodes > 1 else None, u_accept.data_ptr(), u_sample.data_ptr(),
-                      sptr, n.value, st)
-    check(lib().trispec_sample_decide(logits.data_ptr(), draft_tokens.data_ptr(), batch, n_nodes, vocab,
-                                      float(threshold), C.byref(opts), C.byref(out)))
-    res["_scratch"] = scratch   # keeps the scratch alive until the caller drops the result
+    dec = SampleDecider(batch, n_nodes, vocab, logits.device)
+    res = dict(dec.decide(logits, draft_tokens, p_draft, u_accept, u_sample, temperature, threshold, criterion,
+                          n_forced, resample, stream))
+    res["_decider"] = dec   # keeps scratch and outputs alive until the caller drops the result
     return res
 
 

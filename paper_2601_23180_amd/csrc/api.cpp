@@ -697,9 +697,10 @@ int trispec_decide(trispec_model *m, int32_t batch, const int32_t *draft_tokens,
 
 namespace {
 struct SampleLayout {
-  size_t z, l1, l2, idx, pv, q, sel_row, sel_mode, total;
+  size_t z, l1, l2, idx, cs_l1, cs_l2, cs_idx, cs_z, seq_bad, sel_row, sel_mode, chunk_sum, total;
+  int n_chunks;
 };
-SampleLayout sample_layout(int batch, int n_nodes) {
+SampleLayout sample_layout(int batch, int n_nodes, int vocab) {
   const size_t rows = (size_t)batch * n_nodes;
   SampleLayout L;
   size_t off = 0;
@@ -708,10 +709,15 @@ SampleLayout sample_layout(int batch, int n_nodes) {
   L.l1 = take(rows * sizeof(float));
   L.l2 = take(rows * sizeof(float));
   L.idx = take(rows * sizeof(int32_t));
-  L.pv = take(rows * sizeof(float));
-  L.q = take(rows * sizeof(float));
+  L.n_chunks = (vocab + kSampleChunk - 1) / kSampleChunk;
+  L.cs_l1 = take(rows * L.n_chunks * sizeof(float));
+  L.cs_l2 = take(rows * L.n_chunks * sizeof(float));
+  L.cs_idx = take(rows * L.n_chunks * sizeof(int32_t));
+  L.cs_z = take(rows * L.n_chunks * sizeof(double));
+  L.seq_bad = take((size_t)batch * sizeof(int32_t));
   L.sel_row = take((size_t)batch * sizeof(int32_t));
   L.sel_mode = take((size_t)batch * sizeof(int32_t));
+  L.chunk_sum = take((size_t)batch * 2 * L.n_chunks * sizeof(double));
   L.total = off;
   return L;
 }
@@ -720,10 +726,11 @@ bool sample_shape_ok(int batch, int n_nodes) {
 }
 }  // namespace
 
-int trispec_sample_scratch_bytes(int32_t batch, int32_t n_nodes, size_t *bytes) {
+int trispec_sample_scratch_bytes(int32_t batch, int32_t n_nodes, int32_t vocab, size_t *bytes) {
   if (!bytes) return TRISPEC_ENULL;
   if (!sample_shape_ok(batch, n_nodes)) return TRISPEC_ENODES;
-  *bytes = sample_layout(batch, n_nodes).total;
+  if (vocab < 1 || vocab > kSampleMaxVocab) return TRISPEC_EARG;
+  *bytes = sample_layout(batch, n_nodes, vocab).total;
   return TRISPEC_OK;
 }
 
@@ -734,11 +741,11 @@ int trispec_sample_decide(const float *logits, const int32_t *draft_tokens, int3
   if (!sample_shape_ok(batch, n_nodes)) return TRISPEC_ENODES;
   if (n_nodes > 1 && !o->p_draft) return TRISPEC_ENULL;
   if (o->n_forced < 1 || o->n_forced > n_nodes) return TRISPEC_EFORCED;
-  if (!(o->temperature > 0.f) || !std::isfinite(o->temperature) || threshold != threshold || vocab < 1 ||
+  if (!(o->temperature > 0.f) || !std::isfinite(o->temperature) || threshold != threshold || vocab < 1 || vocab > kSampleMaxVocab ||
       (o->criterion != TRISPEC_CRIT_MARGIN && o->criterion != TRISPEC_CRIT_TOP1) ||
       (o->resample != TRISPEC_RESAMPLE_RESIDUAL && o->resample != TRISPEC_RESAMPLE_DIRECT))
     return TRISPEC_EARG;
-  const SampleLayout L = sample_layout(batch, n_nodes);
+  const SampleLayout L = sample_layout(batch, n_nodes, vocab);
   if (!o->scratch || ((uintptr_t)o->scratch & 255) || o->scratch_bytes < L.total) return TRISPEC_EWORKSPACE;
   char *ws = (char *)o->scratch;
   SampleArgs a;
@@ -751,8 +758,11 @@ int trispec_sample_decide(const float *logits, const int32_t *draft_tokens, int3
   a.row_z = (double *)(ws + L.z);
   a.row_l1 = (float *)(ws + L.l1); a.row_l2 = (float *)(ws + L.l2);
   a.row_idx = (int32_t *)(ws + L.idx);
-  a.row_pv = (float *)(ws + L.pv); a.row_q = (float *)(ws + L.q);
+  a.cs_l1 = (float *)(ws + L.cs_l1); a.cs_l2 = (float *)(ws + L.cs_l2);
+  a.cs_idx = (int32_t *)(ws + L.cs_idx); a.cs_z = (double *)(ws + L.cs_z);
+  a.seq_bad = (int32_t *)(ws + L.seq_bad);
   a.sel_row = (int32_t *)(ws + L.sel_row); a.sel_mode = (int32_t *)(ws + L.sel_mode);
+  a.chunk_sum = (double *)(ws + L.chunk_sum); a.n_chunks = L.n_chunks;
   a.out = *out;
   (void)hipGetLastError();
   launch_sample_decide((hipStream_t)o->stream, a);

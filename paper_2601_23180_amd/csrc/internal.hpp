@@ -117,6 +117,8 @@ struct AttnArgs {
   size_t out_panel;     // panel stride (elements) of out
 };
 
+constexpr int kSampleChunk = 4096;   // tokens per chunk of the inverse-CDF draw
+constexpr int kSampleMaxVocab = kSampleChunk * 1024;   // one thread of the pick kernel per chunk
 // Sampling-mode decision on a chain (kernels_sample.hip).  rows = batch * n_nodes.
 struct SampleArgs {
   const float *logits;      // [rows, vocab]
@@ -130,8 +132,13 @@ struct SampleArgs {
   double *row_z;            // [rows] sum exp((l - max) / T)
   float *row_l1, *row_l2;   // [rows] largest and second-largest logit
   int32_t *row_idx;         // [rows] argmax
-  float *row_pv, *row_q;    // [rows] p_v and p_d of the next node's token (row_pv < 0: invalid token id)
+  float *cs_l1, *cs_l2;     // [rows][n_chunks] per chunk of kSampleChunk tokens: largest / second-largest logit,
+  int32_t *cs_idx;          //                  argmax,
+  double *cs_z;             //                  sum exp((l - chunk max) / T)
+  int32_t *seq_bad;         // [batch] 1: a draft token id of the sequence is outside the vocabulary
   int32_t *sel_row, *sel_mode;   // [batch] node whose distribution yields the token; 0 none, 1 direct, 2 residual
+  double *chunk_sum;        // [batch][2][n_chunks] mass per chunk of kSampleChunk tokens: tempered p_v, residual
+  int32_t n_chunks;
   trispec_verify_out out;
 };
 void launch_sample_decide(hipStream_t st, const SampleArgs &a);

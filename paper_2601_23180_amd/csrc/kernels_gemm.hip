@@ -269,9 +269,13 @@ static void dispatch(hipStream_t st, const GemmArgs &a) {
   // (the 4-deep W ring does not fit the register file next to the accumulators of 256 rows)
 #define TS_LAUNCH(MB_, KC_)                                                                   \
   do {                                                                                        \
-    if (MB_ < 8 && a.k_per_split % (4 * KC_) == 0 && a.k % (4 * KC_) == 0)                    \
-      hipLaunchKernelGGL((k_gemm_bf16<MB_, KC_, EPI, false, 4>), grid, block, 0, st, a);      \
-    else if (a.k_per_split % (2 * KC_) == 0 && a.k % (2 * KC_) == 0)                          \
+    bool deep = false;                                                                        \
+    if constexpr (MB_ < 8) {                                                                  \
+      deep = a.k_per_split % (4 * KC_) == 0 && a.k % (4 * KC_) == 0;                          \
+      if (deep) hipLaunchKernelGGL((k_gemm_bf16<MB_, KC_, EPI, false, 4>), grid, block, 0, st, a); \
+    }                                                                                         \
+    if (deep) break;                                                                          \
+    if (a.k_per_split % (2 * KC_) == 0 && a.k % (2 * KC_) == 0)                               \
       hipLaunchKernelGGL((k_gemm_bf16<MB_, KC_, EPI, false, 2>), grid, block, 0, st, a);      \
     else                                                                                      \
       hipLaunchKernelGGL((k_gemm_bf16<MB_, KC_, EPI, true, 1>), grid, block, 0, st, a);       \

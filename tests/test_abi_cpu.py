@@ -167,11 +167,13 @@ def test_kv_commit_rejects_bad_arguments_before_any_launch():
 def test_sample_decide_rejects_bad_arguments_before_any_launch():
     lib = B.lib()
     n = C.c_size_t()
-    assert lib.trispec_sample_scratch_bytes(2, 9, None) == -1
-    assert lib.trispec_sample_scratch_bytes(0, 9, C.byref(n)) == -3
-    assert lib.trispec_sample_scratch_bytes(2, 65, C.byref(n)) == -3
-    assert lib.trispec_sample_scratch_bytes(8, 64, C.byref(n)) == -3       # 512 rows
-    assert lib.trispec_sample_scratch_bytes(2, 9, C.byref(n)) == 0 and n.value >= 18 * 28 and n.value % 256 == 0
+    assert lib.trispec_sample_scratch_bytes(2, 9, 100, None) == -1
+    assert lib.trispec_sample_scratch_bytes(0, 9, 100, C.byref(n)) == -3
+    assert lib.trispec_sample_scratch_bytes(2, 65, 100, C.byref(n)) == -3
+    assert lib.trispec_sample_scratch_bytes(8, 64, 100, C.byref(n)) == -3       # 512 rows
+    assert lib.trispec_sample_scratch_bytes(2, 9, 0, C.byref(n)) == -8
+    assert lib.trispec_sample_scratch_bytes(2, 9, 100000, C.byref(n)) == 0 and n.value >= 18 * 28 + 2 * 2 * 25 * 8
+    assert lib.trispec_sample_scratch_bytes(2, 9, 100, C.byref(n)) == 0 and n.value >= 18 * 28 and n.value % 256 == 0
     out = B.VerifyOut()
 
     def rc(logits=0x1000, tokens=0x2000, batch=2, n_nodes=9, vocab=100, lam=0.1, T=1.0, resample=0, crit=0,
