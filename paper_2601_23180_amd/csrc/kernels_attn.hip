@@ -311,12 +311,14 @@ __global__ __launch_bounds__(64 * NW) void k_attn_bf16(AttnArgs a) {
 // head — in ascending split order, with the draft-node part: for every ancestor-or-self j of the
 // node, score = q . k_j / sqrt(d) and value v_j, all taken in fp32 from this pass's projections
 // (a.qkv: [row][(nq + 2 nkv) * d], q and k already rotated).
-// Memory round trips, not arithmetic, set this kernel's time, so there are only two of them:
-// (1) the ancestor mask, the query rows and the first 16 split partials of this thread's outputs;
-// (2) the keys and values of the ancestors.  Block = group * d / 2 threads, two adjacent output
-// features each; the ancestor list (at most 64 nodes) is scored by (slot x quarter of the
-// features) threads.
+// Memory round trips, not arithmetic, set this kernel's time: the ancestor mask (written at the
+// start of the pass, quick to arrive) is fetched alone, then everything the preceding kernels
+// wrote — query rows, the first 16 split partials, the ancestors' keys and the first ancestors'
+// values — in ONE round trip.  Block = group * d / 2 threads, two adjacent output features each;
+// the ancestor list (at most 64 nodes) is scored by (slot x quarter of the features) threads.
 constexpr int kMergePreV = 8;    // ancestors whose values are fetched ahead of the scores
+// e^x through the hardware exp2 (about 1e-7 |x| relative error; the arguments here are <= 0)
+__device__ __forceinline__ float fast_exp(float x) { return __builtin_amdgcn_exp2f(x * 1.4426950408889634f); }
 
 template <int D>
 __global__ __launch_bounds__(512) void k_attn_merge(AttnArgs a) {
@@ -333,8 +335,16 @@ __global__ __launch_bounds__(512) void k_attn_merge(AttnArgs a) {
   const int al = active ? tid / (D / 2) : 0, f = active ? (tid - al * (D / 2)) * 2 : 0;   // head, first feature
   const int p = al * M + node;
 
-  // ---- round trip 1
+  // ---- the ancestor list first: the mask was written when the pass began and arrives quickly,
+  // and every address of the second group of loads depends on it
   const uint64_t mask = a.anc[r];          // bit j: node j is on the root path of this node (self included)
+  const int n_anc = __popcll(mask);        // >= 1
+  if (tid < kMaxNodes && ((mask >> tid) & 1ull)) s_anc[__popcll(mask & ((1ull << tid) - 1ull))] = tid;
+  __syncthreads();
+
+  // ---- one round trip for everything the kernel before this one wrote: the query rows, the
+  // first 16 split partials of this thread's outputs, the values of the first ancestors and the
+  // keys of the first batch of ancestors
   const float2 q2 = *(const float2 *)(a.qkv + (size_t)r * n_total + (size_t)(kvh * group + al) * D + f);
   float pm[16], pl[16];
   float2 po[16];
@@ -345,25 +355,32 @@ __global__ __launch_bounds__(512) void k_attn_merge(AttnArgs a) {
     pl[i] = a.part_l[idx];
     po[i] = *(const float2 *)(a.part_o + idx * D + f);
   }
-  const int n_anc = __popcll(mask);        // >= 1
-  if (tid < kMaxNodes && ((mask >> tid) & 1ull)) s_anc[__popcll(mask & ((1ull << tid) - 1ull))] = tid;
-  if (active) { s_q[al][f] = q2.x; s_q[al][f + 1] = q2.y; }
-  __syncthreads();
-
-  // ---- round trip 2: values of the first ancestors, keys of all of them
   const float *vbase = a.qkv + (size_t)(a.n_q_heads + a.n_kv_heads + kvh) * D + f;
   float2 vpre[kMergePreV];
 #pragma unroll
   for (int i = 0; i < kMergePreV; ++i)
     vpre[i] = *(const float2 *)(vbase + (size_t)(b * M + s_anc[min(i, n_anc - 1)]) * n_total);
-  const float scale = 1.0f / sqrtf((float)D);
-  for (int s0 = 0; s0 < n_anc; s0 += nt / 4) {
-    const int slot = s0 + (tid >> 2), qq = tid & 3;
-    const int j = s_anc[min(slot, n_anc - 1)];
+  const int qq = tid & 3;
+  f32x4 kv4[D / 16];
+  {
+    const int j = s_anc[min(tid >> 2, n_anc - 1)];
     const float *kp = a.qkv + (size_t)(b * M + j) * n_total + (size_t)(a.n_q_heads + kvh) * D + qq * (D / 4);
-    f32x4 kv4[D / 16];
 #pragma unroll
     for (int i = 0; i < D / 16; ++i) kv4[i] = *(const f32x4 *)(kp + 4 * i);
+  }
+  if (active) { s_q[al][f] = q2.x; s_q[al][f + 1] = q2.y; }
+  __syncthreads();
+
+  // ---- scores of the ancestors: (slot x quarter of the features) threads, nt / 4 slots per batch
+  const float scale = 1.0f / sqrtf((float)D);
+  for (int s0 = 0; s0 < n_anc; s0 += nt / 4) {
+    const int slot = s0 + (tid >> 2);
+    if (s0 > 0) {   // later batches (deep paths on small workgroups) fetch their keys here
+      const int j = s_anc[min(slot, n_anc - 1)];
+      const float *kp = a.qkv + (size_t)(b * M + j) * n_total + (size_t)(a.n_q_heads + kvh) * D + qq * (D / 4);
+#pragma unroll
+      for (int i = 0; i < D / 16; ++i) kv4[i] = *(const f32x4 *)(kp + 4 * i);
+    }
     for (int h = 0; h < group; ++h) {
       float acc = 0.f;
 #pragma unroll
@@ -403,7 +420,7 @@ __global__ __launch_bounds__(512) void k_attn_merge(AttnArgs a) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       if (s0 + i >= a.n_splits || pm[i] == -INFINITY) continue;   // empty split: its o / l were never written
-      const float w = expf(pm[i] - m_tot);
+      const float w = fast_exp(pm[i] - m_tot);
       num0 += po[i].x * w;
       num1 += po[i].y * w;
       den += pl[i] * w;
@@ -412,7 +429,7 @@ __global__ __launch_bounds__(512) void k_attn_merge(AttnArgs a) {
 #pragma unroll
   for (int i = 0; i < kMergePreV; ++i)
     if (i < n_anc) {
-      const float w = expf(s_sc[al][i] - m_tot);
+      const float w = fast_exp(s_sc[al][i] - m_tot);
       num0 += w * vpre[i].x;
       num1 += w * vpre[i].y;
       den += w;
@@ -425,7 +442,7 @@ __global__ __launch_bounds__(512) void k_attn_merge(AttnArgs a) {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
       if (i0 + i < n_anc) {
-        const float w = expf(s_sc[al][i0 + i] - m_tot);
+        const float w = fast_exp(s_sc[al][i0 + i] - m_tot);
         num0 += w * vv[i].x;
         num1 += w * vv[i].y;
         den += w;
