@@ -105,28 +105,8 @@ __global__ __launch_bounds__(64 * NW) void k_attn_bf16(AttnArgs a) {
 
   // ---- this lane's query rows
   int prow[RBW];
-  bf16x8 qf[RBW][D / 16], ql[RBW][D / 16];
 #pragma unroll
-  for (int i = 0; i < RBW; ++i) {
-    const int rb = rg * NW * RBW + wave + NW * i;
-    const int p = rb * 32 + ln;
-    prow[i] = p;
-#pragma unroll
-    for (int t = 0; t < D / 16; ++t)
-#pragma unroll
-      for (int e = 0; e < 8; ++e) { qf[i][t][e] = (bf16)0.f; ql[i][t][e] = (bf16)0.f; }
-    if (p < p_rows) {
-      const int al = p / M, node = p - al * M;
-      const int r = b * M + node;
-      // rotated query as bf16 high part + bf16 low part (written by the QKV epilogue)
-      const bf16 *q = (const bf16 *)a.q + (size_t)r * a.n_q_heads * D + (size_t)(kvh * group + al) * D;
-#pragma unroll
-      for (int t = 0; t < D / 16; ++t) {
-        qf[i][t] = *(const bf16x8 *)(q + 16 * t + 8 * g);
-        ql[i][t] = *(const bf16x8 *)(q + a.q_panel + 16 * t + 8 * g);
-      }
-    }
-  }
+  for (int i = 0; i < RBW; ++i) prow[i] = (rg * NW * RBW + wave + NW * i) * 32 + ln;
 
   if (k_begin >= k_end) {   // empty split: neutral partial
 #pragma unroll
@@ -146,6 +126,8 @@ __global__ __launch_bounds__(64 * NW) void k_attn_bf16(AttnArgs a) {
   typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // native vector: stays in registers
   typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
   u32x4 kreg[KV_PER_T], vreg[KV_PER_T];
+  // load_tile only ISSUES loads — anything that looked at a loaded value here would make the
+  // compiler wait for each load in turn; the slots past the context are zeroed in store_tile.
   auto load_tile = [&](int k0) {
 #pragma unroll
     for (int i = 0; i < KV_PER_T; ++i) {
@@ -157,22 +139,13 @@ __global__ __launch_bounds__(64 * NW) void k_attn_bf16(AttnArgs a) {
       }
       {  // V^T: vector v -> feature v / (KT/8), 8 keys starting at (v % (KT/8)) * 8
         const int f = v / (KT / 8), c = v % (KT / 8);
-        const int kfirst = k0 + c * 8;
-        u32x4 t = *(const u32x4 *)(vc + (size_t)f * a.capacity + min(kfirst, a.capacity - 8));
-        if (kfirst + 8 > n_keys) {   // zero the values of slots that hold no token
-          auto keep = [&](uint32_t x, int e0) {   // x holds keys kfirst + e0 (low half) and kfirst + e0 + 1
-            if (kfirst + e0 >= n_keys) x &= 0xffff0000u;
-            if (kfirst + e0 + 1 >= n_keys) x &= 0x0000ffffu;
-            return x;
-          };
-          t = u32x4{keep(t.x, 0), keep(t.y, 2), keep(t.z, 4), keep(t.w, 6)};
-        }
-        vreg[i] = t;
+        vreg[i] = *(const u32x4 *)(vc + (size_t)f * a.capacity + min(k0 + c * 8, a.capacity - 8));
       }
     }
   };
-  auto store_tile = [&](int buf) {
+  auto store_tile = [&](int buf, int k0) {
     unsigned char *base = lds + buf * L::kBuf;
+    const bool ragged = k0 + KT > n_keys;   // uniform over the workgroup: the context ends inside this tile
 #pragma unroll
     for (int i = 0; i < KV_PER_T; ++i) {
       const int v = tid + NT * i;
@@ -182,9 +155,17 @@ __global__ __launch_bounds__(64 * NW) void k_attn_bf16(AttnArgs a) {
       }
       {
         const int f = v / (KT / 8), c = v % (KT / 8);
+        u32x4 t = vreg[i];
+        if (ragged) {   // zero the values of slots that hold no token (two keys per 32-bit word)
+          const int left = n_keys - (k0 + c * 8);   // keys of this vector inside the context
+          auto keep = [&](uint32_t x, int e0) {
+            return x & ((e0 < left ? 0x0000ffffu : 0u) | (e0 + 1 < left ? 0xffff0000u : 0u));
+          };
+          t = u32x4{keep(t.x, 0), keep(t.y, 2), keep(t.z, 4), keep(t.w, 6)};
+        }
         u32x2 *dst = (u32x2 *)(base + L::kBytesK + f * L::kStrideV + c * 16);
-        dst[0] = u32x2{vreg[i].x, vreg[i].y};
-        dst[1] = u32x2{vreg[i].z, vreg[i].w};
+        dst[0] = u32x2{t.x, t.y};
+        dst[1] = u32x2{t.z, t.w};
       }
     }
   };
@@ -204,7 +185,25 @@ __global__ __launch_bounds__(64 * NW) void k_attn_bf16(AttnArgs a) {
 
   const int n_tiles = (k_end - k_begin + KT - 1) / KT;
   load_tile(k_begin);
-  store_tile(0);
+  // The query rows were written by the kernel before this one and take several times longer to
+  // arrive than the cache does, so they are requested after the first tile (whose wait then does
+  // not include them) and without a branch (a row past the end reads the last row: every lane's
+  // row is independent and such lanes store nothing).
+  // rotated query as bf16 high part + bf16 low part (written by the QKV epilogue)
+  bf16x8 qf[RBW][D / 16], ql[RBW][D / 16];
+#pragma unroll
+  for (int i = 0; i < RBW; ++i) {
+    const int pc = min(prow[i], p_rows - 1);
+    const int al = pc / M, node = pc - al * M;
+    const int r = b * M + node;
+    const bf16 *q = (const bf16 *)a.q + (size_t)r * a.n_q_heads * D + (size_t)(kvh * group + al) * D;
+#pragma unroll
+    for (int t = 0; t < D / 16; ++t) {
+      qf[i][t] = *(const bf16x8 *)(q + 16 * t + 8 * g);
+      ql[i][t] = *(const bf16x8 *)(q + a.q_panel + 16 * t + 8 * g);
+    }
+  }
+  store_tile(0, k_begin);
   __syncthreads();
 
   for (int t = 0; t < n_tiles; ++t) {
@@ -218,18 +217,25 @@ __global__ __launch_bounds__(64 * NW) void k_attn_bf16(AttnArgs a) {
 #pragma unroll
     for (int i = 0; i < RBW; ++i) {
       if ((rg * NW * RBW + wave + NW * i) * 32 >= p_rows) continue;   // wave-uniform
-      // S^T[key][row] for the two 32-key sub-tiles
+      // S^T[key][row] for the 32-key sub-tiles.  Consecutive matrix instructions go to different
+      // accumulators: one that adds to the result of the instruction before it has to wait for it.
       f32x16 s[KT / 32];
 #pragma unroll
-      for (int ks = 0; ks < KT / 32; ++ks) {
+      for (int ks = 0; ks < KT / 32; ++ks)
 #pragma unroll
         for (int e = 0; e < 16; ++e) s[ks][e] = 0.f;
 #pragma unroll
-        for (int tt = 0; tt < D / 16; ++tt) {
-          const bf16x8 kf = *(const bf16x8 *)(kb + (ks * 32 + ln) * L::kStrideK + (16 * tt + 8 * g) * 2);
-          s[ks] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[i][tt], s[ks], 0, 0, 0);
-          s[ks] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, ql[i][tt], s[ks], 0, 0, 0);
-        }
+      for (int tt = 0; tt < D / 16; ++tt) {
+        bf16x8 kf[KT / 32];
+#pragma unroll
+        for (int ks = 0; ks < KT / 32; ++ks)
+          kf[ks] = *(const bf16x8 *)(kb + (ks * 32 + ln) * L::kStrideK + (16 * tt + 8 * g) * 2);
+#pragma unroll
+        for (int ks = 0; ks < KT / 32; ++ks)
+          s[ks] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[i][tt], s[ks], 0, 0, 0);
+#pragma unroll
+        for (int ks = 0; ks < KT / 32; ++ks)
+          s[ks] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], ql[i][tt], s[ks], 0, 0, 0);
       }
       // scale, mask, tile max
       float tmax = -INFINITY;
@@ -262,25 +268,32 @@ __global__ __launch_bounds__(64 * NW) void k_attn_bf16(AttnArgs a) {
           plo[ks * 2 + (e >> 3)][e & 7] = lo;
         }
       l_run[i] = l_run[i] * alpha + psum;
-      // O^T[feature][row] = alpha * O^T + V^T P^T
+      // O^T[feature][row] = alpha * O^T + V^T P^T, the feature blocks interleaved for the same reason
 #pragma unroll
-      for (int db = 0; db < D / 32; ++db) {
+      for (int db = 0; db < D / 32; ++db)
 #pragma unroll
         for (int e = 0; e < 16; ++e) oacc[i][db][e] *= alpha;
 #pragma unroll
-        for (int u = 0; u < KT / 16; ++u) {
+      for (int u = 0; u < KT / 16; ++u) {
+        bf16x8 vf[D / 32];
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db) {
           // key slots of lane half g at step u: 16u + 4g + {0..3} and 16u + 8 + 4g + {0..3}
           const unsigned char *vp = vb + (db * 32 + ln) * L::kStrideV + (16 * u + 4 * g) * 2;
-          const uint2 v0 = *(const uint2 *)vp;
-          const uint2 v1 = *(const uint2 *)(vp + 16);
-          const uint4 vv = make_uint4(v0.x, v0.y, v1.x, v1.y);
-          const bf16x8 vf = *(const bf16x8 *)&vv;
-          oacc[i][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, phi[u], oacc[i][db], 0, 0, 0);
-          oacc[i][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, plo[u], oacc[i][db], 0, 0, 0);
+          const u32x2 v0 = *(const u32x2 *)vp;
+          const u32x2 v1 = *(const u32x2 *)(vp + 16);
+          const u32x4 vv = u32x4{v0.x, v0.y, v1.x, v1.y};
+          vf[db] = *(const bf16x8 *)&vv;
         }
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db)
+          oacc[i][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[db], phi[u], oacc[i][db], 0, 0, 0);
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db)
+          oacc[i][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[db], plo[u], oacc[i][db], 0, 0, 0);
       }
     }
-    if (t + 1 < n_tiles) store_tile(buf ^ 1);
+    if (t + 1 < n_tiles) store_tile(buf ^ 1, k0 + KT);
     __syncthreads();
   }
 

@@ -168,11 +168,14 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(GemmArgs a) {
 #pragma unroll
     for (int t = 0; t < T; ++t) {
       const int kb = t >> 2, j = t & 3;
+      // high parts of every row block, then the low parts: a matrix instruction that adds to the
+      // result of the one just before it would have to wait for it
 #pragma unroll
-      for (int mb = 0; mb < MB; ++mb) {
+      for (int mb = 0; mb < MB; ++mb)
         acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf[t & 1][2 * mb], w[set][kb][j], acc[mb], 0, 0, 0);
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
         acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf[t & 1][2 * mb + 1], w[set][kb][j], acc[mb], 0, 0, 0);
-      }
       if (t + 2 < T) read_frags(t & 1, t + 2, buf);
       if (j == 3 && loadw) load_w_block(set, c_next, kb);
       __builtin_amdgcn_sched_barrier(0);
