@@ -266,27 +266,41 @@ void launch_stats_from_logits(hipStream_t st, const float *logits, int rows, int
   hipLaunchKernelGGL(k_stats_from_logits, dim3(rows), dim3(256), 0, st, logits, vocab, hs);
 }
 
-// Merge the per-tile statistics of every row: one wavefront per row, lanes stride the tiles.
-__global__ __launch_bounds__(64) void k_stats_reduce(HeadStats hs, float *node_l1, float *node_l2,
-                                                     float *node_sum, int32_t *node_idx) {
-  const int r = blockIdx.x;
+// Merge the per-tile statistics of every row: one workgroup of 16 wavefronts per row, threads
+// stride the tiles (every load of a thread is requested before the first merge), then a fixed
+// butterfly per wavefront and the wavefronts in ascending order.
+constexpr int kStatsThreads = 1024;
+__global__ __launch_bounds__(kStatsThreads) void k_stats_reduce(HeadStats hs, float *node_l1, float *node_l2,
+                                                                float *node_sum, int32_t *node_idx) {
+  __shared__ Top2 s_w[kStatsThreads / 64];
+  const int r = blockIdx.x, tid = threadIdx.x;
   Top2 t = top2_empty();
-  for (int i = threadIdx.x; i < hs.n_tiles; i += 64) {
-    Top2 b;
-    const size_t o = (size_t)r * hs.n_tiles + i;
-    b.l1 = hs.l1[o]; b.l2 = hs.l2[o]; b.s = hs.sumexp[o]; b.idx = hs.idx[o];
-    t = top2_merge(t, b);
+  for (int i0 = tid; i0 < hs.n_tiles; i0 += 4 * kStatsThreads) {
+    Top2 b[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int i = i0 + u * kStatsThreads;
+      const size_t o = (size_t)r * hs.n_tiles + min(i, hs.n_tiles - 1);
+      b[u].l1 = hs.l1[o]; b[u].l2 = hs.l2[o]; b[u].s = hs.sumexp[o]; b[u].idx = hs.idx[o];
+      if (i >= hs.n_tiles) b[u] = top2_empty();
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) t = top2_merge(t, b[u]);
   }
 #pragma unroll
   for (int o = 1; o < 64; o <<= 1) t = top2_merge(t, top2_shfl_xor(t, o));
-  if (threadIdx.x == 0) {
+  if ((tid & 63) == 0) s_w[tid >> 6] = t;
+  __syncthreads();
+  if (tid == 0) {
+    t = s_w[0];
+    for (int w = 1; w < kStatsThreads / 64; ++w) t = top2_merge(t, s_w[w]);
     node_l1[r] = t.l1; node_l2[r] = t.l2; node_sum[r] = t.s; node_idx[r] = t.idx;
   }
 }
 
 void launch_stats_reduce(hipStream_t st, const HeadStats &hs, int rows, float *node_l1, float *node_l2,
                          float *node_sum, int32_t *node_idx) {
-  hipLaunchKernelGGL(k_stats_reduce, dim3(rows), dim3(64), 0, st, hs, node_l1, node_l2, node_sum,
+  hipLaunchKernelGGL(k_stats_reduce, dim3(rows), dim3(kStatsThreads), 0, st, hs, node_l1, node_l2, node_sum,
                      node_idx);
 }
 
