@@ -58,26 +58,59 @@ __global__ __launch_bounds__(256) void k_embed_norm(const int32_t *tokens, const
   }
   const AT *e = embed + (size_t)tok * hidden;
   float *xr = x + (size_t)r * hidden;
-  float ss = 0.f;
-  for (int i = threadIdx.x; i < hidden; i += 256) {
-    const float v = to_f32(e[i]);
-    xr[i] = v;
-    ss += v * v;
-  }
-  ss = block_sum<4>(ss, red);
-  const float rstd = 1.0f / sqrtf(ss / (float)hidden + eps);
-  if (ss_out != nullptr) {
-    if (threadIdx.x == 0) ss_out[r] = ss;
-    bf16 *hp = (bf16 *)h;   // operand layout; h_panel carries the number of 32-row blocks
-    for (int i = threadIdx.x; i < hidden; i += 256) {
-      const float v = to_f32(e[i]) * to_f32(norm_w[i]);
-      const bf16 hi = (bf16)v;
-      hp[ol_offset(r, i, 0, (int)h_panel)] = hi;
-      hp[ol_offset(r, i, 1, (int)h_panel)] = (bf16)(v - (float)hi);
+  if constexpr (sizeof(AT) == 2) {
+    // bf16 models (hidden is a multiple of 64): 8 elements = one 16-byte vector per step; a run of
+    // 8 reduction indices is contiguous in the operand layout as well
+    constexpr int MAXV = 4;                         // vectors per thread held in registers (hidden <= 8192)
+    const int nv = hidden / 8;
+    bf16x8 ev[MAXV], wv[MAXV];
+#pragma unroll
+    for (int u = 0; u < MAXV; ++u) {
+      const int v = min((int)threadIdx.x + 256 * u, nv - 1);
+      ev[u] = *(const bf16x8 *)(e + 8 * v);
+      wv[u] = *(const bf16x8 *)(norm_w + 8 * v);
     }
+    float ss = 0.f;
+    for (int v0 = 0; v0 < nv; v0 += 256 * MAXV) {
+#pragma unroll
+      for (int u = 0; u < MAXV; ++u) {
+        const int v = v0 + (int)threadIdx.x + 256 * u;
+        if (v >= nv) continue;
+        bf16x8 evv = ev[u], wvv = wv[u];
+        if (v0 > 0) { evv = *(const bf16x8 *)(e + 8 * v); wvv = *(const bf16x8 *)(norm_w + 8 * v); }   // very wide models
+        f32x4 x0, x1;
+        bf16x8 hi, lo;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          const float xv = (float)evv[k];
+          (k < 4 ? x0 : x1)[k & 3] = xv;
+          ss += xv * xv;
+          const float hv = xv * (float)wvv[k];
+          hi[k] = (bf16)hv;
+          lo[k] = (bf16)(hv - (float)hi[k]);
+        }
+        *(f32x4 *)(xr + 8 * v) = x0;
+        *(f32x4 *)(xr + 8 * v + 4) = x1;
+        bf16 *hp = (bf16 *)h;   // operand layout; h_panel carries the number of 32-row blocks
+        *(bf16x8 *)(hp + ol_offset(r, 8 * v, 0, (int)h_panel)) = hi;
+        *(bf16x8 *)(hp + ol_offset(r, 8 * v, 1, (int)h_panel)) = lo;
+      }
+    }
+    ss = block_sum<4>(ss, red);
+    if (threadIdx.x == 0) ss_out[r] = ss;
+    (void)eps;
   } else {
+    float ss = 0.f;
+    for (int i = threadIdx.x; i < hidden; i += 256) {
+      const float v = to_f32(e[i]);
+      xr[i] = v;
+      ss += v * v;
+    }
+    ss = block_sum<4>(ss, red);
+    const float rstd = 1.0f / sqrtf(ss / (float)hidden + eps);
     float *hp = (float *)h + (size_t)r * hidden;
     for (int i = threadIdx.x; i < hidden; i += 256) hp[i] = to_f32(e[i]) * rstd * to_f32(norm_w[i]);
+    (void)h_panel; (void)ss_out;
   }
 }
 
