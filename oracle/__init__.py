@@ -34,7 +34,7 @@ from .decision import (  # noqa: F401
     tie_flags,
     prune_reroot,
 )
-from .rounds import commit, greedy_decode, trispec_rounds, verify_rounds  # noqa: F401
+from .rounds import commit, greedy_decode, trispec_rounds, trispec_sample_rounds, verify_rounds  # noqa: F401
 from .sampling import (  # noqa: F401
     RESAMPLE_DIRECT,
     RESAMPLE_RESIDUAL,

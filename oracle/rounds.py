@@ -151,3 +151,85 @@ def trispec_rounds(Wp: OracleWeights, shape_p, Wt: OracleWeights, shape_t, promp
         rec.update({"target": dec_t, "target_stats": st_t, "target_nodes": len(tok_t), "n_forced_t": n_forced_t})
         records.append(rec)
     return {"sequence": seq, "rounds": records, "kp": kp, "vp": vp, "kt": kt, "vt": vt}
+
+
+def trispec_sample_rounds(Wp: OracleWeights, shape_p, Wt: OracleWeights, shape_t, prompt: Sequence[int],
+                          draft_fn: Callable[[int, List[int], np.ndarray], Dict[str, np.ndarray]], n_rounds: int,
+                          lam: float, temperature: float, criterion: int = CRIT_MARGIN, resample: int = 0,
+                          max_nodes: int = 64) -> Dict[str, list]:
+    """Rounds of the ternary scheme at temperature > 0 on draft CHAINS — Alg. 1 as printed: the
+    drafter samples x_1..x_k, the proxy accepts each with probability min(1, p_p / p_d) (Eq. 6),
+    the margin rule gives tau_m (Eq. 8, 9), and either the proxy ends the round (tau_a < tau_m) or
+    the target verifies the whole chain with x_1..x_tau_m taken as approved and ends it.
+
+    draft_fn(round, sequence so far, proxy cache length) -> dict with
+      tokens [k+1] (entry 0 is overwritten with the round's root), p_draft [k, V],
+      u_accept_p [k+1], u_sample_p, u_accept_t [k+1], u_sample_t      (uniforms in [0, 1)).
+    The drafter is an input: whatever distributions it reports are the p_d of Eq. 6.
+    Caches, lag of the target and catch-up passes as in trispec_rounds."""
+    from .sampling import sample_decide
+
+    seq = [int(t) for t in prompt]
+
+    def prefill(W, shape):
+        if len(seq) > 1:
+            o = causal_forward(W, shape, seq[:-1])
+            return o["K"], o["V"]
+        z = np.zeros((shape.n_layers, shape.n_kv_heads, 0, shape.head_dim))
+        return z, z.copy()
+
+    kp, vp = prefill(Wp, shape_p)
+    kt, vt = prefill(Wt, shape_t)
+    records = []
+    for r in range(n_rounds):
+        d = draft_fn(r, seq, kp.shape[2])
+        tokens = np.asarray(d["tokens"], dtype=np.int32).copy()
+        tokens[0] = seq[-1]
+        M = len(tokens)
+        p_draft = np.asarray(d["p_draft"], dtype=np.float64)
+        chain = np.arange(-1, M - 1)
+        Cp = kp.shape[2]
+        out = verify_forward(Wp, shape_p, kp, vp, tokens, chain, Cp + np.arange(M))
+        dec = sample_decide(out["logits"], tokens, p_draft, d["u_accept_p"], float(d["u_sample_p"]), temperature,
+                            lam, criterion, 1, resample)
+        path = list(dec["path"])
+        rec = {"proxy": dec, "proxy_logits": out["logits"], "escalate": int(dec["escalate"]), "catch_up": 0,
+               "tokens": tokens}
+        if not dec["escalate"]:                                   # Case I
+            kp, vp = commit(kp, vp, out["k_new"], out["v_new"], path)
+            seq += [int(tokens[i]) for i in path[1:]] + [int(dec["token"])]
+            records.append(rec)
+            continue
+        # Case II: the whole chain goes to the target, nodes 0..tau_m forced
+        tau_m = dec["accepted_len"]
+        t_len = kt.shape[2]
+        unseen = seq[t_len:-1]
+        fits = len(unseen) + M <= max_nodes
+        while unseen and not fits:
+            take = min(len(unseen), max_nodes)
+            chunk = np.asarray(unseen[:take], dtype=np.int32)
+            o = verify_forward(Wt, shape_t, kt, vt, chunk, np.arange(-1, take - 1), t_len + np.arange(take))
+            kt, vt = commit(kt, vt, o["k_new"], o["v_new"], list(range(take)))
+            t_len += take
+            unseen = unseen[take:]
+            rec["catch_up"] += 1
+        u = len(unseen)
+        tok_t = np.concatenate([np.asarray(unseen, dtype=np.int32), tokens])
+        n_t = u + M
+        pd_t = np.zeros((n_t - 1, p_draft.shape[1]))
+        pd_t[u:] = p_draft                                         # row u + i judges node u + i + 1 = draft i + 1
+        ua_t = np.zeros(n_t)
+        ua_t[u:] = d["u_accept_t"]
+        n_forced_t = u + tau_m + 1
+        out_t = verify_forward(Wt, shape_t, kt, vt, tok_t, np.arange(-1, n_t - 1), t_len + np.arange(n_t))
+        dec_t = sample_decide(out_t["logits"], tok_t, pd_t, ua_t, float(d["u_sample_t"]), temperature, 0.0,
+                              CRIT_MARGIN, n_forced_t, resample)
+        path_t = list(dec_t["path"])                              # starts at node n_forced_t - 1
+        kt, vt = commit(kt, vt, out_t["k_new"], out_t["v_new"], list(range(n_forced_t - 1)) + path_t)
+        extra = [n - u for n in path_t[1:]]                       # drafts the target accepted, chain ids
+        kp, vp = commit(kp, vp, out["k_new"], out["v_new"], path + extra)
+        seq += [int(tokens[i]) for i in path[1:] + extra] + [int(dec_t["token"])]
+        rec.update({"target": dec_t, "target_logits": out_t["logits"], "target_nodes": n_t,
+                    "n_forced_t": n_forced_t, "u": u})
+        records.append(rec)
+    return {"sequence": seq, "rounds": records, "kp": kp, "vp": vp, "kt": kt, "vt": vt}

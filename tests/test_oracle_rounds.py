@@ -152,3 +152,107 @@ def test_target_catches_up_on_tokens_it_never_saw(lam, max_nodes, want_catch_up)
     t_len = res["kt"].shape[2]
     reft = causal_forward(Wt, MICRO, seq[:t_len])
     assert np.max(np.abs(res["kt"] - reft["K"])) < 1e-9 and np.max(np.abs(res["vt"] - reft["V"])) < 1e-9
+
+
+# ------------------------------------------------------------------ sampling rounds (Alg. 1 as printed)
+def _self_drafter(Wd, shape, k, temperature, seed, noise=0.0, one_hot=False):
+    """A drafter that is itself a model: x_i drawn from softmax(logits_d / T) (plus optional
+    noise on its logits), autoregressively, with numpy's generator; reports those distributions."""
+    from oracle import tempered_softmax
+
+    def fn(r, seq, _cache_len):
+        rng = np.random.default_rng(seed * 1000 + r)
+        cur = list(seq)
+        toks, rows = [0], []
+        for _ in range(k):
+            lg = causal_forward(Wd, shape, cur, last_only=True)["logits"][0]
+            q = tempered_softmax(lg + noise * rng.standard_normal(lg.shape), temperature)
+            x = int(rng.choice(len(q), p=q))
+            if one_hot:
+                x = int(np.argmax(q)) if rng.random() < 0.7 else x
+                q = np.eye(len(q))[x]
+            toks.append(x); rows.append(q); cur.append(x)
+        return {"tokens": np.array(toks, dtype=np.int32), "p_draft": np.stack(rows),
+                "u_accept_p": rng.random(k + 1), "u_sample_p": rng.random(),
+                "u_accept_t": rng.random(k + 1), "u_sample_t": rng.random()}
+    return fn
+
+
+def test_sampling_rounds_reduce_to_the_greedy_rounds_at_low_temperature():
+    """One-hot drafts and T -> 0: Eq. 6 is the indicator, so the sampling rounds must emit what the
+    (separately pinned) greedy rounds emit for the same drafts, round for round."""
+    from oracle import CRIT_TOP1, trispec_rounds, trispec_sample_rounds
+    Wp, Wt = _two_models(41, 42)
+    prompt = gen_context_tokens(MICRO.vocab, 5, 41).tolist()
+    drafts = _self_drafter(Wp, MICRO, 4, 1.0, 41, one_hot=True)
+    log = {}
+
+    def same_drafts_as_tree(r, seq):
+        d = drafts(r, seq, 0)
+        log[r] = d
+        return gen_chain(5), d["tokens"]
+    # only thresholds on which the trust predicate cannot differ: it is evaluated on the tempered
+    # distribution, whose top-1 probability tends to 1 as T -> 0
+    for lam in (0.0, 2.0):
+        greedy = trispec_rounds(Wp, MICRO, Wt, MICRO, prompt, same_drafts_as_tree, 6, lam, CRIT_TOP1)
+        sampled = trispec_sample_rounds(Wp, MICRO, Wt, MICRO, prompt, lambda r, s, c: log[r], 6, lam, 1e-3,
+                                        CRIT_TOP1)
+        assert sampled["sequence"] == greedy["sequence"], lam
+        assert [r["escalate"] for r in sampled["rounds"]] == [r["escalate"] for r in greedy["rounds"]]
+
+
+def test_sampling_rounds_are_lossless_when_the_proxy_is_never_trusted():
+    """lambda > 1: every round escalates at the root and the target decides by speculative sampling,
+    so the first emitted token follows the TARGET's tempered distribution exactly (Sec. 2.1), whatever
+    the proxy and the drafter are.  Monte Carlo over numpy's generator on the 61-token micro model."""
+    from oracle import tempered_softmax, trispec_sample_rounds
+    Wp, Wt = _two_models(51, 52)
+    prompt = gen_context_tokens(MICRO.vocab, 4, 51).tolist()
+    T, N = 0.9, 2500
+    p_t = tempered_softmax(causal_forward(Wt, MICRO, prompt, last_only=True)["logits"][0], T)
+    counts = np.zeros(MICRO.vocab)
+    lens = []
+    for n in range(N):
+        res = trispec_sample_rounds(Wp, MICRO, Wt, MICRO, prompt, _self_drafter(Wp, MICRO, 2, T, 7000 + n, noise=0.5),
+                                    1, 2.0, T)
+        assert res["rounds"][0]["escalate"] == 1 and res["rounds"][0]["proxy"]["accepted_len"] == 0
+        counts[res["sequence"][len(prompt)]] += 1
+        lens.append(len(res["sequence"]) - len(prompt))
+    big = p_t > 5.0 / N
+    chi2 = float(((counts[big] - N * p_t[big]) ** 2 / (N * p_t[big])).sum())
+    dof = int(big.sum()) - 1
+    assert chi2 < dof + 5 * np.sqrt(2 * dof), (chi2, dof)
+    assert 1.0 < np.mean(lens) < 3.0          # some drafts were accepted by the target, not all
+
+
+def test_sampling_rounds_with_a_perfect_drafter_accept_everything_and_keep_textbook_caches():
+    from oracle import trispec_sample_rounds
+    W = oracle_weights(MICRO, 61)
+    prompt = gen_context_tokens(MICRO.vocab, 5, 61).tolist()
+    T, k = 0.8, 3
+    res = trispec_sample_rounds(W, MICRO, W, MICRO, prompt, _self_drafter(W, MICRO, k, T, 61), 5, 0.0, T)
+    for r in res["rounds"]:        # p_d = p_v: ratio 1, every uniform accepts; margin >= 0 never escalates
+        assert r["escalate"] == 0 and r["proxy"]["accepted_len"] == k and r["proxy"]["row"] == k
+    seq = res["sequence"]
+    assert len(seq) == len(prompt) + 5 * (k + 1)
+    ref = causal_forward(W, MICRO, seq[:-1])
+    assert np.max(np.abs(res["kp"] - ref["K"])) < 1e-9 and np.max(np.abs(res["vp"] - ref["V"])) < 1e-9
+
+
+@pytest.mark.parametrize("max_nodes", [16, 8])
+def test_sampling_rounds_mixed_routing_keeps_both_caches_textbook(max_nodes):
+    from oracle import trispec_sample_rounds
+    Wp, Wt = _two_models(71, 72)
+    prompt = gen_context_tokens(MICRO.vocab, 5, 71).tolist()
+    res = trispec_sample_rounds(Wp, MICRO, Wt, MICRO, prompt, _self_drafter(Wp, MICRO, 3, 0.7, 71, noise=0.8), 14,
+                                0.12, 0.7, max_nodes=max_nodes)
+    esc = [r["escalate"] for r in res["rounds"]]
+    assert 0 < sum(esc) < len(esc)
+    assert any(r["escalate"] and r["u"] > 0 for r in res["rounds"]) or any(r["catch_up"] for r in res["rounds"])
+    assert all(r["target_nodes"] <= max_nodes for r in res["rounds"] if r["escalate"])
+    seq = res["sequence"]
+    refp = causal_forward(Wp, MICRO, seq[:-1])
+    assert np.max(np.abs(res["kp"] - refp["K"])) < 1e-9 and np.max(np.abs(res["vp"] - refp["V"])) < 1e-9
+    t_len = res["kt"].shape[2]
+    reft = causal_forward(Wt, MICRO, seq[:t_len])
+    assert np.max(np.abs(res["kt"] - reft["K"])) < 1e-9 and np.max(np.abs(res["vt"] - reft["V"])) < 1e-9
