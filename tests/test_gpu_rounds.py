@@ -175,3 +175,76 @@ def test_ternary_rounds_match_the_oracle(shape_name, lam, max_nodes):
         kg = kv.k[:, 0, :, :n, :].float().cpu().numpy()
         vg = kv.v[:, 0, :, :, :n].float().cpu().numpy().transpose(0, 1, 3, 2)
         assert np.all(np.abs(kg - kw) <= tol(kw)) and np.all(np.abs(vg - vw) <= tol(vw))
+
+
+# ---- rounds at temperature > 0 on draft chains (Alg. 1 as printed)
+
+def _model_drafter(Wd, shape, k, temperature, seed, noise):
+    """Drafts sampled autoregressively from softmax((oracle logits of Wd + noise) / T) with numpy's
+    generator; the same recorded inputs then go to the GPU driver."""
+    from oracle import causal_forward, tempered_softmax
+
+    def fn(r, seq, _cache_len):
+        rng = np.random.default_rng(seed * 1000 + r)
+        cur, toks, rows = list(seq), [0], []
+        for _ in range(k):
+            lg = causal_forward(Wd, shape, cur, last_only=True, n_cached=len(cur) - 1)["logits"][0]
+            q = tempered_softmax(lg + noise * rng.standard_normal(lg.shape), temperature).astype(np.float32)
+            c = np.cumsum(q.astype(np.float64))
+            x = min(int(np.searchsorted(c, rng.random() * c[-1], side="right")), len(q) - 1)
+            toks.append(x); rows.append(q); cur.append(x)
+        top = np.float32(1.0) - np.float32(2.0 ** -24)
+        u = lambda n: np.minimum(rng.random(n, dtype=np.float32), top)
+        return {"tokens": np.array(toks, dtype=np.int32), "p_draft": np.stack(rows),
+                "u_accept_p": u(k + 1), "u_sample_p": float(u(1)[0]), "u_accept_t": u(k + 1), "u_sample_t": float(u(1)[0])}
+    return fn
+
+
+@pytest.mark.parametrize("shape_name,lam,max_nodes", [("tiny", 0.0, 64), ("tiny", 0.25, 64), ("tiny", 2.0, 64),
+                                                       ("tiny", 0.25, 12), ("tiny_bf16", 0.25, 64)])
+def test_sampling_rounds_match_the_oracle(shape_name, lam, max_nodes):
+    from oracle import trispec_sample_rounds
+    from paper_2601_23180_amd import TernaryDecoder
+    shape, seed_p, seed_t, n_rounds, T, k = SHAPES[shape_name], 41, 42, 8, 0.8, 4
+    Wp, Wt = oracle_weights(shape, seed_p), oracle_weights(shape, seed_t)
+    prompt = gen_context_tokens(shape.vocab, 12, seed_p).tolist()
+    log = {}
+    drafter = _model_drafter(Wp, shape, k, T, seed_p, noise=0.6)
+
+    def recording(r, seq, c):
+        log[r] = drafter(r, seq, c)
+        return log[r]
+    want = trispec_sample_rounds(Wp, shape, Wt, shape, prompt, recording, n_rounds, lam, T, max_nodes=max_nodes)
+    dec = TernaryDecoder(device_model(shape, seed_p), device_model(shape, seed_t), 256, max_nodes=max_nodes)
+    dec.start(prompt)
+    tol = 3e-4 if shape.dtype == "f32" else 5e-3
+    for r in range(n_rounds):
+        d, w = log[r], want["rounds"][r]
+        g = dec.round_sample(d["tokens"], d["p_draft"], d["u_accept_p"], d["u_sample_p"], d["u_accept_t"],
+                             d["u_sample_t"], lam, T)
+        ok = g["escalate"] == w["escalate"] and g["proxy"]["path"] == list(w["proxy"]["path"])
+        if ok and g["escalate"]:
+            ok = (g["target"]["path"] == list(w["target"]["path"]) and g["target"]["token"] == w["target"]["token"]
+                  and g["n_forced_t"] == w["n_forced_t"] and g["catch_up"] == w["catch_up"])
+        elif ok:
+            ok = g["proxy"]["token"] == w["proxy"]["token"]
+        if not ok:   # only a comparison within rounding of its boundary may change a round
+            close = w["proxy"]["slack"] < tol or (w["escalate"] and w["target"]["slack"] < tol)
+            for side in ("proxy", "target"):
+                o = w.get(side)
+                if o is not None and o["mass"] is not None:
+                    c = np.cumsum(o["mass"])
+                    us = d["u_sample_p"] if side == "proxy" else d["u_sample_t"]
+                    pos = np.searchsorted(c, us * c[-1], side="right")
+                    edges = c[max(pos - 1, 0): pos + 1]
+                    close = close or bool(np.any(np.abs(edges - us * c[-1]) < tol))
+            assert close, (r, g, w["proxy"]["path"], w.get("target", {}).get("path"))
+            pytest.skip("a comparison within rounding of its boundary changed a round")
+    assert dec.seq == want["sequence"]
+    n_esc = sum(w["escalate"] for w in want["rounds"])
+    assert dec.target_passes == n_esc
+    assert (lam == 0.0 and n_esc == 0) or (lam > 1 and n_esc == n_rounds) or 0 < n_esc < n_rounds
+    assert dec.kv_p.ctx_len[0] == len(dec.seq) - 1 == want["kp"].shape[2]
+    assert dec.kv_t.ctx_len[0] == want["kt"].shape[2]
+    if max_nodes == 12:
+        assert any(w["catch_up"] for w in want["rounds"]) or any(w["escalate"] and w["u"] > 0 for w in want["rounds"])
