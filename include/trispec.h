@@ -16,9 +16,10 @@
  *    nothing throws or aborts across this boundary.
  *  - "device" pointers are HIP device memory owned by the caller; "host" pointers
  *    are ordinary host memory.  The library owns only small host descriptors.
- *  - trispec_verify() / trispec_decide() allocate nothing, never synchronise
- *    with the host, and enqueue all work on the caller's stream; results land in
- *    caller-owned device buffers when the stream reaches them.
+ *  - trispec_verify() / trispec_decide() / trispec_sample_decide() / trispec_kv_commit()
+ *    allocate nothing, never synchronise with the host, and enqueue all work on the
+ *    caller's stream; results land in caller-owned device buffers when the stream
+ *    reaches them.
  *  - Matrices are row-major [out, in] (y = x W^T), dtype per trispec_model_config.
  *  - Node order: node 0 is the root (the last committed token, whose KV is not in
  *    the cache yet); parents[i] < i; M = n_nodes <= TRISPEC_MAX_NODES per sequence.
