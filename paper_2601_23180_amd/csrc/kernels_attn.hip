@@ -237,18 +237,23 @@ __global__ __launch_bounds__(64 * NW) void k_attn_bf16(AttnArgs a) {
         for (int ks = 0; ks < KT / 32; ++ks)
           s[ks] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], ql[i][tt], s[ks], 0, 0, 0);
       }
-      // scale, mask, tile max
+      // mask (only the tile in which the context or the split ends: a scalar branch), tile max;
+      // the scores arrive scaled: q was pre-multiplied by log2(e) / sqrt(d).  The vector ALU, not
+      // the matrix cores, sets the pace of a tile step, so every instruction saved here counts.
+      if (need_mask) {
+#pragma unroll
+        for (int ks = 0; ks < KT / 32; ++ks)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const int key = k0 + ks * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
+            s[ks][e] = (key < k_end) ? s[ks][e] : -INFINITY;
+          }
+      }
       float tmax = -INFINITY;
 #pragma unroll
       for (int ks = 0; ks < KT / 32; ++ks)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int key = k0 + ks * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
-          float v = s[ks][e];   // q arrives pre-multiplied by log2(e) / sqrt(d)
-          if (need_mask) v = (key < k_end) ? v : -INFINITY;
-          s[ks][e] = v;
-          tmax = fmaxf(tmax, v);
-        }
+        for (int e = 0; e < 16; ++e) tmax = fmaxf(tmax, s[ks][e]);
       tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
       const float m_new = fmaxf(m_run[i], tmax);
       const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
@@ -269,10 +274,12 @@ __global__ __launch_bounds__(64 * NW) void k_attn_bf16(AttnArgs a) {
         }
       l_run[i] = l_run[i] * alpha + psum;
       // O^T[feature][row] = alpha * O^T + V^T P^T, the feature blocks interleaved for the same reason
+      if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {   // the running maximum of some row moved
 #pragma unroll
-      for (int db = 0; db < D / 32; ++db)
+        for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) oacc[i][db][e] *= alpha;
+          for (int e = 0; e < 16; ++e) oacc[i][db][e] *= alpha;
+      }
 #pragma unroll
       for (int u = 0; u < KT / 16; ++u) {
         bf16x8 vf[D / 32];
