@@ -185,10 +185,9 @@ __global__ __launch_bounds__(64 * NW) void k_attn_bf16(AttnArgs a) {
 
   const int n_tiles = (k_end - k_begin + KT - 1) / KT;
   load_tile(k_begin);
-  // The query rows were written by the kernel before this one and take several times longer to
-  // arrive than the cache does, so they are requested after the first tile (whose wait then does
-  // not include them) and without a branch (a row past the end reads the last row: every lane's
-  // row is independent and such lanes store nothing).
+  // The query rows (as many bytes per workgroup as a tile) are requested after the first tile,
+  // whose wait then does not include them, and without a branch (a row past the end reads the
+  // last row: every lane's row is independent and such lanes store nothing).
   // rotated query as bf16 high part + bf16 low part (written by the QKV epilogue)
   bf16x8 qf[RBW][D / 16], ql[RBW][D / 16];
 #pragma unroll
@@ -331,10 +330,9 @@ __global__ __launch_bounds__(64 * NW) void k_attn_bf16(AttnArgs a) {
 // head — in ascending split order, with the draft-node part: for every ancestor-or-self j of the
 // node, score = q . k_j / sqrt(d) and value v_j, all taken in fp32 from this pass's projections
 // (a.qkv: [row][(nq + 2 nkv) * d], q and k already rotated).
-// Memory round trips, not arithmetic, set this kernel's time: the ancestor mask (written at the
-// start of the pass, quick to arrive) is fetched alone, then everything the preceding kernels
-// wrote — query rows, the first 16 split partials, the ancestors' keys and the first ancestors'
-// values — in ONE round trip.  Block = group * d / 2 threads, two adjacent output features each;
+// Memory round trips, not arithmetic, set this kernel's time: the ancestor mask (one word, quick
+// to arrive) is fetched alone, then everything else — query rows, the first 16 split partials,
+// the ancestors' keys and the first ancestors' values — in ONE round trip.  Block = group * d / 2 threads, two adjacent output features each;
 // the ancestor list (at most 64 nodes) is scored by (slot x quarter of the features) threads.
 constexpr int kMergePreV = 8;    // ancestors whose values are fetched ahead of the scores
 // e^x through the hardware exp2 (about 1e-7 |x| relative error; the arguments here are <= 0)
@@ -355,14 +353,14 @@ __global__ __launch_bounds__(512) void k_attn_merge(AttnArgs a) {
   const int al = active ? tid / (D / 2) : 0, f = active ? (tid - al * (D / 2)) * 2 : 0;   // head, first feature
   const int p = al * M + node;
 
-  // ---- the ancestor list first: the mask was written when the pass began and arrives quickly,
-  // and every address of the second group of loads depends on it
+  // ---- the ancestor list first: one word per workgroup arrives quickly, and every address of
+  // the second group of loads depends on it
   const uint64_t mask = a.anc[r];          // bit j: node j is on the root path of this node (self included)
   const int n_anc = __popcll(mask);        // >= 1
   if (tid < kMaxNodes && ((mask >> tid) & 1ull)) s_anc[__popcll(mask & ((1ull << tid) - 1ull))] = tid;
   __syncthreads();
 
-  // ---- one round trip for everything the kernel before this one wrote: the query rows, the
+  // ---- one round trip for everything else: the query rows, the
   // first 16 split partials of this thread's outputs, the values of the first ancestors and the
   // keys of the first batch of ancestors
   const float2 q2 = *(const float2 *)(a.qkv + (size_t)r * n_total + (size_t)(kvh * group + al) * D + f);
