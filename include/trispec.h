@@ -250,7 +250,8 @@ int trispec_decide(trispec_model *m, int32_t batch, const int32_t *draft_tokens,
  *   scratch       device, 256-byte aligned, trispec_sample_scratch_bytes() bytes
  * out: accepted_len, token (-1 in Case II), escalate, path, argmax, confidence and margin (of the
  * tempered distribution), status (bit 0: a draft token id outside [0, vocab); such a token is
- * never accepted).  Any out pointer may be NULL.  Enqueues four kernels on `stream`, allocates
+ * never accepted; bit 1: a draw found no usable mass — a logit, a draft probability or a uniform
+ * that is NaN or infinite — and returned that node's argmax instead).  Any out pointer may be NULL.  Enqueues four kernels on `stream`, allocates
  * nothing, does not synchronise.
  * Errors (host side, before any launch): TRISPEC_ENULL, TRISPEC_ENODES, TRISPEC_EFORCED,
  * TRISPEC_EWORKSPACE (scratch), TRISPEC_EARG (temperature not finite and positive, threshold NaN,

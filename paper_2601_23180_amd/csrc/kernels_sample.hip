@@ -73,6 +73,8 @@ __global__ __launch_bounds__(kStatThreads) void k_sample_chunkstats(SampleArgs a
   __shared__ Max2 s_m[kStatThreads / 64];
   __shared__ double s_w[kStatThreads / 64];
   const int chunk = blockIdx.x, r = blockIdx.y, tid = threadIdx.x, V = a.vocab;
+  // status word of the whole call: cleared by the first kernel, bits are OR-ed in by the later ones
+  if (chunk == 0 && r == 0 && tid == 0 && a.out.status) *a.out.status = 0;
   const float *row = a.logits + (size_t)r * V;
   const int c0 = chunk * kChunk + tid * kPerThread;
   float v[kPerThread];
@@ -151,7 +153,10 @@ __global__ __launch_bounds__(64) void k_sample_walk(SampleArgs a) {
     }
   }
   bad = __syncthreads_or(bad);
-  if (i == 0) a.seq_bad[b] = bad;
+  if (i == 0) {
+    a.seq_bad[b] = bad;
+    if (bad && a.out.status) atomicOr(a.out.status, 1);
+  }
   if (i < M) {
     const int r = b * M + i;
     const double z = a.row_z[r];
@@ -254,11 +259,6 @@ __global__ __launch_bounds__(kDrawThreads) void k_sample_pick(SampleArgs a) {
   __shared__ double s_target;
   __shared__ int s_chunk, s_kind, s_tok, s_last;
   const int b = blockIdx.x, tid = threadIdx.x;
-  if (b == 0 && tid == 0 && a.out.status) {   // status word of the whole call
-    int bad = 0;
-    for (int s = 0; s < a.batch; ++s) bad |= a.seq_bad[s];
-    *a.out.status = bad ? 1 : 0;
-  }
   DrawRow d;
   if (!a.out.token || !draw_row(a, b, &d)) return;   // uniform over the workgroup
   // chunk totals in ascending order: thread c holds chunk c (at most kDrawThreads chunks)
@@ -277,6 +277,16 @@ __global__ __launch_bounds__(kDrawThreads) void k_sample_pick(SampleArgs a) {
   __syncthreads();
   if (tid == s_chunk) { s_target = ctarget - cbegin; s_kind = kind; }
   __syncthreads();
+  if (s_chunk < 0) {
+    // No chunk qualifies: the total or the target is NaN (a NaN or infinite logit, draft
+    // probability or uniform) or there is no mass at all.  No draw is possible; the node's argmax
+    // is returned and bit 1 of the status word says so.  (Uniform over the workgroup.)
+    if (tid == 0) {
+      a.out.token[b] = a.row_idx[b * a.n_nodes + a.sel_row[b]];
+      if (a.out.status) atomicOr(a.out.status, 2);
+    }
+    return;
+  }
   const int chunk = s_chunk;
   kind = s_kind;
   const double target = s_target;

@@ -139,6 +139,26 @@ def test_invalid_token_and_massless_residual():
     assert got["path"][1, :3].tolist() == [0, 1, -1]
 
 
+def test_a_draw_without_usable_mass_reports_it_and_stays_in_range():
+    """A NaN uniform leaves the inverse CDF without a target: the call must say so in the status word
+    (bit 1) and return a token of the vocabulary (the node's argmax), not read outside the logits."""
+    rng = np.random.default_rng(12)
+    B, M, V = 3, 4, 9000
+    logits = (rng.standard_normal((B, M, V)) * 2).astype(np.float32)
+    pd, tk = zip(*[gen_draft_distributions(logits[b], 1.0, 50 + b) for b in range(B)])
+    ua, us = gen_uniforms(5, B, M)
+    us = us.copy()
+    us[1] = np.nan
+    got = run_gpu(logits, np.stack(tk), np.stack(pd), ua, us, 1.0, 0.0, CRIT_MARGIN, 1, RESAMPLE_RESIDUAL)
+    assert got["status"][0] == 2
+    assert np.all((got["token"] >= 0) & (got["token"] < V))
+    row = int(got["accepted_len"][1])
+    assert int(got["token"][1]) == int(np.argmax(logits[1, row]))
+    us[1] = 0.5                                               # the same call with a proper uniform: clean status
+    got = run_gpu(logits, np.stack(tk), np.stack(pd), ua, us, 1.0, 0.0, CRIT_MARGIN, 1, RESAMPLE_RESIDUAL)
+    assert got["status"][0] == 0
+
+
 @pytest.mark.parametrize("key,tol", [("tiny", 3e-4), ("tiny_bf16", 5e-3)])
 def test_after_a_real_verification_pass(key, tol):
     """Logits from trispec_verify on a chain, decision from trispec_sample_decide; the oracle runs its
