@@ -279,6 +279,27 @@ int trispec_sample_decide(const float *logits, const int32_t *draft_tokens, int3
                           const trispec_sample_opts *opts, const trispec_verify_out *out);
 
 /*
+ * trispec_sample_decide for callers that cannot allocate device memory at all — code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc — and so cannot bring the
+ * scratch buffer: the same four kernels run on a scratch area that is part of this library's
+ * device image (TRISPEC_STATIC_SCRATCH_BYTES bytes per GPU, held until the process ends).
+ * Arguments, outputs and host-side errors are those of trispec_sample_decide, except that
+ * opts->scratch and opts->scratch_bytes are ignored; a (batch, n_nodes, vocab) whose
+ * trispec_sample_scratch_bytes() exceeds TRISPEC_STATIC_SCRATCH_BYTES is refused with
+ * TRISPEC_EWORKSPACE before anything is enqueued (batch 8 x 9 nodes x vocabulary 151936 needs
+ * about 60 KB).  Call it with the GPU that owns opts->stream current.  It calls no hipMalloc /
+ * hipFree and no allocating library routine; the first call on a GPU looks the area's address up
+ * once (TRISPEC_ELAUNCH if that fails).  Every call on one GPU shares that GPU's area: calls that
+ * overlap in time on one GPU (different streams, different threads) race and must be serialised
+ * by the caller; calls in sequence need no clearing in between (no kernel reads an entry that the
+ * same call has not written).
+ */
+#define TRISPEC_STATIC_SCRATCH_BYTES (1 << 20)
+int trispec_sample_decide_static(const float *logits, const int32_t *draft_tokens, int32_t batch,
+                                 int32_t n_nodes, int32_t vocab, float threshold,
+                                 const trispec_sample_opts *opts, const trispec_verify_out *out);
+
+/*
  * Measurement aid: HIP events recorded on the pass's own stream around every launch of one
  * kernel class, so a benchmark can price that kernel against the HBM roofline.
  *   TRISPEC_K_GEMM  the weight-streaming projection / FFN matmul (4 launches per layer)

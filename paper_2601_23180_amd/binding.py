@@ -29,6 +29,7 @@ EXPORTS = [
     "trispec_strerror", "trispec_timer_create", "trispec_timer_reset", "trispec_timer_read",
     "trispec_timer_destroy", "trispec_model_pack_bytes", "trispec_model_pack", "trispec_copy_probe",
     "trispec_kv_commit", "trispec_sample_scratch_bytes", "trispec_sample_decide",
+    "trispec_sample_decide_static",
 ]
 K_GEMM, K_HEAD, K_ATTN = 0, 1, 2
 
@@ -111,6 +112,7 @@ def lib() -> C.CDLL:
         l.trispec_sample_scratch_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
         l.trispec_sample_decide.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_float,
                                             C.POINTER(SampleOpts), C.POINTER(VerifyOut)]
+        l.trispec_sample_decide_static.argtypes = l.trispec_sample_decide.argtypes
         l.trispec_timer_create.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]
         l.trispec_timer_reset.argtypes = [C.c_void_p]
         l.trispec_timer_read.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_double),
@@ -294,13 +296,19 @@ class SampleDecider:
     """Pre-allocated scratch and output buffers for repeated trispec_sample_decide calls on
     [batch, n_nodes, vocab] logits."""
 
-    def __init__(self, batch: int, n_nodes: int, vocab: int, device="cuda"):
+    def __init__(self, batch: int, n_nodes: int, vocab: int, device="cuda", static_scratch: bool = False):
+        """static_scratch: call trispec_sample_decide_static (the library's own scratch area; no
+        scratch tensor is allocated here) instead of trispec_sample_decide."""
         self.batch, self.n_nodes, self.vocab = batch, n_nodes, vocab
         n = C.c_size_t()
         check(lib().trispec_sample_scratch_bytes(batch, n_nodes, vocab, C.byref(n)))
         self.scratch_bytes = n.value
-        self.scratch = torch.empty(n.value + 256, dtype=torch.uint8, device=device)
-        self._sptr = self.scratch.data_ptr() + (-self.scratch.data_ptr()) % 256
+        self.static_scratch = static_scratch
+        if static_scratch:
+            self.scratch, self._sptr = None, None
+        else:
+            self.scratch = torch.empty(n.value + 256, dtype=torch.uint8, device=device)
+            self._sptr = self.scratch.data_ptr() + (-self.scratch.data_ptr()) % 256
         i32 = dict(dtype=torch.int32, device=device)
         f32 = dict(dtype=torch.float32, device=device)
         self.out = {
@@ -329,9 +337,10 @@ class SampleDecider:
         st = stream if stream is not None else torch.cuda.current_stream().cuda_stream
         opts = SampleOpts(float(temperature), int(resample), int(criterion), int(n_forced),
                           p_draft.data_ptr() if n_nodes > 1 else None, u_accept.data_ptr(), u_sample.data_ptr(),
-                          self._sptr, self.scratch_bytes, st)
-        check(lib().trispec_sample_decide(logits.data_ptr(), draft_tokens.data_ptr(), batch, n_nodes, vocab,
-                                          float(threshold), C.byref(opts), C.byref(self._out)))
+                          self._sptr, self.scratch_bytes if not self.static_scratch else 0, st)
+        fn = lib().trispec_sample_decide_static if self.static_scratch else lib().trispec_sample_decide
+        check(fn(logits.data_ptr(), draft_tokens.data_ptr(), batch, n_nodes, vocab, float(threshold),
+                 C.byref(opts), C.byref(self._out)))
         return self.out
 
 

@@ -5,6 +5,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -734,9 +735,10 @@ int trispec_sample_scratch_bytes(int32_t batch, int32_t n_nodes, int32_t vocab, 
   return TRISPEC_OK;
 }
 
-int trispec_sample_decide(const float *logits, const int32_t *draft_tokens, int32_t batch, int32_t n_nodes,
-                          int32_t vocab, float threshold, const trispec_sample_opts *o,
-                          const trispec_verify_out *out) {
+namespace {
+// Host-side checks shared by the two sampling entry points (everything but the scratch buffer).
+int sample_check(const float *logits, const int32_t *draft_tokens, int32_t batch, int32_t n_nodes, int32_t vocab,
+                 float threshold, const trispec_sample_opts *o, const trispec_verify_out *out) {
   if (!logits || !draft_tokens || !o || !out || !o->u_accept || !o->u_sample) return TRISPEC_ENULL;
   if (!sample_shape_ok(batch, n_nodes)) return TRISPEC_ENODES;
   if (n_nodes > 1 && !o->p_draft) return TRISPEC_ENULL;
@@ -745,9 +747,70 @@ int trispec_sample_decide(const float *logits, const int32_t *draft_tokens, int3
       (o->criterion != TRISPEC_CRIT_MARGIN && o->criterion != TRISPEC_CRIT_TOP1) ||
       (o->resample != TRISPEC_RESAMPLE_RESIDUAL && o->resample != TRISPEC_RESAMPLE_DIRECT))
     return TRISPEC_EARG;
+  return TRISPEC_OK;
+}
+
+// Carves `ws` (sample_layout bytes, 256-byte aligned) and enqueues the four kernels.
+int sample_launch(const float *logits, const int32_t *draft_tokens, int32_t batch, int32_t n_nodes, int32_t vocab,
+                  float threshold, const trispec_sample_opts *o, const trispec_verify_out *out,
+                  const SampleLayout &L, char *ws);
+}  // namespace
+
+int trispec_sample_decide(const float *logits, const int32_t *draft_tokens, int32_t batch, int32_t n_nodes,
+                          int32_t vocab, float threshold, const trispec_sample_opts *o,
+                          const trispec_verify_out *out) {
+  const int rc = sample_check(logits, draft_tokens, batch, n_nodes, vocab, threshold, o, out);
+  if (rc) return rc;
   const SampleLayout L = sample_layout(batch, n_nodes, vocab);
   if (!o->scratch || ((uintptr_t)o->scratch & 255) || o->scratch_bytes < L.total) return TRISPEC_EWORKSPACE;
-  char *ws = (char *)o->scratch;
+  return sample_launch(logits, draft_tokens, batch, n_nodes, vocab, threshold, o, out, L, (char *)o->scratch);
+}
+
+// ---- the entry point that allocates nothing: the scratch of the sampling kernels lives in a
+// device array of this library instead of a caller buffer.  Each GPU holds its own copy of the
+// array at its own address; in host code the array's NAME is only a handle for
+// hipGetSymbolAddress, never a device address, so kernels always get the looked-up pointer.
+static __device__ __align__(256) unsigned char scratch[TRISPEC_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices];   // per device, filled on the first call with that device current
+
+int static_scratch(void **out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return TRISPEC_ELAUNCH;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return TRISPEC_ELAUNCH;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return TRISPEC_OK;
+}
+}  // namespace
+
+int trispec_sample_decide_static(const float *logits, const int32_t *draft_tokens, int32_t batch,
+                                 int32_t n_nodes, int32_t vocab, float threshold,
+                                 const trispec_sample_opts *o, const trispec_verify_out *out) {
+  const int rc = sample_check(logits, draft_tokens, batch, n_nodes, vocab, threshold, o, out);
+  if (rc) return rc;
+  const SampleLayout L = sample_layout(batch, n_nodes, vocab);
+  if (L.total > (size_t)TRISPEC_STATIC_SCRATCH_BYTES) return TRISPEC_EWORKSPACE;
+  void *ws = nullptr;
+  const int rs = static_scratch(&ws);
+  if (rs) return rs;
+  // Nothing in the scratch has to start at zero: every kernel of the call writes each entry it
+  // or a later kernel reads (per chunk statistics, per row merges, the selected row and the
+  // chunk masses of the kinds that are drawn from), so the previous call's contents are inert.
+  return sample_launch(logits, draft_tokens, batch, n_nodes, vocab, threshold, o, out, L, (char *)ws);
+}
+
+namespace {
+int sample_launch(const float *logits, const int32_t *draft_tokens, int32_t batch, int32_t n_nodes, int32_t vocab,
+                  float threshold, const trispec_sample_opts *o, const trispec_verify_out *out,
+                  const SampleLayout &L, char *ws) {
   SampleArgs a;
   memset(&a, 0, sizeof(a));
   a.logits = logits; a.tokens = draft_tokens; a.p_draft = o->p_draft;
@@ -768,6 +831,7 @@ int trispec_sample_decide(const float *logits, const int32_t *draft_tokens, int3
   launch_sample_decide((hipStream_t)o->stream, a);
   return hipGetLastError() == hipSuccess ? TRISPEC_OK : TRISPEC_ELAUNCH;
 }
+}  // namespace
 
 int trispec_timer_create(int32_t kernel_class, int32_t capacity, trispec_timer **out) {
   if (!out) return TRISPEC_ENULL;
