@@ -112,6 +112,9 @@ def main():
     ap.add_argument("--seed", type=int, default=1003)
     ap.add_argument("--threshold", type=float, default=0.5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--launch-mode", choices=("per-matmul", "per-layer"), default="per-matmul",
+                    help="per-matmul: one launch per matmul (default, the faster cut); per-layer: the matmuls "
+                         "between two attention calls as one launch with device-side barriers")
     ap.add_argument("--launch", choices=("eager", "graph"), default="eager",
                     help="graph: the pass is captured once into a HIP graph and the timed steps replay it")
     args = ap.parse_args()
@@ -133,6 +136,8 @@ def main():
     shape = SHAPES["qwen3_8b"].with_(n_layers=4) if key == "qwen3_8b_L4" else SHAPES[key]
     inp = build_inputs(shape, batch, ctx, n_nodes, kind, args.seed)
     ver, kv, tok, pos, parents = inp["ver"], inp["kv"], inp["tok"], inp["pos"], inp["parents"]
+    from paper_2601_23180_amd.binding import LAUNCH_PER_LAYER, LAUNCH_PER_MATMUL
+    ver.launch_mode = LAUNCH_PER_LAYER if args.launch_mode == "per-layer" else LAUNCH_PER_MATMUL
 
     def step():
         ver.verify(kv, tok, parents, pos, args.threshold, want_logits=False)

@@ -172,7 +172,23 @@ typedef struct {
                                 every node — the final-norm output the LM head reads — which the
                                 drafter is re-seeded with after the round (Sec. 3.2, "Drafter
                                 selection and adapter training"); NULL = not exported */
+  int32_t launch_mode;       /* TRISPEC_LAUNCH_PER_MATMUL (0, default) | TRISPEC_LAUNCH_PER_LAYER: how the pass
+                                is cut into kernel launches (same arithmetic either way) */
+  uint64_t *stamps;          /* optional device [n_layers][16] (measurement only): 100 MHz wall-clock ticks of
+                                one workgroup at the phase boundaries of each layer launch — [0] start, then
+                                per matmul (O, gate+up, down, next QKV) [1+3p] past the barrier, [2+3p] end of
+                                the weight stream, [3+3p] arrived at the next barrier; NULL on the hot path */
 } trispec_verify_opts;
+
+/* TRISPEC_LAUNCH_PER_MATMUL: one launch per matmul (the faster cut on MI355X as measured, hence
+ * the default).  TRISPEC_LAUNCH_PER_LAYER: bf16 models of up to 128 rows (batch * n_nodes) whose
+ * widths allow it run the O projection, gate + up, down projection and the next layer's QKV
+ * projection of every layer as ONE launch of a grid that is resident all at once, with device-side
+ * barriers between the four and the next matmul's first weights requested while the last
+ * workgroups of a matmul finish; shapes it cannot take fall back to one launch per matmul.  The
+ * barrier waits are bounded: should the grid ever not be resident at once, the pass still ends,
+ * with bit 2 of the status word set and meaningless outputs. */
+enum { TRISPEC_LAUNCH_PER_MATMUL = 0, TRISPEC_LAUNCH_PER_LAYER = 1 };
 
 #define TRISPEC_PATH_STRIDE (TRISPEC_MAX_NODES)
 
@@ -186,7 +202,8 @@ typedef struct {             /* device pointers, caller-owned; any may be NULL t
   int32_t *argmax;           /* [batch, n_nodes] verifier top-1 token at each node */
   float *confidence;         /* [batch, n_nodes] top-1 softmax probability */
   float *margin;             /* [batch, n_nodes] top-1 minus top-2 probability (Eq. 8) */
-  int32_t *status;           /* [1] device-side error bits: 1 = a draft token id outside [0, vocab) */
+  int32_t *status;           /* [1] device-side error bits: 1 = a draft token id outside [0, vocab);
+                                         4 = a device-side barrier wait expired (results are not valid) */
 } trispec_verify_out;
 
 /*
@@ -324,6 +341,16 @@ int trispec_timer_destroy(trispec_timer *t);
  * "node_idx").  Errors: TRISPEC_ENULL, TRISPEC_ENODES, TRISPEC_EARG (unknown name). */
 int trispec_workspace_region(const trispec_model *m, int32_t batch, int32_t n_nodes,
                              const char *name, size_t *offset, size_t *bytes);
+
+/* Test hooks of the bounded device-side wait.  trispec_debug_set_spin_limit: longest wait of any
+ * later call, in ticks of the 100 MHz wall clock (0 restores the default of 2 s).
+ * trispec_wait_probe: one workgroup waits on `counter_dev` (an int32 the caller leaves below
+ * `expect`) exactly as a layer launch waits at a barrier — it must give up after limit_ticks, set
+ * *abort_dev to 1 and OR 4 into *status_dev, and end normally; with *abort_dev already non-zero it
+ * must not wait at all.  Errors: TRISPEC_ENULL, TRISPEC_ELAUNCH. */
+int trispec_debug_set_spin_limit(uint64_t ticks);
+int trispec_wait_probe(int32_t *counter_dev, int32_t expect, uint64_t limit_ticks, int32_t *abort_dev,
+                       int32_t *status_dev, void *stream);
 
 /* Algorithmic HBM bytes of one verify pass at this shape: layer weights once + LM head
  * once + context K/V once + draft K/V written (the figure the roofline is priced on). */

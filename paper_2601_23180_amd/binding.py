@@ -29,9 +29,10 @@ EXPORTS = [
     "trispec_strerror", "trispec_timer_create", "trispec_timer_reset", "trispec_timer_read",
     "trispec_timer_destroy", "trispec_model_pack_bytes", "trispec_model_pack", "trispec_copy_probe",
     "trispec_kv_commit", "trispec_sample_scratch_bytes", "trispec_sample_decide",
-    "trispec_sample_decide_static",
+    "trispec_sample_decide_static", "trispec_debug_set_spin_limit", "trispec_wait_probe",
 ]
 K_GEMM, K_HEAD, K_ATTN = 0, 1, 2
+LAUNCH_PER_MATMUL, LAUNCH_PER_LAYER = 0, 1
 
 
 class ModelConfig(C.Structure):
@@ -51,7 +52,8 @@ class Weights(C.Structure):
 class VerifyOpts(C.Structure):
     _fields_ = [("criterion", C.c_int32), ("n_forced", C.c_int32), ("workspace", C.c_void_p),
                 ("workspace_bytes", C.c_size_t), ("debug_logits", C.c_void_p), ("stream", C.c_void_p),
-                ("timer", C.c_void_p), ("hidden_out", C.c_void_p)]
+                ("timer", C.c_void_p), ("hidden_out", C.c_void_p), ("launch_mode", C.c_int32),
+                ("stamps", C.c_void_p)]
 
 
 class VerifyOut(C.Structure):
@@ -113,6 +115,8 @@ def lib() -> C.CDLL:
         l.trispec_sample_decide.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_float,
                                             C.POINTER(SampleOpts), C.POINTER(VerifyOut)]
         l.trispec_sample_decide_static.argtypes = l.trispec_sample_decide.argtypes
+        l.trispec_debug_set_spin_limit.argtypes = [C.c_uint64]
+        l.trispec_wait_probe.argtypes = [C.c_void_p, C.c_int32, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]
         l.trispec_timer_create.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]
         l.trispec_timer_reset.argtypes = [C.c_void_p]
         l.trispec_timer_read.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_double),
@@ -377,6 +381,8 @@ class Verifier:
         self.logits = torch.zeros((batch, max_nodes, model.cfg.vocab), **f32) if debug_logits else None
         self.hidden = torch.zeros((batch, max_nodes, model.cfg.hidden), **f32) if export_hidden else None
         self.timer = None   # optional KernelTimer attached to every verify call
+        self.launch_mode = LAUNCH_PER_MATMUL
+        self.stamps = None  # optional int64 device tensor [n_layers, 16] (phase time stamps of the layer launches)
 
     def _opts(self, criterion, n_forced, stream, want_logits):
         o = VerifyOpts()
@@ -387,6 +393,8 @@ class Verifier:
         o.stream = s.cuda_stream
         o.timer = self.timer.handle if self.timer is not None else None
         o.hidden_out = self.hidden.data_ptr() if self.hidden is not None else None
+        o.launch_mode = self.launch_mode
+        o.stamps = self.stamps.data_ptr() if self.stamps is not None else None
         return o
 
     def _out(self, n_nodes):

@@ -19,6 +19,7 @@ struct trispec_model {
   std::vector<const void *> wq, wk, wv, wo, w_gate, w_up, w_down, norm_attn, norm_ffn;
   // bf16 models: packed copies of the matrices (device, inside the caller's pack buffer)
   bool packed;
+  int layer_grid[3][2];   // largest resident grid of the layer kernel for rows_pad 32 / 64 / 128 and ring depth 8 / 4 (-1: not asked yet)
   const void *p_lm_head;
   std::vector<const void *> p_wq, p_wk, p_wv, p_wo, p_gate, p_up, p_down;
 };
@@ -70,9 +71,13 @@ int rows_pad_for(int rows) {
 
 // Workspace regions, in order.  Offsets are a pure function of (model, batch, n_nodes).
 struct Layout {
-  size_t anc, parent, status, cos_t, sin_t, x, h, q, qkv_f32, attn_out, act, part, counters, ss_part, attn_o, attn_m, attn_l, head_l1, head_l2, head_sum, head_idx, node_l1, node_l2, node_sum,
+  size_t anc, parent, status, cos_t, sin_t, x, x2, h, h2, q, qkv_f32, attn_out, act, part, counters, ss_part, attn_o, attn_m, attn_l, head_l1, head_l2, head_sum, head_idx, node_l1, node_l2, node_sum,
       node_idx, logits, total;
   int rows_max, rows_pad_max, head_tiles, max_tiles;
+  // `counters` holds, in this order: max_tiles + 1 tile counters of the split-K matmuls, kLayerPhases
+  // barrier counters per layer, the abort word — n_zero ints that the set-up kernel clears
+  int bar_index, abort_index, n_zero;
+  size_t part_phase;   // floats per partial region of one phase of the layer kernel
 };
 
 // Decomposition of one bf16 matmul into (128-column tile, k split) workgroups: about kTargetWgs
@@ -82,6 +87,12 @@ struct SplitPlan {
   int tile_n, n_tiles, n_splits, k_per_split;
 };
 constexpr int kTargetWgs = 192;
+constexpr int kLayerMaxGrid = 256;   // workgroups of the layer kernel (one per CU)
+constexpr int kLayerSplitCap = 8;    // k splits of one matmul inside the layer kernel
+// Longest wait at a device-side barrier, in ticks of the 100 MHz wall clock (2 s: three orders of
+// magnitude above a whole pass).  trispec_debug_set_spin_limit changes it (tests of the expiry path).
+unsigned long long g_spin_limit = 200000000ull;
+
 SplitPlan plan_gemm(int epi, int n_cols, int k, int rows_pad) {
   (void)rows_pad;
   SplitPlan p;
@@ -106,6 +117,30 @@ SplitPlan plan_gemm(int epi, int n_cols, int k, int rows_pad) {
 }
 inline int tiles_of(int n) { return (n + kGemmTileN - 1) / kGemmTileN; }
 
+// Decomposition of one matmul inside the layer kernel: at most max_items (tile, split) items, every
+// split the same whole number of `unit`-deep steps (unit = ring depth x chunk depth of the kernel
+// for this row count).  n_splits = 0: not possible for this shape.
+SplitPlan plan_layer(int n_cols, int k, int unit, int max_items, int split_cap) {
+  SplitPlan p;
+  p.tile_n = kGemmTileN;
+  p.n_tiles = (n_cols + p.tile_n - 1) / p.tile_n;
+  p.n_splits = 0;
+  p.k_per_split = 0;
+  if (p.n_tiles > max_items || k % unit != 0) return p;
+  int smax = max_items / p.n_tiles;
+  if (smax > kMaxSplitK) smax = kMaxSplitK;
+  if (smax > k / unit) smax = k / unit;
+  if (smax > split_cap) smax = split_cap;
+  for (int s = smax; s >= 1; --s)
+    if (k % s == 0 && (k / s) % unit == 0) {
+      p.n_splits = s;
+      p.k_per_split = k / s;
+      break;
+    }
+  return p;
+}
+
+
 Layout make_layout(const trispec_model_config &c, int batch, int max_nodes) {
   Layout L;
   memset(&L, 0, sizeof(L));
@@ -125,8 +160,10 @@ Layout make_layout(const trispec_model_config &c, int batch, int max_nodes) {
   L.cos_t = take(sizeof(float) * rows * (c.head_dim / 2));
   L.sin_t = take(sizeof(float) * rows * (c.head_dim / 2));
   L.x = take(sizeof(float) * (size_t)rp * c.hidden);
+  L.x2 = take(f32 ? 0 : sizeof(float) * (size_t)rp * c.hidden);   // the layer kernel alternates two copies
   // matmul operands: fp32 models one fp32 panel; bf16 models a bf16 hi panel + a bf16 lo panel
   L.h = take(sizeof(float) * (size_t)rp * c.hidden);
+  L.h2 = take(f32 ? 0 : sizeof(float) * (size_t)rp * c.hidden);
   L.q = take(sizeof(float) * (size_t)rp * qd);
   L.qkv_f32 = take(f32 ? 0 : sizeof(float) * (size_t)rp * nqkv);
   L.attn_out = take(sizeof(float) * (size_t)rp * qd);
@@ -148,9 +185,16 @@ Layout make_layout(const trispec_model_config &c, int batch, int max_nodes) {
       if (e > m) m = e;
       if (p.n_tiles > L.max_tiles) L.max_tiles = p.n_tiles;
     }
+    // the layer kernel runs at most kLayerMaxGrid (tile, split) items per matmul and gives each
+    // of its matmuls a partial region of its own
+    L.part_phase = (size_t)kLayerMaxGrid * kGemmTileN * rp;
+    if (kLayerPhases * (size_t)kLayerMaxGrid * kGemmTileN > m) m = kLayerPhases * (size_t)kLayerMaxGrid * kGemmTileN;
     L.part = take(sizeof(float) * m * rp);
   }
-  L.counters = take(sizeof(int32_t) * (L.max_tiles + 1));
+  L.bar_index = L.max_tiles + 1;
+  L.abort_index = L.bar_index + kLayerPhases * c.n_layers;
+  L.n_zero = L.abort_index + 1;
+  L.counters = take(sizeof(int32_t) * L.n_zero);
   // sums of squares per (tile, row): two buffers, a matmul reads its producer's while writing its own
   L.ss_part = take(2 * sizeof(float) * (size_t)tiles_of(c.hidden) * rp);   // sized for the narrower tile
   const int group = c.n_q_heads / c.n_kv_heads;
@@ -263,6 +307,7 @@ int trispec_model_create(const trispec_model_config *cfg, const trispec_weights 
   m->norm_attn.assign(w->norm_attn, w->norm_attn + L);
   m->norm_ffn.assign(w->norm_ffn, w->norm_ffn + L);
   m->packed = false;
+  for (int i = 0; i < 3; ++i) m->layer_grid[i][0] = m->layer_grid[i][1] = -1;
   m->p_lm_head = nullptr;
   *out = m;
   return TRISPEC_OK;
@@ -515,7 +560,8 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
   };
 
   (void)hipGetLastError();
-  launch_setup(st, tab, rows, (uint64_t *)(ws + L.anc), (int32_t *)(ws + L.parent), status);
+  launch_setup(st, tab, rows, (uint64_t *)(ws + L.anc), (int32_t *)(ws + L.parent), status,
+               (int32_t *)(ws + L.counters), L.n_zero);
   launch_rope_table(st, positions, rows, c.head_dim, c.rope_base, cos_t, sin_t);
 
   if (f32) {
@@ -566,20 +612,20 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
       launch_export_hidden(st, c.dtype, h, nullptr, nullptr, 0, rows, rp, c.hidden, c.rms_eps, opts->hidden_out);
   } else {
     // ---------------- bf16 models: per layer QKV, attention (+ merge), O, gate/up, down
-    void *h = ws + L.h;
+    void *h = ws + L.h, *h2 = ws + L.h2;
+    float *x2 = (float *)(ws + L.x2);
     int32_t *counters = (int32_t *)(ws + L.counters);
     float *qkv_f32 = (float *)(ws + L.qkv_f32);
     at.qkv = qkv_f32;
     at.q = ws + L.q;
     at.q_panel = pan_q;
-    launch_zero_counters(st, counters, L.max_tiles + 1);
     // ss[0]: written by the embedding (1 tile) and by every down projection; ss[1]: by every O projection
     float *ss0 = (float *)(ws + L.ss_part), *ss1 = ss0 + (size_t)tiles_of(c.hidden) * rp;
     launch_embed_norm(st, c.dtype, draft_tokens, m->embed, m->norm_attn[0], rows, c.hidden, c.vocab, c.rms_eps,
                       x, h, (size_t)(rp / 32), ss0, status);
-    int ss0_tiles = 1, o_tiles = 1;
+    const int hid_tiles = tiles_of(c.hidden);
     auto base = [&](int epi, const void *xin, size_t xpanel, const float *ss_in, int ss_tiles, int k,
-                    int n_total) {
+                    int n_total, const SplitPlan &p) {
       GemmArgs g;
       memset(&g, 0, sizeof(g));
       g.epi = epi;
@@ -592,7 +638,6 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
       g.k = k;
       g.rows = rows;
       g.rows_pad = rp;
-      const SplitPlan p = plan_gemm(epi, n_total, k, rp);
       g.tile_n = p.tile_n;
       g.n_tiles = p.n_tiles;
       g.n_splits = p.n_splits;
@@ -601,68 +646,147 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
       g.counters = counters;
       return g;
     };
-    auto launch_gemm = [&](hipStream_t s_, const GemmArgs &g) {
-      launch_gemm_bf16(s_, g);
+    // The four matmuls of a layer.  `ss_tiles` of a consumer = tiles of its producer (1 after the embedding).
+    auto mk_qkv = [&](int l, const SplitPlan &p, int ss_tiles) {
+      GemmArgs g = base(EPI_QKV, h, pan_h, ss0, ss_tiles, c.hidden, nqkv, p);
+      g.seg[0] = {m->p_wq[l], qd, 0};
+      g.seg[1] = {m->p_wk[l], kvd, qd};
+      g.seg[2] = {m->p_wv[l], kvd, qd + kvd};
+      g.n_seg = 3;
+      g.q_out = ws + L.q; g.q_panel = pan_q;
+      g.cos_t = cos_t; g.sin_t = sin_t; g.qkv_f32 = qkv_f32; g.ctx = ctx;
+      g.k_cache = (char *)kv->k + (size_t)l * kv_layer;
+      g.v_cache = (char *)kv->v + (size_t)l * kv_layer;
+      g.n_nodes = n_nodes; g.n_q_heads = c.n_q_heads; g.n_kv_heads = c.n_kv_heads; g.head_dim = c.head_dim;
+      g.capacity = kv->capacity;
+      return g;
     };
-    auto resid = [&](GemmArgs &g, const void *next_norm, float *ss_out) {
-      g.x_resid = x; g.xw_out = h; g.out_panel = pan_h; g.next_norm_w = next_norm; g.ss_part = ss_out;
+    auto mk_o = [&](int l, const SplitPlan &p, const float *x_in, float *x_out, void *h_out) {
+      GemmArgs g = base(EPI_RESID, attn_out, pan_q, nullptr, 0, qd, c.hidden, p);
+      g.seg[0] = {m->p_wo[l], c.hidden, 0};
+      g.n_seg = 1;
+      g.x_resid = x_in; g.x_resid_out = x_out; g.xw_out = h_out; g.out_panel = pan_h;
+      g.next_norm_w = m->norm_ffn[l]; g.ss_part = ss1;
+      return g;
     };
-    for (int l = 0; l < c.n_layers; ++l) {
-      char *kl = (char *)kv->k + (size_t)l * kv_layer, *vl = (char *)kv->v + (size_t)l * kv_layer;
-      {
-        GemmArgs g = base(EPI_QKV, h, pan_h, ss0, ss0_tiles, c.hidden, nqkv);
-        g.seg[0] = {m->p_wq[l], qd, 0};
-        g.seg[1] = {m->p_wk[l], kvd, qd};
-        g.seg[2] = {m->p_wv[l], kvd, qd + kvd};
-        g.n_seg = 3;
-        g.q_out = ws + L.q; g.q_panel = pan_q;
-        g.cos_t = cos_t; g.sin_t = sin_t; g.qkv_f32 = qkv_f32; g.k_cache = kl; g.v_cache = vl; g.ctx = ctx;
-        g.n_nodes = n_nodes; g.n_q_heads = c.n_q_heads; g.n_kv_heads = c.n_kv_heads; g.head_dim = c.head_dim;
-        g.capacity = kv->capacity;
-        TimedLaunch tl(opts->timer, TRISPEC_K_GEMM, st, (double)nqkv * c.hidden * es);
-        launch_gemm(st, g);
+    auto mk_gu = [&](int l, const SplitPlan &p, const void *h_in) {
+      GemmArgs g = base(EPI_SWIGLU, h_in, pan_h, ss1, hid_tiles, c.hidden, 2 * c.ffn, p);
+      g.seg[0] = {m->p_gate[l], c.ffn, 0};
+      g.seg[1] = {m->p_up[l], c.ffn, c.ffn};
+      g.n_seg = 2;
+      g.act_out = act; g.ffn = c.ffn; g.out_panel = pan_f;
+      return g;
+    };
+    auto mk_dn = [&](int l, const SplitPlan &p, const float *x_in, float *x_out) {
+      GemmArgs g = base(EPI_RESID, act, pan_f, nullptr, 0, c.ffn, c.hidden, p);
+      g.seg[0] = {m->p_down[l], c.hidden, 0};
+      g.n_seg = 1;
+      g.x_resid = x_in; g.x_resid_out = x_out; g.xw_out = h; g.out_panel = pan_h;
+      g.next_norm_w = (l + 1 < c.n_layers) ? m->norm_attn[l + 1] : m->final_norm; g.ss_part = ss0;
+      return g;
+    };
+    const SplitPlan pq = plan_gemm(EPI_QKV, nqkv, c.hidden, rp), po = plan_gemm(EPI_RESID, c.hidden, qd, rp);
+    const SplitPlan pg = plan_gemm(EPI_SWIGLU, 2 * c.ffn, c.hidden, rp), pd = plan_gemm(EPI_RESID, c.hidden, c.ffn, rp);
+    auto timed_gemm = [&](const GemmArgs &g, double bytes) {
+      TimedLaunch tl(opts->timer, TRISPEC_K_GEMM, st, bytes);
+      launch_gemm_bf16(st, g);
+    };
+    const double b_qkv = (double)nqkv * c.hidden * es, b_o = (double)c.hidden * qd * es;
+    const double b_gu = 2.0 * c.ffn * c.hidden * es, b_dn = (double)c.hidden * c.ffn * es;
+
+    // ---- one launch for O, gate + up, down and the next QKV when the shapes allow it and the
+    // whole grid is resident at once on this device (asked once per model and row count)
+    bool layered = opts->launch_mode == TRISPEC_LAUNCH_PER_LAYER && rp <= 128;
+    SplitPlan lq, lo, lg, ld;
+    int lgrid = 0, ring_depth = 0;
+    if (layered) {
+      const int slot = rp == 32 ? 0 : (rp == 64 ? 1 : 2);
+      auto plans = [&](int max_items, int depth) {
+        const int unit = layer_step(rp, depth);
+        lq = plan_layer(nqkv, c.hidden, unit, max_items, kLayerSplitCap);
+        lo = plan_layer(c.hidden, qd, unit, max_items, kLayerSplitCap);
+        lg = plan_layer(2 * c.ffn, c.hidden, unit, max_items, 1);
+        ld = plan_layer(c.hidden, c.ffn, unit, max_items, kLayerSplitCap);
+        return lq.n_splits > 0 && lo.n_splits > 0 && lg.n_splits > 0 && ld.n_splits > 0;
+      };
+      auto probe_grid = [&](int depth) {
+        LayerArgs probe;
+        memset(&probe, 0, sizeof(probe));
+        probe.n_phases = 3;
+        probe.ring_depth = depth;
+        probe.ph[0] = mk_o(0, lo, x, x2, h2);
+        probe.ph[1] = mk_gu(0, lg, h2);
+        probe.ph[2] = mk_dn(0, ld, x2, x);
+        return layer_kernel_max_grid(probe);
+      };
+      layered = false;
+      for (int depth = 8; depth >= 4 && !layered; depth -= 4) {
+        if (!plans(kLayerMaxGrid, depth)) continue;
+        int &cap = m->layer_grid[slot][depth == 8 ? 0 : 1];
+        if (cap < 0) cap = probe_grid(depth);
+        const int lim = cap < kLayerMaxGrid ? cap : kLayerMaxGrid;
+        if (lim <= 0 || !plans(lim, depth)) continue;
+        layered = true;
+        ring_depth = depth;
       }
-      attention(kl, vl);
-      {
-        GemmArgs g = base(EPI_RESID, attn_out, pan_q, nullptr, 0, qd, c.hidden);
-        g.seg[0] = {m->p_wo[l], c.hidden, 0};
-        g.n_seg = 1;
-        resid(g, m->norm_ffn[l], ss1);
-        o_tiles = g.n_tiles;
-        TimedLaunch tl(opts->timer, TRISPEC_K_GEMM, st, (double)c.hidden * qd * es);
-        launch_gemm(st, g);
+      if (layered) {
+        auto items = [](const SplitPlan &p) { return p.n_tiles * p.n_splits; };
+        lgrid = items(lq);
+        if (items(lo) > lgrid) lgrid = items(lo);
+        if (items(lg) > lgrid) lgrid = items(lg);
+        if (items(ld) > lgrid) lgrid = items(ld);
       }
-      {
-        GemmArgs g = base(EPI_SWIGLU, h, pan_h, ss1, o_tiles, c.hidden, 2 * c.ffn);
-        g.seg[0] = {m->p_gate[l], c.ffn, 0};
-        g.seg[1] = {m->p_up[l], c.ffn, c.ffn};
-        g.n_seg = 2;
-        g.act_out = act; g.ffn = c.ffn; g.out_panel = pan_f;
-        TimedLaunch tl(opts->timer, TRISPEC_K_GEMM, st, 2.0 * c.ffn * c.hidden * es);
-        launch_gemm(st, g);
+    }
+
+    if (!layered) {
+      int ss0_tiles = 1;
+      for (int l = 0; l < c.n_layers; ++l) {
+        char *kl = (char *)kv->k + (size_t)l * kv_layer, *vl = (char *)kv->v + (size_t)l * kv_layer;
+        timed_gemm(mk_qkv(l, pq, ss0_tiles), b_qkv);
+        attention(kl, vl);
+        timed_gemm(mk_o(l, po, x, x, h), b_o);
+        timed_gemm(mk_gu(l, pg, h), b_gu);
+        timed_gemm(mk_dn(l, pd, x, x), b_dn);
+        ss0_tiles = hid_tiles;
       }
-      {
-        GemmArgs g = base(EPI_RESID, act, pan_f, nullptr, 0, c.ffn, c.hidden);
-        g.seg[0] = {m->p_down[l], c.hidden, 0};
-        g.n_seg = 1;
-        resid(g, (l + 1 < c.n_layers) ? m->norm_attn[l + 1] : m->final_norm, ss0);
-        ss0_tiles = g.n_tiles;
-        TimedLaunch tl(opts->timer, TRISPEC_K_GEMM, st, (double)c.hidden * c.ffn * es);
-        launch_gemm(st, g);
+    } else {
+      timed_gemm(mk_qkv(0, pq, 1), b_qkv);
+      for (int l = 0; l < c.n_layers; ++l) {
+        char *kl = (char *)kv->k + (size_t)l * kv_layer, *vl = (char *)kv->v + (size_t)l * kv_layer;
+        attention(kl, vl);
+        LayerArgs la;
+        memset(&la, 0, sizeof(la));
+        const bool more = l + 1 < c.n_layers;
+        la.n_phases = more ? 4 : 3;
+        la.ring_depth = ring_depth;
+        la.ph[0] = mk_o(l, lo, x, x2, h2);
+        la.ph[1] = mk_gu(l, lg, h2);
+        la.ph[2] = mk_dn(l, ld, x2, x);
+        if (more) la.ph[3] = mk_qkv(l + 1, lq, hid_tiles);
+        for (int p = 0; p < kLayerPhases; ++p) la.ph[p].part = part + (size_t)p * L.part_phase;
+        la.bar = counters + L.bar_index + kLayerPhases * l;
+        la.abort_word = counters + L.abort_index;
+        la.status = status;
+        la.spin_limit = g_spin_limit;
+        la.stamps = opts->stamps ? (unsigned long long *)opts->stamps + (size_t)16 * l : nullptr;
+        la.stamp_wg = 0;
+        la.poll_naps = 1;
+        TimedLaunch tl(opts->timer, TRISPEC_K_GEMM, st, b_o + b_gu + b_dn + (more ? b_qkv : 0.0));
+        if (!launch_layer_bf16(st, la, lgrid)) return TRISPEC_ELAUNCH;
       }
     }
     {
-      GemmArgs g = base(EPI_HEAD, h, pan_h, ss0, ss0_tiles, c.hidden, c.vocab);
+      GemmArgs g = base(EPI_HEAD, h, pan_h, ss0, hid_tiles, c.hidden, c.vocab, plan_gemm(EPI_HEAD, c.vocab, c.hidden, rp));
       g.seg[0] = {m->p_lm_head, c.vocab, 0};
       g.n_seg = 1;
       hs.n_tiles = g.n_tiles;
       g.hs = hs;
       g.debug_logits = opts->debug_logits;
       TimedLaunch tl(opts->timer, TRISPEC_K_HEAD, st, (double)c.vocab * c.hidden * es);
-      launch_gemm(st, g);
+      launch_gemm_bf16(st, g);
     }
     if (opts->hidden_out)   // x after the last layer, the final norm's weight, the sums of squares the last down projection left
-      launch_export_hidden(st, c.dtype, x, m->final_norm, ss0, ss0_tiles, rows, rp, c.hidden, c.rms_eps,
+      launch_export_hidden(st, c.dtype, x, m->final_norm, ss0, hid_tiles, rows, rp, c.hidden, c.rms_eps,
                            opts->hidden_out);
   }
 
@@ -912,6 +1036,19 @@ int trispec_kv_commit(trispec_kv *kv, const int32_t *nodes_host, const int32_t *
   }
   for (int b = 0; b < kv->batch; ++b) kv->ctx_len[b] += t.n[b];
   return TRISPEC_OK;
+}
+
+int trispec_debug_set_spin_limit(uint64_t ticks) {
+  g_spin_limit = ticks ? ticks : 200000000ull;
+  return TRISPEC_OK;
+}
+
+int trispec_wait_probe(int32_t *counter_dev, int32_t expect, uint64_t limit_ticks, int32_t *abort_dev,
+                       int32_t *status_dev, void *stream) {
+  if (!counter_dev || !abort_dev || !status_dev) return TRISPEC_ENULL;
+  (void)hipGetLastError();
+  launch_wait_probe((hipStream_t)stream, counter_dev, expect, limit_ticks, abort_dev, status_dev);
+  return hipGetLastError() == hipSuccess ? TRISPEC_OK : TRISPEC_ELAUNCH;
 }
 
 int trispec_copy_probe(void *dst_dev, const void *src_dev, size_t bytes, void *stream) {

@@ -40,6 +40,80 @@ __device__ __forceinline__ void st_agent(float *p, float v) {
 __device__ __forceinline__ float ld_agent(const float *p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// 8- and 16-byte forms: a vector is moved as 64-bit agent-scope pieces (the widest scalar the
+// atomic builtins take), so each piece still writes through / bypasses the per-XCD L2.
+__device__ __forceinline__ void st_agent_u64(void *p, uint64_t v) {
+  __hip_atomic_store((uint64_t *)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint64_t ld_agent_u64(const void *p) {
+  return __hip_atomic_load((const uint64_t *)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ f32x4 ld_agent_f32x4(const float *p) {
+  union { uint64_t u[2]; f32x4 v; } t;
+  t.u[0] = ld_agent_u64(p);
+  t.u[1] = ld_agent_u64(p + 2);
+  return t.v;
+}
+// Stores of a kernel's results.  WT = false: plain stores (the end of the kernel makes them
+// visible).  WT = true: write-through, for results that another workgroup of the SAME launch reads
+// after a device-side barrier.
+template <bool WT>
+__device__ __forceinline__ void store_f32x4(float *p, f32x4 v) {
+  if constexpr (WT) {
+    union { uint64_t u[2]; f32x4 v; } t;
+    t.v = v;
+    st_agent_u64(p, t.u[0]);
+    st_agent_u64(p + 2, t.u[1]);
+  } else {
+    *(f32x4 *)p = v;
+  }
+}
+template <bool WT>
+__device__ __forceinline__ void store_bf16x4(bf16 *p, bf16x4 v) {
+  if constexpr (WT) {
+    union { uint64_t u; bf16x4 v; } t;
+    t.v = v;
+    st_agent_u64(p, t.u);
+  } else {
+    *(bf16x4 *)p = v;
+  }
+}
+template <bool WT>
+__device__ __forceinline__ void store_f32(float *p, float v) {
+  if constexpr (WT) st_agent(p, v);
+  else *p = v;
+}
+
+// Device-side barrier between the phases of one launch (every workgroup of the grid is resident:
+// the host checks that before it chooses such a kernel).  bar_arrive: called by every thread after
+// its write-through stores; the stores are acknowledged before the counter moves.  bar_wait:
+// thread 0 polls until `expect` workgroups have arrived, for at most `limit` ticks of the 100 MHz
+// wall clock; on expiry it raises the sticky abort word (later waits return at once) and bit 2 of
+// the status word, and the kernel carries on to its normal end with meaningless results.
+constexpr int kStatusWaitExpired = 4;
+__device__ __forceinline__ void bar_arrive(int32_t *counter) {
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+  if (threadIdx.x == 0) __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void bar_wait(const int32_t *counter, int expect, unsigned long long limit,
+                                         int32_t *abort_word, int32_t *status, int naps = 1) {
+  if (threadIdx.x == 0) {
+    const unsigned long long t0 = wall_clock64();
+    if (__hip_atomic_load(abort_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) {
+      while (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < expect) {
+        for (int i = 0; i < naps; ++i) __builtin_amdgcn_s_sleep(8);
+        if (wall_clock64() - t0 > limit) {
+          __hip_atomic_store(abort_word, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          atomicOr(status, kStatusWaitExpired);
+          break;
+        }
+      }
+    }
+  }
+  __syncthreads();
+}
+
 // Called by every thread of the workgroup after its st_agent stores.  Returns (to all threads)
 // whether this workgroup was the `expected`-th, i.e. last, to arrive; the counter is reset by the
 // last arriver so that it is zero again for the next launch.

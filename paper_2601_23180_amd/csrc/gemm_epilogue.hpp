@@ -51,13 +51,20 @@ __device__ __forceinline__ void rstd_finish(const GemmArgs &a, const float (&x)[
   }
 }
 
+template <int N>
+struct SplitGroup {
+  static constexpr int value = N;
+};
+
 // Epilogue of one (tile, split).  A wavefront owns NB adjacent 32-column sub-tiles of the tile:
 // acc[nb][mb][e] of lane (ln, g) of wavefront `wave` holds
 //   y[mb*32 + 8*(e/4) + 4*g + e%4][(wave*NB + nb)*32 + ln].
 // The reduced fp32 tile goes through LDS in groups of MG 32-row blocks (MG = MB when the whole
 // tile fits).  lds: at least MG*32*(TN+4)*4 bytes, free for reuse (every wavefront has passed a
 // barrier after its last operand read).  s_rs: 1/rms per input row.
-template <int MB, int EPI, int NW, int NB = 1, int MG = MB>
+// WT: the results that a later PHASE of the same launch reads (residual stream, operand panels,
+// sums of squares) are written through to memory; false for a kernel whose consumer is a later launch.
+template <int MB, int EPI, int NW, int NB = 1, int MG = MB, bool WT = false>
 __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, f32x16 (&acc)[NB][MB], unsigned char *lds,
                                               int *s_last, const float *s_rs, int tile, int split) {
   constexpr int TN = NW * NB * 32, NT = NW * 64;
@@ -171,39 +178,53 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, f32x16 (&acc)[N
           }
     } else {
       // Last workgroup of the tile: sum the splits, in ascending order.  The partial tiles were
-      // written through to memory (st_agent) and nobody on this chip has read these lines before,
-      // so plain vector loads see them.  A memory round trip costs far more than the additions, so
-      // the loads of two splits (UB vectors each) are in flight together.
+      // written through to memory (st_agent) by workgroups anywhere on the chip and are read here
+      // with plain vector loads, which may be served by this XCD's L2.  That is correct because a
+      // line of the partial buffer cannot be in this L2 from before it was written: every launch
+      // starts with the invalidation of the L2s that makes a kernel see its predecessors' results
+      // at all on this multi-XCD chip, and inside one launch a partial line is read only here, by
+      // the one workgroup that combines its tile, after the counter says all of it is written (a
+      // launch that runs several matmuls gives each its own partial region for the same reason).
+      // Agent-scope loads would not need that argument, but they exist only up to 8 bytes and,
+      // measured, cost 0.15 ms per pass here.
+      // Every load of up to SG splits (UB vectors each) is in flight before the first addition: the
+      // reduction then costs one or two memory round trips, not one per pair of splits — it is the
+      // longest link of the serial chain that ends a matmul.
       constexpr int PER = MG * 32 * (TN / 4) / NT;   // 4-column vectors per thread
-      constexpr int UB = PER < 8 ? PER : 8;
+      constexpr int UB = PER < 4 ? PER : 4;
       const float *p0 = a.part + (size_t)tile * tile_elems + (size_t)row0 * TN + (size_t)tid * 4;
       const size_t split_stride = (size_t)a.n_tiles * tile_elems;
+      auto reduce_groups = [&](auto sg_c) {
+        constexpr int SG = decltype(sg_c)::value;
 #pragma unroll 1
-      for (int ub = 0; ub < PER; ub += UB) {
-        f32x4 sum[UB];
+        for (int ub = 0; ub < PER; ub += UB) {
+          f32x4 sum[UB];
+#pragma unroll 1
+          for (int s0 = 0; s0 < a.n_splits; s0 += SG) {
+            f32x4 v[SG][UB];
 #pragma unroll
-        for (int u = 0; u < UB; ++u) sum[u] = *(const f32x4 *)(p0 + (size_t)(ub + u) * NT * 4);
-        for (int s = 1; s < a.n_splits; s += 2) {
-          const bool two = s + 1 < a.n_splits;
-          const float *pa = p0 + (size_t)s * split_stride, *pb = pa + (two ? split_stride : 0);
-          f32x4 va[UB], vb[UB];
+            for (int q = 0; q < SG; ++q) {
+              const float *ps = p0 + (size_t)min(s0 + q, a.n_splits - 1) * split_stride;
 #pragma unroll
-          for (int u = 0; u < UB; ++u) {
-            va[u] = *(const f32x4 *)(pa + (size_t)(ub + u) * NT * 4);
-            vb[u] = *(const f32x4 *)(pb + (size_t)(ub + u) * NT * 4);
+              for (int u = 0; u < UB; ++u) v[q][u] = *(const f32x4 *)(ps + (size_t)(ub + u) * NT * 4);
+            }
+#pragma unroll
+            for (int q = 0; q < SG; ++q)
+#pragma unroll
+              for (int u = 0; u < UB; ++u) {
+                if (s0 + q == 0) sum[u] = v[q][u];
+                else if (s0 + q < a.n_splits) sum[u] += v[q][u];
+              }
           }
 #pragma unroll
           for (int u = 0; u < UB; ++u) {
-            sum[u] += va[u];
-            if (two) sum[u] += vb[u];
+            const int idx = tid + (ub + u) * NT, r = idx / (TN / 4), c = (idx % (TN / 4)) * 4;
+            *(f32x4 *)(tl + r * EPI_LD + c) = sum[u];
           }
         }
-#pragma unroll
-        for (int u = 0; u < UB; ++u) {
-          const int idx = tid + (ub + u) * NT, r = idx / (TN / 4), c = (idx % (TN / 4)) * 4;
-          *(f32x4 *)(tl + r * EPI_LD + c) = sum[u];
-        }
-      }
+      };
+      if (a.n_splits <= 4) reduce_groups(SplitGroup<4>{});
+      else reduce_groups(SplitGroup<8>{});
     }
     __syncthreads();
     auto reduced4 = [&](int lr, int c) {   // 4 consecutive columns of row (row0 + lr) of the reduced tile
@@ -285,8 +306,8 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, f32x16 (&acc)[N
           lo[e] = (bf16)(o - (float)hi[e]);
         }
         bf16 *dst = (bf16 *)a.act_out;   // operand layout of the down projection (K = ffn)
-        *(bf16x4 *)(dst + ol_offset(r, feat, 0, MB)) = hi;
-        *(bf16x4 *)(dst + ol_offset(r, feat, 1, MB)) = lo;
+        store_bf16x4<WT>(dst + ol_offset(r, feat, 0, MB), hi);
+        store_bf16x4<WT>(dst + ol_offset(r, feat, 1, MB), lo);
       }
     } else {
       // ---- EPI_RESID: x += y; per-row sum of squares of the new x over this tile's columns.
@@ -316,7 +337,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, f32x16 (&acc)[N
           ss[u] = 0.f;
           if (r < a.rows && col_ok) {
             const f32x4 v = xv[u] + reduced4(lr, c);
-            *(f32x4 *)(a.x_resid + (size_t)r * a.n_total + col) = v;
+            store_f32x4<WT>(a.x_resid_out + (size_t)r * a.n_total + col, v);
             ss[u] = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
             // operand of the next matmul: x * (next RMSNorm weight), as bf16 hi + lo
             bf16x4 hi, lo;
@@ -327,8 +348,8 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, f32x16 (&acc)[N
               lo[e] = (bf16)(o - (float)hi[e]);
             }
             bf16 *dst = (bf16 *)a.xw_out;   // operand layout of the next matmul (K = hidden)
-            *(bf16x4 *)(dst + ol_offset(r, col, 0, MB)) = hi;
-            *(bf16x4 *)(dst + ol_offset(r, col, 1, MB)) = lo;
+            store_bf16x4<WT>(dst + ol_offset(r, col, 0, MB), hi);
+            store_bf16x4<WT>(dst + ol_offset(r, col, 1, MB), lo);
           }
         }
         // the UB row sums are reduced side by side, so the exchanges of one hide behind the others'
@@ -339,7 +360,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, f32x16 (&acc)[N
 #pragma unroll
         for (int u = 0; u < UB; ++u) {
           const int r = row0 + r0 + (ub + u) * RPP;
-          if (tid % LPR == 0 && r < a.rows) ssp[r] = ss[u];   // read by the next kernel
+          if (tid % LPR == 0 && r < a.rows) store_f32<WT>(ssp + r, ss[u]);   // read by the next matmul
         }
       }
     }

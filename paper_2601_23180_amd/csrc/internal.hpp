@@ -83,7 +83,8 @@ struct GemmArgs {
   CtxLens ctx;
   int32_t n_nodes, n_q_heads, n_kv_heads, head_dim, capacity;
   // RESID epilogue
-  float *x_resid;      // [rows_pad][n_total] residual stream, updated in place
+  const float *x_resid;  // [rows_pad][n_total] residual stream before this matmul
+  float *x_resid_out;  // the same after it (may be x_resid itself: every element is read and written by one thread)
   void *xw_out;        // bf16 hi/lo panels [rows_pad][n_total]: x * next norm weight
   const void *next_norm_w;  // bf16 [n_total]
   float *ss_part;      // [n_tiles][rows_pad] sums of squares of the updated rows, per tile
@@ -96,6 +97,29 @@ struct GemmArgs {
   HeadStats hs;
   float *debug_logits;
 };
+
+// The matmuls between two attention calls as phases of one launch (kernels_layer.hip): O
+// projection, gate + up, down projection and, unless this is the last layer, the next layer's QKV.
+constexpr int kLayerPhases = 4;
+struct LayerArgs {
+  GemmArgs ph[kLayerPhases];
+  int32_t n_phases;               // 3 or 4
+  int32_t ring_depth;             // 8 or 4 weight chunks in flight per wavefront (see layer_step)
+  int32_t *bar;                   // [n_phases] arrival counters of this launch, zero at its start
+  int32_t *abort_word;            // sticky: a wait has expired somewhere in this pass
+  int32_t *status;                // status word of the pass
+  unsigned long long spin_limit;  // longest wait at a barrier, in ticks of the 100 MHz wall clock
+  unsigned long long *stamps;     // optional [16]: wall clock of workgroup stamp_wg at the phase boundaries
+  int32_t stamp_wg;
+  int32_t poll_naps;              // naps of 512 clocks between two polls of a barrier counter
+};
+// k granularity of a (tile, split) item of the layer kernel: ring depth x chunk depth
+inline int layer_step(int rows_pad, int ring_depth) { return ring_depth * (rows_pad <= 64 ? 128 : 64); }
+int layer_kernel_max_grid(const LayerArgs &la);
+bool launch_layer_bf16(hipStream_t st, const LayerArgs &la, int grid);
+// `counter` never reaches `expect`: one workgroup waits `limit` ticks, then reports (test hook)
+void launch_wait_probe(hipStream_t st, int32_t *counter, int expect, unsigned long long limit,
+                       int32_t *abort_word, int32_t *status);
 
 struct AttnArgs {
   const void *q;        // fp32 path: [rows_pad, nq*d] fp32 queries; bf16 path: bf16 hi panel, lo q_panel later
@@ -158,7 +182,7 @@ struct DecideArgs {
 // ---- launchers (one per kernel family); all enqueue on `st` and return nothing:
 // the caller checks hipGetLastError once at the end of the pass.
 void launch_setup(hipStream_t st, const NodeTable &tab, int rows, uint64_t *anc, int32_t *parent,
-                  int32_t *status);
+                  int32_t *status, int32_t *zero, int n_zero);
 void launch_rope_table(hipStream_t st, const int32_t *positions, int rows, int head_dim, float base,
                        float *cos_t, float *sin_t);
 void launch_embed_norm(hipStream_t st, int dtype, const int32_t *tokens, const void *embed,

@@ -57,7 +57,10 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(GemmArgs a) {
   __shared__ float s_rs[kMaxRows];   // 1/rms of the rows of the matmul's input
   __shared__ float s_rsp[4 * kMaxRows];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  // scalar: what is selected by it (this wavefront's weight segment) is then fetched with scalar
+  // loads from the kernel arguments, not with a vector load that the first weight request waits for
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int ln = lane & 31, g = lane >> 5;
   const int tile = blockIdx.x, split = blockIdx.y;
   const int k_begin = split * a.k_per_split;

@@ -7,18 +7,32 @@
 namespace ts {
 
 // ------------------------------------------------------------------ set-up
-__global__ void k_setup(NodeTable tab, int rows, uint64_t *anc, int32_t *parent, int32_t *status) {
+// Also clears `zero[0 .. n_zero)`: the tile counters of the split-K matmuls and the barrier
+// counters / abort word of the layer kernels, which must be zero when the pass starts.
+__global__ void k_setup(NodeTable tab, int rows, uint64_t *anc, int32_t *parent, int32_t *status, int32_t *zero,
+                        int n_zero) {
   const int i = threadIdx.x;
   if (i < rows) {
     anc[i] = tab.anc[i];
     parent[i] = tab.parent[i];
   }
   if (i == 0) *status = 0;
+  for (int j = i; j < n_zero; j += kMaxRows) zero[j] = 0;
 }
 
 void launch_setup(hipStream_t st, const NodeTable &tab, int rows, uint64_t *anc, int32_t *parent,
-                  int32_t *status) {
-  hipLaunchKernelGGL(k_setup, dim3(1), dim3(kMaxRows), 0, st, tab, rows, anc, parent, status);
+                  int32_t *status, int32_t *zero, int n_zero) {
+  hipLaunchKernelGGL(k_setup, dim3(1), dim3(kMaxRows), 0, st, tab, rows, anc, parent, status, zero, n_zero);
+}
+
+__global__ void k_wait_probe(int32_t *counter, int expect, unsigned long long limit, int32_t *abort_word,
+                             int32_t *status) {
+  bar_wait(counter, expect, limit, abort_word, status);
+}
+
+void launch_wait_probe(hipStream_t st, int32_t *counter, int expect, unsigned long long limit,
+                       int32_t *abort_word, int32_t *status) {
+  hipLaunchKernelGGL(k_wait_probe, dim3(1), dim3(64), 0, st, counter, expect, limit, abort_word, status);
 }
 
 // angle[r][j] = position_r * base^(-2j/d), evaluated in fp64 so that large positions keep

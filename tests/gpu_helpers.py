@@ -43,7 +43,7 @@ class Case:
         return outs
 
     def run_gpu(self, threshold, criterion=CRIT_MARGIN, n_forced=1, model=None, want_logits=True,
-                export_hidden=False):
+                export_hidden=False, launch_mode=0):
         model = model or device_model(self.shape, self.seed)
         cap = capacity_for(max(self.ctx_len) + self.n_nodes)
         kv = KVCache(model, self.batch, cap)
@@ -58,6 +58,7 @@ class Case:
                 kv.v[l, b, :, :, :C] = vt.transpose(-1, -2)
         kv.set_len(self.ctx_len)
         ver = Verifier(model, self.batch, self.n_nodes, debug_logits=want_logits, export_hidden=export_hidden)
+        ver.launch_mode = launch_mode
         tok = torch.from_numpy(self.tokens).cuda()
         pos = torch.from_numpy(self.positions).cuda()
         out = ver.verify(kv, tok, self.parents, pos, threshold, criterion, n_forced)

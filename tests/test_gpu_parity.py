@@ -66,9 +66,9 @@ def plant_paths(case, leaves):
             case.tokens[b][c] = node_stats(lg)["argmax"][a]
 
 
-def full_check(case, thresholds=(0.0, 0.3, 0.5, 0.9, 1.5), n_forced=1):
+def full_check(case, thresholds=(0.0, 0.3, 0.5, 0.9, 1.5), n_forced=1, launch_mode=0):
     oracle_out = case.run_oracle()
-    gpu = case.run_gpu(thresholds[0], CRIT_MARGIN, n_forced)
+    gpu = case.run_gpu(thresholds[0], CRIT_MARGIN, n_forced, launch_mode=launch_mode)
     assert gpu["status"][0] == 0
     for b in range(case.batch):
         logits_ok(case.shape, gpu["logits"][b], oracle_out[b]["logits"])
@@ -146,6 +146,16 @@ BF16_CASES = [
      lambda s: gen_tree(50, 8, 4, s)),
     ("rows240_hidden1024_splits", TB.with_(n_layers=1, hidden=1024, ffn=1024, vocab=4001, lm_head_std=6.5 / 32),
      [40, 0, 129, 77], lambda s: gen_tree(60, 8, 4, s)),
+    # widths that the one-launch-per-layer kernel takes (every reduction a multiple of its step:
+    # 1024 at up to 32 rows, 512 at up to 64, 256 at up to 128), with and without k splits
+    ("layer_rows60_three_layers", TB.with_(n_layers=3, hidden=512, ffn=1024, lm_head_std=6.5 / 22.6), [90],
+     lambda s: gen_tree(60, 8, 4, s)),
+    ("layer_rows60_k_splits", TB.with_(n_layers=2, hidden=1024, ffn=2048, n_q_heads=8, lm_head_std=6.5 / 32), [150],
+     lambda s: gen_tree(60, 8, 4, s)),
+    ("layer_rows9_chain", TB.with_(n_layers=2, hidden=1024, ffn=2048, n_q_heads=8, lm_head_std=6.5 / 32), [70],
+     lambda s: gen_chain(9)),
+    ("layer_rows90_batch3", TB.with_(n_layers=2, hidden=768, ffn=1280, n_q_heads=6, n_kv_heads=2, lm_head_std=6.5 / 27.7),
+     [33, 0, 101], lambda s: gen_tree(30, 6, 4, s)),
 ]
 
 
@@ -156,13 +166,98 @@ def test_bf16_small_models(name, shape, ctx_lens, tree):
     depth = [tree_depths(p) for p in parents]
     plant = [(int(np.argmax(d)), min(3, int(d.max()))) for d in depth]
     case = make_case(shape, seed, ctx_lens, parents, plant=plant)
-    gpu, oracle_out, excused = full_check(case)
+    # the cases named layer_* (and two older ones of fitting widths) go through the one-launch-per-layer
+    # cut, with its phase stamps as the proof that it ran; everything else through the default cut
+    per_layer = name.startswith("layer_") or name in ("wide_hidden1024", "rows100_hidden1024_splits")
+    gpu, oracle_out, excused = full_check(case, launch_mode=1 if per_layer else 0)
+    if per_layer:
+        ver, kv = gpu["_ver"], gpu["_kv"]
+        ver.stamps = torch.zeros((shape.n_layers, 16), dtype=torch.int64, device="cuda")
+        ver.verify(kv, gpu["_tok"], case.parents, torch.from_numpy(case.positions).cuda(), 0.0)
+        torch.cuda.synchronize()
+        assert bool((ver.stamps[:, :10] > 0).all()), "the per-layer launch did not run"
+        ver.stamps = None
     # the planted prefix is accepted at lambda = 0
     out = gpu["_ver"].decide(gpu["_tok"], case.parents, 0.0, CRIT_MARGIN)
     torch.cuda.synchronize()
     for b in range(case.batch):
         assert out["accepted_len"][b].item() >= plant[b][1] or excused
         assert out["accepted_len"][b].item() <= depth[b].max()
+
+
+LAYER_SHAPE = TB.with_(n_layers=2, hidden=1024, ffn=2048, n_q_heads=8, lm_head_std=6.5 / 32)
+
+
+def test_one_launch_per_layer_and_one_per_matmul_agree():
+    """The same pass cut into launches both ways: same arithmetic up to the order of the k splits."""
+    from paper_2601_23180_amd.binding import LAUNCH_PER_LAYER, LAUNCH_PER_MATMUL
+    case = make_case(LAYER_SHAPE, 77, [120], [gen_tree(60, 8, 4, 77)])
+    oracle_out = case.run_oracle()
+    gpu = case.run_gpu(0.3)
+    ver, kv, tok = gpu["_ver"], gpu["_kv"], gpu["_tok"]
+    pos = torch.from_numpy(case.positions).cuda()
+    stamps = torch.zeros((LAYER_SHAPE.n_layers, 16), dtype=torch.int64, device="cuda")
+    ver.stamps = stamps
+    res = {}
+    for mode in (LAUNCH_PER_LAYER, LAUNCH_PER_MATMUL):
+        stamps.zero_()
+        ver.launch_mode = mode
+        ver.verify(kv, tok, case.parents, pos, 0.3)
+        torch.cuda.synchronize()
+        assert ver.out["status"].item() == 0
+        res[mode] = (ver.logits.cpu().numpy().copy(), {k: v.cpu().numpy().copy() for k, v in ver.out.items()})
+        logits_ok(case.shape, res[mode][0][0], oracle_out[0]["logits"])
+        compare_decisions(case, res[mode][1], oracle_out, 0.3, CRIT_MARGIN)
+        st = stamps.cpu().numpy()
+        if mode == LAUNCH_PER_LAYER:   # the layer launches really ran: their phase stamps are there, in order
+            assert np.all(st[0, :13] > 0) and np.all(np.diff(st[0, :13]) >= 0)
+            assert np.all(st[1, :10] > 0) and np.all(st[1, 10:] == 0)      # last layer: three phases
+        else:
+            assert np.all(st == 0)
+    assert np.abs(res[LAUNCH_PER_LAYER][0] - res[LAUNCH_PER_MATMUL][0]).max() <= 1e-3
+
+
+def test_layer_launch_is_repeatable_bit_for_bit():
+    case = make_case(LAYER_SHAPE, 78, [64], [gen_tree(60, 8, 4, 78)])
+    gpu = case.run_gpu(0.4, launch_mode=1)
+    ver, kv, tok = gpu["_ver"], gpu["_kv"], gpu["_tok"]
+    pos = torch.from_numpy(case.positions).cuda()
+    logits = ver.logits.clone()
+    first = {k: v.clone() for k, v in ver.out.items()}
+    for _ in range(20):
+        ver.verify(kv, tok, case.parents, pos, 0.4)
+        torch.cuda.synchronize()
+        assert torch.equal(ver.logits, logits)
+        for k, v in ver.out.items():
+            assert torch.equal(v, first[k]), k
+
+
+def test_bounded_wait_gives_up_and_reports():
+    """The wait of the device-side barrier, driven from the host: the counter is never raised, so the
+    workgroup must give up after its limit, raise the abort word and status bit 2, and end normally;
+    with the abort word already raised it must not wait at all."""
+    import ctypes as C
+    import time
+    from paper_2601_23180_amd import binding as B
+    lib = B.lib()
+    buf = torch.zeros(4, dtype=torch.int32, device="cuda")     # counter, abort, status
+    p = buf.data_ptr()
+    st = torch.cuda.current_stream().cuda_stream
+    t0 = time.perf_counter()
+    assert lib.trispec_wait_probe(p, 5, 2_000_000, p + 4, p + 8, st) == 0     # 20 ms
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    assert buf.tolist()[:3] == [0, 1, 4]
+    assert 0.015 <= dt < 2.0, dt
+    t0 = time.perf_counter()
+    assert lib.trispec_wait_probe(p, 5, 100_000_000, p + 4, p + 8, st) == 0   # would be 1 s
+    torch.cuda.synchronize()
+    assert time.perf_counter() - t0 < 0.5
+    buf.zero_()
+    buf[0] = 5                                                               # already satisfied: no report
+    assert lib.trispec_wait_probe(p, 5, 2_000_000, p + 4, p + 8, st) == 0
+    torch.cuda.synchronize()
+    assert buf.tolist()[:3] == [5, 0, 0]
 
 
 def test_cache_append_matches_oracle_rounding():
