@@ -153,6 +153,32 @@ int trispec_kv_destroy(trispec_kv *kv);
 int trispec_kv_commit(trispec_kv *kv, const int32_t *nodes_host, const int32_t *n_commit_host,
                       void *stream);
 
+/*
+ * Case II hand-over (Sec. 3.2 (ii), Eq. 10; Algorithm 1's target call): the input of the target
+ * pass after the proxy approved path = [v_0 .. v_tau_m] of its draft tree.  Host integers only, no
+ * GPU work.  The target has no KV for the approved tokens yet, so they stay in the input as a
+ * forced chain; of the draft tree only the subtree below v_tau_m survives (the target conditions
+ * on x_1..x_tau_m and verifies the rest); every other branch is dropped.  Tokens that earlier
+ * rounds emitted without running the target (Case I rounds) and that the target therefore has not
+ * cached either go in front as `prefix`, at positions prefix_pos0, prefix_pos0 + 1, ...
+ *   tokens, parents, positions  HOST [n_nodes]: the proxy pass's tree (parents[0] = -1, parents[i] < i)
+ *   path                        HOST [path_len]: node ids v_0 = 0 .. v_tau_m, each the parent of the next
+ *                               (trispec_verify's `path` output, accepted_len + 1 entries)
+ *   prefix_tokens               HOST [n_prefix] (may be NULL when n_prefix = 0)
+ * Outputs, HOST arrays of TRISPEC_MAX_NODES entries each: the new tokens / parents / positions in
+ * the order prefix, path, subtree (ascending old id); old_id = the proxy-tree node of every entry
+ * (-1 for prefix entries); *out_n_nodes; *out_n_forced = n_prefix + path_len, the n_forced of the
+ * target's trispec_verify call.
+ * Errors: TRISPEC_ENULL, TRISPEC_ENODES (n_nodes out of range, or more than TRISPEC_MAX_NODES
+ * entries result: ingest the prefix by plain passes first), TRISPEC_ETREE (parents not a
+ * topologically ordered tree, or path not a root path), TRISPEC_EARG (negative counts).
+ */
+int trispec_prune_reroot(const int32_t *tokens, const int32_t *parents, const int32_t *positions,
+                         int32_t n_nodes, const int32_t *path, int32_t path_len,
+                         const int32_t *prefix_tokens, int32_t n_prefix, int32_t prefix_pos0,
+                         int32_t *out_tokens, int32_t *out_parents, int32_t *out_positions,
+                         int32_t *out_old_id, int32_t *out_n_nodes, int32_t *out_n_forced);
+
 /* Device scratch needed by trispec_verify for up to `batch` sequences of up to
  * `max_nodes` nodes (256-byte aligned buffer).  Errors: TRISPEC_ENULL, TRISPEC_ENODES. */
 int trispec_workspace_bytes(const trispec_model *m, int32_t batch, int32_t max_nodes,
@@ -234,7 +260,8 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
  * last trispec_verify left in this workspace — threshold / criterion sweeps.
  * batch / n_nodes / workspace must be those of that verify call (the statistics are found
  * by offset); calling it on a workspace no verify has filled yields unspecified decisions.
- * Same argument meaning and host-side errors as trispec_verify.
+ * draft_tokens and tree_parents are those of THIS call: the walk may run over other drafts than
+ * the pass did (same number of nodes).  Same argument meaning and host-side errors as trispec_verify.
  */
 int trispec_decide(trispec_model *m, int32_t batch, const int32_t *draft_tokens,
                    const int32_t *tree_parents, int32_t n_nodes, float threshold,

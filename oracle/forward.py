@@ -109,7 +109,8 @@ def _lm_head(h: np.ndarray, W: OracleWeights, vocab: int) -> np.ndarray:
 
 def causal_forward(W: OracleWeights, shape, tokens: Sequence[int],
                    positions: Optional[Sequence[int]] = None,
-                   last_only: bool = False, n_cached: int = 0) -> Dict[str, np.ndarray]:
+                   last_only: bool = False, n_cached: int = 0,
+                   in_pass_kv: str = "unrounded") -> Dict[str, np.ndarray]:
     """Plain causal decoder forward over tokens[0..T-1].
 
     Returns logits [T, V] (or [1, V] for the last row if last_only), and the
@@ -120,7 +121,14 @@ def causal_forward(W: OracleWeights, shape, tokens: Sequence[int],
     were processed by an earlier pass, so queries at t >= n_cached see those keys /
     values as the cache holds them (rounded); every other (query, key) pair belongs to
     one pass and uses unrounded values.  With f32 storage it has no effect.
+
+    in_pass_kv = "stored" is the other reading of a bf16 cache: every key / value attention
+    reads, the query's own included, is the stored (rounded) one — a decoder that appends to
+    its cache before it attends.  n_cached is then immaterial.  (The paper fixes neither; the
+    build's reading is "unrounded", and tests bound the difference between the two.)
     """
+    if in_pass_kv not in ("unrounded", "stored"):
+        raise ValueError(in_pass_kv)
     rnd = bf16_round if shape.dtype == "bf16" else _identity
     T = len(tokens)
     H, nq, nkv, d = shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim
@@ -142,6 +150,8 @@ def causal_forward(W: OracleWeights, shape, tokens: Sequence[int],
         o = np.zeros((T, nq, d))
         for t in range(T):
             nc = n_cached if t >= n_cached else 0     # keys this query reads back from the cache
+            if in_pass_kv == "stored":
+                nc = t + 1
             kt = np.concatenate([rnd(k[:nc]), k[nc: t + 1]], axis=0)
             vt = np.concatenate([rnd(v[:nc]), v[nc: t + 1]], axis=0)
             for a in range(nq):
@@ -177,7 +187,8 @@ def ancestor_sets(parents: Sequence[int]) -> List[List[int]]:
 
 def verify_forward(W: OracleWeights, shape, k_ctx, v_ctx, tokens: Sequence[int],
                    parents: Sequence[int], positions: Sequence[int],
-                   keep_hidden: bool = False, trace: Optional[list] = None) -> Dict[str, np.ndarray]:
+                   keep_hidden: bool = False, trace: Optional[list] = None,
+                   in_pass_kv: str = "unrounded") -> Dict[str, np.ndarray]:
     """One verification pass (Eq. 2 / Eq. 5): the M tree nodes against a cache.
 
     k_ctx, v_ctx: either arrays [L, n_kv, C, d] or callables layer -> [n_kv, C, d]
@@ -190,7 +201,11 @@ def verify_forward(W: OracleWeights, shape, k_ctx, v_ctx, tokens: Sequence[int],
     is a list, one dict of intermediates per layer is appended to it (q, k, v as fed to
     attention, the unrounded attention output o, the residual stream after attention and
     after the FFN, the SiLU(gate)*up product).
+    in_pass_kv = "stored": the nodes attend to each other with the stored (rounded) keys and
+    values as well — the other reading of a bf16 cache, see causal_forward.
     """
+    if in_pass_kv not in ("unrounded", "stored"):
+        raise ValueError(in_pass_kv)
     rnd = bf16_round if shape.dtype == "bf16" else _identity
     M = len(tokens)
     H, nq, nkv, d = shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim
@@ -212,12 +227,13 @@ def verify_forward(W: OracleWeights, shape, k_ctx, v_ctx, tokens: Sequence[int],
         k = apply_rope(k, ang)
         k_new[l] = rnd(k).transpose(1, 0, 2)      # what enters the cache
         v_new[l] = rnd(v).transpose(1, 0, 2)
+        kd, vd = (rnd(k), rnd(v)) if in_pass_kv == "stored" else (k, v)   # what the nodes see of each other
         o = np.zeros((M, nq, d))
         for i in range(M):
             for a in range(nq):
                 g = a // group
-                keys = np.concatenate([kc[g], k[anc[i], g]], axis=0)
-                vals = np.concatenate([vc[g], v[anc[i], g]], axis=0)
+                keys = np.concatenate([kc[g], kd[anc[i], g]], axis=0)
+                vals = np.concatenate([vc[g], vd[anc[i], g]], axis=0)
                 s = (keys @ q[i, a]) / np.sqrt(d)
                 o[i, a] = _softmax(s) @ vals
         x = x + o.reshape(M, nq * d) @ W("wo", l).T

@@ -30,6 +30,7 @@ EXPORTS = [
     "trispec_timer_destroy", "trispec_model_pack_bytes", "trispec_model_pack", "trispec_copy_probe",
     "trispec_kv_commit", "trispec_sample_scratch_bytes", "trispec_sample_decide",
     "trispec_sample_decide_static", "trispec_debug_set_spin_limit", "trispec_wait_probe",
+    "trispec_prune_reroot",
 ]
 K_GEMM, K_HEAD, K_ATTN = 0, 1, 2
 LAUNCH_PER_MATMUL, LAUNCH_PER_LAYER = 0, 1
@@ -117,6 +118,9 @@ def lib() -> C.CDLL:
         l.trispec_sample_decide_static.argtypes = l.trispec_sample_decide.argtypes
         l.trispec_debug_set_spin_limit.argtypes = [C.c_uint64]
         l.trispec_wait_probe.argtypes = [C.c_void_p, C.c_int32, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]
+        _pi = C.POINTER(C.c_int32)
+        l.trispec_prune_reroot.argtypes = [_pi, _pi, _pi, C.c_int32, _pi, C.c_int32, _pi, C.c_int32, C.c_int32,
+                                           _pi, _pi, _pi, _pi, _pi, _pi]
         l.trispec_timer_create.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]
         l.trispec_timer_reset.argtypes = [C.c_void_p]
         l.trispec_timer_read.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_double),
@@ -294,6 +298,25 @@ def copy_probe(dst, src, stream=None) -> None:
         raise ValueError("copy_probe: sizes differ")
     st = stream if stream is not None else torch.cuda.current_stream().cuda_stream
     check(lib().trispec_copy_probe(dst.data_ptr(), src.data_ptr(), nbytes, st))
+
+
+def prune_reroot(tokens, parents, positions, path, prefix_tokens=(), prefix_pos0: int = 0) -> Dict[str, object]:
+    """trispec_prune_reroot on host integer sequences (argument marshalling only)."""
+    def arr(v):
+        v = [int(x) for x in v]
+        return (C.c_int32 * max(len(v), 1))(*v), len(v)
+    tok, n = arr(tokens)
+    par, _ = arr(parents)
+    pos, _ = arr(positions)
+    pth, n_path = arr(path)
+    pre, n_pre = arr(prefix_tokens)
+    out = [(C.c_int32 * MAX_NODES)() for _ in range(4)]
+    n_out, n_forced = C.c_int32(), C.c_int32()
+    check(lib().trispec_prune_reroot(tok, par, pos, n, pth, n_path, pre if n_pre else None, n_pre, int(prefix_pos0),
+                                     out[0], out[1], out[2], out[3], C.byref(n_out), C.byref(n_forced)))
+    m = n_out.value
+    return {"tokens": list(out[0][:m]), "parents": list(out[1][:m]), "positions": list(out[2][:m]),
+            "old_id": list(out[3][:m]), "n_forced": n_forced.value}
 
 
 class SampleDecider:

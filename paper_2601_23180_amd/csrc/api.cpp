@@ -815,6 +815,9 @@ int trispec_decide(trispec_model *m, int32_t batch, const int32_t *draft_tokens,
   hipStream_t st = (hipStream_t)opts->stream;
   char *ws = (char *)opts->workspace;
   (void)hipGetLastError();
+  // the tree of THIS call (it may differ from the last verify's, e.g. after pruning): parents into
+  // the workspace, the status word and the counters left alone
+  launch_setup(st, tab, batch * n_nodes, (uint64_t *)(ws + L.anc), (int32_t *)(ws + L.parent), nullptr, nullptr, 0);
   DecideArgs d = make_decide(L, ws, draft_tokens, batch, n_nodes, threshold, opts, out);
   launch_decide(st, d);
   return hipGetLastError() == hipSuccess ? TRISPEC_OK : TRISPEC_ELAUNCH;
@@ -1049,6 +1052,54 @@ int trispec_wait_probe(int32_t *counter_dev, int32_t expect, uint64_t limit_tick
   (void)hipGetLastError();
   launch_wait_probe((hipStream_t)stream, counter_dev, expect, limit_ticks, abort_dev, status_dev);
   return hipGetLastError() == hipSuccess ? TRISPEC_OK : TRISPEC_ELAUNCH;
+}
+
+int trispec_prune_reroot(const int32_t *tokens, const int32_t *parents, const int32_t *positions, int32_t n_nodes,
+                         const int32_t *path, int32_t path_len, const int32_t *prefix_tokens, int32_t n_prefix,
+                         int32_t prefix_pos0, int32_t *out_tokens, int32_t *out_parents, int32_t *out_positions,
+                         int32_t *out_old_id, int32_t *out_n_nodes, int32_t *out_n_forced) {
+  if (!tokens || !parents || !positions || !path || !out_tokens || !out_parents || !out_positions || !out_old_id ||
+      !out_n_nodes || !out_n_forced || (n_prefix > 0 && !prefix_tokens))
+    return TRISPEC_ENULL;
+  if (n_prefix < 0 || path_len < 1) return TRISPEC_EARG;
+  if (n_nodes < 1 || n_nodes > kMaxNodes || path_len > n_nodes) return TRISPEC_ENODES;
+  if (parents[0] != -1) return TRISPEC_ETREE;
+  for (int i = 1; i < n_nodes; ++i)
+    if (parents[i] < 0 || parents[i] >= i) return TRISPEC_ETREE;
+  if (path[0] != 0) return TRISPEC_ETREE;
+  for (int i = 1; i < path_len; ++i)
+    if (path[i] <= 0 || path[i] >= n_nodes || parents[path[i]] != path[i - 1]) return TRISPEC_ETREE;
+  // kept nodes: the path, then every descendant of its last node in ascending id order
+  // (parents[i] < i, so one ascending sweep marks the whole subtree)
+  int keep[kMaxNodes], new_id[kMaxNodes], n_keep = 0;
+  bool below[kMaxNodes];
+  for (int i = 0; i < n_nodes; ++i) { below[i] = false; new_id[i] = -1; }
+  for (int i = 0; i < path_len; ++i) keep[n_keep++] = path[i];
+  const int last = path[path_len - 1];
+  below[last] = true;
+  for (int i = last + 1; i < n_nodes; ++i)
+    if (below[parents[i]]) {
+      below[i] = true;
+      keep[n_keep++] = i;
+    }
+  if ((long long)n_prefix + n_keep > kMaxNodes) return TRISPEC_ENODES;
+  for (int j = 0; j < n_keep; ++j) new_id[keep[j]] = n_prefix + j;
+  for (int j = 0; j < n_prefix; ++j) {
+    out_tokens[j] = prefix_tokens[j];
+    out_parents[j] = j - 1;
+    out_positions[j] = prefix_pos0 + j;
+    out_old_id[j] = -1;
+  }
+  for (int j = 0; j < n_keep; ++j) {
+    const int old = keep[j], o = n_prefix + j;
+    out_tokens[o] = tokens[old];
+    out_parents[o] = j == 0 ? n_prefix - 1 : new_id[parents[old]];
+    out_positions[o] = positions[old];
+    out_old_id[o] = old;
+  }
+  *out_n_nodes = n_prefix + n_keep;
+  *out_n_forced = n_prefix + path_len;
+  return TRISPEC_OK;
 }
 
 int trispec_copy_probe(void *dst_dev, const void *src_dev, size_t bytes, void *stream) {

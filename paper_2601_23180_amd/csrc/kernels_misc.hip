@@ -16,7 +16,7 @@ __global__ void k_setup(NodeTable tab, int rows, uint64_t *anc, int32_t *parent,
     anc[i] = tab.anc[i];
     parent[i] = tab.parent[i];
   }
-  if (i == 0) *status = 0;
+  if (i == 0 && status != nullptr) *status = 0;
   for (int j = i; j < n_zero; j += kMaxRows) zero[j] = 0;
 }
 

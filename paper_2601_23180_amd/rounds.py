@@ -21,7 +21,8 @@ from typing import Dict, List, Sequence
 import numpy as np
 import torch
 
-from .binding import CRIT_MARGIN, MAX_NODES, RESAMPLE_RESIDUAL, KVCache, Model, SampleDecider, Verifier
+from .binding import (CRIT_MARGIN, MAX_NODES, RESAMPLE_RESIDUAL, KVCache, Model, SampleDecider, TriSpecError, Verifier,
+                      prune_reroot)
 
 
 def _depths(parents: Sequence[int]) -> np.ndarray:
@@ -29,21 +30,6 @@ def _depths(parents: Sequence[int]) -> np.ndarray:
     for i in range(1, len(parents)):
         d[i] = d[parents[i]] + 1
     return d
-
-
-def _subtree_below(parents: Sequence[int], path: Sequence[int]):
-    """Nodes kept for the target pass: the path, then every descendant of its last node, in
-    ascending id order; and their parents in the new numbering."""
-    last = path[-1]
-    keep = [int(v) for v in path]
-    inside = {last}
-    for i in range(last + 1, len(parents)):
-        if int(parents[i]) in inside:
-            inside.add(i)
-            keep.append(i)
-    renum = {old: new for new, old in enumerate(keep)}
-    new_parents = [-1] + [renum[int(parents[old])] for old in keep[1:]]
-    return keep, new_parents
 
 
 class TernaryDecoder:
@@ -106,23 +92,24 @@ class TernaryDecoder:
             self.kv_p.commit([path])
             self.seq += [tokens[i] for i in path[1:]] + [pr["token"]]
             return rec
-        keep, sub_parents = _subtree_below(parents, path)                    # Case II
-        t_len = self.kv_t.ctx_len[0]
+        t_len = self.kv_t.ctx_len[0]                                         # Case II
         unseen = self.seq[t_len:-1]
-        if len(unseen) + len(keep) > self.max_nodes:
+        sub = None
+        try:       # the pruned, re-rooted tree behind the tokens the target has not cached yet (library call)
+            sub = prune_reroot(tokens, parents, positions, path, unseen, t_len)
+        except TriSpecError as e:
+            if e.code != -3:                                                 # TRISPEC_ENODES: does not fit
+                raise
+        if sub is None or len(sub["tokens"]) > self.max_nodes:
             before = self.kv_t.ctx_len[0]
             self._ingest("t", unseen)
             rec["catch_up"] = (self.kv_t.ctx_len[0] - before + self.max_nodes - 1) // self.max_nodes
-            t_len, unseen = self.kv_t.ctx_len[0], []
-        u = len(unseen)
-        tok_t = unseen + [tokens[i] for i in keep]
-        par_t = list(range(-1, u - 1)) + [u - 1 if p < 0 else p + u for p in sub_parents]
-        pos_t = list(range(t_len, t_len + u)) + [int(positions[i]) for i in keep]
-        n_forced = u + len(path)
-        tr = self._pass("t", tok_t, par_t, pos_t, 0.0, CRIT_MARGIN, n_forced)
+            sub = prune_reroot(tokens, parents, positions, path)
+        tok_t, n_forced = sub["tokens"], sub["n_forced"]
+        tr = self._pass("t", tok_t, sub["parents"], sub["positions"], 0.0, CRIT_MARGIN, n_forced)
         self.target_passes += 1
         self.kv_t.commit([list(range(n_forced - 1)) + tr["path"]])
-        extra = [keep[n - u] for n in tr["path"][1:]]                        # drafts the target accepted, old ids
+        extra = [sub["old_id"][n] for n in tr["path"][1:]]                   # drafts the target accepted, old ids
         self.kv_p.commit([path + extra])
         self.seq += [tokens[i] for i in path[1:] + extra] + [tr["token"]]
         rec.update({"target": tr, "target_nodes": len(tok_t), "n_forced_t": n_forced})

@@ -11,6 +11,15 @@ values.  Run (about 40 minutes on 8 cores, one case at a time to bound memory):
 Each file holds the inputs that are not a pure function of the seed (planted draft tokens,
 pruned trees) and, per node: argmax, confidence, margin, the two largest logits, and the logits
 at a fixed sample of vocabulary indices; plus sampled entries of the K/V rows the pass appends.
+Beside it, fullsize_<case>_tilecols.npz holds, per pass, the logits of every node at one column
+of every 128-column vocabulary tile and at every column of the last (ragged) tile — the unit the
+fused LM-head kernel works in — as float32.
+
+    python tests/golden/make_fullsize_expected.py --tilecols-only [case ...]
+
+recomputes only the final pass of each case from the tokens and trees the JSON file already
+holds, checks that it reproduces the stored statistics, and writes just the .npz (about an hour
+for all four cases on 8 cores).
 """
 from __future__ import annotations
 
@@ -31,6 +40,19 @@ from workloads import (SHAPES, WeightSource, gen_chain, gen_draft_tokens, gen_kv
 
 N_SAMPLE_LOGITS = 24
 N_SAMPLE_KV = 96
+TILE = 128   # vocabulary columns per tile of the fused LM-head kernel
+
+
+def tile_columns(vocab):
+    """One column of every full 128-column tile (its place inside the tile varies from tile to
+    tile) and every column of the last tile."""
+    n_tiles = (vocab + TILE - 1) // TILE
+    cols = [t * TILE + (t * 37 + 11) % TILE for t in range(n_tiles - 1)]
+    cols += list(range((n_tiles - 1) * TILE, vocab))
+    return np.asarray(cols, dtype=np.int64)
+
+
+TILECOLS = {}   # pass name -> float32 [M, n_cols], filled by summarise()
 
 
 def path_to(parents, node):
@@ -56,10 +78,11 @@ def oracle_pass(shape, seed, kv_seed, b, batch, ctx, tokens, parents, positions)
                           positions)
 
 
-def summarise(shape, seed, out, tokens):
+def summarise(shape, seed, out, tokens, name):
     lg = out["logits"]
     st = node_stats(lg)
     M, V = lg.shape
+    TILECOLS[name] = lg[:, tile_columns(V)].astype(np.float32)
     rng = np.random.Generator(np.random.Philox(key=[seed, 777]))
     cols = np.sort(rng.choice(V, size=N_SAMPLE_LOGITS, replace=False))
     L, nkv, _, d = out["k_new"].shape
@@ -105,7 +128,7 @@ def case_cfg2(log):
     positions = (ctx + tree_depths(parents)).astype(np.int32)
     tokens, out = planted(shape, seed, seed, ctx, parents, tokens, positions, 5, log)
     return {"shape": "qwen3_0p6b", "seed": seed, "ctx": ctx, "parents": parents.tolist(),
-            "positions": positions.tolist(), "seqs": [summarise(shape, seed, out, tokens)]}
+            "positions": positions.tolist(), "seqs": [summarise(shape, seed, out, tokens, "seq0")]}
 
 
 def case_cfg3(log):
@@ -115,7 +138,7 @@ def case_cfg3(log):
     positions = (ctx + tree_depths(parents)).astype(np.int32)
     tokens, out = planted(shape, seed, seed, ctx, parents, tokens, positions, 2, log)
     return {"shape": "qwen3_8b", "seed": seed, "ctx": ctx, "parents": parents.tolist(),
-            "positions": positions.tolist(), "seqs": [summarise(shape, seed, out, tokens)]}
+            "positions": positions.tolist(), "seqs": [summarise(shape, seed, out, tokens, "seq0")]}
 
 
 def case_cfg4(log):
@@ -132,7 +155,7 @@ def case_cfg4(log):
     st = node_stats(out["logits"])
     res = {"proxy_shape": "qwen3_1p7b", "target_shape": "qwen3_8b", "seed": seed, "target_seed": tseed,
            "ctx": ctx, "parents": parents.tolist(), "positions": positions.tolist(),
-           "proxy": summarise(pshape, seed, out, tokens), "routes": [], "targets": {}}
+           "proxy": summarise(pshape, seed, out, tokens, "proxy"), "routes": [], "targets": {}}
     for crit, cname in ((CRIT_TOP1, "top1"), (CRIT_MARGIN, "margin")):
         for lam in (0.5, 0.7, 0.9):
             dec = decide(tokens, parents, st["argmax"], st["conf"], st["margin"], lam, crit, 1)
@@ -148,7 +171,7 @@ def case_cfg4(log):
                     t0 = time.time()
                     tout = oracle_pass(tshape, tseed, tseed, 0, 1, ctx, pr["tokens"], pr["parents"], pr["positions"])
                     log(f"  done ({time.time() - t0:.0f}s)")
-                    s = summarise(tshape, tseed, tout, pr["tokens"])
+                    s = summarise(tshape, tseed, tout, pr["tokens"], "target:" + key)
                     ts = node_stats(tout["logits"])
                     td = decide(pr["tokens"], pr["parents"], ts["argmax"], ts["conf"], ts["margin"], 0.0,
                                 CRIT_MARGIN, pr["n_forced"])
@@ -171,7 +194,7 @@ def case_cfg5(log):
         t0 = time.time()
         out = oracle_pass(shape, seed, seed, b, batch, ctx, tokens, parents, positions)
         log(f"  sequence {b} ({time.time() - t0:.0f}s)")
-        seqs.append(summarise(shape, seed + b, out, tokens))
+        seqs.append(summarise(shape, seed + b, out, tokens, f"seq{b}"))
         par.append(parents.tolist()); pos.append(positions.tolist())
     return {"shape": "llama3_8b", "seed": seed, "ctx": ctx, "batch": batch, "parents": par, "positions": pos,
             "seqs": seqs}
@@ -180,8 +203,39 @@ def case_cfg5(log):
 CASES = {"cfg2": case_cfg2, "cfg3": case_cfg3, "cfg4": case_cfg4, "cfg5": case_cfg5}
 
 
+def tilecols_only(name, log):
+    """The final pass of every sequence / target of a case, from the tokens and trees its JSON
+    file holds; the stored statistics must come out again."""
+    with open(os.path.join(HERE, f"fullsize_{name}.json")) as f:
+        g = json.load(f)
+
+    def redo(shape, seed, kv_seed, b, batch, stored, parents, positions, key):
+        t0 = time.time()
+        out = oracle_pass(shape, seed, kv_seed, b, batch, g["ctx"], np.asarray(stored["tokens"], dtype=np.int32),
+                          np.asarray(parents, dtype=np.int32), np.asarray(positions, dtype=np.int32))
+        st = node_stats(out["logits"])
+        assert [int(v) for v in st["argmax"]] == stored["argmax"], key
+        assert np.allclose(st["l1"], stored["l1"], rtol=0, atol=1e-9) and np.allclose(st["conf"], stored["conf"], rtol=0, atol=1e-12), key
+        TILECOLS[key] = out["logits"][:, tile_columns(shape.vocab)].astype(np.float32)
+        log(f"  {key} ({time.time() - t0:.0f}s)")
+
+    if name == "cfg4":
+        redo(SHAPES[g["proxy_shape"]], g["seed"], g["seed"], 0, 1, g["proxy"], g["parents"], g["positions"], "proxy")
+        for key, t in g["targets"].items():
+            redo(SHAPES[g["target_shape"]], g["target_seed"], g["target_seed"], 0, 1, t, t["parents"], t["positions"],
+                 "target:" + key)
+    else:
+        batch = g.get("batch", 1)
+        for b, s in enumerate(g["seqs"]):
+            par = g["parents"][b] if batch > 1 else g["parents"]
+            pos = g["positions"][b] if batch > 1 else g["positions"]
+            redo(SHAPES[g["shape"]], g["seed"], g["seed"], b, batch, s, par, pos, f"seq{b}")
+
+
 def main():
-    names = sys.argv[1:] or list(CASES)
+    args = sys.argv[1:]
+    only = "--tilecols-only" in args
+    names = [a for a in args if not a.startswith("--")] or list(CASES)
     for name in names:
         t0 = time.time()
 
@@ -189,11 +243,18 @@ def main():
             print(f"[{name} +{time.time() - t0:.0f}s] {msg}", flush=True)
 
         log("start")
-        res = CASES[name](log)
-        path = os.path.join(HERE, f"fullsize_{name}.json")
-        with open(path, "w") as f:
-            json.dump(res, f, separators=(",", ":"))
-            f.write("\n")
+        TILECOLS.clear()
+        if only:
+            tilecols_only(name, log)
+        else:
+            res = CASES[name](log)
+            path = os.path.join(HERE, f"fullsize_{name}.json")
+            with open(path, "w") as f:
+                json.dump(res, f, separators=(",", ":"))
+                f.write("\n")
+            log(f"wrote {path}")
+        path = os.path.join(HERE, f"fullsize_{name}_tilecols.npz")
+        np.savez_compressed(path, **TILECOLS)
         log(f"wrote {path}")
 
 

@@ -189,3 +189,72 @@ def test_sample_decide_rejects_bad_arguments_before_any_launch():
     assert rc(T=0.0) == -8 and rc(T=-1.0) == -8 and rc(T=float("inf")) == -8 and rc(T=float("nan")) == -8
     assert rc(lam=float("nan")) == -8 and rc(vocab=0) == -8 and rc(resample=2) == -8 and rc(crit=5) == -8
     assert rc(scratch=None) == -7 and rc(scratch=0x10010) == -7 and rc(scratch_bytes=64) == -7
+
+
+# ------------------------------------------------------------------ Case II hand-over (host integers only)
+
+def _root_paths(parents):
+    """Every root path [0, ..., v] of a tree."""
+    out = []
+    for v in range(len(parents)):
+        p = [v]
+        while parents[p[-1]] >= 0:
+            p.append(int(parents[p[-1]]))
+        out.append(p[::-1])
+    return out
+
+
+def test_prune_reroot_equals_the_oracle_on_every_root_path():
+    from oracle import prune_reroot as oracle_prune
+    from workloads import gen_draft_tokens, gen_eagle2_tree, gen_tree, tree_depths
+    n_paths = 0
+    for seed in range(6):
+        for parents in (gen_tree(60, 8, 4, seed), gen_tree(23, 5, 3, seed), gen_eagle2_tree(seed), gen_tree(64, 12, 3, seed),
+                        np.arange(-1, 8, dtype=np.int32), np.array([-1], dtype=np.int32)):
+            tokens = gen_draft_tokens(parents, 50000, seed)
+            positions = 1000 + tree_depths(parents)
+            for path in _root_paths(parents):
+                want = oracle_prune(tokens, parents, positions, path)
+                got = B.prune_reroot(tokens, parents, positions, path)
+                assert got["tokens"] == want["tokens"].tolist() and got["parents"] == want["parents"].tolist()
+                assert got["positions"] == want["positions"].tolist() and got["old_id"] == want["old_id"].tolist()
+                assert got["n_forced"] == want["n_forced"]
+                n_paths += 1
+    assert n_paths > 1000
+
+
+def test_prune_reroot_with_a_prefix_equals_the_oracle_on_the_extended_tree():
+    """Tokens the target has not cached ride in front: the same as pruning a tree that has them as a
+    chain above its root, along the path that runs through that chain."""
+    from oracle import prune_reroot as oracle_prune
+    from workloads import gen_draft_tokens, gen_tree, tree_depths
+    for seed, u in ((1, 1), (2, 5), (3, 17)):
+        parents = gen_tree(40, 8, 4, seed)
+        tokens = gen_draft_tokens(parents, 3000, seed)
+        positions = 500 + u + tree_depths(parents)
+        prefix = list(range(7000, 7000 + u))
+        ext_par = np.concatenate([np.arange(-1, u - 1), np.where(parents < 0, u - 1, parents + u)]).astype(np.int32)
+        ext_tok = np.concatenate([prefix, tokens]).astype(np.int32)
+        ext_pos = np.concatenate([500 + np.arange(u), positions]).astype(np.int32)
+        for path in _root_paths(parents)[::3]:
+            want = oracle_prune(ext_tok, ext_par, ext_pos, list(range(u)) + [v + u for v in path])
+            got = B.prune_reroot(tokens, parents, positions, path, prefix, 500)
+            assert got["tokens"] == want["tokens"].tolist() and got["parents"] == want["parents"].tolist()
+            assert got["positions"] == want["positions"].tolist() and got["n_forced"] == want["n_forced"]
+            assert got["old_id"] == [-1] * u + [int(v) - u for v in want["old_id"][u:]]
+
+
+def test_prune_reroot_errors():
+    par = [-1, 0, 0, 1]
+    tok, pos = [5, 6, 7, 8], [10, 11, 11, 12]
+    for path, code in (([1], -4), ([0, 3], -4), ([0, 2, 3], -4), ([0, 1, 3, 3, 3], -3)):
+        with pytest.raises(B.TriSpecError) as e:
+            B.prune_reroot(tok, par, pos, path)
+        assert e.value.code == code, (path, e.value.code)
+    with pytest.raises(B.TriSpecError) as e:      # parents not topological
+        B.prune_reroot(tok, [-1, 2, 0, 1], pos, [0])
+    assert e.value.code == -4
+    with pytest.raises(B.TriSpecError) as e:      # prefix + kept nodes exceed the node limit
+        B.prune_reroot(tok, par, pos, [0], list(range(62)), 0)
+    assert e.value.code == -3
+    assert len(B.prune_reroot(tok, par, pos, [0], list(range(60)), 0)["tokens"]) == 64

@@ -4,8 +4,9 @@ times (same shapes, context lengths, trees, seeds and generators).
 The oracle's answers for these workloads take minutes of CPU time, so they are stored:
 tests/golden/fullsize_<case>.json, written by tests/golden/make_fullsize_expected.py, which
 calls only oracle/ and the seeded generators.  Compared per node: argmax, confidence, margin,
-the two largest logits, logits at sampled vocabulary indices, sampled appended K/V entries, and
-the decisions over the configs' threshold sweeps.  On top of that, properties that hold at any
+the two largest logits, the logits at one column of every 128-column vocabulary tile and at every
+column of the last tile (fullsize_<case>_tilecols.npz, about 1.2 k columns per node) and at 24 more
+sampled columns, sampled appended K/V entries, and the decisions over the configs' threshold sweeps.  On top of that, properties that hold at any
 size: every probability statistic equals a direct fp64 softmax of the GPU's own logits, the cache
 slots the pass must not touch stay untouched, and a repeated call is bit-identical.
 """
@@ -18,6 +19,7 @@ import torch
 
 from oracle import CRIT_MARGIN, CRIT_TOP1, decide, tie_flags
 from paper_2601_23180_amd import KVCache, Verifier, fill_kv_layer, model_from_arrays
+from paper_2601_23180_amd.binding import prune_reroot
 from workloads import SHAPES, WeightSource, gen_kv_cache
 
 pytestmark = pytest.mark.gpu
@@ -27,10 +29,21 @@ GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 
 def golden(name):
     path = os.path.join(GOLDEN, f"fullsize_{name}.json")
-    if not os.path.exists(path):
-        pytest.skip(f"{path} not generated (run tests/golden/make_fullsize_expected.py {name})")
+    assert os.path.exists(path), f"{path} not generated (run tests/golden/make_fullsize_expected.py {name})"
     with open(path) as f:
-        return json.load(f)
+        g = json.load(f)
+    tpath = os.path.join(GOLDEN, f"fullsize_{name}_tilecols.npz")
+    assert os.path.exists(tpath), f"{tpath} not generated (make_fullsize_expected.py --tilecols-only {name})"
+    g["_tilecols"] = np.load(tpath)     # plain float32 arrays, no pickled objects
+    return g
+
+
+def tile_columns(vocab, tile=128):
+    """The columns the .npz files hold: one per full 128-column vocabulary tile (its place inside the
+    tile varies from tile to tile) and every column of the last tile."""
+    n_tiles = (vocab + tile - 1) // tile
+    cols = [t * tile + (t * 37 + 11) % tile for t in range(n_tiles - 1)]
+    return np.asarray(cols + list(range((n_tiles - 1) * tile, vocab)), dtype=np.int64)
 
 
 _models = {}
@@ -71,10 +84,16 @@ def run_pass(shape, model, kv_seed, ctx, tokens, parents, positions, threshold, 
     return res, ver, kv, tok, pos, parents
 
 
-def check_seq(shape, g, res, b, ctx, kv, n_forced=1):
+def check_seq(shape, g, res, b, ctx, kv, n_forced=1, tilecols=None):
     """Per-node comparison of sequence b against the stored oracle values."""
     M = len(g["tokens"])
     lg = res["logits"][b].astype(np.float64)
+    # every vocabulary tile of the fused LM-head kernel (one column each) and the whole ragged last tile
+    tc = tile_columns(shape.vocab)
+    assert tilecols is not None and tilecols.shape == (M, len(tc)), "tile-column fixture missing or of another shape"
+    trel = np.max(np.abs(lg[:, tc] - tilecols.astype(np.float64)) / np.asarray(g["max_abs_logit"])[:, None])
+    print(f"tile columns ({len(tc)} per node): max rel err {trel:.3g}")
+    assert trel <= 2e-4, trel                    # stored as float32: 6e-8 relative of their own
     cols = np.asarray(g["logit_cols"])
     want = np.asarray(g["logits"])
     scale = np.asarray(g["max_abs_logit"])[:, None]
@@ -108,15 +127,32 @@ def check_seq(shape, g, res, b, ctx, kv, n_forced=1):
 
 def check_decision(g, tokens, parents, got, lam, crit, n_forced=1):
     """Bit-exact against the oracle's decision on the ORACLE's statistics, unless a node the walk
-    touches is tie-flagged (statistic within 1e-3 of the threshold, or top-2 logit gap < 1e-3)."""
+    touches is tie-flagged (statistic within 1e-3 of the threshold, or top-2 logit gap < 1e-3); the
+    GPU's answer must then be the oracle's under another resolution of those ties (the statistic on
+    the other side of the threshold; the GPU's own argmax where the two top logits tie)."""
+    import itertools
     st = {k: np.asarray(g[k]) for k in ("argmax", "conf", "margin", "l1", "l2")}
-    want = decide(np.asarray(tokens), np.asarray(parents), st["argmax"], st["conf"], st["margin"], lam, crit, n_forced)
+    tokens, parents = np.asarray(tokens), np.asarray(parents)
+    want = decide(tokens, parents, st["argmax"], st["conf"], st["margin"], lam, crit, n_forced)
     got_path = [int(v) for v in got["path"] if v >= 0]
-    same = (int(got["accepted_len"]) == want["accepted_len"] and int(got["token"]) == want["token"]
-            and int(got["escalate"]) == want["escalate"] and got_path == [int(v) for v in want["path"]])
+    key = lambda d, path: (int(d["accepted_len"]), int(d["token"]), int(d["escalate"]), [int(v) for v in path])
+    same = key(got, got_path) == key(want, want["path"])
     if not same:
         flags = tie_flags(st, lam, crit)
-        assert any(flags[i] for i in set(got_path) | set(int(v) for v in want["path"])), (want, got_path)
+        tied = [i for i in sorted(set(got_path) | set(int(v) for v in want["path"])) if flags[i]]
+        assert tied, (want, got_path)
+        stat = st["margin"] if crit == CRIT_MARGIN else st["conf"]
+        ok = False
+        for mask in itertools.product((0, 1, 2, 3), repeat=len(tied)):
+            argmax, conf, margin = st["argmax"].copy(), st["conf"].copy(), st["margin"].copy()
+            for i, m in zip(tied, mask):
+                if m & 1 and abs(stat[i] - lam) < 1e-3:
+                    conf[i] = margin[i] = (lam - 1.0) if stat[i] >= lam else (lam + 1.0)
+                if m & 2 and st["l1"][i] - st["l2"][i] < 1e-3 and "argmax" in got:
+                    argmax[i] = int(got["argmax"][i])
+            alt = decide(tokens, parents, argmax, conf, margin, lam, crit, n_forced)
+            ok = ok or key(got, got_path) == key(alt, alt["path"])
+        assert ok, (want, key(got, got_path))
     return want, same
 
 
@@ -127,7 +163,7 @@ def sweep(ver, tok, parents, g_seqs, thresholds, n_forced=1):
             out = ver.decide(tok, parents, lam, crit, n_forced)
             torch.cuda.synchronize()
             for b, g in enumerate(g_seqs):
-                got = {k: out[k][b].cpu().numpy() for k in ("accepted_len", "token", "escalate", "path")}
+                got = {k: out[k][b].cpu().numpy() for k in ("accepted_len", "token", "escalate", "path", "argmax")}
                 _, same = check_decision(g, g["tokens"], parents[b], got, lam, crit, n_forced)
                 n_same += same
     return n_same
@@ -141,7 +177,7 @@ def test_config2_qwen3_0p6b_chain_threshold_sweep():
     res, ver, kv, tok, pos, parents = run_pass(shape, model, g["seed"], g["ctx"], s["tokens"], g["parents"],
                                                g["positions"], 0.3, CRIT_MARGIN, 1)
     assert res["status"][0] == 0
-    check_seq(shape, s, res, 0, g["ctx"], kv)
+    check_seq(shape, s, res, 0, g["ctx"], kv, tilecols=g["_tilecols"]["seq0"])
     sweep(ver, tok, parents, [s], (0.0, 0.3, 0.6, 0.9, 1.5))
     # the planted chain: five drafts are the verifier's own greedy tokens
     out = ver.decide(tok, parents, 0.0, CRIT_MARGIN, 1)
@@ -156,7 +192,7 @@ def test_config3_qwen3_8b_tree60_is_the_bench_workload():
     res, ver, kv, tok, pos, parents = run_pass(shape, model, g["seed"], g["ctx"], s["tokens"], g["parents"],
                                                g["positions"], 0.5, CRIT_MARGIN, 1)
     assert res["status"][0] == 0
-    check_seq(shape, s, res, 0, g["ctx"], kv)
+    check_seq(shape, s, res, 0, g["ctx"], kv, tilecols=g["_tilecols"]["seq0"])
     sweep(ver, tok, parents, [s], (0.0, 0.3, 0.5, 0.7, 0.9, 1.5))
     # repeatable: the pass does not advance the cache, a second call is bit-identical
     again = ver.verify(kv, tok, parents, pos, 0.5, CRIT_MARGIN, 1)
@@ -176,7 +212,7 @@ def test_config4_ternary_pipeline_proxy_then_pruned_target():
     res, ver, kv, tok, pos, parents = run_pass(pshape, model, g["seed"], g["ctx"], p["tokens"], g["parents"],
                                                g["positions"], 0.5, CRIT_TOP1, 1)
     assert res["status"][0] == 0
-    check_seq(pshape, p, res, 0, g["ctx"], kv)
+    check_seq(pshape, p, res, 0, g["ctx"], kv, tilecols=g["_tilecols"]["proxy"])
     todo = {}
     for route in g["routes"]:
         crit = CRIT_TOP1 if route["criterion"] == "top1" else CRIT_MARGIN
@@ -192,26 +228,20 @@ def test_config4_ternary_pipeline_proxy_then_pruned_target():
     model = get_model(g["target_shape"], g["target_seed"])
     for key, path in todo.items():
         t = g["targets"][key]
-        # host step of Case II, product side: keep the approved path as a forced chain and the
-        # subtree under its last node, in the original node order
-        keep = [i for i in range(len(g["parents"])) if i in path or _under(g["parents"], i, path[-1])]
-        assert len(keep) == len(t["tokens"]) and t["n_forced"] == len(path)
-        res, ver, kv, tok, pos, parents = run_pass(tshape, model, g["target_seed"], g["ctx"], t["tokens"],
-                                                   t["parents"], t["positions"], 0.0, CRIT_MARGIN, t["n_forced"])
+        # host step of Case II through the library (trispec_prune_reroot) on the path the GPU's proxy
+        # pass returned: the forced chain and the subtree under its last node.  The target pass runs
+        # on THAT tree; it must be the tree the oracle pruned for the stored target values.
+        sub = prune_reroot(p["tokens"], g["parents"], g["positions"], path)
+        assert sub["tokens"] == t["tokens"] and sub["parents"] == t["parents"]
+        assert sub["positions"] == t["positions"] and sub["n_forced"] == t["n_forced"] == len(path)
+        res, ver, kv, tok, pos, parents = run_pass(tshape, model, g["target_seed"], g["ctx"], sub["tokens"],
+                                                   sub["parents"], sub["positions"], 0.0, CRIT_MARGIN, sub["n_forced"])
         assert res["status"][0] == 0
-        check_seq(tshape, t, res, 0, g["ctx"], kv, t["n_forced"])
+        check_seq(tshape, t, res, 0, g["ctx"], kv, t["n_forced"], tilecols=g["_tilecols"]["target:" + key])
         got = {k: res[k][0] for k in ("accepted_len", "token", "escalate", "path")}
         want, same = check_decision(t, t["tokens"], t["parents"], got, 0.0, CRIT_MARGIN, t["n_forced"])
         assert want["escalate"] == 0 and want["accepted_len"] == t["decision"]["accepted_len"]
         del ver, kv, res
-
-
-def _under(parents, i, root):
-    while i >= 0:
-        if i == root:
-            return True
-        i = parents[i]
-    return False
 
 
 def test_config5_llama3_8b_batch4_ctx16384():
@@ -223,6 +253,6 @@ def test_config5_llama3_8b_batch4_ctx16384():
                                                g["positions"], 0.5, CRIT_MARGIN, 1)
     assert (res["status"] == 0).all()
     for b, s in enumerate(g["seqs"]):
-        check_seq(shape, s, res, b, g["ctx"], kv)
+        check_seq(shape, s, res, b, g["ctx"], kv, tilecols=g["_tilecols"][f"seq{b}"])
     sweep(ver, tok, parents, g["seqs"], (0.0, 0.5, 0.9, 1.5))
     _models.clear()

@@ -260,6 +260,35 @@ def test_bounded_wait_gives_up_and_reports():
     assert buf.tolist()[:3] == [5, 0, 0]
 
 
+def test_decide_walks_the_tree_it_is_given():
+    """trispec_decide after a pass, with ANOTHER tree and other draft tokens over the same per-node
+    statistics: the walk must follow the arguments of this call, not the tree of the pass."""
+    case = make_case(TB, 31, [80], [gen_tree(40, 8, 4, 31)])
+    oracle_out = case.run_oracle()
+    gpu = case.run_gpu(0.0)
+    st = oracle_out[0]["stats"]
+    ver = gpu["_ver"]
+    for seed in (1, 2, 3):
+        parents = gen_tree(40, 10, 3, 500 + seed)
+        tokens = gen_draft_tokens(parents, TB.vocab, 900 + seed)
+        leaf = int(np.argmax(tree_depths(parents)))
+        p = path_to(parents, leaf)
+        for a, c in list(zip(p[:-1], p[1:]))[: 2 + seed]:
+            tokens[c] = st["argmax"][a]
+        tok = torch.from_numpy(tokens[None].astype(np.int32)).cuda()
+        for lam, crit in ((0.0, CRIT_MARGIN), (0.2, CRIT_TOP1)):
+            out = ver.decide(tok, parents[None], lam, crit)
+            torch.cuda.synchronize()
+            want = decide(tokens, parents, st["argmax"], st["conf"], st["margin"], lam, crit, 1)
+            if tie_flags(st, lam, crit)[want["path"]].any():
+                continue
+            assert out["accepted_len"].item() == want["accepted_len"] and out["token"].item() == want["token"]
+            assert out["escalate"].item() == want["escalate"]
+            assert out["path"][0, : len(want["path"])].tolist() == list(want["path"])
+            if lam == 0.0:
+                assert want["accepted_len"] >= 2 + seed
+
+
 def test_cache_append_matches_oracle_rounding():
     shape = TB
     case = make_case(shape, 9, [100], [gen_tree(24, 6, 3, 9)])

@@ -68,8 +68,22 @@ def gpu_rounds(shape, seed, prompt, draft_fn, n_rounds, n_nodes):
     return seq, rounds, kv
 
 
+def until_compared_in_full(run, seeds):
+    """A tie inside the tolerance may change a round, and then every round after it: such a run is
+    excused (its excuse is asserted inside `run`, which returns False) and COUNTED, and the next
+    seed is taken, until one run compares in full.  Returns the number of excused runs."""
+    for n, seed in enumerate(seeds):
+        if run(seed):
+            return n
+    pytest.fail(f"all {len(seeds)} seeds were changed by a tie: nothing was compared in full")
+
+
 @pytest.mark.parametrize("shape_name,seed", [("tiny", 3), ("tiny_bf16", 4)])
 def test_rounds_match_the_oracle_and_greedy_decoding(shape_name, seed):
+    assert until_compared_in_full(lambda s: _rounds_vs_oracle(shape_name, s), [seed, seed + 50, seed + 100]) <= 1
+
+
+def _rounds_vs_oracle(shape_name, seed):
     shape, n_nodes, n_rounds = SHAPES[shape_name], 12, 5
     W = oracle_weights(shape, seed)
     prompt = gen_context_tokens(shape.vocab, 20, seed).tolist()
@@ -83,7 +97,7 @@ def test_rounds_match_the_oracle_and_greedy_decoding(shape_name, seed):
         if not same:
             flags = tie_flags(w["stats"], 0.0, CRIT_MARGIN)
             assert any(flags[i] for i in set(g["path"]) | set(int(v) for v in d["path"])), (r, g, d)
-            pytest.skip("tie inside the tolerance changed a round")
+            return False
         assert g["ctx_len"] == w["ctx_len"] and g["escalate"] == 0
     assert seq == want["sequence"]
     assert max(g["accepted_len"] for g in rounds) >= 3            # the planted prefixes were accepted and committed
@@ -97,6 +111,7 @@ def test_rounds_match_the_oracle_and_greedy_decoding(shape_name, seed):
     tol = (lambda w: 1e-4) if shape.dtype == "f32" else (lambda w: np.abs(w) * 2 ** -7 + 1e-4)
     assert np.all(np.abs(kg - want["k_ctx"]) <= tol(want["k_ctx"]))
     assert np.all(np.abs(vg - want["v_ctx"]) <= tol(want["v_ctx"]))
+    return True
 
 
 def test_commit_moves_exactly_the_path_rows():
@@ -134,8 +149,13 @@ def _run_decoder(shape, seed_p, seed_t, prompt, drafts, n_rounds, lam, max_nodes
 @pytest.mark.parametrize("shape_name,lam,max_nodes", [("tiny", 0.0, 64), ("tiny", 0.35, 64), ("tiny", 2.0, 64),
                                                        ("tiny", 0.35, 16), ("tiny_bf16", 0.35, 64)])
 def test_ternary_rounds_match_the_oracle(shape_name, lam, max_nodes):
+    run = lambda s: _ternary_rounds_vs_oracle(shape_name, lam, max_nodes, s, s + 1)
+    assert until_compared_in_full(run, [41, 141, 241]) <= 1
+
+
+def _ternary_rounds_vs_oracle(shape_name, lam, max_nodes, seed_p, seed_t):
     from oracle import trispec_rounds
-    shape, seed_p, seed_t, n_rounds = SHAPES[shape_name], 41, 42, 8
+    shape, n_rounds = SHAPES[shape_name], 8
     Wp, Wt = oracle_weights(shape, seed_p), oracle_weights(shape, seed_t)
     prompt = gen_context_tokens(shape.vocab, 12, seed_p).tolist()
     drafts = mixed_drafts(Wt if lam > 1 else Wp, shape, seed_p, 12)
@@ -152,7 +172,7 @@ def test_ternary_rounds_match_the_oracle(shape_name, lam, max_nodes):
             flags = tie_flags(w["proxy_stats"], lam, CRIT_MARGIN)
             tflags = tie_flags(w["target_stats"], 0.0, CRIT_MARGIN) if w["escalate"] else []
             assert any(flags) or any(tflags), (r, g, w["proxy"], w.get("target"))
-            pytest.skip("tie inside the tolerance changed a round")
+            return False
     assert dec.seq == want["sequence"]
     n_esc = sum(g["escalate"] for g in recs)
     assert dec.target_passes == n_esc
@@ -175,6 +195,7 @@ def test_ternary_rounds_match_the_oracle(shape_name, lam, max_nodes):
         kg = kv.k[:, 0, :, :n, :].float().cpu().numpy()
         vg = kv.v[:, 0, :, :, :n].float().cpu().numpy().transpose(0, 1, 3, 2)
         assert np.all(np.abs(kg - kw) <= tol(kw)) and np.all(np.abs(vg - vw) <= tol(vw))
+    return True
 
 
 # ---- rounds at temperature > 0 on draft chains (Alg. 1 as printed)
@@ -203,9 +224,14 @@ def _model_drafter(Wd, shape, k, temperature, seed, noise):
 @pytest.mark.parametrize("shape_name,lam,max_nodes", [("tiny", 0.0, 64), ("tiny", 0.25, 64), ("tiny", 2.0, 64),
                                                        ("tiny", 0.25, 12), ("tiny_bf16", 0.25, 64)])
 def test_sampling_rounds_match_the_oracle(shape_name, lam, max_nodes):
+    run = lambda s: _sampling_rounds_vs_oracle(shape_name, lam, max_nodes, s, s + 1)
+    assert until_compared_in_full(run, [41, 141, 241]) <= 1
+
+
+def _sampling_rounds_vs_oracle(shape_name, lam, max_nodes, seed_p, seed_t):
     from oracle import trispec_sample_rounds
     from paper_2601_23180_amd import TernaryDecoder
-    shape, seed_p, seed_t, n_rounds, T, k = SHAPES[shape_name], 41, 42, 8, 0.8, 4
+    shape, n_rounds, T, k = SHAPES[shape_name], 8, 0.8, 4
     Wp, Wt = oracle_weights(shape, seed_p), oracle_weights(shape, seed_t)
     prompt = gen_context_tokens(shape.vocab, 12, seed_p).tolist()
     log = {}
@@ -239,7 +265,7 @@ def test_sampling_rounds_match_the_oracle(shape_name, lam, max_nodes):
                     edges = c[max(pos - 1, 0): pos + 1]
                     close = close or bool(np.any(np.abs(edges - us * c[-1]) < tol))
             assert close, (r, g, w["proxy"]["path"], w.get("target", {}).get("path"))
-            pytest.skip("a comparison within rounding of its boundary changed a round")
+            return False
     assert dec.seq == want["sequence"]
     n_esc = sum(w["escalate"] for w in want["rounds"])
     assert dec.target_passes == n_esc
@@ -248,3 +274,4 @@ def test_sampling_rounds_match_the_oracle(shape_name, lam, max_nodes):
     assert dec.kv_t.ctx_len[0] == want["kt"].shape[2]
     if max_nodes == 12:
         assert any(w["catch_up"] for w in want["rounds"]) or any(w["escalate"] and w["u"] > 0 for w in want["rounds"])
+    return True

@@ -162,3 +162,30 @@ def test_prune_reroot_keeps_the_subtree_and_its_logits(seed):
             cur, acc = nxt[0], acc + 1
         assert a["accepted_len"] == acc and a["token"] == st_full["argmax"][cur] and a["escalate"] == 0
         assert [kept[j] for j in a["path"]] == path_to(parents, cur)[len(path) - 1:]
+
+
+def test_tie_resolutions_enumerate_the_other_outcomes():
+    """The helper the GPU tests use to excuse a tie: on a chain whose statistic at node 1 sits on the
+    threshold and whose top two logits at node 2 are equal within the tolerance, the enumerated
+    decisions are exactly the four outcomes of resolving the two ties either way."""
+    from types import SimpleNamespace
+    from gpu_helpers import tie_resolutions
+    from oracle import CRIT_TOP1, node_stats
+    V = 11
+    logits = np.full((4, V), -5.0)
+    logits[0, 3] = 5.0                       # node 0: confident, argmax 3
+    logits[1, 4] = 0.0; logits[1, 5] = -0.1; logits[1, 9] = -0.2  # node 1: argmax 4, top-1 probability near 0.36
+    logits[2, 6] = 1.0; logits[2, 7] = 1.0 - 5e-4   # node 2: top two within 1e-3
+    logits[3, 8] = 4.0
+    st = node_stats(logits)
+    lam = float(st["conf"][1]) + 4e-4        # node 1's statistic within 1e-3 below the threshold
+    tokens = np.array([[0, 3, 4, 7]], dtype=np.int32)    # chain 0 -> 1 -> 2 -> 3; node 3 holds the RUNNER-UP of node 2
+    parents = np.array([[-1, 0, 1, 2]], dtype=np.int32)
+    case = SimpleNamespace(tokens=tokens, parents=parents)
+    out = [{"stats": st, "logits": logits}]
+    alts = tie_resolutions(case, out, 0, lam, CRIT_TOP1, 1, [1, 2])
+    got = sorted((a["accepted_len"], a["token"], a["escalate"]) for a in alts)
+    # node 1 untrusted -> escalate after 1 draft (twice: node 2's tie no longer matters);
+    # node 1 trusted, node 2's argmax 6 -> no child matches: stop after 2 with token 6;
+    # node 1 trusted, node 2's argmax 7 -> node 3 accepted, then node 3's own argmax 8 as the bonus
+    assert got == sorted([(1, -1, 1), (1, -1, 1), (2, 6, 0), (3, 8, 0)]), got
