@@ -26,6 +26,8 @@ from .forward import (  # noqa: F401
 from .decision import (  # noqa: F401
     CRIT_MARGIN,
     CRIT_TOP1,
+    CRIT_ENTROPY,
+    draft_ranks,
     node_stats,
     decide,
     chain_tau_a,

@@ -189,3 +189,84 @@ def test_tie_resolutions_enumerate_the_other_outcomes():
     # node 1 trusted, node 2's argmax 6 -> no child matches: stop after 2 with token 6;
     # node 1 trusted, node 2's argmax 7 -> node 3 accepted, then node 3's own argmax 8 as the bonus
     assert got == sorted([(1, -1, 1), (1, -1, 1), (2, 6, 0), (3, 8, 0)]), got
+
+
+# ---- entropy statistic / criterion and the top-k rank of the appendix's relaxed verification
+
+def test_entropy_closed_forms_and_library():
+    from scipy.special import softmax
+    from scipy.stats import entropy as scipy_entropy
+    from oracle import node_stats
+    V = 1000
+    rng = np.random.default_rng(5)
+    uniform = np.zeros((1, V))
+    assert abs(node_stats(uniform)["entropy"][0] - np.log(V)) < 1e-12
+    one_hot = np.full((1, V), -1e4); one_hot[0, 17] = 0.0
+    assert node_stats(one_hot)["entropy"][0] == 0.0                     # exp underflows to exactly 0: 0 ln 0 = 0
+    two = np.full((1, V), -np.inf); two[0, 3] = np.log(0.25); two[0, 900] = np.log(0.75)
+    assert abs(node_stats(two)["entropy"][0] - (-(0.25 * np.log(0.25) + 0.75 * np.log(0.75)))) < 1e-12
+    logits = rng.standard_normal((7, V)) * 4
+    got = node_stats(logits)["entropy"]
+    assert np.allclose(got, scipy_entropy(softmax(logits, axis=1), axis=1), rtol=0, atol=1e-12)
+    assert np.all(got >= 0) and np.all(got <= np.log(V) + 1e-12)
+    assert np.allclose(node_stats(logits + 123.0)["entropy"], got, atol=1e-10)     # shift invariance
+    # k equal maxima far above the rest: H = ln k
+    flat3 = np.full((1, V), -1e4); flat3[0, [1, 50, 700]] = 2.0
+    assert abs(node_stats(flat3)["entropy"][0] - np.log(3)) < 1e-12
+
+
+def test_entropy_criterion_in_the_walk():
+    """g = 1{H <= lambda}: lambda = ln V trusts every node, lambda < 0 none; in between exactly the
+    nodes whose entropy is at most lambda, so on a chain tau_m is the first node above it."""
+    from oracle import CRIT_ENTROPY, decide, node_stats
+    rng = np.random.default_rng(6)
+    V, M = 50, 7
+    logits = rng.standard_normal((M, V)) * rng.uniform(0.5, 6, (M, 1))
+    st = node_stats(logits)
+    tokens = np.concatenate([[0], st["argmax"][:-1]]).astype(np.int32)       # every draft is the greedy token
+    parents = np.arange(-1, M - 1)
+    kw = dict(entropy=st["entropy"])
+    d = decide(tokens, parents, st["argmax"], st["conf"], st["margin"], np.log(V), CRIT_ENTROPY, 1, **kw)
+    assert (d["accepted_len"], d["escalate"]) == (M - 1, 0)
+    d = decide(tokens, parents, st["argmax"], st["conf"], st["margin"], -0.1, CRIT_ENTROPY, 1, **kw)
+    assert (d["accepted_len"], d["escalate"], d["token"]) == (0, 1, -1)
+    for lam in np.sort(st["entropy"])[:-1] + 1e-9:
+        d = decide(tokens, parents, st["argmax"], st["conf"], st["margin"], lam, CRIT_ENTROPY, 1, **kw)
+        above = np.nonzero(st["entropy"] > lam)[0]
+        assert d["escalate"] == 1 and d["accepted_len"] == above[0]
+
+
+def test_draft_ranks_against_a_sort_and_the_top_k_walk():
+    from oracle import decide, draft_ranks, node_stats
+    from workloads import gen_tree
+    rng = np.random.default_rng(7)
+    V, M = 40, 25
+    parents = gen_tree(M, 6, 3, 7)
+    logits = np.round(rng.standard_normal((M, V)) * 2, 1)                 # rounded: equal logits do occur
+    tokens = rng.integers(0, V, M).astype(np.int32)
+    ranks = draft_ranks(logits, tokens, parents)
+    assert ranks[0] == -1
+    for i in range(1, M):
+        order = np.argsort(-logits[parents[i]], kind="stable")            # descending logit, ties by token id
+        assert order[ranks[i]] == tokens[i]
+    st = node_stats(logits)
+    # top_k = 1 is the greedy walk; top_k = V accepts the first child of every node down to a leaf
+    a = decide(tokens, parents, st["argmax"], st["conf"], st["margin"], 0.0, 0, 1)
+    tok1 = tokens.copy()
+    b = decide(tok1, parents, st["argmax"], st["conf"], st["margin"], 0.0, 0, 1, ranks=ranks, top_k=1)
+    assert a == b
+    c = decide(tokens, parents, st["argmax"], st["conf"], st["margin"], 0.0, 0, 1, ranks=ranks, top_k=V)
+    cur, n = 0, 0
+    while True:
+        kids = [j for j in range(M) if parents[j] == cur]
+        if not kids:
+            break
+        cur, n = kids[0], n + 1
+    assert c["accepted_len"] == n and c["path"][-1] == cur and c["token"] == st["argmax"][cur]
+    # monotone in k: a larger k never shortens the accepted prefix of a CHAIN
+    chain = np.arange(-1, M - 1)
+    rk = draft_ranks(logits, tokens, chain)
+    lens = [decide(tokens, chain, st["argmax"], st["conf"], st["margin"], 0.0, 0, 1, ranks=rk, top_k=k)["accepted_len"]
+            for k in (1, 2, 4, 8, 16, V)]
+    assert lens == sorted(lens) and lens[-1] == M - 1
+    assert lens[1] == next((i for i in range(1, M) if rk[i] >= 2), M) - 1
