@@ -58,7 +58,10 @@ enum { TRISPEC_F32 = 0, TRISPEC_BF16 = 1 };
 /* Trust predicate g (Sec. 3.2 Eq. 8; alternatives in Sec. 4.3 "Routing Criteria"). */
 enum {
   TRISPEC_CRIT_MARGIN = 0,   /* g = 1{ top1(p) - top2(p) >= threshold }  (the paper's default) */
-  TRISPEC_CRIT_TOP1 = 1      /* g = 1{ top1(p) >= threshold }            (max-softmax confidence) */
+  TRISPEC_CRIT_TOP1 = 1,     /* g = 1{ top1(p) >= threshold }            (max-softmax confidence) */
+  TRISPEC_CRIT_ENTROPY = 2   /* g = 1{ H(p) <= threshold }, H = -sum p ln p in nats.  Sec. 4.3 names an entropy
+                                criterion among the routing rules it compares but only cites its definition;
+                                this is the plain Shannon entropy of the verifier's distribution */
 };
 
 typedef struct {             /* plain data, copied by trispec_model_create */
@@ -200,6 +203,13 @@ typedef struct {
                                 selection and adapter training"); NULL = not exported */
   int32_t launch_mode;       /* TRISPEC_LAUNCH_PER_MATMUL (0, default) | TRISPEC_LAUNCH_PER_LAYER: how the pass
                                 is cut into kernel launches (same arithmetic either way) */
+  const int32_t *draft_ranks; /* optional device [batch, n_nodes] from trispec_draft_ranks, see accept_top_k */
+  int32_t accept_top_k;      /* 0 or 1: a draft token is accepted iff it equals the verifier's argmax (Eq. 6,
+                                greedy form).  k > 1: the relaxed acceptance that the appendix "relaxed
+                                verification" studies — accepted iff it is among the verifier's top-k candidates
+                                at its parent node (draft_ranks[child] < k; lowest-numbered such child first);
+                                the verifier's own token where the walk stops is still its argmax.  Needs
+                                draft_ranks (TRISPEC_EARG otherwise) */
   uint64_t *stamps;          /* optional device [n_layers][16] (measurement only): 100 MHz wall-clock ticks of
                                 one workgroup at the phase boundaries of each layer launch — [0] start, then
                                 per matmul (O, gate+up, down, next QKV) [1+3p] past the barrier, [2+3p] end of
@@ -228,6 +238,8 @@ typedef struct {             /* device pointers, caller-owned; any may be NULL t
   int32_t *argmax;           /* [batch, n_nodes] verifier top-1 token at each node */
   float *confidence;         /* [batch, n_nodes] top-1 softmax probability */
   float *margin;             /* [batch, n_nodes] top-1 minus top-2 probability (Eq. 8) */
+  float *entropy;            /* [batch, n_nodes] Shannon entropy of the verifier's distribution at each node, nats
+                                         (written by trispec_verify / trispec_decide only) */
   int32_t *status;           /* [1] device-side error bits: 1 = a draft token id outside [0, vocab);
                                          4 = a device-side barrier wait expired (results are not valid) */
 } trispec_verify_out;
@@ -368,6 +380,21 @@ int trispec_timer_destroy(trispec_timer *t);
  * "node_idx").  Errors: TRISPEC_ENULL, TRISPEC_ENODES, TRISPEC_EARG (unknown name). */
 int trispec_workspace_region(const trispec_model *m, int32_t batch, int32_t n_nodes,
                              const char *name, size_t *offset, size_t *bytes);
+
+/*
+ * Rank of every draft token under the verifier (appendix "relaxed verification", top-k
+ * verification): ranks[b][i], i > 0, = the number of vocabulary entries that the verifier puts
+ * before tokens[b][i] in the distribution emitted at node i's parent (larger logit, or equal
+ * logit and lower token id); 0 = the parent's argmax; -1 for the root and for token ids outside
+ * [0, vocab).  A pure function of materialised logits:
+ *   logits        device [batch, n_nodes, vocab] fp32 (trispec_verify's debug_logits buffer)
+ *   draft_tokens  device [batch, n_nodes];  tree_parents  HOST [batch, n_nodes]
+ *   ranks         device [batch, n_nodes] int32, written when `stream` reaches the kernel
+ * Feed it to trispec_decide through opts->draft_ranks with opts->accept_top_k = k.
+ * Errors: TRISPEC_ENULL, TRISPEC_ENODES, TRISPEC_ETREE, TRISPEC_EARG (vocab < 1), TRISPEC_ELAUNCH.
+ */
+int trispec_draft_ranks(const float *logits, const int32_t *draft_tokens, const int32_t *tree_parents,
+                        int32_t batch, int32_t n_nodes, int32_t vocab, int32_t *ranks, void *stream);
 
 /* Test hooks of the bounded device-side wait.  trispec_debug_set_spin_limit: longest wait of any
  * later call, in ticks of the 100 MHz wall clock (0 restores the default of 2 s).

@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtrispec.so")
 
 TRISPEC_F32, TRISPEC_BF16 = 0, 1
-CRIT_MARGIN, CRIT_TOP1 = 0, 1
+CRIT_MARGIN, CRIT_TOP1, CRIT_ENTROPY = 0, 1, 2
 RESAMPLE_RESIDUAL, RESAMPLE_DIRECT = 0, 1
 MAX_NODES, MAX_BATCH, MAX_ROWS, PATH_STRIDE = 64, 8, 256, 64
 
@@ -30,7 +30,7 @@ EXPORTS = [
     "trispec_timer_destroy", "trispec_model_pack_bytes", "trispec_model_pack", "trispec_copy_probe",
     "trispec_kv_commit", "trispec_sample_scratch_bytes", "trispec_sample_decide",
     "trispec_sample_decide_static", "trispec_debug_set_spin_limit", "trispec_wait_probe",
-    "trispec_prune_reroot",
+    "trispec_prune_reroot", "trispec_draft_ranks",
 ]
 K_GEMM, K_HEAD, K_ATTN = 0, 1, 2
 LAUNCH_PER_MATMUL, LAUNCH_PER_LAYER = 0, 1
@@ -54,12 +54,12 @@ class VerifyOpts(C.Structure):
     _fields_ = [("criterion", C.c_int32), ("n_forced", C.c_int32), ("workspace", C.c_void_p),
                 ("workspace_bytes", C.c_size_t), ("debug_logits", C.c_void_p), ("stream", C.c_void_p),
                 ("timer", C.c_void_p), ("hidden_out", C.c_void_p), ("launch_mode", C.c_int32),
-                ("stamps", C.c_void_p)]
+                ("draft_ranks", C.c_void_p), ("accept_top_k", C.c_int32), ("stamps", C.c_void_p)]
 
 
 class VerifyOut(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in
-                ("accepted_len", "token", "escalate", "path", "argmax", "confidence", "margin", "status")]
+                ("accepted_len", "token", "escalate", "path", "argmax", "confidence", "margin", "entropy", "status")]
 
 
 class SampleOpts(C.Structure):
@@ -121,6 +121,8 @@ def lib() -> C.CDLL:
         _pi = C.POINTER(C.c_int32)
         l.trispec_prune_reroot.argtypes = [_pi, _pi, _pi, C.c_int32, _pi, C.c_int32, _pi, C.c_int32, C.c_int32,
                                            _pi, _pi, _pi, _pi, _pi, _pi]
+        l.trispec_draft_ranks.argtypes = [C.c_void_p, C.c_void_p, _pi, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                          C.c_void_p]
         l.trispec_timer_create.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]
         l.trispec_timer_reset.argtypes = [C.c_void_p]
         l.trispec_timer_read.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_double),
@@ -342,7 +344,8 @@ class SampleDecider:
             "accepted_len": torch.zeros(batch, **i32), "token": torch.zeros(batch, **i32),
             "escalate": torch.zeros(batch, **i32), "path": torch.zeros((batch, PATH_STRIDE), **i32),
             "argmax": torch.zeros((batch, n_nodes), **i32), "confidence": torch.zeros((batch, n_nodes), **f32),
-            "margin": torch.zeros((batch, n_nodes), **f32), "status": torch.zeros(1, **i32),
+            "margin": torch.zeros((batch, n_nodes), **f32), "entropy": torch.zeros((batch, n_nodes), **f32),
+            "status": torch.zeros(1, **i32),
         }
         self._out = VerifyOut(*[self.out[k].data_ptr() for k, _ in VerifyOut._fields_])
 
@@ -399,11 +402,14 @@ class Verifier:
             "accepted_len": torch.zeros(batch, **i32), "token": torch.zeros(batch, **i32),
             "escalate": torch.zeros(batch, **i32), "path": torch.zeros((batch, PATH_STRIDE), **i32),
             "argmax": torch.zeros((batch, max_nodes), **i32), "confidence": torch.zeros((batch, max_nodes), **f32),
-            "margin": torch.zeros((batch, max_nodes), **f32), "status": torch.zeros(1, **i32),
+            "margin": torch.zeros((batch, max_nodes), **f32), "entropy": torch.zeros((batch, max_nodes), **f32),
+            "status": torch.zeros(1, **i32),
         }
         self.logits = torch.zeros((batch, max_nodes, model.cfg.vocab), **f32) if debug_logits else None
         self.hidden = torch.zeros((batch, max_nodes, model.cfg.hidden), **f32) if export_hidden else None
         self.timer = None   # optional KernelTimer attached to every verify call
+        self.ranks = None   # int32 [batch, max_nodes], filled by draft_ranks()
+        self.accept_top_k = 0
         self.launch_mode = LAUNCH_PER_MATMUL
         self.stamps = None  # optional int64 device tensor [n_layers, 16] (phase time stamps of the layer launches)
 
@@ -417,6 +423,8 @@ class Verifier:
         o.timer = self.timer.handle if self.timer is not None else None
         o.hidden_out = self.hidden.data_ptr() if self.hidden is not None else None
         o.launch_mode = self.launch_mode
+        o.draft_ranks = self.ranks.data_ptr() if (self.ranks is not None and self.accept_top_k > 1) else None
+        o.accept_top_k = self.accept_top_k if self.ranks is not None else 0
         o.stamps = self.stamps.data_ptr() if self.stamps is not None else None
         return o
 
@@ -449,6 +457,18 @@ class Verifier:
                                    par.ctypes.data_as(C.POINTER(C.c_int32)), n_nodes, float(threshold),
                                    C.byref(opts), C.byref(out)))
         return self.out
+
+    def draft_ranks(self, draft_tokens: torch.Tensor, tree_parents: np.ndarray, stream=None) -> torch.Tensor:
+        """trispec_draft_ranks on the logits of the last verify call (needs debug_logits=True)."""
+        assert self.logits is not None, "draft_ranks needs the materialised logits (debug_logits=True)"
+        if self.ranks is None:
+            self.ranks = torch.zeros((self.batch, self.max_nodes), dtype=torch.int32, device=self.logits.device)
+        par = np.ascontiguousarray(tree_parents, dtype=np.int32)
+        s = stream if stream is not None else torch.cuda.current_stream()
+        check(lib().trispec_draft_ranks(self.logits.data_ptr(), draft_tokens.data_ptr(),
+                                        par.ctypes.data_as(C.POINTER(C.c_int32)), self.batch, self.max_nodes,
+                                        self.model.cfg.vocab, self.ranks.data_ptr(), s.cuda_stream))
+        return self.ranks
 
     def region(self, name: str, n_nodes: Optional[int] = None) -> torch.Tensor:
         """Raw bytes of a named workspace region (test hook)."""

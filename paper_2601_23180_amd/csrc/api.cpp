@@ -71,8 +71,8 @@ int rows_pad_for(int rows) {
 
 // Workspace regions, in order.  Offsets are a pure function of (model, batch, n_nodes).
 struct Layout {
-  size_t anc, parent, status, cos_t, sin_t, x, x2, h, h2, q, qkv_f32, attn_out, act, part, counters, ss_part, attn_o, attn_m, attn_l, head_l1, head_l2, head_sum, head_idx, node_l1, node_l2, node_sum,
-      node_idx, logits, total;
+  size_t anc, parent, status, cos_t, sin_t, x, x2, h, h2, q, qkv_f32, attn_out, act, part, counters, ss_part, attn_o, attn_m, attn_l, head_l1, head_l2, head_sum, head_ent, head_idx, node_l1, node_l2, node_sum,
+      node_ent, node_idx, logits, total;
   int rows_max, rows_pad_max, head_tiles, max_tiles;
   // `counters` holds, in this order: max_tiles + 1 tile counters of the split-K matmuls, kLayerPhases
   // barrier counters per layer, the abort word — n_zero ints that the set-up kernel clears
@@ -206,10 +206,12 @@ Layout make_layout(const trispec_model_config &c, int batch, int max_nodes) {
   L.head_l1 = take(sizeof(float) * hs);
   L.head_l2 = take(sizeof(float) * hs);
   L.head_sum = take(sizeof(float) * hs);
+  L.head_ent = take(sizeof(float) * hs);
   L.head_idx = take(sizeof(int32_t) * hs);
   L.node_l1 = take(sizeof(float) * kMaxRows);
   L.node_l2 = take(sizeof(float) * kMaxRows);
   L.node_sum = take(sizeof(float) * kMaxRows);
+  L.node_ent = take(sizeof(float) * kMaxRows);
   L.node_idx = take(sizeof(int32_t) * kMaxRows);
   L.logits = take(f32 ? sizeof(float) * (size_t)rows * c.vocab : 0);
   L.total = off;
@@ -249,8 +251,10 @@ int build_nodes(const int32_t *parents, int batch, int n_nodes, int n_forced, No
 
 int check_opts(const trispec_verify_opts *o, float threshold) {
   if (!o) return TRISPEC_ENULL;
-  if (o->criterion != TRISPEC_CRIT_MARGIN && o->criterion != TRISPEC_CRIT_TOP1) return TRISPEC_EARG;
+  if (o->criterion != TRISPEC_CRIT_MARGIN && o->criterion != TRISPEC_CRIT_TOP1 && o->criterion != TRISPEC_CRIT_ENTROPY)
+    return TRISPEC_EARG;
   if (threshold != threshold) return TRISPEC_EARG;
+  if (o->accept_top_k < 0 || (o->accept_top_k > 1 && !o->draft_ranks)) return TRISPEC_EARG;
   if (!o->workspace) return TRISPEC_EWORKSPACE;
   if (((uintptr_t)o->workspace) & 255) return TRISPEC_EWORKSPACE;
   return TRISPEC_OK;
@@ -269,6 +273,9 @@ DecideArgs make_decide(const Layout &L, char *ws, const int32_t *tokens, int bat
   d.node_l1 = (float *)(ws + L.node_l1);
   d.node_l2 = (float *)(ws + L.node_l2);
   d.node_sum = (float *)(ws + L.node_sum);
+  d.node_ent = (float *)(ws + L.node_ent);
+  d.draft_ranks = o->draft_ranks;
+  d.accept_top_k = o->accept_top_k;
   d.node_idx = (int32_t *)(ws + L.node_idx);
   d.status_src = (const int32_t *)(ws + L.status);
   d.out = *out;
@@ -442,6 +449,7 @@ int trispec_workspace_region(const trispec_model *m, int32_t batch, int32_t max_
       {"node_l1", L.node_l1, sizeof(float) * kMaxRows},
       {"node_l2", L.node_l2, sizeof(float) * kMaxRows},
       {"node_sum", L.node_sum, sizeof(float) * kMaxRows},
+      {"node_ent", L.node_ent, sizeof(float) * kMaxRows},
       {"node_idx", L.node_idx, sizeof(int32_t) * kMaxRows},
   };
   for (auto &t : tab)
@@ -515,6 +523,7 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
   hs.l1 = (float *)(ws + L.head_l1);
   hs.l2 = (float *)(ws + L.head_l2);
   hs.sumexp = (float *)(ws + L.head_sum);
+  hs.ent = (float *)(ws + L.head_ent);
   hs.idx = (int32_t *)(ws + L.head_idx);
   hs.n_tiles = L.head_tiles;
 
@@ -791,7 +800,7 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
   }
 
   launch_stats_reduce(st, hs, rows, (float *)(ws + L.node_l1), (float *)(ws + L.node_l2),
-                      (float *)(ws + L.node_sum), (int32_t *)(ws + L.node_idx));
+                      (float *)(ws + L.node_sum), (float *)(ws + L.node_ent), (int32_t *)(ws + L.node_idx));
   DecideArgs d = make_decide(L, ws, draft_tokens, B, n_nodes, threshold, opts, out);
   launch_decide(st, d);
   return hipGetLastError() == hipSuccess ? TRISPEC_OK : TRISPEC_ELAUNCH;
@@ -1039,6 +1048,21 @@ int trispec_kv_commit(trispec_kv *kv, const int32_t *nodes_host, const int32_t *
   }
   for (int b = 0; b < kv->batch; ++b) kv->ctx_len[b] += t.n[b];
   return TRISPEC_OK;
+}
+
+int trispec_draft_ranks(const float *logits, const int32_t *draft_tokens, const int32_t *tree_parents, int32_t batch,
+                        int32_t n_nodes, int32_t vocab, int32_t *ranks, void *stream) {
+  if (!logits || !draft_tokens || !tree_parents || !ranks) return TRISPEC_ENULL;
+  if (batch < 1 || batch > kMaxBatch || n_nodes < 1 || n_nodes > kMaxNodes || batch * n_nodes > kMaxRows)
+    return TRISPEC_ENODES;
+  if (vocab < 1) return TRISPEC_EARG;
+  NodeTable tab;
+  memset(&tab, 0, sizeof(tab));
+  const int rc = build_nodes(tree_parents, batch, n_nodes, 1, tab);
+  if (rc) return rc;
+  (void)hipGetLastError();
+  launch_draft_ranks((hipStream_t)stream, logits, draft_tokens, tab, batch, n_nodes, vocab, ranks);
+  return hipGetLastError() == hipSuccess ? TRISPEC_OK : TRISPEC_ELAUNCH;
 }
 
 int trispec_debug_set_spin_limit(uint64_t ticks) {

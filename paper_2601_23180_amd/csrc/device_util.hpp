@@ -158,13 +158,15 @@ __device__ __forceinline__ float block_sum(float v, float *red) {
 
 // Running (largest, its column, second largest, sum of exp relative to the largest) of a set of
 // logits.  Among equal maxima the lowest column wins, in push order and in any merge order.
+// t = sum of exp(l - l1) * (l - l1) rides along for the entropy: with d = l - l1 and s = sum e^d,
+// p = e^d / s and H = -sum p ln p = ln s - t / s.
 struct Top2 {
-  float l1, l2, s;
+  float l1, l2, s, t;
   int idx;
 };
 __device__ __forceinline__ Top2 top2_empty() {
   Top2 t;
-  t.l1 = -INFINITY; t.l2 = -INFINITY; t.s = 0.f; t.idx = 0x7fffffff;
+  t.l1 = -INFINITY; t.l2 = -INFINITY; t.s = 0.f; t.t = 0.f; t.idx = 0x7fffffff;
   return t;
 }
 __device__ __forceinline__ Top2 top2_merge(const Top2 &a, const Top2 &b) {
@@ -172,23 +174,35 @@ __device__ __forceinline__ Top2 top2_merge(const Top2 &a, const Top2 &b) {
   if (a.l1 == -INFINITY) return b;
   Top2 r;
   if (b.l1 > a.l1 || (b.l1 == a.l1 && b.idx < a.idx)) {
+    const float d = a.l1 - b.l1, e = expf(d);     // a's terms move down by d <= 0
     r.l1 = b.l1; r.idx = b.idx;
     r.l2 = fmaxf(a.l1, b.l2);
-    r.s = a.s * expf(a.l1 - b.l1) + b.s;
+    r.s = a.s * e + b.s;
+    r.t = (a.t + a.s * d) * e + b.t;
   } else {
+    const float d = b.l1 - a.l1, e = expf(d);
     r.l1 = a.l1; r.idx = a.idx;
     r.l2 = fmaxf(b.l1, a.l2);
-    r.s = a.s + b.s * expf(b.l1 - a.l1);
+    r.s = a.s + b.s * e;
+    r.t = a.t + (b.t + b.s * d) * e;
   }
   return r;
 }
 __device__ __forceinline__ void top2_push(Top2 &t, float v, int col) {
   // columns arrive in ascending order
   if (v > t.l1) {
-    t.s = (t.l1 == -INFINITY) ? 1.f : t.s * expf(t.l1 - v) + 1.f;
+    if (t.l1 == -INFINITY) {
+      t.s = 1.f; t.t = 0.f;
+    } else {
+      const float d = t.l1 - v, e = expf(d);
+      t.t = (t.t + t.s * d) * e;                 // the new maximum itself adds e^0 * 0
+      t.s = t.s * e + 1.f;
+    }
     t.l2 = t.l1; t.l1 = v; t.idx = col;
   } else if (v != -INFINITY) {
-    t.s += expf(v - t.l1);
+    const float d = v - t.l1, e = expf(d);
+    t.s += e;
+    t.t += e * d;
     t.l2 = fmaxf(t.l2, v);
   }
 }
@@ -197,6 +211,7 @@ __device__ __forceinline__ Top2 top2_shfl_xor(const Top2 &t, int o) {
   r.l1 = __shfl_xor(t.l1, o, 64);
   r.l2 = __shfl_xor(t.l2, o, 64);
   r.s = __shfl_xor(t.s, o, 64);
+  r.t = __shfl_xor(t.t, o, 64);
   r.idx = __shfl_xor(t.idx, o, 64);
   return r;
 }

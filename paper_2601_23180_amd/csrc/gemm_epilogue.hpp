@@ -105,7 +105,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, f32x16 (&acc)[N
         for (int o = 1; o < PARTS; o <<= 1) t = top2_merge(t, top2_shfl_xor(t, o));
         if (part == 0 && r < a.rows) {
           const size_t o = (size_t)r * a.hs.n_tiles + tile;
-          a.hs.l1[o] = t.l1; a.hs.l2[o] = t.l2; a.hs.sumexp[o] = t.s; a.hs.idx[o] = t.idx;
+          a.hs.l1[o] = t.l1; a.hs.l2[o] = t.l2; a.hs.sumexp[o] = t.s; a.hs.ent[o] = t.t; a.hs.idx[o] = t.idx;
         }
       }
     }

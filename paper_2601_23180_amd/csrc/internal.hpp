@@ -40,6 +40,7 @@ struct HeadStats {
   float *l1;      // largest logit
   float *l2;      // second largest logit (-inf if none)
   float *sumexp;  // sum over the tile of exp(logit - l1)
+  float *ent;     // sum over the tile of exp(logit - l1) * (logit - l1)   (entropy = ln sum - ent / sum)
   int32_t *idx;   // column of l1 (lowest column among equals)
   int32_t n_tiles;
 };
@@ -173,8 +174,10 @@ struct DecideArgs {
   int32_t batch, n_nodes, n_forced, criterion;
   float threshold;
   // per-node statistics (workspace)
-  float *node_l1, *node_l2, *node_sum;
+  float *node_l1, *node_l2, *node_sum, *node_ent;
   int32_t *node_idx;
+  const int32_t *draft_ranks;   // [B*M] or nullptr: rank of each node's token in its parent's distribution
+  int32_t accept_top_k;         // > 1: a child is followed when its rank is below it (needs draft_ranks)
   const int32_t *status_src;   // device status word of the pass (workspace)
   trispec_verify_out out;
 };
@@ -220,7 +223,11 @@ void launch_stats_from_logits(hipStream_t st, const float *logits, int rows, int
 void launch_attn_f32(hipStream_t st, const AttnArgs &a);
 void launch_attn_bf16(hipStream_t st, const AttnArgs &a);
 void launch_stats_reduce(hipStream_t st, const HeadStats &hs, int rows, float *node_l1, float *node_l2,
-                         float *node_sum, int32_t *node_idx);
+                         float *node_sum, float *node_ent, int32_t *node_idx);
+// rank[r] of node r > 0 of every sequence: vocabulary entries that precede tokens[r] in the logits of
+// its parent's row (larger, or equal with a lower id); -1 for roots and token ids outside the vocabulary
+void launch_draft_ranks(hipStream_t st, const float *logits, const int32_t *tokens, const NodeTable &tab,
+                        int batch, int n_nodes, int vocab, int32_t *ranks);
 void launch_decide(hipStream_t st, const DecideArgs &a);
 
 }  // namespace ts

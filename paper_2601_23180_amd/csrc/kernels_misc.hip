@@ -304,7 +304,7 @@ __global__ __launch_bounds__(256) void k_stats_from_logits(const float *logits, 
   if (threadIdx.x == 0) {
     Top2 a = sm[0];
     for (int w = 1; w < 4; ++w) a = top2_merge(a, sm[w]);
-    hs.l1[r] = a.l1; hs.l2[r] = a.l2; hs.sumexp[r] = a.s; hs.idx[r] = a.idx;
+    hs.l1[r] = a.l1; hs.l2[r] = a.l2; hs.sumexp[r] = a.s; hs.ent[r] = a.t; hs.idx[r] = a.idx;
   }
 }
 
@@ -318,7 +318,7 @@ void launch_stats_from_logits(hipStream_t st, const float *logits, int rows, int
 // butterfly per wavefront and the wavefronts in ascending order.
 constexpr int kStatsThreads = 1024;
 __global__ __launch_bounds__(kStatsThreads) void k_stats_reduce(HeadStats hs, float *node_l1, float *node_l2,
-                                                                float *node_sum, int32_t *node_idx) {
+                                                                float *node_sum, float *node_ent, int32_t *node_idx) {
   __shared__ Top2 s_w[kStatsThreads / 64];
   const int r = blockIdx.x, tid = threadIdx.x;
   Top2 t = top2_empty();
@@ -328,7 +328,7 @@ __global__ __launch_bounds__(kStatsThreads) void k_stats_reduce(HeadStats hs, fl
     for (int u = 0; u < 4; ++u) {
       const int i = i0 + u * kStatsThreads;
       const size_t o = (size_t)r * hs.n_tiles + min(i, hs.n_tiles - 1);
-      b[u].l1 = hs.l1[o]; b[u].l2 = hs.l2[o]; b[u].s = hs.sumexp[o]; b[u].idx = hs.idx[o];
+      b[u].l1 = hs.l1[o]; b[u].l2 = hs.l2[o]; b[u].s = hs.sumexp[o]; b[u].t = hs.ent[o]; b[u].idx = hs.idx[o];
       if (i >= hs.n_tiles) b[u] = top2_empty();
     }
 #pragma unroll
@@ -341,14 +341,44 @@ __global__ __launch_bounds__(kStatsThreads) void k_stats_reduce(HeadStats hs, fl
   if (tid == 0) {
     t = s_w[0];
     for (int w = 1; w < kStatsThreads / 64; ++w) t = top2_merge(t, s_w[w]);
-    node_l1[r] = t.l1; node_l2[r] = t.l2; node_sum[r] = t.s; node_idx[r] = t.idx;
+    node_l1[r] = t.l1; node_l2[r] = t.l2; node_sum[r] = t.s; node_ent[r] = t.t; node_idx[r] = t.idx;
   }
 }
 
 void launch_stats_reduce(hipStream_t st, const HeadStats &hs, int rows, float *node_l1, float *node_l2,
-                         float *node_sum, int32_t *node_idx) {
+                         float *node_sum, float *node_ent, int32_t *node_idx) {
   hipLaunchKernelGGL(k_stats_reduce, dim3(rows), dim3(kStatsThreads), 0, st, hs, node_l1, node_l2, node_sum,
-                     node_idx);
+                     node_ent, node_idx);
+}
+
+// One workgroup per node: count the vocabulary entries that precede the node's token in its
+// parent's row of logits (exact integer sum: any order gives the same count).
+__global__ __launch_bounds__(256) void k_draft_ranks(const float *logits, const int32_t *tokens, NodeTable tab,
+                                                     int n_nodes, int vocab, int32_t *ranks) {
+  __shared__ int red[4];
+  const int r = blockIdx.x, tid = threadIdx.x;
+  const int b = r / n_nodes, par = tab.parent[r], x = tokens[r];
+  if (par < 0 || x < 0 || x >= vocab) {   // uniform over the workgroup
+    if (tid == 0) ranks[r] = -1;
+    return;
+  }
+  const float *row = logits + (size_t)(b * n_nodes + par) * vocab;
+  const float lx = row[x];
+  int n = 0;
+  for (int c = tid; c < vocab; c += 256) {
+    const float v = row[c];
+    n += (v > lx) || (v == lx && c < x);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) n += __shfl_xor(n, o, 64);
+  if ((tid & 63) == 0) red[tid >> 6] = n;
+  __syncthreads();
+  if (tid == 0) ranks[r] = red[0] + red[1] + red[2] + red[3];
+}
+
+void launch_draft_ranks(hipStream_t st, const float *logits, const int32_t *tokens, const NodeTable &tab,
+                        int batch, int n_nodes, int vocab, int32_t *ranks) {
+  hipLaunchKernelGGL(k_draft_ranks, dim3(batch * n_nodes), dim3(256), 0, st, logits, tokens, tab, n_nodes, vocab, ranks);
 }
 
 // ------------------------------------------------------------------ decision
@@ -356,8 +386,8 @@ void launch_stats_reduce(hipStream_t st, const HeadStats &hs, int rows, float *n
 // at the current node test the trust predicate first (tau_a = tau_m is an escalation), then
 // follow the lowest-numbered child whose draft token equals the verifier's argmax.
 __global__ __launch_bounds__(64) void k_decide(DecideArgs a) {
-  __shared__ float s_conf[kMaxNodes], s_margin[kMaxNodes];
-  __shared__ int s_arg[kMaxNodes], s_tok[kMaxNodes], s_par[kMaxNodes];
+  __shared__ float s_conf[kMaxNodes], s_margin[kMaxNodes], s_ent[kMaxNodes];
+  __shared__ int s_arg[kMaxNodes], s_tok[kMaxNodes], s_par[kMaxNodes], s_rank[kMaxNodes];
   const int b = blockIdx.x, i = threadIdx.x, M = a.n_nodes;
   if (i < M) {
     const int r = b * M + i;
@@ -366,25 +396,32 @@ __global__ __launch_bounds__(64) void k_decide(DecideArgs a) {
     const float p2 = expf(a.node_l2[r] - a.node_l1[r]) / s;        // 0 when there is no second entry
     s_conf[i] = conf;
     s_margin[i] = conf - p2;
+    s_ent[i] = logf(s) - a.node_ent[r] / s;                        // ln sum e^d - sum e^d d / sum e^d
+    s_rank[i] = a.draft_ranks != nullptr ? a.draft_ranks[r] : -1;
     s_arg[i] = a.node_idx[r];
     s_tok[i] = a.tokens[r];
     s_par[i] = a.parent[r];
     if (a.out.argmax) a.out.argmax[r] = s_arg[i];
     if (a.out.confidence) a.out.confidence[r] = conf;
     if (a.out.margin) a.out.margin[r] = s_margin[i];
+    if (a.out.entropy) a.out.entropy[r] = s_ent[i];
   }
   if (a.out.path) a.out.path[b * TRISPEC_PATH_STRIDE + i] = -1;
   __syncthreads();
   if (i != 0) return;
   int cur = a.n_forced - 1, acc = 0, token = -1, esc = 0;
   if (a.out.path) a.out.path[b * TRISPEC_PATH_STRIDE] = cur;
+  const bool relaxed = a.accept_top_k > 1 && a.draft_ranks != nullptr;
   for (int step = 0; step <= M; ++step) {
-    const float stat = (a.criterion == TRISPEC_CRIT_MARGIN) ? s_margin[cur] : s_conf[cur];
-    if (!(stat >= a.threshold)) { esc = 1; token = -1; break; }
+    // trusted: statistic on the right side of the threshold (a NaN statistic is never trusted)
+    const bool trusted = a.criterion == TRISPEC_CRIT_ENTROPY
+                             ? (s_ent[cur] <= a.threshold)
+                             : ((a.criterion == TRISPEC_CRIT_MARGIN ? s_margin[cur] : s_conf[cur]) >= a.threshold);
+    if (!trusted) { esc = 1; token = -1; break; }
     const int t = s_arg[cur];
     int nxt = -1;
     for (int c = cur + 1; c < M; ++c)
-      if (s_par[c] == cur && s_tok[c] == t) { nxt = c; break; }
+      if (s_par[c] == cur && (relaxed ? (s_rank[c] >= 0 && s_rank[c] < a.accept_top_k) : s_tok[c] == t)) { nxt = c; break; }
     if (nxt < 0) { token = t; break; }
     cur = nxt;
     ++acc;

@@ -3,7 +3,7 @@ HIP path and the oracle on the same inputs."""
 import numpy as np
 import torch
 
-from oracle import (CRIT_MARGIN, OracleWeights, causal_forward, decide, node_stats, tie_flags,
+from oracle import (CRIT_ENTROPY, CRIT_MARGIN, OracleWeights, causal_forward, decide, node_stats, tie_flags,
                     verify_forward)
 from paper_2601_23180_amd import KVCache, Model, Verifier, fill_kv_layer, model_from_arrays
 from workloads import WeightSource, gen_kv_cache, tree_depths
@@ -75,7 +75,7 @@ class Case:
 def oracle_decision(case, oracle_out, b, threshold, criterion, n_forced=1):
     st = oracle_out[b]["stats"]
     return decide(case.tokens[b], case.parents[b], st["argmax"], st["conf"], st["margin"], threshold,
-                  criterion, n_forced)
+                  criterion, n_forced, entropy=st["entropy"])
 
 
 def tie_resolutions(case, oracle_out, b, threshold, criterion, n_forced, nodes, tol=1e-3):
@@ -84,7 +84,7 @@ def tie_resolutions(case, oracle_out, b, threshold, criterion, n_forced, nodes, 
     logits within tol of each other either may be the argmax."""
     import itertools
     st = oracle_out[b]["stats"]
-    stat = st["margin"] if criterion == CRIT_MARGIN else st["conf"]
+    stat = st["entropy"] if criterion == CRIT_ENTROPY else (st["margin"] if criterion == CRIT_MARGIN else st["conf"])
     logits = oracle_out[b]["logits"]
     options = []
     for i in nodes:
@@ -97,16 +97,17 @@ def tie_resolutions(case, oracle_out, b, threshold, criterion, n_forced, nodes, 
         options.append([tuple(f for k, f in enumerate(flips) if m >> k & 1) for m in range(1 << len(flips))])
     out = []
     for combo in itertools.islice(itertools.product(*options), 256):
-        argmax, conf, margin = st["argmax"].copy(), st["conf"].copy(), st["margin"].copy()
+        argmax, conf, margin, ent = st["argmax"].copy(), st["conf"].copy(), st["margin"].copy(), st["entropy"].copy()
         for c in combo:
             for kind, i in c:
                 if kind == "g":       # the other side of the threshold
-                    trusted = stat[i] >= threshold
-                    conf[i] = margin[i] = (threshold - 1.0) if trusted else (threshold + 1.0)
+                    conf[i] = margin[i] = (threshold - 1.0) if stat[i] >= threshold else (threshold + 1.0)
+                    ent[i] = (threshold + 1.0) if stat[i] <= threshold else (threshold - 1.0)
                 else:                 # the runner-up as the argmax
                     order = np.argsort(-logits[i], kind="stable")
                     argmax[i] = order[1]
-        out.append(decide(case.tokens[b], case.parents[b], argmax, conf, margin, threshold, criterion, n_forced))
+        out.append(decide(case.tokens[b], case.parents[b], argmax, conf, margin, threshold, criterion, n_forced,
+                          entropy=ent))
     return out
 
 

@@ -14,8 +14,8 @@ import numpy as np
 import pytest
 import torch
 
-from oracle import (CRIT_MARGIN, CRIT_TOP1, bf16_round, decide, node_stats, prune_reroot, tie_flags,
-                    verify_forward)
+from oracle import (CRIT_ENTROPY, CRIT_MARGIN, CRIT_TOP1, bf16_round, decide, draft_ranks, node_stats, prune_reroot,
+                    tie_flags, verify_forward)
 from workloads import (SHAPES, ModelShape, gen_chain, gen_context_tokens, gen_draft_tokens,
                        gen_eagle2_tree, gen_tree, tree_depths)
 from helpers import oracle_weights, path_to, prefill
@@ -37,6 +37,7 @@ def stats_ok(gpu, oracle_out, b):
     st = oracle_out[b]["stats"]
     assert np.abs(gpu["confidence"][b] - st["conf"]).max() <= 1e-3
     assert np.abs(gpu["margin"][b] - st["margin"]).max() <= 1e-3
+    assert np.abs(gpu["entropy"][b] - st["entropy"]).max() <= 1e-3
 
 
 def make_case(shape, seed, ctx_lens, parents_list, start_pos=0, plant=None):
@@ -82,6 +83,17 @@ def full_check(case, thresholds=(0.0, 0.3, 0.5, 0.9, 1.5), n_forced=1, launch_mo
             torch.cuda.synchronize()
             res = {k: v.cpu().numpy() for k, v in out.items()}
             excused += compare_decisions(case, res, oracle_out, lam, crit, n_forced)
+    # entropy criterion (trusted when the entropy is AT MOST the threshold): none, some, all nodes trusted
+    ents = np.concatenate([o["stats"]["entropy"] for o in oracle_out])
+    for lam in (-1.0, float(np.quantile(ents, 0.3)), float(np.quantile(ents, 0.7)), 1e3):
+        out = ver.decide(tok, case.parents, lam, CRIT_ENTROPY, n_forced)
+        torch.cuda.synchronize()
+        res = {k: v.cpu().numpy() for k, v in out.items()}
+        excused += compare_decisions(case, res, oracle_out, lam, CRIT_ENTROPY, n_forced)
+        if lam < 0:
+            assert np.all(res["escalate"] == 1) and np.all(res["accepted_len"] == 0)
+        if lam > 100:
+            assert np.all(res["escalate"] == 0)
     return gpu, oracle_out, excused
 
 
@@ -258,6 +270,56 @@ def test_bounded_wait_gives_up_and_reports():
     assert lib.trispec_wait_probe(p, 5, 2_000_000, p + 4, p + 8, st) == 0
     torch.cuda.synchronize()
     assert buf.tolist()[:3] == [5, 0, 0]
+
+
+def test_draft_ranks_and_top_k_acceptance():
+    """Relaxed verification of the appendix: the rank of every draft token in its parent's
+    distribution (a pure function of the pass's logits: the same fp32 logits go to both sides, so the
+    integers must be equal), then the walk that follows a child whose token is among the top-k."""
+    shape = TB
+    B, M = 2, 30
+    parents = [gen_tree(M, 6, 4, 60 + b) for b in range(B)]
+    case = make_case(shape, 19, [70, 41], parents)
+    # drafts near the top of the verifier's distribution, so that ranks below k do occur: the oracle's
+    # own 1st..6th candidates at the parent
+    # (level by level: a node's distribution depends on the tokens above it)
+    rng = np.random.default_rng(3)
+    depth = [tree_depths(p) for p in parents]
+    for lvl in range(1, max(int(d.max()) for d in depth) + 1):
+        oracle_out = case.run_oracle()
+        for b in range(B):
+            order = np.argsort(-oracle_out[b]["logits"], axis=1, kind="stable")
+            for i in np.nonzero(depth[b] == lvl)[0]:
+                case.tokens[b][i] = order[case.parents[b][i], rng.integers(0, 6)]
+    oracle_out = case.run_oracle()
+    gpu = case.run_gpu(0.0)
+    ver, tok = gpu["_ver"], gpu["_tok"]
+    ranks = ver.draft_ranks(tok, case.parents).cpu().numpy()
+    torch.cuda.synchronize()
+    st_all = []
+    for b in range(B):
+        want = draft_ranks(gpu["logits"][b], case.tokens[b], case.parents[b])
+        assert np.array_equal(ranks[b], want), b
+        # against the oracle's own logits: equal unless another logit sits within 1e-3 of the token's
+        ro = draft_ranks(oracle_out[b]["logits"], case.tokens[b], case.parents[b])
+        for i in np.nonzero(ro != want)[0]:
+            row = oracle_out[b]["logits"][case.parents[b][i]]
+            assert np.sum(np.abs(row - row[case.tokens[b][i]]) < 1e-3) > 1, (b, i)
+        assert (want[1:] < 6).mean() > 0.8 and len(set(want[1:].tolist())) >= 4
+        st_all.append(node_stats(gpu["logits"][b]))
+    for k in (1, 2, 4, 100000):
+        ver.accept_top_k = k
+        out = ver.decide(tok, case.parents, 0.0, CRIT_MARGIN)
+        torch.cuda.synchronize()
+        for b in range(B):
+            st = st_all[b]
+            want = decide(case.tokens[b], case.parents[b], st["argmax"], st["conf"], st["margin"], 0.0, CRIT_MARGIN, 1,
+                          ranks=ranks[b], top_k=k)
+            if (st["l1"] - st["l2"])[want["path"]].min() < 1e-3:
+                continue
+            assert out["accepted_len"][b].item() == want["accepted_len"] and out["token"][b].item() == want["token"]
+            assert out["path"][b, : len(want["path"])].tolist() == list(want["path"])
+    ver.accept_top_k = 0
 
 
 def test_decide_walks_the_tree_it_is_given():
