@@ -3,11 +3,23 @@
 
 A step = one trispec_verify() call: the whole hot path (embedding, every layer's projections,
 tree-masked attention and FFN, fused LM head, decision) over one batch of synthetic input that
-is already resident in HBM.  Prints ONE JSON line.
+is already resident in HBM.  Prints ONE JSON line:
+
+* the driver's contract fields (`value` = draft tokens verified per second over the K timed steps);
+* `latency_ms`: median / p10 / p90 of per-pass HIP-event times over 200 more passes;
+* `roofline`: the dominant kernel (the weight-streaming layer matmul) priced against 8 TB/s with
+  HIP events around every launch, and what one event bracket adds to a launch;
+* `kernels`: the same for the LM head and attention;
+* `cpu_baseline` + `parity`: the CPU oracle run once on the SAME inputs on the host cores, its wall
+  time, and the GPU's logits and decisions of this run compared with it;
+* `workloads`: latency and fraction of the HBM roofline of the other workloads (small proxy, the
+  two halves of the ternary pipeline, the long-context batch), and for the pipeline the expected
+  verification time per round t_p + P_esc * t_t at thresholds 0.5 / 0.7 / 0.9.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -20,26 +32,28 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E vendor peak
 
-# name -> (shape key, batch, ctx_len, n_nodes, tree kind)
+# name -> (shape key, batch, ctx_len, n_nodes, tree kind, seed)
 WORKLOADS = {
-    "qwen3_8b_tree60_ctx4096": ("qwen3_8b", 1, 4096, 60, "tree"),        # workload 3 (headline)
-    "qwen3_0p6b_chain8_ctx2048": ("qwen3_0p6b", 1, 2048, 9, "chain"),    # workload 2
-    "qwen3_1p7b_tree60_ctx8192": ("qwen3_1p7b", 1, 8192, 60, "tree"),    # workload 4, proxy
-    "qwen3_8b_tree60_ctx8192": ("qwen3_8b", 1, 8192, 60, "tree"),        # workload 4, target
-    "llama3_8b_b4_tree60_ctx16384": ("llama3_8b", 4, 16384, 60, "tree"),  # workload 5
-    "tiny_bf16_tree60_ctx256": ("tiny_bf16", 1, 256, 60, "tree"),        # plumbing check only
-    "qwen3_8b_4layers_tree60_ctx4096": ("qwen3_8b_L4", 1, 4096, 60, "tree"),  # kernel tuning aid (not a result)
+    "qwen3_8b_tree60_ctx4096": ("qwen3_8b", 1, 4096, 60, "tree", 1003),         # workload 3 (headline)
+    "qwen3_0p6b_chain8_ctx2048": ("qwen3_0p6b", 1, 2048, 9, "chain", 1002),     # workload 2
+    "qwen3_1p7b_tree60_ctx8192": ("qwen3_1p7b", 1, 8192, 60, "tree", 2004),     # workload 4, proxy
+    "qwen3_8b_tree60_ctx8192": ("qwen3_8b", 1, 8192, 60, "tree", 2014),         # workload 4, target
+    "llama3_8b_b4_tree60_ctx16384": ("llama3_8b", 4, 16384, 60, "tree", 1005),  # workload 5
+    "tiny_bf16_tree60_ctx256": ("tiny_bf16", 1, 256, 60, "tree", 7),            # plumbing check only
 }
+EXTRA = ["qwen3_0p6b_chain8_ctx2048", "qwen3_1p7b_tree60_ctx8192", "qwen3_8b_tree60_ctx8192",
+         "llama3_8b_b4_tree60_ctx16384"]
 
 
-def build_inputs(shape, batch, ctx, n_nodes, kind, seed):
+def build_inputs(shape, batch, ctx, n_nodes, kind, seed, model=None, debug_logits=False):
     import torch
     from paper_2601_23180_amd import KVCache, Verifier, fill_kv_layer, model_from_arrays
     from workloads import (WeightSource, gen_chain, gen_draft_tokens, gen_kv_cache, gen_tree, tree_depths)
 
     ws = WeightSource(shape, seed)
     t0 = time.time()
-    model = model_from_arrays(shape, ws.bits if shape.dtype == "bf16" else ws.get)
+    if model is None:
+        model = model_from_arrays(shape, ws.bits if shape.dtype == "bf16" else ws.get)
     cap = (ctx + n_nodes + 63) // 64 * 64
     kv = KVCache(model, batch, cap)
     for l in range(shape.n_layers):
@@ -50,7 +64,7 @@ def build_inputs(shape, batch, ctx, n_nodes, kind, seed):
                         for b in range(batch)])
     tokens = np.stack([gen_draft_tokens(parents[b], shape.vocab, seed + b) for b in range(batch)])
     positions = np.stack([ctx + tree_depths(parents[b]) for b in range(batch)]).astype(np.int32)
-    ver = Verifier(model, batch, n_nodes)
+    ver = Verifier(model, batch, n_nodes, debug_logits=debug_logits)
     tok = torch.from_numpy(tokens).cuda()
     pos = torch.from_numpy(positions).cuda()
     torch.cuda.synchronize()
@@ -58,49 +72,142 @@ def build_inputs(shape, batch, ctx, n_nodes, kind, seed):
                 positions=positions, setup_s=time.time() - t0)
 
 
-def cpu_baseline(shape, batch, ctx, n_nodes, kind, seed):
-    """The oracle as it stands, timed on the host cores on a bounded sample of the workload:
-    the full-width model cut to 2 and to 10 layers (full LM head both times), sequence 0 only,
-    about 10 s of oracle time; the per-layer time is the difference / 8 and the whole pass is
-    extrapolated from it."""
-    from oracle import OracleWeights, verify_forward
-    from workloads import WeightSource, gen_chain, gen_draft_tokens, gen_kv_cache, gen_tree, tree_depths
+def wall_ms(step, steps, warmup):
+    """Mean wall-clock time of `steps` passes, the stream idle on both sides."""
+    import torch
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps * 1e3
+
+
+def event_percentiles(step, n):
+    """Per-pass times from one HIP event pair per pass on the pass's stream (torch's current stream)."""
+    import torch
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+    for a, b in ev:
+        a.record()
+        step()
+        b.record()
+    torch.cuda.synchronize()
+    t = np.array([a.elapsed_time(b) for a, b in ev])
+    return {"n": n, "median": float(np.median(t)), "p10": float(np.percentile(t, 10)),
+            "p90": float(np.percentile(t, 90)), "mean": float(t.mean())}
+
+
+def kernel_classes(ver, step, shape, steps):
+    """HIP events on the pass's stream around every launch of one kernel class, `steps` passes each."""
+    import torch
+    from paper_2601_23180_amd import K_ATTN, K_GEMM, K_HEAD, KernelTimer
+    kernels = {}
+    for cls, name, per_pass in ((K_GEMM, "gemm", 4 * shape.n_layers), (K_HEAD, "lm_head", 1),
+                                (K_ATTN, "attention", shape.n_layers)):
+        timer = KernelTimer(cls, per_pass * steps)
+        ver.timer = timer
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        n, tms, by = timer.read()
+        ver.timer = None
+        kernels[name] = {"launches": n, "avg_us": tms / n * 1e3, "bytes_per_launch": by / n,
+                         "achieved_GBs": by / (tms * 1e-3) / 1e9, "ms_per_pass": tms / steps}
+    return kernels
+
+
+def source_digest():
+    """Digest of the kernel sources: counter summaries under profiles/ carry the digest they were
+    measured at, and are quoted only while it still matches."""
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2601_23180_amd", "csrc")
+    for f in sorted(os.listdir(d)):
+        with open(os.path.join(d, f), "rb") as fh:
+            h.update(f.encode() + b"\0" + fh.read())
+    return h.hexdigest()[:16]
+
+
+def oracle_leg(shape, batch, ctx, n_nodes, kind, seed, inp, threshold, budget_s):
+    """The oracle as it stands on the host cores, on the inputs of this run.  If a one-layer cut
+    says a whole pass fits `budget_s`, the whole pass of sequence 0 is run once and timed, and the
+    GPU's logits and decision of sequence 0 are compared with it; else the model is cut to 2 and
+    to 10 layers at full width and the pass time extrapolated (no parity then)."""
+    import torch
+    from oracle import CRIT_MARGIN, OracleWeights, decide, node_stats, tie_flags, verify_forward
+    from workloads import WeightSource, gen_kv_cache
 
     ws = WeightSource(shape, seed)
-    cache = {}
-
-    def get(name, layer):   # weights generated outside the timed region
-        return cache[(name, layer)]
-
-    for name in ("embed", "lm_head", "final_norm"):
-        cache[(name, 0)] = ws.get(name, 0)
-    cuts = (2, 10) if shape.n_layers >= 10 else (1, min(4, shape.n_layers))
-    for l in range(cuts[1]):
-        for name in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "norm_attn", "norm_ffn"):
-            cache[(name, l)] = ws.get(name, l)
-    kvs = [tuple(a[0] for a in gen_kv_cache(shape, 1, ctx, seed, l)) for l in range(cuts[1])]
-    parents = gen_chain(n_nodes) if kind == "chain" else gen_tree(n_nodes, 8, 4, seed)
-    tokens = gen_draft_tokens(parents, shape.vocab, seed)
-    positions = ctx + tree_depths(parents)
-    W = OracleWeights(get)
-    times = []
-    for nl in cuts:
-        sh = shape.with_(n_layers=nl)
-        t0 = time.perf_counter()
-        verify_forward(W, sh, lambda l: kvs[l][0], lambda l: kvs[l][1], tokens, parents, positions)
-        times.append(time.perf_counter() - t0)
-    per_layer = max((times[1] - times[0]) / (cuts[1] - cuts[0]), 1e-9)
-    full = (times[0] + (shape.n_layers - 1) * per_layer) * batch
+    tokens, parents, positions = inp["tokens"][0], inp["parents"][0], inp["positions"][0]
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = os.cpu_count() or 1
-    return {"value": batch * (n_nodes - 1) / full, "unit": "draft tokens/s", "cores": int(cores),
-            "kind": "oracle", "seconds_per_pass_extrapolated": full,
-            "sample": f"numpy fp64 oracle, sequence 0, model cut to {cuts[0]} and {cuts[1]} layers at full width + "
-                      f"full LM head ({times[0]:.2f}s, {times[1]:.2f}s); per layer = (t{cuts[1]}-t{cuts[0]})/{cuts[1] - cuts[0]}, "
-                      f"pass = t{cuts[0]} + (L-{cuts[0]})*per layer, times batch"}
+    small = ("embed", "lm_head", "final_norm")
+    names = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "norm_attn", "norm_ffn")
+    cache = {(n, 0): ws.get(n, 0) for n in small}
+
+    def need(layers):   # weights and cache of these layers, generated outside the timed regions
+        for l in layers:
+            for n in names:
+                if (n, l) not in cache:
+                    cache[(n, l)] = ws.get(n, l)
+            if ("kv", l) not in cache:
+                k, v = gen_kv_cache(shape, batch, ctx, seed, l)
+                cache[("kv", l)] = (k[0], v[0])
+
+    W = OracleWeights(lambda n, l: cache[(n, l)])
+
+    def run(n_layers):
+        need(range(n_layers))
+        t0 = time.perf_counter()
+        out = verify_forward(W, shape.with_(n_layers=n_layers), lambda l: cache[("kv", l)][0],
+                             lambda l: cache[("kv", l)][1], tokens, parents, positions)
+        return time.perf_counter() - t0, out
+
+    t1, _ = run(1)
+    t2, _ = run(2)
+    per_layer = max(t2 - t1, 1e-9)
+    estimate = t1 + (shape.n_layers - 1) * per_layer
+    base = {"unit": "draft tokens/s", "cores": int(cores), "kind": "oracle"}
+    if estimate > budget_s:
+        cut = min(10, shape.n_layers)
+        tc, _ = run(cut)
+        per_layer = (tc - t2) / max(cut - 2, 1)
+        full = (t2 + (shape.n_layers - 2) * per_layer) * batch
+        base.update({"value": batch * (n_nodes - 1) / full, "seconds_per_pass": full, "extrapolated": True,
+                     "sample": f"numpy fp64 oracle, sequence 0, model cut to 2 and {cut} layers at full width + full LM "
+                               f"head ({t2:.2f}s, {tc:.2f}s); pass = t2 + (L-2) * (t{cut}-t2)/{cut - 2}, times batch "
+                               f"(a whole pass was estimated at {estimate:.0f}s, over the {budget_s:.0f}s allowed)"})
+        return base, None
+    t_full, out = run(shape.n_layers)
+    base.update({"value": batch * (n_nodes - 1) / (t_full * batch), "seconds_per_pass": t_full * batch,
+                 "extrapolated": False,
+                 "sample": f"numpy fp64 oracle, the whole pass of sequence 0 on this run's inputs, once: {t_full:.1f}s"
+                           + (f" (times {batch} sequences)" if batch > 1 else "")})
+    # ---- parity of this run's GPU pass with that oracle pass (sequence 0)
+    ver = inp["ver_logits"]
+    res = ver.verify(inp["kv"], inp["tok"], inp["parents"], inp["pos"], threshold)
+    torch.cuda.synchronize()
+    lg = ver.logits[0].cpu().numpy().astype(np.float64)
+    want = out["logits"]
+    rel = float(np.max(np.abs(lg - want).max(axis=1) / np.abs(want).max(axis=1)))
+    st = node_stats(want)
+    d = decide(tokens, parents, st["argmax"], st["conf"], st["margin"], threshold, CRIT_MARGIN, 1)
+    got_path = [int(v) for v in res["path"][0].cpu().numpy() if v >= 0]
+    same = (int(res["accepted_len"][0]) == d["accepted_len"] and int(res["token"][0]) == d["token"]
+            and int(res["escalate"][0]) == d["escalate"] and got_path == [int(v) for v in d["path"]])
+    flags = tie_flags(st, threshold, CRIT_MARGIN)
+    tied = bool(any(flags[i] for i in set(got_path) | set(int(v) for v in d["path"])))
+    clear = (st["l1"] - st["l2"]) >= 1e-3
+    arg_ok = bool(np.array_equal(res["argmax"][0].cpu().numpy()[clear], st["argmax"][clear]))
+    parity = {"max_rel_logit_err": rel, "logits_within_2e-2": rel <= 2e-2, "argmax_equal_outside_ties": arg_ok,
+              "decision_equal": bool(same), "decision_touches_a_tie": tied,
+              "conf_max_abs_err": float(np.max(np.abs(res["confidence"][0].cpu().numpy() - st["conf"]))),
+              "ok": bool(rel <= 2e-2 and arg_ok and (same or tied))}
+    return base, parity
 
 
 def main():
@@ -109,9 +216,13 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="qwen3_8b_tree60_ctx4096", choices=sorted(WORKLOADS))
-    ap.add_argument("--seed", type=int, default=1003)
+    ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--threshold", type=float, default=0.5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-budget", type=float, default=90.0,
+                    help="longest whole oracle pass (seconds, estimated from a one-layer cut) that is run in full")
+    ap.add_argument("--no-extra-workloads", action="store_true",
+                    help="skip the latency block of the other workloads")
     ap.add_argument("--launch-mode", choices=("per-matmul", "per-layer"), default="per-matmul",
                     help="per-matmul: one launch per matmul (default, the faster cut); per-layer: the matmuls "
                          "between two attention calls as one launch with device-side barriers")
@@ -127,17 +238,19 @@ def main():
     if not os.path.exists(LIB_PATH):     # load what is built; build only if nothing is
         from paper_2601_23180_amd.build import build
         build()
-    from paper_2601_23180_amd import K_ATTN, K_GEMM, K_HEAD, KernelTimer
+    from paper_2601_23180_amd import CRIT_MARGIN, CRIT_TOP1, Verifier
+    from paper_2601_23180_amd.binding import LAUNCH_PER_LAYER, LAUNCH_PER_MATMUL
     from workloads import SHAPES
 
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU (there is no CPU fallback of the product path)")
-    key, batch, ctx, n_nodes, kind = WORKLOADS[args.workload]
-    shape = SHAPES["qwen3_8b"].with_(n_layers=4) if key == "qwen3_8b_L4" else SHAPES[key]
-    inp = build_inputs(shape, batch, ctx, n_nodes, kind, args.seed)
+    key, batch, ctx, n_nodes, kind, wseed = WORKLOADS[args.workload]
+    seed = args.seed if args.seed is not None else wseed
+    shape = SHAPES[key]
+    mode = LAUNCH_PER_LAYER if args.launch_mode == "per-layer" else LAUNCH_PER_MATMUL
+    inp = build_inputs(shape, batch, ctx, n_nodes, kind, seed)
     ver, kv, tok, pos, parents = inp["ver"], inp["kv"], inp["tok"], inp["pos"], inp["parents"]
-    from paper_2601_23180_amd.binding import LAUNCH_PER_LAYER, LAUNCH_PER_MATMUL
-    ver.launch_mode = LAUNCH_PER_LAYER if args.launch_mode == "per-layer" else LAUNCH_PER_MATMUL
+    ver.launch_mode = mode
 
     def step():
         ver.verify(kv, tok, parents, pos, args.threshold, want_logits=False)
@@ -156,31 +269,21 @@ def main():
         with torch.cuda.graph(graph):
             step()
         timed_step = graph.replay
-    for _ in range(args.warmup):
-        timed_step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        timed_step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms = dt / args.steps * 1e3
+    ms = wall_ms(timed_step, args.steps, args.warmup)
     pass_bytes = inp["model"].pass_bytes(batch, n_nodes, [ctx] * batch)
+    latency = event_percentiles(timed_step, 200)
 
-    # per-kernel durations: HIP events on the pass's stream around every launch of one class,
-    # over `steps` more passes each (same inputs, same launch configuration)
-    kernels = {}
-    for cls, name, per_pass in ((K_GEMM, "gemm", 4 * shape.n_layers), (K_HEAD, "lm_head", 1),
-                                (K_ATTN, "attention", shape.n_layers)):
-        timer = KernelTimer(cls, per_pass * args.steps)
-        ver.timer = timer
-        for _ in range(args.steps):
-            step()
-        torch.cuda.synchronize()
-        n, tms, by = timer.read()
-        ver.timer = None
-        kernels[name] = {"launches": n, "avg_us": tms / n * 1e3, "bytes_per_launch": by / n,
-                         "achieved_GBs": by / (tms * 1e-3) / 1e9, "ms_per_pass": tms / args.steps}
+    # per-kernel durations, and what the event brackets add: the same passes with and without them
+    kernels = kernel_classes(ver, step, shape, args.steps)
+    bracketed = kernels["gemm"]["launches"] // args.steps
+    ver.timer = None
+    plain = wall_ms(step, args.steps, 2)
+    from paper_2601_23180_amd import K_GEMM, KernelTimer
+    ver.timer = KernelTimer(K_GEMM, bracketed * (args.steps + 2))
+    with_brackets = wall_ms(step, args.steps, 2)
+    ver.timer = None
+    bracket_us = max(with_brackets - plain, 0.0) * 1e3 / max(bracketed, 1)
+
     # measured streaming ceiling of this card: a plain copy of 1 GiB (read + write counted)
     from paper_2601_23180_amd import copy_probe
     src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
@@ -195,20 +298,27 @@ def main():
     copy_gbs = 5 * 2 * src.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
     del src, dst
 
-    # HBM traffic of the dominant kernel from the committed counter summary of the same command
-    # (two rocprofv3 --pmc runs, scaled by the copy kernel of known size; see profiles/)
-    traffic, traffic_note = None, None
+    # HBM traffic and kernel-trace duration of the dominant kernel from the committed counter summary
+    # of this command (rocprofv3 runs, see profiles/), quoted only if the kernel sources are unchanged
+    traffic = traffic_note = trace_us = None
     tpath = os.path.join(ROOT, "profiles", f"traffic_{args.workload}.json")
+    digest = source_digest()
     if os.path.exists(tpath):
         with open(tpath) as f:
             tj = json.load(f)
-        traffic, traffic_note = tj.get("gemm_bytes_per_launch"), tj.get("source")
+        if tj.get("source_digest") == digest:
+            traffic, trace_us = tj.get("gemm_bytes_per_launch"), tj.get("gemm_trace_avg_us")
+            traffic_note = tj.get("source")
+        else:
+            traffic_note = "profiles/ summary was measured on other kernel sources: not quoted"
 
     g = kernels["gemm"]
     roofline = {"bound": "hbm", "kernel": "k_gemm_bf16 (weight-streaming projection / FFN matmul)",
                 "achieved": g["achieved_GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": g["achieved_GBs"] / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_note,
-                "avg_launch_us": g["avg_us"], "bytes_per_launch": g["bytes_per_launch"]}
+                "avg_launch_us": g["avg_us"], "bytes_per_launch": g["bytes_per_launch"],
+                "event_bracket_adds_us": bracket_us, "rocprof_trace_avg_us": trace_us,
+                "source_digest": digest}
 
     out = {
         "metric": "draft_tokens_verified_per_sec", "value": batch * (n_nodes - 1) / (ms * 1e-3),
@@ -216,8 +326,10 @@ def main():
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if shape.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "batch": batch, "ctx_len": ctx, "n_nodes": n_nodes,
-                   "tree": kind, "threshold": args.threshold, "launch": args.launch},
+                   "tree": kind, "threshold": args.threshold, "launch": args.launch,
+                   "launch_mode": args.launch_mode},
         "verify_latency_ms": ms,
+        "latency_ms": latency,
         "pass_bytes": pass_bytes,
         "pass_achieved_GBs": pass_bytes / (ms * 1e-3) / 1e9,
         "pass_frac_of_hbm_peak": pass_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
@@ -228,9 +340,64 @@ def main():
         "escalate": ver.out["escalate"].cpu().tolist(),
         "setup_seconds": inp["setup_s"],
     }
+
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(shape, batch, ctx, n_nodes, kind, args.seed)
+        inp["ver_logits"] = Verifier(inp["model"], batch, n_nodes, debug_logits=True)
+        inp["ver_logits"].launch_mode = mode
+        out["cpu_baseline"], parity = oracle_leg(shape, batch, ctx, n_nodes, kind, seed, inp, args.threshold,
+                                                 args.cpu_budget)
+        if parity is not None:
+            out["parity"] = parity
+        del inp["ver_logits"]
+
+    if not args.no_extra_workloads and args.workload == "qwen3_8b_tree60_ctx4096":
+        # ---- the other workloads: latency and fraction of the roofline, same protocol, fewer passes
+        extra, models = {}, {key: inp["model"]}
+        del ver, kv, inp
+        torch.cuda.empty_cache()
+        p_esc = None
+        for name in EXTRA:
+            k2, b2, c2, m2, kind2, s2 = WORKLOADS[name]
+            i2 = build_inputs(SHAPES[k2], b2, c2, m2, kind2, s2, model=models.get(k2))
+            models[k2] = i2["model"]
+            i2["ver"].launch_mode = mode
+            st2 = lambda: i2["ver"].verify(i2["kv"], i2["tok"], i2["parents"], i2["pos"], args.threshold, want_logits=False)
+            ms2 = wall_ms(st2, 20, 3)
+            lat2 = event_percentiles(st2, 50)
+            by2 = i2["model"].pass_bytes(b2, m2, [c2] * b2)
+            extra[name] = {"ms_per_pass": ms2, "median_ms": lat2["median"], "p10_ms": lat2["p10"], "p90_ms": lat2["p90"],
+                           "draft_tokens_per_s": b2 * (m2 - 1) / (ms2 * 1e-3), "pass_bytes": by2,
+                           "frac_of_hbm_peak": by2 / (ms2 * 1e-3) / 1e9 / HBM_PEAK_GBS}
+            if name == "qwen3_1p7b_tree60_ctx8192":
+                # escalation frequency of the proxy on this synthetic data: 16 seeded draft trees, the
+                # routing decision re-run per threshold from each pass's statistics (Eq. 8 - 9, Cases I / II)
+                from workloads import gen_draft_tokens, gen_tree, tree_depths
+                p_esc = {"0.5": 0, "0.7": 0, "0.9": 0}
+                n_trees = 16
+                for t in range(n_trees):
+                    par = gen_tree(m2, 8, 4, 7000 + t)[None]
+                    tk = torch.from_numpy(gen_draft_tokens(par[0], SHAPES[k2].vocab, 7000 + t)[None]).cuda()
+                    ps = torch.from_numpy((c2 + tree_depths(par[0]))[None].astype(np.int32)).cuda()
+                    i2["ver"].verify(i2["kv"], tk, par, ps, 0.5, want_logits=False)
+                    for lam in p_esc:
+                        o = i2["ver"].decide(tk, par, float(lam), CRIT_MARGIN)
+                        torch.cuda.synchronize()
+                        p_esc[lam] += int(o["escalate"][0])
+                p_esc = {lam: v / n_trees for lam, v in p_esc.items()}
+            del i2
+            torch.cuda.empty_cache()
+        tp, tt = extra["qwen3_1p7b_tree60_ctx8192"]["ms_per_pass"], extra["qwen3_8b_tree60_ctx8192"]["ms_per_pass"]
+        extra["ternary_pipeline_ctx8192"] = {
+            "t_proxy_ms": tp, "t_target_ms": tt,
+            "per_threshold": {lam: {"p_escalate_synthetic": p, "t_verify_ms": tp + p * tt} for lam, p in p_esc.items()},
+            "at_paper_derived_p_escalate_0.46": tp + 0.46 * tt,
+            "note": "t_verify = t_proxy + P_esc * t_target (margin criterion); P_esc counted over 16 seeded synthetic draft "
+                    "trees on random-init weights (not an acceptance statistic of trained models); 0.46 is the escalation "
+                    "frequency implied by the paper's Table 3 (r_t * tau for Qwen3 on MATH500)"}
+        out["workloads"] = extra
     print(json.dumps(out))
+    if "parity" in out and not out["parity"]["ok"]:
+        sys.exit(3)
 
 
 if __name__ == "__main__":

@@ -223,8 +223,48 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, f32x16 (&acc)[N
           }
         }
       };
-      if (a.n_splits <= 4) reduce_groups(SplitGroup<4>{});
-      else reduce_groups(SplitGroup<8>{});
+      // the group size is the number of splits itself where that is small: no load is wasted on a
+      // clamped duplicate (a 256-row partial tile is 128 KB per split)
+      if constexpr (MG * 32 >= 256) {
+        // 256-row tiles: the workgroup is out of registers here (rotary tables or residual rows are
+        // held across the reduction), so two splits of 8 vectors at a time
+        constexpr int UB8 = PER < 8 ? PER : 8;
+#pragma unroll 1
+        for (int ub = 0; ub < PER; ub += UB8) {
+          f32x4 sum[UB8];
+#pragma unroll
+          for (int u = 0; u < UB8; ++u) sum[u] = *(const f32x4 *)(p0 + (size_t)(ub + u) * NT * 4);
+          for (int s = 1; s < a.n_splits; s += 2) {
+            const bool two = s + 1 < a.n_splits;
+            const float *pa = p0 + (size_t)s * split_stride, *pb = pa + (two ? split_stride : 0);
+            f32x4 va[UB8], vb[UB8];
+#pragma unroll
+            for (int u = 0; u < UB8; ++u) {
+              va[u] = *(const f32x4 *)(pa + (size_t)(ub + u) * NT * 4);
+              vb[u] = *(const f32x4 *)(pb + (size_t)(ub + u) * NT * 4);
+            }
+#pragma unroll
+            for (int u = 0; u < UB8; ++u) {
+              sum[u] += va[u];
+              if (two) sum[u] += vb[u];
+            }
+          }
+#pragma unroll
+          for (int u = 0; u < UB8; ++u) {
+            const int idx = tid + (ub + u) * NT, r = idx / (TN / 4), c = (idx % (TN / 4)) * 4;
+            *(f32x4 *)(tl + r * EPI_LD + c) = sum[u];
+          }
+        }
+      } else
+      switch (a.n_splits) {
+        case 2: reduce_groups(SplitGroup<2>{}); break;
+        case 3: reduce_groups(SplitGroup<3>{}); break;
+        case 4: reduce_groups(SplitGroup<4>{}); break;
+        case 5: reduce_groups(SplitGroup<5>{}); break;
+        case 6: reduce_groups(SplitGroup<6>{}); break;
+        case 7: reduce_groups(SplitGroup<7>{}); break;
+        default: reduce_groups(SplitGroup<8>{}); break;
+      }
     }
     __syncthreads();
     auto reduced4 = [&](int lr, int c) {   // 4 consecutive columns of row (row0 + lr) of the reduced tile
