@@ -13,6 +13,10 @@ fixes.  Two functions compute it:
 * `verify_forward` — the same model over the M tree nodes against a given KV
   cache; node i attends to the whole context and to its ancestors and itself.
 
+shape.qk_norm (an option of the model family the paper evaluates on, not of the paper): queries
+and keys pass through an RMSNorm over the head dimension, with weights q_norm / k_norm shared by
+all heads of a layer, before the rotary embedding.
+
 Storage modes.  "f32": nothing is rounded (all fp64).  "bf16": what the model
 STORES is bf16 — the weights (already rounded by whoever supplies them) and the
 KV cache: keys (after the rotary embedding) and values are rounded to bf16
@@ -143,6 +147,9 @@ def causal_forward(W: OracleWeights, shape, tokens: Sequence[int],
         q = (h @ W("wq", l).T).reshape(T, nq, d)
         k = (h @ W("wk", l).T).reshape(T, nkv, d)
         v = (h @ W("wv", l).T).reshape(T, nkv, d)
+        if getattr(shape, "qk_norm", False):
+            q = rmsnorm(q, W("q_norm", l), shape.rms_eps)
+            k = rmsnorm(k, W("k_norm", l), shape.rms_eps)
         q = apply_rope(q, ang)
         k = apply_rope(k, ang)
         Ks[l] = rnd(k).transpose(1, 0, 2)
@@ -223,6 +230,9 @@ def verify_forward(W: OracleWeights, shape, k_ctx, v_ctx, tokens: Sequence[int],
         q = (h @ W("wq", l).T).reshape(M, nq, d)
         k = (h @ W("wk", l).T).reshape(M, nkv, d)
         v = (h @ W("wv", l).T).reshape(M, nkv, d)
+        if getattr(shape, "qk_norm", False):
+            q = rmsnorm(q, W("q_norm", l), shape.rms_eps)
+            k = rmsnorm(k, W("k_norm", l), shape.rms_eps)
         q = apply_rope(q, ang)
         k = apply_rope(k, ang)
         k_new[l] = rnd(k).transpose(1, 0, 2)      # what enters the cache

@@ -22,6 +22,8 @@ VARIANTS = [
     MICRO.with_(name="wide_q", n_q_heads=6, n_kv_heads=2, head_dim=16),   # nq*d != hidden
     MICRO.with_(name="bf16", dtype="bf16"),
     MICRO.with_(name="three_layers", n_layers=3, rope_base=5e5),
+    MICRO.with_(name="qk_norm", qk_norm=True, n_layers=3),
+    MICRO.with_(name="qk_norm_bf16", qk_norm=True, dtype="bf16"),
 ]
 
 
@@ -42,8 +44,12 @@ def torch_causal_forward(shape, seed, tokens, positions):
 
     for l in range(shape.n_layers):
         h = F.rms_norm(x, (shape.hidden,), t("norm_attn", l), shape.rms_eps)
-        q = rope(F.linear(h, t("wq", l)).view(T, nq, d)).transpose(0, 1)   # [nq, T, d]
-        k = rope(F.linear(h, t("wk", l)).view(T, nkv, d)).transpose(0, 1)
+        q, k = F.linear(h, t("wq", l)).view(T, nq, d), F.linear(h, t("wk", l)).view(T, nkv, d)
+        if shape.qk_norm:   # RMSNorm over the head dimension, before the rotary embedding
+            q = F.rms_norm(q, (d,), t("q_norm", l), shape.rms_eps)
+            k = F.rms_norm(k, (d,), t("k_norm", l), shape.rms_eps)
+        q = rope(q).transpose(0, 1)   # [nq, T, d]
+        k = rope(k).transpose(0, 1)
         v = F.linear(h, t("wv", l)).view(T, nkv, d).transpose(0, 1)
         k = k.repeat_interleave(nq // nkv, dim=0)
         v = v.repeat_interleave(nq // nkv, dim=0)

@@ -45,6 +45,7 @@ class ModelShape:
     rms_eps: float = 1e-6
     rope_base: float = 1e4
     lm_head_std: float = 0.02  # std of the LM-head entries
+    qk_norm: bool = False      # per-head RMSNorm of queries and keys before the rotary embedding (Qwen3)
 
     def with_(self, **kw) -> "ModelShape":
         return replace(self, **kw)
@@ -145,7 +146,7 @@ def _rng(seed: int, stream: int) -> np.random.Generator:
 # tensor ids
 _T_EMBED, _T_LMHEAD, _T_FNORM = 0, 1, 2
 _LAYER_BASE, _LAYER_STRIDE = 16, 16
-_LAYER_TENSORS = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "norm_attn", "norm_ffn")
+_LAYER_TENSORS = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "norm_attn", "norm_ffn", "q_norm", "k_norm")
 _T_KV = 1 << 20  # KV-cache streams start here
 
 
@@ -178,6 +179,8 @@ class WeightSource:
             "w_down": (s.hidden, s.ffn),
             "norm_attn": (s.hidden,),
             "norm_ffn": (s.hidden,),
+            "q_norm": (s.head_dim,),
+            "k_norm": (s.head_dim,),
         }[name]
 
     def _tensor_id(self, name: str, layer: int) -> int:
@@ -193,7 +196,7 @@ class WeightSource:
         dims = self.dims(name)
         n = int(np.prod(dims))
         z = _normal(self.seed, self._tensor_id(name, layer), n)
-        if name in ("final_norm", "norm_attn", "norm_ffn"):
+        if name in ("final_norm", "norm_attn", "norm_ffn", "q_norm", "k_norm"):
             z *= np.float32(0.1)
             z += np.float32(1.0)
         elif name == "lm_head":
