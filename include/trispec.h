@@ -71,6 +71,9 @@ typedef struct {             /* plain data, copied by trispec_model_create */
                                 as bf16 high + low pairs (~16 bits), accumulation is fp32 */
   float rms_eps;
   float rope_base;
+  int32_t qk_norm;           /* 1: queries and keys pass through an RMSNorm over head_dim (weights q_norm /
+                                k_norm, shared by the heads of a layer, eps = rms_eps) before the rotary
+                                embedding, as in the Qwen3 family the paper evaluates on; 0: no such norm */
 } trispec_model_config;
 
 typedef struct {             /* device pointers into caller-owned memory */
@@ -87,6 +90,8 @@ typedef struct {             /* device pointers into caller-owned memory */
   const void *const *w_down; /* [hidden, ffn] */
   const void *const *norm_attn; /* [hidden] */
   const void *const *norm_ffn;  /* [hidden] */
+  const void *const *q_norm;    /* [head_dim]; read only when qk_norm = 1 (may be NULL otherwise) */
+  const void *const *k_norm;    /* [head_dim] */
 } trispec_weights;
 
 typedef struct trispec_model trispec_model;

@@ -39,7 +39,7 @@ LAUNCH_PER_MATMUL, LAUNCH_PER_LAYER = 0, 1
 class ModelConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
                 ("n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim", "ffn", "vocab", "dtype")] + \
-               [("rms_eps", C.c_float), ("rope_base", C.c_float)]
+               [("rms_eps", C.c_float), ("rope_base", C.c_float), ("qk_norm", C.c_int32)]
 
 
 _PP = C.POINTER(C.c_void_p)
@@ -47,7 +47,8 @@ _PP = C.POINTER(C.c_void_p)
 
 class Weights(C.Structure):
     _fields_ = [("embed", C.c_void_p), ("lm_head", C.c_void_p), ("final_norm", C.c_void_p)] + \
-               [(n, _PP) for n in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "norm_attn", "norm_ffn")]
+               [(n, _PP) for n in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "norm_attn", "norm_ffn",
+                                   "q_norm", "k_norm")]
 
 
 class VerifyOpts(C.Structure):
@@ -152,9 +153,9 @@ class Model:
     """
 
     def __init__(self, *, n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab, dtype,
-                 rms_eps, rope_base, tensors: Dict[str, object]):
+                 rms_eps, rope_base, tensors: Dict[str, object], qk_norm: bool = False):
         self.cfg = ModelConfig(n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab, dtype,
-                               rms_eps, rope_base)
+                               rms_eps, rope_base, 1 if qk_norm else 0)
         self.tensors = tensors
         self.dtype = dtype
         w = Weights()
@@ -162,7 +163,7 @@ class Model:
         w.lm_head = tensors["lm_head"].data_ptr()
         w.final_norm = tensors["final_norm"].data_ptr()
         self._tables = []
-        for n in _LAYER_NAMES:
+        for n in _LAYER_NAMES + (("q_norm", "k_norm") if qk_norm else ()):
             arr = (C.c_void_p * n_layers)(*[t.data_ptr() for t in tensors[n]])
             self._tables.append(arr)
             setattr(w, n, C.cast(arr, _PP))

@@ -16,7 +16,7 @@ using namespace ts;
 struct trispec_model {
   trispec_model_config cfg;
   const void *embed, *lm_head, *final_norm;
-  std::vector<const void *> wq, wk, wv, wo, w_gate, w_up, w_down, norm_attn, norm_ffn;
+  std::vector<const void *> wq, wk, wv, wo, w_gate, w_up, w_down, norm_attn, norm_ffn, q_norm, k_norm;
   // bf16 models: packed copies of the matrices (device, inside the caller's pack buffer)
   bool packed;
   int layer_grid[3][2];   // largest resident grid of the layer kernel for rows_pad 32 / 64 / 128 and ring depth 8 / 4 (-1: not asked yet)
@@ -298,6 +298,12 @@ int trispec_model_create(const trispec_model_config *cfg, const trispec_weights 
     if (!w->wq[l] || !w->wk[l] || !w->wv[l] || !w->wo[l] || !w->w_gate[l] || !w->w_up[l] || !w->w_down[l] ||
         !w->norm_attn[l] || !w->norm_ffn[l])
       return TRISPEC_ENULL;
+  if (cfg->qk_norm != 0 && cfg->qk_norm != 1) return TRISPEC_ESHAPE;
+  if (cfg->qk_norm) {
+    if (!w->q_norm || !w->k_norm) return TRISPEC_ENULL;
+    for (int l = 0; l < L; ++l)
+      if (!w->q_norm[l] || !w->k_norm[l]) return TRISPEC_ENULL;
+  }
   trispec_model *m = new (std::nothrow) trispec_model;
   if (!m) return TRISPEC_EARG;
   m->cfg = *cfg;
@@ -313,6 +319,10 @@ int trispec_model_create(const trispec_model_config *cfg, const trispec_weights 
   m->w_down.assign(w->w_down, w->w_down + L);
   m->norm_attn.assign(w->norm_attn, w->norm_attn + L);
   m->norm_ffn.assign(w->norm_ffn, w->norm_ffn + L);
+  if (cfg->qk_norm) {
+    m->q_norm.assign(w->q_norm, w->q_norm + L);
+    m->k_norm.assign(w->k_norm, w->k_norm + L);
+  }
   m->packed = false;
   for (int i = 0; i < 3; ++i) m->layer_grid[i][0] = m->layer_grid[i][1] = -1;
   m->p_lm_head = nullptr;
@@ -601,7 +611,8 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
       gemm(h, c.hidden, 3, m->wq[l], qd, m->wk[l], kvd, m->wv[l], kvd, part);
       char *kl = (char *)kv->k + (size_t)l * kv_layer, *vl = (char *)kv->v + (size_t)l * kv_layer;
       launch_qkv_epilogue(st, c.dtype, part, 1, rows, rp, c.n_q_heads, c.n_kv_heads, c.head_dim, cos_t, sin_t,
-                          n_nodes, ctx, kv->capacity, q, kl, vl);
+                          n_nodes, ctx, kv->capacity, q, kl, vl, c.qk_norm ? (const float *)m->q_norm[l] : nullptr,
+                          c.qk_norm ? (const float *)m->k_norm[l] : nullptr, c.rms_eps);
       attention(kl, vl);
       gemm((const float *)attn_out, qd, 1, m->wo[l], c.hidden, nullptr, 0, nullptr, 0, part);
       launch_reduce_residual_norm(st, c.dtype, part, 1, rows, rp, c.hidden, m->norm_ffn[l], c.rms_eps, x, h);
@@ -668,6 +679,8 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
       g.v_cache = (char *)kv->v + (size_t)l * kv_layer;
       g.n_nodes = n_nodes; g.n_q_heads = c.n_q_heads; g.n_kv_heads = c.n_kv_heads; g.head_dim = c.head_dim;
       g.capacity = kv->capacity;
+      g.q_norm_w = c.qk_norm ? m->q_norm[l] : nullptr;
+      g.k_norm_w = c.qk_norm ? m->k_norm[l] : nullptr;
       return g;
     };
     auto mk_o = [&](int l, const SplitPlan &p, const float *x_in, float *x_out, void *h_out) {

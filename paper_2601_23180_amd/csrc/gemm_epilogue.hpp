@@ -280,14 +280,28 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, f32x16 (&acc)[N
       for (int u = 0; u < QKV_PASSES; ++u) {
         const int t = tid + u * NT;
         const int lr = t / quads, qi = t - lr * quads, r = row0 + lr;
-        if (r >= a.rows) continue;
         const int hl = (qi * 4) / half, j = qi * 4 - hl * half;   // head within the tile, first pair
         const int c_lo = hl * d + j;                          // tile-local column of the low elements
         const int col = tile * TN + c_lo;                     // global column
-        if (col >= a.n_total) continue;
+        const bool live = r < a.rows && col < a.n_total;
         const int hh = col / d;                               // global head index (q heads, k heads, v heads)
-        const float rsc = s_rs[r];
+        const float rsc = live ? s_rs[r] : 0.f;
         f32x4 lo = reduced4(lr, c_lo) * rsc, hi = reduced4(lr, c_lo + half) * rsc;
+        if (a.q_norm_w != nullptr) {
+          // RMSNorm of a query / key head over its d features: the half / 4 consecutive lanes that hold
+          // the head add their sums of squares (every lane takes part: no early exit above)
+          float ss = lo[0] * lo[0] + lo[1] * lo[1] + lo[2] * lo[2] + lo[3] * lo[3] + hi[0] * hi[0] + hi[1] * hi[1] +
+                     hi[2] * hi[2] + hi[3] * hi[3];
+          for (int o = 1; o < half / 4; o <<= 1) ss += __shfl_xor(ss, o, 64);
+          if (live && hh < n_q + n_kv) {
+            const float rn = 1.0f / sqrtf(ss / (float)d + a.eps);
+            const bf16 *nw = (const bf16 *)(hh < n_q ? a.q_norm_w : a.k_norm_w);
+            const bf16x4 wl = *(const bf16x4 *)(nw + j), wh = *(const bf16x4 *)(nw + j + half);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { lo[e] *= rn * (float)wl[e]; hi[e] *= rn * (float)wh[e]; }
+          }
+        }
+        if (!live) continue;
         const int b = r / a.n_nodes, node = r - b * a.n_nodes;
         const int slot = a.ctx.v[b] + node;
         if (hh < n_q + n_kv) {

@@ -81,6 +81,7 @@ struct GemmArgs {
   void *q_out;         // bf16 hi/lo panels [rows_pad][nq*d] of the rotated queries
   size_t q_panel;
   void *k_cache, *v_cache;
+  const void *q_norm_w, *k_norm_w;   // [head_dim] each, or nullptr: no per-head norm of q / k
   CtxLens ctx;
   int32_t n_nodes, n_q_heads, n_kv_heads, head_dim, capacity;
   // RESID epilogue
@@ -208,7 +209,8 @@ void launch_zero_counters(hipStream_t st, int32_t *counters, int n_counters);
 void launch_qkv_epilogue(hipStream_t st, int dtype, const float *part, int n_splits, int rows,
                          int rows_pad, int n_q_heads, int n_kv_heads, int head_dim,
                          const float *cos_t, const float *sin_t, int n_nodes, CtxLens ctx,
-                         int capacity, void *q_out, void *k_cache, void *v_cache);
+                         int capacity, void *q_out, void *k_cache, void *v_cache, const float *q_norm_w,
+                         const float *k_norm_w, float eps);
 void launch_reduce_residual_norm(hipStream_t st, int dtype, const float *part, int n_splits, int rows,
                                  int rows_pad, int hidden, const void *norm_w, float eps, float *x,
                                  void *h);

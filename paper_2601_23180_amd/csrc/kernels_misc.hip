@@ -161,15 +161,25 @@ __device__ __forceinline__ float sum_splits(const float *part, int n_splits, siz
 __global__ void k_qkv_epilogue_f32(const float *part, int n_splits, int rows_pad, int n_q_heads,
                                    int n_kv_heads, int head_dim, const float *cos_t, const float *sin_t,
                                    int n_nodes, CtxLens ctx, int capacity, float *q_out, float *k_cache,
-                                   float *v_cache) {
-  const int r = blockIdx.x, hh = blockIdx.y, j = threadIdx.x;
+                                   float *v_cache, const float *q_norm_w, const float *k_norm_w, float eps) {
+  __shared__ float s_sq[64];
+  const int r = blockIdx.x, hh = blockIdx.y, j = threadIdx.x;   // head_dim / 2 threads
   const int half = head_dim >> 1;
-  if (j >= half) return;
   const int n_total = (n_q_heads + 2 * n_kv_heads) * head_dim;
   const size_t slice = (size_t)rows_pad * n_total;
   const size_t off = (size_t)r * n_total + (size_t)hh * head_dim + j;
   float a = sum_splits(part, n_splits, slice, off);
   float b = sum_splits(part, n_splits, slice, off + half);
+  if (q_norm_w != nullptr && hh < n_q_heads + n_kv_heads) {   // RMSNorm over the head (uniform branch)
+    s_sq[j] = a * a + b * b;
+    __syncthreads();
+    float ss = 0.f;
+    for (int i = 0; i < half; ++i) ss += s_sq[i];           // ascending: the same order in every thread
+    const float rn = 1.0f / sqrtf(ss / (float)head_dim + eps);
+    const float *nw = hh < n_q_heads ? q_norm_w : k_norm_w;
+    a *= rn * nw[j];
+    b *= rn * nw[j + half];
+  }
   const int bidx = r / n_nodes, node = r - bidx * n_nodes;
   const int slot = ctx.v[bidx] + node;
   if (hh < n_q_heads + n_kv_heads) {
@@ -198,12 +208,13 @@ __global__ void k_qkv_epilogue_f32(const float *part, int n_splits, int rows_pad
 void launch_qkv_epilogue(hipStream_t st, int dtype, const float *part, int n_splits, int rows,
                          int rows_pad, int n_q_heads, int n_kv_heads, int head_dim,
                          const float *cos_t, const float *sin_t, int n_nodes, CtxLens ctx,
-                         int capacity, void *q_out, void *k_cache, void *v_cache) {
+                         int capacity, void *q_out, void *k_cache, void *v_cache, const float *q_norm_w,
+                         const float *k_norm_w, float eps) {
   (void)dtype;
   dim3 grid(rows, n_q_heads + 2 * n_kv_heads), block(head_dim / 2);
   hipLaunchKernelGGL(k_qkv_epilogue_f32, grid, block, 0, st, part, n_splits, rows_pad, n_q_heads,
                      n_kv_heads, head_dim, cos_t, sin_t, n_nodes, ctx, capacity, (float *)q_out,
-                     (float *)k_cache, (float *)v_cache);
+                     (float *)k_cache, (float *)v_cache, q_norm_w, k_norm_w, eps);
 }
 
 // ------------------------------------------------------------------ fp32 pipeline: residual + RMSNorm

@@ -26,12 +26,13 @@ def model_from_arrays(shape, get: Callable[[str, int], np.ndarray], device="cuda
     values or (bf16 models) as uint16 bit patterns."""
     bf16 = shape.dtype == "bf16"
     tensors = {n: _to_device(get(n, 0), bf16, device) for n in ("embed", "lm_head", "final_norm")}
-    for n in _LAYER_NAMES:
+    qk_norm = bool(getattr(shape, "qk_norm", False))
+    for n in _LAYER_NAMES + (("q_norm", "k_norm") if qk_norm else ()):
         tensors[n] = [_to_device(get(n, l), bf16, device) for l in range(shape.n_layers)]
     m = Model(n_layers=shape.n_layers, hidden=shape.hidden, n_q_heads=shape.n_q_heads,
                  n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim, ffn=shape.ffn, vocab=shape.vocab,
                  dtype=TRISPEC_BF16 if bf16 else TRISPEC_F32, rms_eps=shape.rms_eps,
-                 rope_base=shape.rope_base, tensors=tensors)
+                 rope_base=shape.rope_base, tensors=tensors, qk_norm=qk_norm)
     m.pack(release_originals=release_originals)
     return m
 

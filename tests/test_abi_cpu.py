@@ -29,7 +29,7 @@ def test_library_exports_every_declared_symbol():
 
 def _cfg(**kw):
     base = dict(n_layers=2, hidden=256, n_q_heads=4, n_kv_heads=2, head_dim=64, ffn=512, vocab=4096,
-                dtype=B.TRISPEC_F32, rms_eps=1e-6, rope_base=1e4)
+                dtype=B.TRISPEC_F32, rms_eps=1e-6, rope_base=1e4, qk_norm=0)
     base.update(kw)
     return B.ModelConfig(*[base[k] for k, _ in B.ModelConfig._fields_])
 
@@ -39,7 +39,7 @@ def _fake_weights(n_layers):
     fake = 0x1000
     w.embed = w.lm_head = w.final_norm = fake
     keep = []
-    for n in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "norm_attn", "norm_ffn"):
+    for n in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "norm_attn", "norm_ffn", "q_norm", "k_norm"):
         arr = (C.c_void_p * n_layers)(*([fake] * n_layers))
         keep.append(arr)
         setattr(w, n, C.cast(arr, C.POINTER(C.c_void_p)))
@@ -62,6 +62,12 @@ def test_model_create_validation():
     assert _model(n_q_heads=5)[0] == -2
     assert _model(dtype=7)[0] == -2
     assert _model(dtype=B.TRISPEC_BF16, hidden=250)[0] == -2
+    assert _model(qk_norm=1)[0] == 0 and _model(qk_norm=2)[0] == -2
+    cfg = _cfg(qk_norm=1)                      # the per-head norm weights are required when it is on
+    w, keep = _fake_weights(2)
+    w.q_norm = None
+    h = C.c_void_p()
+    assert lib.trispec_model_create(C.byref(cfg), C.byref(w), C.byref(h)) == -1
     cfg = _cfg()
     w, keep = _fake_weights(2)
     w.lm_head = None

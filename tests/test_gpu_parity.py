@@ -110,6 +110,12 @@ def test_config1_tiny_fp32_chain_threshold_half():
     assert out["accepted_len"].item() == 0 and out["escalate"].item() == 1 and out["token"].item() == -1
 
 
+def test_fp32_model_with_qk_norm():
+    shape = SHAPES["tiny"].with_(qk_norm=True)
+    case = make_case(shape, 23, [100], [gen_tree(20, 6, 3, 23)])
+    full_check(case, thresholds=(0.0, 0.5))
+
+
 @pytest.mark.parametrize("r", [0, 3, 8])
 def test_config1_planted_chain_accepts_r_tokens(r):
     shape = SHAPES["tiny"]
@@ -158,6 +164,12 @@ BF16_CASES = [
      lambda s: gen_tree(50, 8, 4, s)),
     ("rows240_hidden1024_splits", TB.with_(n_layers=1, hidden=1024, ffn=1024, vocab=4001, lm_head_std=6.5 / 32),
      [40, 0, 129, 77], lambda s: gen_tree(60, 8, 4, s)),
+    # per-head RMSNorm of queries and keys before the rotary embedding (head_dim 128 and 64)
+    ("qk_norm", TB.with_(qk_norm=True), [90], lambda s: gen_tree(40, 8, 4, s)),
+    ("qk_norm_head_dim64_batch2", TB.with_(qk_norm=True, head_dim=64, n_q_heads=8, n_kv_heads=4, n_layers=3), [33, 70],
+     lambda s: gen_tree(25, 6, 3, s)),
+    ("layer_qk_norm", TB.with_(qk_norm=True, n_layers=2, hidden=512, ffn=1024, lm_head_std=6.5 / 22.6), [64],
+     lambda s: gen_tree(50, 8, 4, s)),
     # widths that the one-launch-per-layer kernel takes (every reduction a multiple of its step:
     # 1024 at up to 32 rows, 512 at up to 64, 256 at up to 128), with and without k splits
     ("layer_rows60_three_layers", TB.with_(n_layers=3, hidden=512, ffn=1024, lm_head_std=6.5 / 22.6), [90],
