@@ -145,6 +145,13 @@ int trispec_kv_create(const trispec_model *m, void *k_dev, void *v_dev, int32_t 
 int trispec_kv_set_len(trispec_kv *kv, const int32_t *ctx_len_host);
 int trispec_kv_destroy(trispec_kv *kv);
 
+/* Repack of ONE row-major bf16 matrix [n_rows, k] (k a multiple of 64) into the streaming layout of
+ * trispec_model_pack — for matrices that are not part of a model, i.e. the adapter of
+ * trispec_verify_opts.  `packed_dev`: 256-byte aligned, trispec_pack_matrix_bytes() bytes.
+ * Errors: TRISPEC_ENULL, TRISPEC_EARG (sizes, alignment), TRISPEC_ELAUNCH. */
+int trispec_pack_matrix_bytes(int32_t n_rows, int32_t k, size_t *bytes);
+int trispec_pack_matrix(const void *w_dev, int32_t n_rows, int32_t k, void *packed_dev, void *stream);
+
 /* Makes a verified path part of the context (Sec. 2.1 / Alg. 1: after a round the accepted
  * prefix is appended to the sequence; the token the verifier adds on top becomes the root of
  * the next round and is not cached yet).  For every sequence b the K/V rows that the last
@@ -208,6 +215,21 @@ typedef struct {
                                 selection and adapter training"); NULL = not exported */
   int32_t launch_mode;       /* TRISPEC_LAUNCH_PER_MATMUL (0, default) | TRISPEC_LAUNCH_PER_LAYER: how the pass
                                 is cut into kernel launches (same arithmetic either way) */
+  /* Features for the drafter (Sec. 3.2 "Drafter selection and adapter training"; all optional, off on
+     the plain hot path).  The drafter is re-seeded after a round with the verifier's features at the
+     verified nodes; when the verifier was the proxy they first pass through a one-layer adapter into
+     the feature space the drafter expects. */
+  const int32_t *feature_layers; /* HOST [n_feature_layers], ascending layer indices in [0, n_layers): */
+  int32_t n_feature_layers;      /* 0 .. TRISPEC_MAX_FEATURE_LAYERS                                     */
+  float *features_out;       /* device [n_feature_layers][batch, n_nodes, hidden] fp32: the residual stream after
+                                those layers (low / middle / high features of a multi-layer drafter) */
+  const void *adapter_w;     /* device: the adapter matrix [adapter_dim, hidden], y = f W^T + b on the final-norm
+                                features f (what hidden_out exports).  bf16 models: the PACKED copy made by
+                                trispec_pack_matrix; fp32 models: the row-major fp32 matrix.  The paper gives
+                                neither shape nor non-linearity of its "one-layer MLP adapter": one affine map */
+  const float *adapter_bias; /* device [adapter_dim] fp32, or NULL */
+  int32_t adapter_dim;       /* a multiple of 4, >= 4 */
+  float *adapter_out;        /* device [batch, n_nodes, adapter_dim] fp32 */
   const int32_t *draft_ranks; /* optional device [batch, n_nodes] from trispec_draft_ranks, see accept_top_k */
   int32_t accept_top_k;      /* 0 or 1: a draft token is accepted iff it equals the verifier's argmax (Eq. 6,
                                 greedy form).  k > 1: the relaxed acceptance that the appendix "relaxed
@@ -232,6 +254,7 @@ typedef struct {
 enum { TRISPEC_LAUNCH_PER_MATMUL = 0, TRISPEC_LAUNCH_PER_LAYER = 1 };
 
 #define TRISPEC_PATH_STRIDE (TRISPEC_MAX_NODES)
+#define TRISPEC_MAX_FEATURE_LAYERS 8
 
 typedef struct {             /* device pointers, caller-owned; any may be NULL to skip it */
   int32_t *accepted_len;     /* [batch]  min(tau_a, tau_m): approved draft tokens (Eq. 7, Eq. 9) */

@@ -22,6 +22,7 @@ from .forward import (  # noqa: F401
     causal_forward,
     verify_forward,
     ancestor_sets,
+    adapter,
 )
 from .decision import (  # noqa: F401
     CRIT_MARGIN,

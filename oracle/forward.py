@@ -175,6 +175,14 @@ def causal_forward(W: OracleWeights, shape, tokens: Sequence[int],
     return {"logits": _lm_head(hf, W, shape.vocab), "K": Ks, "V": Vs}
 
 
+def adapter(features: np.ndarray, weight: np.ndarray, bias: Optional[np.ndarray] = None) -> np.ndarray:
+    """The one-layer adapter that maps a proxy's features into the feature space the drafter
+    expects (Sec. 3.2, "Drafter selection and adapter training"): y = f W^T + b.  The paper states
+    neither its shape nor a non-linearity; one affine map [adapter_dim, hidden] is this build's reading."""
+    y = np.asarray(features, dtype=np.float64) @ np.asarray(weight, dtype=np.float64).T
+    return y if bias is None else y + np.asarray(bias, dtype=np.float64)
+
+
 # --------------------------------------------------------------------------
 # tree-masked verification forward against a KV cache
 

@@ -30,7 +30,7 @@ EXPORTS = [
     "trispec_timer_destroy", "trispec_model_pack_bytes", "trispec_model_pack", "trispec_copy_probe",
     "trispec_kv_commit", "trispec_sample_scratch_bytes", "trispec_sample_decide",
     "trispec_sample_decide_static", "trispec_debug_set_spin_limit", "trispec_wait_probe",
-    "trispec_prune_reroot", "trispec_draft_ranks",
+    "trispec_prune_reroot", "trispec_draft_ranks", "trispec_pack_matrix_bytes", "trispec_pack_matrix",
 ]
 K_GEMM, K_HEAD, K_ATTN = 0, 1, 2
 LAUNCH_PER_MATMUL, LAUNCH_PER_LAYER = 0, 1
@@ -55,6 +55,9 @@ class VerifyOpts(C.Structure):
     _fields_ = [("criterion", C.c_int32), ("n_forced", C.c_int32), ("workspace", C.c_void_p),
                 ("workspace_bytes", C.c_size_t), ("debug_logits", C.c_void_p), ("stream", C.c_void_p),
                 ("timer", C.c_void_p), ("hidden_out", C.c_void_p), ("launch_mode", C.c_int32),
+                ("feature_layers", C.POINTER(C.c_int32)), ("n_feature_layers", C.c_int32),
+                ("features_out", C.c_void_p), ("adapter_w", C.c_void_p), ("adapter_bias", C.c_void_p),
+                ("adapter_dim", C.c_int32), ("adapter_out", C.c_void_p),
                 ("draft_ranks", C.c_void_p), ("accept_top_k", C.c_int32), ("stamps", C.c_void_p)]
 
 
@@ -122,6 +125,8 @@ def lib() -> C.CDLL:
         _pi = C.POINTER(C.c_int32)
         l.trispec_prune_reroot.argtypes = [_pi, _pi, _pi, C.c_int32, _pi, C.c_int32, _pi, C.c_int32, C.c_int32,
                                            _pi, _pi, _pi, _pi, _pi, _pi]
+        l.trispec_pack_matrix_bytes.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
+        l.trispec_pack_matrix.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         l.trispec_draft_ranks.argtypes = [C.c_void_p, C.c_void_p, _pi, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                           C.c_void_p]
         l.trispec_timer_create.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]
@@ -409,6 +414,9 @@ class Verifier:
         self.logits = torch.zeros((batch, max_nodes, model.cfg.vocab), **f32) if debug_logits else None
         self.hidden = torch.zeros((batch, max_nodes, model.cfg.hidden), **f32) if export_hidden else None
         self.timer = None   # optional KernelTimer attached to every verify call
+        self.feature_layers: List[int] = []   # layers whose residual stream is exported to self.features
+        self.features = None                  # fp32 [n_feature_layers, batch, max_nodes, hidden]
+        self._adapter = None                  # (weights as the kernels read them, bias or None, dim, out)
         self.ranks = None   # int32 [batch, max_nodes], filled by draft_ranks()
         self.accept_top_k = 0
         self.launch_mode = LAUNCH_PER_MATMUL
@@ -424,6 +432,19 @@ class Verifier:
         o.timer = self.timer.handle if self.timer is not None else None
         o.hidden_out = self.hidden.data_ptr() if self.hidden is not None else None
         o.launch_mode = self.launch_mode
+        if self.feature_layers:
+            if self.features is None or self.features.shape[0] != len(self.feature_layers):
+                self.features = torch.zeros((len(self.feature_layers), self.batch, self.max_nodes, self.model.cfg.hidden),
+                                            dtype=torch.float32, device=self.workspace.device)
+            self._fl = (C.c_int32 * len(self.feature_layers))(*self.feature_layers)
+            o.feature_layers, o.n_feature_layers = self._fl, len(self.feature_layers)
+            o.features_out = self.features.data_ptr()
+        if self._adapter is not None:
+            w, b, dim, out = self._adapter
+            packed = self.model.dtype == TRISPEC_BF16      # the packed copy sits at the next 256-byte boundary
+            o.adapter_w = w.data_ptr() + ((-w.data_ptr()) % 256 if packed else 0)
+            o.adapter_dim, o.adapter_out = dim, out.data_ptr()
+            o.adapter_bias = b.data_ptr() if b is not None else None
         o.draft_ranks = self.ranks.data_ptr() if (self.ranks is not None and self.accept_top_k > 1) else None
         o.accept_top_k = self.accept_top_k if self.ranks is not None else 0
         o.stamps = self.stamps.data_ptr() if self.stamps is not None else None
@@ -458,6 +479,25 @@ class Verifier:
                                    par.ctypes.data_as(C.POINTER(C.c_int32)), n_nodes, float(threshold),
                                    C.byref(opts), C.byref(out)))
         return self.out
+
+    def set_adapter(self, weight: torch.Tensor, bias: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """weight: [adapter_dim, hidden] device tensor in the model's dtype; bias: fp32 [adapter_dim] or None.
+        bf16 models: the matrix is repacked once (trispec_pack_matrix).  Returns the output tensor
+        [batch, max_nodes, adapter_dim] that every later verify call fills."""
+        dim, hid = weight.shape
+        assert hid == self.model.cfg.hidden and weight.is_contiguous()
+        if self.model.dtype == TRISPEC_BF16:
+            n = C.c_size_t()
+            check(lib().trispec_pack_matrix_bytes(dim, hid, C.byref(n)))
+            w = torch.empty(n.value + 256, dtype=torch.uint8, device=weight.device)
+            check(lib().trispec_pack_matrix(weight.data_ptr(), dim, hid, w.data_ptr() + (-w.data_ptr()) % 256,
+                                            torch.cuda.current_stream().cuda_stream))
+            torch.cuda.current_stream().synchronize()
+        else:
+            w = weight
+        out = torch.zeros((self.batch, self.max_nodes, dim), dtype=torch.float32, device=weight.device)
+        self._adapter = (w, bias, dim, out)
+        return out
 
     def draft_ranks(self, draft_tokens: torch.Tensor, tree_parents: np.ndarray, stream=None) -> torch.Tensor:
         """trispec_draft_ranks on the logits of the last verify call (needs debug_logits=True)."""

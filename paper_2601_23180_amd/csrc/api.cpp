@@ -255,6 +255,9 @@ int check_opts(const trispec_verify_opts *o, float threshold) {
     return TRISPEC_EARG;
   if (threshold != threshold) return TRISPEC_EARG;
   if (o->accept_top_k < 0 || (o->accept_top_k > 1 && !o->draft_ranks)) return TRISPEC_EARG;
+  if (o->n_feature_layers < 0 || o->n_feature_layers > TRISPEC_MAX_FEATURE_LAYERS) return TRISPEC_EARG;
+  if (o->n_feature_layers > 0 && (!o->feature_layers || !o->features_out)) return TRISPEC_ENULL;
+  if (o->adapter_w && (!o->adapter_out || o->adapter_dim < 4 || o->adapter_dim % 4)) return TRISPEC_EARG;
   if (!o->workspace) return TRISPEC_EWORKSPACE;
   if (((uintptr_t)o->workspace) & 255) return TRISPEC_EWORKSPACE;
   return TRISPEC_OK;
@@ -392,6 +395,21 @@ int trispec_model_pack(trispec_model *m, void *packed_dev, void *stream) {
   return TRISPEC_OK;
 }
 
+int trispec_pack_matrix_bytes(int32_t n_rows, int32_t k, size_t *bytes) {
+  if (!bytes) return TRISPEC_ENULL;
+  if (n_rows < 1 || k < 64 || k % 64) return TRISPEC_EARG;
+  *bytes = packed_weight_bytes(n_rows, k);
+  return TRISPEC_OK;
+}
+
+int trispec_pack_matrix(const void *w_dev, int32_t n_rows, int32_t k, void *packed_dev, void *stream) {
+  if (!w_dev || !packed_dev) return TRISPEC_ENULL;
+  if (n_rows < 1 || k < 64 || k % 64 || (((uintptr_t)packed_dev) & 255) || (((uintptr_t)w_dev) & 15)) return TRISPEC_EARG;
+  (void)hipGetLastError();
+  launch_pack_weights((hipStream_t)stream, w_dev, n_rows, k, packed_dev);
+  return hipGetLastError() == hipSuccess ? TRISPEC_OK : TRISPEC_ELAUNCH;
+}
+
 int trispec_kv_bytes(const trispec_model *m, int32_t batch, int32_t capacity, size_t *bytes) {
   if (!m || !bytes) return TRISPEC_ENULL;
   if (batch < 1 || batch > kMaxBatch) return TRISPEC_ENODES;
@@ -512,10 +530,23 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
   if (rc) return rc;
   const Layout L = make_layout(c, B, n_nodes);
   if (opts->workspace_bytes < L.total) return TRISPEC_EWORKSPACE;
+  for (int i = 0; i < opts->n_feature_layers; ++i)
+    if (opts->feature_layers[i] < 0 || opts->feature_layers[i] >= c.n_layers ||
+        (i > 0 && opts->feature_layers[i] <= opts->feature_layers[i - 1]))
+      return TRISPEC_EARG;
 
   hipStream_t st = (hipStream_t)opts->stream;
   char *ws = (char *)opts->workspace;
   const int rows = B * n_nodes, rp = rows_pad_for(rows);
+  // residual stream after layer l -> features_out, if l is one of the requested layers
+  int next_feature = 0;
+  auto export_layer = [&](int l, const float *xs) {
+    if (next_feature < opts->n_feature_layers && opts->feature_layers[next_feature] == l) {
+      launch_export_hidden(st, c.dtype, xs, nullptr, nullptr, 0, rows, rows_pad_for(rows), c.hidden, c.rms_eps,
+                           opts->features_out + (size_t)next_feature * rows * c.hidden);
+      ++next_feature;
+    }
+  };
   const bool f32 = c.dtype == TRISPEC_F32;
   const size_t es = esize(c.dtype);
   const int qd = c.n_q_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim, nqkv = qd + 2 * kvd;
@@ -621,6 +652,7 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
       gemm((const float *)act, c.ffn, 1, m->w_down[l], c.hidden, nullptr, 0, nullptr, 0, part);
       const void *next_norm = (l + 1 < c.n_layers) ? m->norm_attn[l + 1] : m->final_norm;
       launch_reduce_residual_norm(st, c.dtype, part, 1, rows, rp, c.hidden, next_norm, c.rms_eps, x, h);
+      export_layer(l, x);
     }
     float *logits = opts->debug_logits ? opts->debug_logits : (float *)(ws + L.logits);
     {
@@ -630,6 +662,21 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
     }
     if (opts->hidden_out)
       launch_export_hidden(st, c.dtype, h, nullptr, nullptr, 0, rows, rp, c.hidden, c.rms_eps, opts->hidden_out);
+    if (opts->adapter_w) {   // y = f W^T + b on the final-norm features (h is already normalised here)
+      GemmArgs g;
+      memset(&g, 0, sizeof(g));
+      g.x = h;
+      g.seg[0] = {opts->adapter_w, opts->adapter_dim, 0};
+      g.n_seg = 1;
+      g.n_total = opts->adapter_dim;
+      g.k = c.hidden;
+      g.rows = rows;
+      g.rows_pad = rp;
+      g.n_splits = 1;
+      g.out = opts->adapter_out;
+      g.bias = opts->adapter_bias;
+      launch_gemm_f32(st, g);
+    }
   } else {
     // ---------------- bf16 models: per layer QKV, attention (+ merge), O, gate/up, down
     void *h = ws + L.h, *h2 = ws + L.h2;
@@ -769,6 +816,7 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
         timed_gemm(mk_o(l, po, x, x, h), b_o);
         timed_gemm(mk_gu(l, pg, h), b_gu);
         timed_gemm(mk_dn(l, pd, x, x), b_dn);
+        export_layer(l, x);
         ss0_tiles = hid_tiles;
       }
     } else {
@@ -795,6 +843,7 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
         la.poll_naps = 1;
         TimedLaunch tl(opts->timer, TRISPEC_K_GEMM, st, b_o + b_gu + b_dn + (more ? b_qkv : 0.0));
         if (!launch_layer_bf16(st, la, lgrid)) return TRISPEC_ELAUNCH;
+        export_layer(l, x);
       }
     }
     {
@@ -805,6 +854,21 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
       g.hs = hs;
       g.debug_logits = opts->debug_logits;
       TimedLaunch tl(opts->timer, TRISPEC_K_HEAD, st, (double)c.vocab * c.hidden * es);
+      launch_gemm_bf16(st, g);
+    }
+    if (opts->adapter_w) {
+      // the adapter on the final-norm features: the LM head's operand panels and 1/rms again, another
+      // matrix, a plain fp32 result (+ bias)
+      SplitPlan pa = plan_gemm(EPI_RESID, opts->adapter_dim, c.hidden, rp);
+      if (pa.n_splits > 1 && pa.n_tiles > L.max_tiles) {   // no counters for that many tiles: one split
+        pa.n_splits = 1;
+        pa.k_per_split = (int)align_up(c.hidden, (c.hidden % 256 == 0) ? 256 : 64);
+      }
+      GemmArgs g = base(EPI_PLAIN, h, pan_h, ss0, hid_tiles, c.hidden, opts->adapter_dim, pa);
+      g.seg[0] = {opts->adapter_w, opts->adapter_dim, 0};
+      g.n_seg = 1;
+      g.out = opts->adapter_out;
+      g.bias = opts->adapter_bias;
       launch_gemm_bf16(st, g);
     }
     if (opts->hidden_out)   // x after the last layer, the final norm's weight, the sums of squares the last down projection left

@@ -363,6 +363,16 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, f32x16 (&acc)[N
         store_bf16x4<WT>(dst + ol_offset(r, feat, 0, MB), hi);
         store_bf16x4<WT>(dst + ol_offset(r, feat, 1, MB), lo);
       }
+    } else if constexpr (EPI == EPI_PLAIN) {
+      // ---- y = (x W^T) / rms + bias, written as it is (the adapter on the exported features)
+      constexpr int Q4 = TN / 4;
+      for (int t = tid; t < MG * 32 * Q4; t += NT) {
+        const int lr = t / Q4, c = (t % Q4) * 4, r = row0 + lr, col = tile * TN + c;
+        if (r >= a.rows || col >= a.n_total) continue;
+        f32x4 v = reduced4(lr, c) * s_rs[r];
+        if (a.bias != nullptr) v += *(const f32x4 *)(a.bias + col);
+        *(f32x4 *)(a.out + (size_t)r * a.n_total + col) = v;
+      }
     } else {
       // ---- EPI_RESID: x += y; per-row sum of squares of the new x over this tile's columns.
       // TN/4 consecutive lanes (4 columns each) cover one row of the tile.

@@ -51,7 +51,7 @@ struct GemmSeg {
   int32_t n_rows;
   int32_t col0;    // first output column of this segment
 };
-enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_HEAD = 3 };
+enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_HEAD = 3, EPI_PLAIN = 4 };
 struct GemmArgs {
   // fp32 reference-precision path: x is [rows_pad, K] fp32, out is [rows][n_total].
   // bf16 path: x is the bf16 hi panel [rows_pad, K], the lo panel follows x_panel elements later.
@@ -72,7 +72,8 @@ struct GemmArgs {
   int32_t n_tiles;
   int32_t tile_n;      // output columns per workgroup (128)
   int32_t epi;
-  float *out;          // fp32 path only
+  float *out;          // fp32 path, and the PLAIN epilogue: [rows][n_total] fp32
+  const float *bias;   // PLAIN epilogue / fp32 path: [n_total] added to every row, or nullptr
   float *part;         // [n_splits][n_tiles][rows_pad][128] split-K partial tiles
   int32_t *counters;   // [n_tiles + 1], zero between launches
   // QKV epilogue

@@ -300,6 +300,7 @@ void launch_gemm_bf16(hipStream_t st, const GemmArgs &a) {
     case EPI_QKV: dispatch<EPI_QKV>(st, a); break;
     case EPI_RESID: dispatch<EPI_RESID>(st, a); break;
     case EPI_SWIGLU: dispatch<EPI_SWIGLU>(st, a); break;
+    case EPI_PLAIN: dispatch<EPI_PLAIN>(st, a); break;
     default: dispatch<EPI_HEAD>(st, a); break;
   }
 }

@@ -289,7 +289,8 @@ __global__ __launch_bounds__(64) void k_gemm_f32(GemmArgs a) {
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     const float v = wave_sum(acc[j]);
-    if (threadIdx.x == 0 && r0 + j < a.rows) a.out[(size_t)(r0 + j) * a.n_total + col] = v;
+    if (threadIdx.x == 0 && r0 + j < a.rows)
+      a.out[(size_t)(r0 + j) * a.n_total + col] = v + (a.bias != nullptr ? a.bias[col] : 0.f);
   }
 }
 

@@ -524,3 +524,43 @@ def test_exported_features_equal_the_final_norm_output(key, tol):
         err = np.abs(got["hidden"][b] - ref).max(axis=1) / np.abs(ref).max(axis=1)
         assert err.max() <= tol, (b, err.max())
         logits_ok(shape, got["logits"][b], want[b]["logits"])      # the export does not disturb the pass
+
+
+@pytest.mark.parametrize("key,tol,mode", [("tiny", 2e-5, 0), ("tiny_bf16", 3e-4, 0), ("layer", 3e-4, 1)])
+def test_feature_layers_and_adapter(key, tol, mode):
+    """The drafter's inputs (Sec. 3.2, drafter selection and adapter): the residual stream after chosen
+    layers, and the adapter y = f W^T + b on the final-norm features, against the oracle."""
+    from oracle import adapter
+    shape = LAYER_SHAPE.with_(n_layers=3) if key == "layer" else SHAPES[key].with_(n_layers=3)
+    parents = [gen_tree(24, 6, 3, 5), gen_tree(24, 6, 3, 6)]
+    case = make_case(shape, 78, [40, 21], parents)
+    want = []
+    W = oracle_weights(shape, 78)
+    for b in range(2):
+        want.append(verify_forward(W, shape, case.k_ctx[b], case.v_ctx[b], case.tokens[b], case.parents[b],
+                                   case.positions[b], keep_hidden=True))
+    rng = np.random.default_rng(2)
+    dim = 200                                              # ragged against the 128-column tiles
+    A = (rng.standard_normal((dim, shape.hidden)) * 0.05).astype(np.float32)
+    bias = rng.standard_normal(dim).astype(np.float32)
+    gpu = case.run_gpu(0.5, launch_mode=mode)
+    ver, kv, tok = gpu["_ver"], gpu["_kv"], gpu["_tok"]
+    wt = torch.from_numpy(A).cuda()
+    if shape.dtype == "bf16":
+        wt = wt.to(torch.bfloat16)
+        A = wt.float().cpu().numpy()                       # the adapter as stored
+    out = ver.set_adapter(wt.contiguous(), torch.from_numpy(bias).cuda())
+    ver.feature_layers = [0, 2]
+    ver.verify(kv, tok, case.parents, torch.from_numpy(case.positions).cuda(), 0.5)
+    torch.cuda.synchronize()
+    feats = ver.features.cpu().numpy()
+    y = out.cpu().numpy()
+    for b in range(2):
+        for i, l in enumerate((0, 2)):
+            ref = want[b]["hidden"][l]
+            err = np.abs(feats[i, b] - ref).max(axis=1) / np.abs(ref).max(axis=1)
+            assert err.max() <= tol, (b, l, err.max())
+        ref = adapter(want[b]["final_hidden"], A, bias)
+        err = np.abs(y[b] - ref).max(axis=1) / np.abs(ref).max(axis=1)
+        assert err.max() <= tol, (b, err.max())
+        logits_ok(shape, ver.logits[b].cpu().numpy(), want[b]["logits"])

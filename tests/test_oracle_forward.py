@@ -286,3 +286,33 @@ def test_the_two_cache_boundary_readings_differ_by_less_than_the_tie_tolerances(
     assert worst[0] <= 1e-2 and worst[1] <= 5e-4 and worst[2] <= 3e-3
     assert worst[0] >= 1e-4          # the readings do differ: the bound is not vacuous
     assert compared >= 12
+
+
+def test_per_layer_hidden_states_and_the_adapter():
+    """hidden[l] (the residual stream after layer l, what a multi-layer drafter is fed) is pinned by
+    consistency with passes that are themselves pinned: it is the last hidden state of the same model
+    cut to l + 1 layers, and its final RMSNorm is final_hidden.  The adapter is one affine map:
+    identity weights return the features plus the bias, and it is linear."""
+    from oracle import adapter, rmsnorm
+    shape, seed, C, M = MICRO.with_(n_layers=3), 8, 7, 9
+    W = oracle_weights(shape, seed)
+    ctx = gen_context_tokens(shape.vocab, C, seed)
+    parents = gen_tree(M, 4, 3, seed)
+    toks = gen_draft_tokens(parents, shape.vocab, seed)
+    pos = C + tree_depths(parents)
+    Kc, Vc = prefill(shape, seed, ctx)
+    full = verify_forward(W, shape, Kc, Vc, toks, parents, pos, keep_hidden=True)
+    assert full["hidden"].shape == (3, M, shape.hidden)
+    for l in range(3):
+        cut = verify_forward(W, shape.with_(n_layers=l + 1), Kc[: l + 1], Vc[: l + 1], toks, parents, pos, keep_hidden=True)
+        assert np.array_equal(cut["hidden"][l], full["hidden"][l])
+    assert np.allclose(rmsnorm(full["hidden"][2], W("final_norm"), shape.rms_eps), full["final_hidden"], rtol=0, atol=1e-12)
+    assert np.abs(full["hidden"][0] - full["hidden"][2]).max() > 1e-3
+    f = full["final_hidden"]
+    rng = np.random.default_rng(1)
+    b = rng.standard_normal(shape.hidden)
+    assert np.allclose(adapter(f, np.eye(shape.hidden), b), f + b, rtol=0, atol=1e-14)
+    A = rng.standard_normal((20, shape.hidden))
+    want = np.array([[sum(A[o, i] * f[r, i] for i in range(shape.hidden)) for o in range(20)] for r in range(M)])
+    assert np.allclose(adapter(f, A), want, rtol=0, atol=1e-12)
+    assert np.allclose(adapter(2 * f, A, b), 2 * adapter(f, A) + b, rtol=0, atol=1e-12)
