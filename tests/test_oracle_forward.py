@@ -315,4 +315,5 @@ def test_per_layer_hidden_states_and_the_adapter():
     A = rng.standard_normal((20, shape.hidden))
     want = np.array([[sum(A[o, i] * f[r, i] for i in range(shape.hidden)) for o in range(20)] for r in range(M)])
     assert np.allclose(adapter(f, A), want, rtol=0, atol=1e-12)
-    assert np.allclose(adapter(2 * f, A, b), 2 * adapter(f, A) + b, rtol=0, atol=1e-12)
+    b20 = rng.standard_normal(20)
+    assert np.allclose(adapter(2 * f, A, b20), 2 * adapter(f, A) + b20, rtol=0, atol=1e-12)
