@@ -86,7 +86,7 @@ struct Layout {
 struct SplitPlan {
   int tile_n, n_tiles, n_splits, k_per_split;
 };
-constexpr int kTargetWgs = 192;
+constexpr int kTargetWgs = 192;   // swept 128 .. 384 at the 8B shape: 192 - 224 is the flat optimum
 constexpr int kLayerMaxGrid = 256;   // workgroups of the layer kernel (one per CU)
 constexpr int kLayerSplitCap = 8;    // k splits of one matmul inside the layer kernel
 // Longest wait at a device-side barrier, in ticks of the 100 MHz wall clock (2 s: three orders of
