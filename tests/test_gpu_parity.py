@@ -392,7 +392,7 @@ def test_verify_is_repeatable_and_deterministic():
     pos = torch.from_numpy(case.positions).cuda()
     first = {k: v.clone() for k, v in ver.out.items()}
     logits = ver.logits.clone()
-    for _ in range(3):
+    for _ in range(100):   # split-K and tile merges are order-fixed: every replay is the same bits
         ver.verify(kv, tok, case.parents, pos, 0.4)
         torch.cuda.synchronize()
         for k, v in ver.out.items():
