@@ -194,6 +194,10 @@ int trispec_prune_reroot(const int32_t *tokens, const int32_t *parents, const in
                          int32_t *out_tokens, int32_t *out_parents, int32_t *out_positions,
                          int32_t *out_old_id, int32_t *out_n_nodes, int32_t *out_n_forced);
 
+/* The context lengths a cache object holds now (they grow with trispec_kv_commit).
+ *   ctx_len_host  HOST [batch], written.   Errors: TRISPEC_ENULL. */
+int trispec_kv_get_len(const trispec_kv *kv, int32_t *ctx_len_host);
+
 /* Device scratch needed by trispec_verify for up to `batch` sequences of up to
  * `max_nodes` nodes (256-byte aligned buffer).  Errors: TRISPEC_ENULL, TRISPEC_ENODES. */
 int trispec_workspace_bytes(const trispec_model *m, int32_t batch, int32_t max_nodes,
@@ -400,6 +404,73 @@ int trispec_timer_create(int32_t kernel_class, int32_t capacity, trispec_timer *
 int trispec_timer_reset(trispec_timer *t);
 int trispec_timer_read(trispec_timer *t, int32_t *n_launches, double *total_ms, double *total_bytes);
 int trispec_timer_destroy(trispec_timer *t);
+
+/*
+ * One sequence decoded by the ternary scheme, greedy form on draft trees (Algorithm 1; Sec. 3.2
+ * Cases I and II, Eq. 10): the routing between proxy and target and the bookkeeping of the two
+ * caches, as host code on top of trispec_verify, trispec_prune_reroot and trispec_kv_commit.
+ * A round: the proxy verifies the draft tree at threshold lambda.  Case I (no escalation): the
+ * approved path is committed to the proxy's cache and the proxy's own token ends the round; the
+ * target does not run.  Case II: the target verifies, at threshold 0, the forced chain [tokens it
+ * has not cached yet] + [approved path v_0..v_tau_m] plus the subtree under v_tau_m; both caches
+ * commit what it accepted and its token ends the round.  The target's cache lags while rounds end
+ * at the proxy; when lagging tokens and tree do not fit one pass of max_nodes nodes, plain passes
+ * of the target ingest them first.
+ * Unlike the calls above these BLOCK: routing is a host decision, so every pass is followed by a
+ * copy of its decision to the host and a stream synchronisation.  They allocate no device memory.
+ * The drafter is the caller's: every round brings its own tree.
+ */
+typedef struct trispec_ternary trispec_ternary;
+#define TRISPEC_TERNARY_SCRATCH_INTS 512
+typedef struct {
+  trispec_model *proxy, *target;              /* M_p and M_t; the same vocabulary */
+  trispec_kv *kv_proxy, *kv_target;           /* caches of ONE sequence (batch 1), one per model */
+  void *workspace_proxy, *workspace_target;   /* device; trispec_workspace_bytes(model, 1, max_nodes) each */
+  size_t workspace_proxy_bytes, workspace_target_bytes;
+  int32_t *scratch_dev;                       /* device, TRISPEC_TERNARY_SCRATCH_INTS int32 */
+  int32_t criterion;                          /* TRISPEC_CRIT_* of the proxy pass (the target pass trusts itself) */
+  int32_t max_nodes;                          /* 1 .. TRISPEC_MAX_NODES: the largest pass */
+  void *stream;                               /* hipStream_t; NULL = the default stream */
+} trispec_ternary_config;
+
+typedef struct {                              /* decision of one pass, on the host */
+  int32_t accepted_len, token, escalate, status, path_len;
+  int32_t path[TRISPEC_PATH_STRIDE];
+} trispec_pass_result;
+
+typedef struct {
+  int32_t escalate;                           /* 1 = Case II: the target ran */
+  int32_t catch_up;                           /* plain target passes that first ingested lagging tokens */
+  int32_t target_nodes, n_forced_target;      /* shape of the target's pass (Case II) */
+  int32_t n_emitted;                          /* tokens this round appended to the sequence */
+  int32_t ctx_len_proxy, ctx_len_target;      /* after the round */
+  trispec_pass_result proxy, target;          /* `target` is meaningful in Case II only; its path is in
+                                                 node ids of the target's (pruned, re-rooted) pass */
+} trispec_round_info;
+
+/* Copies the config; the objects it names must outlive the decoder.  Makes no HIP call.
+ * Errors: TRISPEC_ENULL, TRISPEC_ENODES (max_nodes, cache batch != 1), TRISPEC_EMISMATCH (a cache of
+ * another model, different vocabularies), TRISPEC_EARG (criterion), TRISPEC_EWORKSPACE. */
+int trispec_ternary_create(const trispec_ternary_config *cfg, trispec_ternary **out);
+int trispec_ternary_destroy(trispec_ternary *t);
+/* New sequence: both caches are emptied and take in prompt[0 .. n_prompt-2] by plain passes; the
+ * last prompt token is the first root.  prompt_host: HOST [n_prompt], n_prompt >= 1.
+ * Errors: those of trispec_verify / trispec_kv_commit, TRISPEC_EARG (token ids, n_prompt). */
+int trispec_ternary_start(trispec_ternary *t, const int32_t *prompt_host, int32_t n_prompt);
+/* Takes over a sequence whose caches the caller has advanced by other means (e.g. rounds of the
+ * sampling form): seq_host HOST [n_seq] is the emitted sequence; the proxy's cache must hold
+ * n_seq - 1 tokens and the target's at most that.  Errors: TRISPEC_ENULL, TRISPEC_EARG. */
+int trispec_ternary_resume(trispec_ternary *t, const int32_t *seq_host, int32_t n_seq);
+/* One round.  parents_host / tokens_host: HOST [n_nodes], the draft tree (tokens_host[0] is ignored:
+ * the root is the last token of the sequence); positions follow from the proxy cache's length and
+ * the depths.  info_host (optional) receives what happened.  On an error from a pass nothing has
+ * been committed by the failing step, but earlier steps of the round (catch-up passes) stay.
+ * Errors: those of trispec_verify / trispec_prune_reroot / trispec_kv_commit, TRISPEC_EARG (a token id
+ * outside the vocabulary, or a device-side status bit after a pass), TRISPEC_ESTATE (no sequence started). */
+int trispec_ternary_round(trispec_ternary *t, const int32_t *parents_host, const int32_t *tokens_host,
+                          int32_t n_nodes, float lambda, trispec_round_info *info_host);
+/* View of the sequence emitted so far (prompt included), valid until the next call on `t`. */
+int trispec_ternary_sequence(const trispec_ternary *t, const int32_t **tokens_host, int32_t *n_tokens);
 
 /* Test hook: byte offset and size, inside the workspace of a verify call with these
  * (batch, n_nodes), of a named intermediate of the LAST layer ("x" residual stream fp32;

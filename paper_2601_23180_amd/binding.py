@@ -31,6 +31,8 @@ EXPORTS = [
     "trispec_kv_commit", "trispec_sample_scratch_bytes", "trispec_sample_decide",
     "trispec_sample_decide_static", "trispec_debug_set_spin_limit", "trispec_wait_probe",
     "trispec_prune_reroot", "trispec_draft_ranks", "trispec_pack_matrix_bytes", "trispec_pack_matrix",
+    "trispec_kv_get_len", "trispec_ternary_create", "trispec_ternary_destroy", "trispec_ternary_start",
+    "trispec_ternary_resume", "trispec_ternary_round", "trispec_ternary_sequence",
 ]
 K_GEMM, K_HEAD, K_ATTN = 0, 1, 2
 LAUNCH_PER_MATMUL, LAUNCH_PER_LAYER = 0, 1
@@ -43,6 +45,26 @@ class ModelConfig(C.Structure):
 
 
 _PP = C.POINTER(C.c_void_p)
+TERNARY_SCRATCH_INTS = 512
+
+
+class TernaryConfig(C.Structure):
+    _fields_ = [("proxy", C.c_void_p), ("target", C.c_void_p), ("kv_proxy", C.c_void_p), ("kv_target", C.c_void_p),
+                ("workspace_proxy", C.c_void_p), ("workspace_target", C.c_void_p),
+                ("workspace_proxy_bytes", C.c_size_t), ("workspace_target_bytes", C.c_size_t),
+                ("scratch_dev", C.c_void_p), ("criterion", C.c_int32), ("max_nodes", C.c_int32),
+                ("stream", C.c_void_p)]
+
+
+class PassResult(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("accepted_len", "token", "escalate", "status", "path_len")] + \
+               [("path", C.c_int32 * 64)]
+
+
+class RoundInfo(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("escalate", "catch_up", "target_nodes", "n_forced_target", "n_emitted",
+                                         "ctx_len_proxy", "ctx_len_target")] + \
+               [("proxy", PassResult), ("target", PassResult)]
 
 
 class Weights(C.Structure):
@@ -104,6 +126,14 @@ def lib() -> C.CDLL:
         l.trispec_kv_create.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                         C.POINTER(C.c_void_p)]
         l.trispec_kv_set_len.argtypes = [C.c_void_p, C.POINTER(C.c_int32)]
+        l.trispec_kv_get_len.argtypes = [C.c_void_p, C.POINTER(C.c_int32)]
+        l.trispec_ternary_create.argtypes = [C.POINTER(TernaryConfig), C.POINTER(C.c_void_p)]
+        l.trispec_ternary_destroy.argtypes = [C.c_void_p]
+        l.trispec_ternary_start.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.c_int32]
+        l.trispec_ternary_resume.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.c_int32]
+        l.trispec_ternary_round.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int32,
+                                            C.c_float, C.POINTER(RoundInfo)]
+        l.trispec_ternary_sequence.argtypes = [C.c_void_p, C.POINTER(C.POINTER(C.c_int32)), C.POINTER(C.c_int32)]
         l.trispec_kv_destroy.argtypes = [C.c_void_p]
         l.trispec_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
         l.trispec_workspace_region.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_char_p,
@@ -248,6 +278,12 @@ class KVCache:
         arr = (C.c_int32 * self.batch)(*ctx_len)
         check(lib().trispec_kv_set_len(self.handle, arr))
         self.ctx_len = list(ctx_len)
+
+    def sync_len(self) -> None:
+        """Re-read the context lengths from the library (after calls that commit inside it)."""
+        arr = (C.c_int32 * self.batch)()
+        check(lib().trispec_kv_get_len(self.handle, arr))
+        self.ctx_len = list(arr)
 
     def commit(self, nodes: Sequence[Sequence[int]], stream=None) -> None:
         """trispec_kv_commit: nodes[b] = node ids of sequence b's verified path, root first."""

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtrispec.so")
-SOURCES = ["api.cpp", "kernels_misc.hip", "kernels_gemm.hip", "kernels_layer.hip", "kernels_attn.hip", "kernels_sample.hip"]
+SOURCES = ["api.cpp", "ternary.cpp", "kernels_misc.hip", "kernels_gemm.hip", "kernels_layer.hip", "kernels_attn.hip", "kernels_sample.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -10,32 +10,9 @@
 #include <vector>
 
 #include "internal.hpp"
+#include "host_objects.hpp"
 
 using namespace ts;
-
-struct trispec_model {
-  trispec_model_config cfg;
-  const void *embed, *lm_head, *final_norm;
-  std::vector<const void *> wq, wk, wv, wo, w_gate, w_up, w_down, norm_attn, norm_ffn, q_norm, k_norm;
-  // bf16 models: packed copies of the matrices (device, inside the caller's pack buffer)
-  bool packed;
-  int layer_grid[3][2];   // largest resident grid of the layer kernel for rows_pad 32 / 64 / 128 and ring depth 8 / 4 (-1: not asked yet)
-  const void *p_lm_head;
-  std::vector<const void *> p_wq, p_wk, p_wv, p_wo, p_gate, p_up, p_down;
-};
-
-struct trispec_kv {
-  const trispec_model *model;
-  void *k, *v;
-  int32_t batch, capacity;
-  int32_t ctx_len[kMaxBatch];
-};
-
-struct trispec_timer {
-  int32_t kernel_class, capacity, count;
-  double bytes;
-  std::vector<hipEvent_t> start, stop;
-};
 
 namespace {
 
@@ -443,6 +420,12 @@ int trispec_kv_set_len(trispec_kv *kv, const int32_t *ctx_len_host) {
   for (int b = 0; b < kv->batch; ++b)
     if (ctx_len_host[b] < 0 || ctx_len_host[b] > kv->capacity) return TRISPEC_ECAPACITY;
   for (int b = 0; b < kv->batch; ++b) kv->ctx_len[b] = ctx_len_host[b];
+  return TRISPEC_OK;
+}
+
+int trispec_kv_get_len(const trispec_kv *kv, int32_t *ctx_len_host) {
+  if (!kv || !ctx_len_host) return TRISPEC_ENULL;
+  for (int b = 0; b < kv->batch; ++b) ctx_len_host[b] = kv->ctx_len[b];
   return TRISPEC_OK;
 }
 

@@ -1,35 +1,31 @@
-"""Round driver of the ternary scheme on top of the C ABI (Alg. 1 of the paper; greedy on draft
-trees, and the sampling form on draft chains).
+"""The ternary scheme's rounds (Alg. 1 of the paper) for one sequence (batch 1).
 
-Host control flow only — a few dozen integers per round; every model pass is one
-trispec_verify call and every cache update one trispec_kv_commit call.  One sequence (batch 1).
-
-  round:  draft tree -> proxy pass (threshold lambda)
-          Case I  (no escalation): commit the approved path to the proxy cache; the proxy's
-                  correction / bonus token is the next root.  The target is not run.
-          Case II (escalation): the target verifies [tokens it has not cached yet] + [approved
-                  path v_0..v_tau_m] as a forced chain, plus the subtree under v_tau_m
-                  (Eq. 10), with lambda = 0; both caches commit what was accepted; the target's
-                  token is the next root.
-The target's cache lags behind while rounds end at the proxy; tokens it has not seen ride along
-as the head of the forced chain, or go in by plain catch-up passes when they do not fit.
+The greedy form on draft trees runs inside the library (`trispec_ternary_*`: proxy pass, routing
+into Case I / Case II, prune and re-root, target pass, cache commits and target catch-up); this
+class allocates the device buffers and marshals arguments.  The sampling form on draft chains
+(`round_sample`) is host control flow here on top of trispec_verify / trispec_sample_decide /
+trispec_kv_commit: a few dozen integers per round.
 """
 from __future__ import annotations
 
+import ctypes as C
 from typing import Dict, List, Sequence
 
 import numpy as np
 import torch
 
-from .binding import (CRIT_MARGIN, MAX_NODES, RESAMPLE_RESIDUAL, KVCache, Model, SampleDecider, TriSpecError, Verifier,
-                      prune_reroot)
+from .binding import (CRIT_MARGIN, MAX_NODES, RESAMPLE_RESIDUAL, TERNARY_SCRATCH_INTS, KVCache, Model, RoundInfo,
+                      SampleDecider, TernaryConfig, Verifier, check, lib)
 
 
-def _depths(parents: Sequence[int]) -> np.ndarray:
-    d = np.zeros(len(parents), dtype=np.int32)
-    for i in range(1, len(parents)):
-        d[i] = d[parents[i]] + 1
-    return d
+def _aligned(n_bytes: int):
+    t = torch.zeros(n_bytes + 256, dtype=torch.uint8, device="cuda")
+    return t, t.data_ptr() + (-t.data_ptr()) % 256
+
+
+def _pass_dict(r) -> Dict[str, object]:
+    return {"accepted_len": int(r.accepted_len), "token": int(r.token), "escalate": int(r.escalate),
+            "path": [int(r.path[i]) for i in range(r.path_len)]}
 
 
 class TernaryDecoder:
@@ -42,8 +38,70 @@ class TernaryDecoder:
         self._dec: Dict[tuple, SampleDecider] = {}
         self.seq: List[int] = []
         self.target_passes = 0          # passes of the target that verified drafts (not catch-up)
+        cfg = TernaryConfig()
+        cfg.proxy, cfg.target = proxy.handle, target.handle
+        cfg.kv_proxy, cfg.kv_target = self.kv_p.handle, self.kv_t.handle
+        cfg.workspace_proxy_bytes = proxy.workspace_bytes(1, max_nodes)
+        cfg.workspace_target_bytes = target.workspace_bytes(1, max_nodes)
+        self._ws_p, cfg.workspace_proxy = _aligned(cfg.workspace_proxy_bytes)
+        self._ws_t, cfg.workspace_target = _aligned(cfg.workspace_target_bytes)
+        self._scratch = torch.zeros(TERNARY_SCRATCH_INTS, dtype=torch.int32, device="cuda")
+        cfg.scratch_dev = self._scratch.data_ptr()
+        cfg.criterion, cfg.max_nodes = criterion, max_nodes
+        cfg.stream = torch.cuda.current_stream().cuda_stream
+        self.handle = C.c_void_p()
+        check(lib().trispec_ternary_create(C.byref(cfg), C.byref(self.handle)))
+        self._stale = False             # the library's copy of the sequence is behind self.seq
 
-    # -- one pass --------------------------------------------------------------------------
+    def close(self):
+        if self.handle:
+            lib().trispec_ternary_destroy(self.handle)
+            self.handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _pull(self) -> None:
+        """Sequence and cache lengths as the library holds them now."""
+        p, n = C.POINTER(C.c_int32)(), C.c_int32()
+        check(lib().trispec_ternary_sequence(self.handle, C.byref(p), C.byref(n)))
+        self.seq = [int(p[i]) for i in range(n.value)]
+        self.kv_p.sync_len()
+        self.kv_t.sync_len()
+
+    # -- API -------------------------------------------------------------------------------
+    def start(self, prompt: Sequence[int]) -> None:
+        """Caches of both models over the prompt but its last token (the first root)."""
+        arr = (C.c_int32 * len(prompt))(*[int(t) for t in prompt])
+        torch.cuda.current_stream().synchronize()
+        check(lib().trispec_ternary_start(self.handle, arr, len(prompt)))
+        self._pull()
+        self._stale = False
+
+    def round(self, parents: Sequence[int], tokens: Sequence[int], lam: float) -> Dict[str, object]:
+        """One round on a draft tree (tokens[0] is replaced by the current root).  Returns what
+        happened; self.seq has grown by the accepted drafts and one verifier token."""
+        n = len(tokens)
+        if self._stale:
+            arr = (C.c_int32 * len(self.seq))(*self.seq)
+            check(lib().trispec_ternary_resume(self.handle, arr, len(self.seq)))
+            self._stale = False
+        par = (C.c_int32 * n)(*[int(p) for p in parents])
+        tok = (C.c_int32 * n)(*[int(t) for t in tokens])
+        info = RoundInfo()
+        check(lib().trispec_ternary_round(self.handle, par, tok, n, float(lam), C.byref(info)))
+        self._pull()
+        rec = {"proxy": _pass_dict(info.proxy), "escalate": int(info.escalate), "catch_up": int(info.catch_up)}
+        if info.escalate:
+            self.target_passes += 1
+            rec.update({"target": _pass_dict(info.target), "target_nodes": int(info.target_nodes),
+                        "n_forced_t": int(info.n_forced_target)})
+        return rec
+
+    # -- passes driven from here (sampling form) ------------------------------------------------
     def _pass(self, which: str, tokens, parents, positions, lam: float, criterion: int, n_forced: int):
         model, kv = (self.proxy, self.kv_p) if which == "p" else (self.target, self.kv_t)
         n = len(tokens)
@@ -53,11 +111,8 @@ class TernaryDecoder:
         tok = torch.tensor([list(map(int, tokens))], dtype=torch.int32, device="cuda")
         pos = torch.tensor([list(map(int, positions))], dtype=torch.int32, device="cuda")
         par = np.asarray([list(map(int, parents))], dtype=np.int32)
-        out = ver.verify(kv, tok, par, pos, lam, criterion, n_forced, want_logits=False)
+        ver.verify(kv, tok, par, pos, lam, criterion, n_forced, want_logits=False)
         torch.cuda.synchronize()
-        return {"accepted_len": int(out["accepted_len"][0]), "token": int(out["token"][0]),
-                "escalate": int(out["escalate"][0]),
-                "path": [int(v) for v in out["path"][0].cpu().numpy() if v >= 0]}
 
     def _ingest(self, which: str, tokens: Sequence[int]) -> None:
         """Plain passes over certain tokens: a forced chain, everything committed."""
@@ -68,52 +123,6 @@ class TernaryDecoder:
             n, c = len(chunk), kv.ctx_len[0]
             self._pass(which, chunk, range(-1, n - 1), range(c, c + n), 0.0, CRIT_MARGIN, n)
             kv.commit([list(range(n))])
-
-    # -- API -------------------------------------------------------------------------------
-    def start(self, prompt: Sequence[int]) -> None:
-        """Caches of both models over the prompt but its last token (the first root)."""
-        self.seq = [int(t) for t in prompt]
-        self.kv_p.set_len([0]); self.kv_t.set_len([0])
-        self._ingest("p", self.seq[:-1])
-        self._ingest("t", self.seq[:-1])
-
-    def round(self, parents: Sequence[int], tokens: Sequence[int], lam: float) -> Dict[str, object]:
-        """One round on a draft tree (tokens[0] is replaced by the current root).  Returns what
-        happened; self.seq has grown by the accepted drafts and one verifier token."""
-        parents = [int(p) for p in parents]
-        tokens = [int(t) for t in tokens]
-        tokens[0] = self.seq[-1]
-        cp = self.kv_p.ctx_len[0]
-        positions = cp + _depths(parents)
-        pr = self._pass("p", tokens, parents, positions, lam, self.criterion, 1)
-        rec = {"proxy": pr, "escalate": pr["escalate"], "catch_up": 0}
-        path = pr["path"]
-        if not pr["escalate"]:                                               # Case I
-            self.kv_p.commit([path])
-            self.seq += [tokens[i] for i in path[1:]] + [pr["token"]]
-            return rec
-        t_len = self.kv_t.ctx_len[0]                                         # Case II
-        unseen = self.seq[t_len:-1]
-        sub = None
-        try:       # the pruned, re-rooted tree behind the tokens the target has not cached yet (library call)
-            sub = prune_reroot(tokens, parents, positions, path, unseen, t_len)
-        except TriSpecError as e:
-            if e.code != -3:                                                 # TRISPEC_ENODES: does not fit
-                raise
-        if sub is None or len(sub["tokens"]) > self.max_nodes:
-            before = self.kv_t.ctx_len[0]
-            self._ingest("t", unseen)
-            rec["catch_up"] = (self.kv_t.ctx_len[0] - before + self.max_nodes - 1) // self.max_nodes
-            sub = prune_reroot(tokens, parents, positions, path)
-        tok_t, n_forced = sub["tokens"], sub["n_forced"]
-        tr = self._pass("t", tok_t, sub["parents"], sub["positions"], 0.0, CRIT_MARGIN, n_forced)
-        self.target_passes += 1
-        self.kv_t.commit([list(range(n_forced - 1)) + tr["path"]])
-        extra = [sub["old_id"][n] for n in tr["path"][1:]]                   # drafts the target accepted, old ids
-        self.kv_p.commit([path + extra])
-        self.seq += [tokens[i] for i in path[1:] + extra] + [tr["token"]]
-        rec.update({"target": tr, "target_nodes": len(tok_t), "n_forced_t": n_forced})
-        return rec
 
     # -- sampling form (temperature > 0), draft chains -----------------------------------------
     def _pass_sample(self, which: str, tokens, positions, p_draft, u_accept, u_sample, lam: float, criterion: int,
@@ -160,6 +169,7 @@ class TernaryDecoder:
         if not pr["escalate"]:                                               # Case I
             self.kv_p.commit([path])
             self.seq += [tokens[i] for i in path[1:]] + [pr["token"]]
+            self._stale = True
             return rec
         tau_m = pr["accepted_len"]                                           # Case II
         t_len = self.kv_t.ctx_len[0]
@@ -183,5 +193,6 @@ class TernaryDecoder:
         extra = [n - u for n in tr["path"][1:]]                              # drafts the target accepted, chain ids
         self.kv_p.commit([path + extra])
         self.seq += [tokens[i] for i in path[1:] + extra] + [tr["token"]]
+        self._stale = True
         rec.update({"target": tr, "target_nodes": u + M, "n_forced_t": n_forced})
         return rec

@@ -206,7 +206,68 @@ static void verify_args() {
   EXPECT(trispec_sample_scratch_bytes(2, 9, 50000, nullptr) == TRISPEC_ENULL);
 }
 
+// The round driver's host-side checks (Algorithm 1's routing lives behind the boundary).
+static void ternary_args() {
+  std::vector<const void *> tp, tt;
+  trispec_model *mp = make_model(TRISPEC_F32, tp), *mt = make_model(TRISPEC_F32, tt);
+  trispec_kv *kp = nullptr, *kt = nullptr;
+  EXPECT(trispec_kv_create(mp, (void *)0x10000, (void *)0x20000, 1, 256, &kp) == TRISPEC_OK);
+  EXPECT(trispec_kv_create(mt, (void *)0x30000, (void *)0x40000, 1, 256, &kt) == TRISPEC_OK);
+  trispec_ternary_config c;
+  memset(&c, 0, sizeof c);
+  c.proxy = mp; c.target = mt; c.kv_proxy = kp; c.kv_target = kt;
+  c.workspace_proxy = (void *)0x100000; c.workspace_target = (void *)0x200000;
+  c.workspace_proxy_bytes = c.workspace_target_bytes = (size_t)1 << 40;
+  c.scratch_dev = (int32_t *)0x300000; c.criterion = TRISPEC_CRIT_MARGIN; c.max_nodes = 24;
+  trispec_ternary *t = nullptr;
+  for (int it = 0; it < 200; ++it) {
+    trispec_ternary_config d = c;
+    switch (rnd() % 6) {
+      case 0: d.max_nodes = rint_in(-3, 80); break;
+      case 1: d.criterion = rint_in(-2, 6); break;
+      case 2: d.kv_target = kp; break;
+      case 3: d.workspace_proxy_bytes = rnd() % 4096; break;
+      case 4: d.scratch_dev = nullptr; break;
+      default: break;
+    }
+    trispec_ternary *x = nullptr;
+    const int rc = trispec_ternary_create(&d, &x);
+    EXPECT(rc == TRISPEC_OK || rc == TRISPEC_ENULL || rc == TRISPEC_ENODES || rc == TRISPEC_EMISMATCH ||
+           rc == TRISPEC_EARG || rc == TRISPEC_EWORKSPACE);
+    if (rc == TRISPEC_OK) EXPECT(trispec_ternary_destroy(x) == TRISPEC_OK);
+  }
+  EXPECT(trispec_ternary_create(&c, &t) == TRISPEC_OK && t);
+  int32_t par[80], tok[80];
+  trispec_round_info info;
+  EXPECT(trispec_ternary_round(t, par, tok, 4, 0.5f, &info) == TRISPEC_ESTATE);
+  const int32_t one = 17;
+  EXPECT(trispec_ternary_resume(t, &one, 1) == TRISPEC_OK);
+  for (int it = 0; it < 3000; ++it) {
+    const int n = rint_in(-1, 30);
+    const int nn = n < 1 ? 1 : n;
+    par[0] = (rnd() % 20 == 0) ? 0 : -1;
+    for (int i = 1; i < nn; ++i) par[i] = rint_in(0, i - 1);
+    for (int i = 0; i < nn; ++i) tok[i] = rint_in(0, 4098);
+    // always wrong somewhere, so that no pass is ever launched: too many nodes, a bad parent or a bad token
+    if (n >= 2 && n <= 24) {
+      if (rnd() & 1) par[rint_in(1, n - 1)] = n + rint_in(0, 5);
+      else tok[rint_in(1, n - 1)] = (rnd() & 1) ? -1 - (int)(rnd() % 9) : 4099 + (int)(rnd() % 9);
+    } else if (n == 1) {
+      par[0] = 0;
+    }
+    const int rc = trispec_ternary_round(t, par, tok, n, 0.5f, (rnd() & 1) ? &info : nullptr);
+    EXPECT(rc == TRISPEC_ENODES || rc == TRISPEC_ETREE || rc == TRISPEC_EARG);
+  }
+  const int32_t *seq = nullptr;
+  int32_t nseq = 0;
+  EXPECT(trispec_ternary_sequence(t, &seq, &nseq) == TRISPEC_OK && nseq == 1 && seq[0] == 17);
+  EXPECT(trispec_ternary_destroy(t) == TRISPEC_OK);
+  EXPECT(trispec_kv_destroy(kp) == TRISPEC_OK && trispec_kv_destroy(kt) == TRISPEC_OK);
+  EXPECT(trispec_model_destroy(mp) == TRISPEC_OK && trispec_model_destroy(mt) == TRISPEC_OK);
+}
+
 int main() {
+  ternary_args();
   shapes();
   prune();
   verify_args();

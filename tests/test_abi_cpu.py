@@ -264,3 +264,70 @@ def test_prune_reroot_errors():
         B.prune_reroot(tok, par, pos, [0], list(range(62)), 0)
     assert e.value.code == -3
     assert len(B.prune_reroot(tok, par, pos, [0], list(range(60)), 0)["tokens"]) == 64
+
+
+def test_ternary_driver_rejects_bad_arguments_and_kv_len_round_trip():
+    """trispec_ternary_* (Alg. 1's routing behind the boundary): what can be refused on the host is
+    refused there; nothing here reaches a GPU."""
+    lib = B.lib()
+    _, mp, keep_p = _model()
+    _, mt, keep_t = _model(n_layers=3)
+    _, mv, keep_v = _model(vocab=4097)
+    kvs = []
+    for m, batch in ((mp, 1), (mt, 1), (mt, 2), (mv, 1)):
+        h = C.c_void_p()
+        assert lib.trispec_kv_create(m, 0x10000, 0x20000, batch, 256, C.byref(h)) == 0
+        kvs.append(h)
+    kv_p, kv_t, kv_t2, kv_v = kvs
+    lens = (C.c_int32 * 2)(7, 9)
+    assert lib.trispec_kv_set_len(kv_t2, lens) == 0
+    got = (C.c_int32 * 2)()
+    assert lib.trispec_kv_get_len(kv_t2, got) == 0 and list(got) == [7, 9]
+    assert lib.trispec_kv_get_len(None, got) == -1
+
+    def make(**kw):
+        cfg = B.TernaryConfig()
+        cfg.proxy, cfg.target, cfg.kv_proxy, cfg.kv_target = mp, mt, kv_p, kv_t
+        cfg.workspace_proxy, cfg.workspace_target = 0x100000, 0x200000
+        cfg.workspace_proxy_bytes = cfg.workspace_target_bytes = 1 << 40
+        cfg.scratch_dev, cfg.criterion, cfg.max_nodes = 0x300000, B.CRIT_MARGIN, 16
+        for k, v in kw.items():
+            setattr(cfg, k, v)
+        h = C.c_void_p()
+        return lib.trispec_ternary_create(C.byref(cfg), C.byref(h)), h
+
+    rc, t = make()
+    assert rc == 0
+    assert make(scratch_dev=None)[0] == -1 and make(proxy=None)[0] == -1
+    assert make(max_nodes=0)[0] == -3 and make(max_nodes=65)[0] == -3
+    assert make(kv_target=kv_t2)[0] == -3                        # a cache of two sequences
+    assert make(kv_target=kv_p)[0] == -9                         # the other model's cache
+    assert make(target=mv, kv_target=kv_v)[0] == -9              # vocabularies differ
+    assert make(criterion=5)[0] == -8
+    assert make(workspace_proxy_bytes=1024)[0] == -7 and make(workspace_target=None)[0] == -7
+    assert lib.trispec_ternary_create(None, None) == -1
+    # no sequence yet; bad trees and tokens
+    par = (C.c_int32 * 4)(-1, 0, 1, 1)
+    tok = (C.c_int32 * 4)(0, 5, 6, 7)
+    info = B.RoundInfo()
+    assert lib.trispec_ternary_round(t, par, tok, 4, 0.5, C.byref(info)) == -11
+    assert lib.trispec_ternary_start(t, None, 3) == -1
+    assert lib.trispec_ternary_start(t, tok, 0) == -8
+    assert lib.trispec_ternary_start(t, (C.c_int32 * 2)(3, 4096), 2) == -8       # token id outside the vocabulary
+    # take over a sequence of one token with empty caches (no pass needed), then argument checks of a round
+    zero = (C.c_int32 * 1)(0)
+    assert lib.trispec_kv_set_len(kv_p, zero) == 0 and lib.trispec_kv_set_len(kv_t, zero) == 0
+    assert lib.trispec_ternary_resume(t, (C.c_int32 * 2)(3, 4), 2) == -8          # the proxy cache holds 0 tokens, not 1
+    assert lib.trispec_ternary_resume(t, (C.c_int32 * 1)(3), 1) == 0
+    p, n = C.POINTER(C.c_int32)(), C.c_int32()
+    assert lib.trispec_ternary_sequence(t, C.byref(p), C.byref(n)) == 0 and n.value == 1 and p[0] == 3
+    assert lib.trispec_ternary_round(t, par, tok, 17, 0.5, C.byref(info)) == -3   # more than max_nodes
+    assert lib.trispec_ternary_round(t, (C.c_int32 * 4)(-1, 0, 2, 1), tok, 4, 0.5, C.byref(info)) == -4
+    assert lib.trispec_ternary_round(t, (C.c_int32 * 4)(0, 0, 1, 1), tok, 4, 0.5, C.byref(info)) == -4
+    assert lib.trispec_ternary_round(t, par, (C.c_int32 * 4)(0, 5, -1, 7), 4, 0.5, C.byref(info)) == -8
+    assert lib.trispec_ternary_round(t, None, tok, 4, 0.5, C.byref(info)) == -1
+    assert lib.trispec_ternary_destroy(t) == 0
+    for h in kvs:
+        lib.trispec_kv_destroy(h)
+    for m in (mp, mt, mv):
+        lib.trispec_model_destroy(m)

@@ -24,18 +24,22 @@ def _run(cmd):
 
 @pytest.mark.skipif(shutil.which(B.HIPCC) is None, reason="no hipcc")
 def test_host_paths_under_address_and_undefined_behaviour_sanitizers(tmp_path):
-    kernel_objs = [os.path.join(B.BUILD, os.path.splitext(s)[0] + ".o") for s in B.SOURCES if s != "api.cpp"]
+    host_srcs = ("api.cpp", "ternary.cpp")
+    kernel_objs = [os.path.join(B.BUILD, os.path.splitext(s)[0] + ".o") for s in B.SOURCES if s not in host_srcs]
     if not all(os.path.exists(o) for o in kernel_objs):
         B.build(verbose=False)
-    api_o, drv_o, exe = (str(tmp_path / n) for n in ("api_san.o", "driver.o", "driver"))
+    drv_o, exe = str(tmp_path / "driver.o"), str(tmp_path / "driver")
+    host_objs = [str(tmp_path / (os.path.splitext(s)[0] + "_san.o")) for s in host_srcs]
     host_san = [x for f in SAN for x in ("-Xarch_host", f)]      # the host pass only
     flags = [f for f in B.FLAGS if f != "-O3"]
-    _run([B.HIPCC, "-O1", "-g", *flags, *host_san, "-c", os.path.join(B.CSRC, "api.cpp"), "-o", api_o])
+    for src, obj in zip(host_srcs, host_objs):
+        _run([B.HIPCC, "-O1", "-g", *flags, *host_san, "-c", os.path.join(B.CSRC, src), "-o", obj])
     _run([B.HIPCC, "-O1", "-g", "-std=c++17", "-I", os.path.join(ROOT, "include"), *SAN, "-x", "c++", "-c",
           os.path.join(ROOT, "tests", "sanitize", "abi_host_paths.cpp"), "-o", drv_o])
-    _run([B.HIPCC, "--offload-arch=gfx950", *SAN, "-fno-gpu-sanitize", "-o", exe, drv_o, api_o, *kernel_objs])
-    syms = subprocess.run(["nm", api_o], capture_output=True, text=True).stdout
-    assert "__asan_" in syms and "__ubsan_" in syms          # the instrumentation is really there
+    _run([B.HIPCC, "--offload-arch=gfx950", *SAN, "-fno-gpu-sanitize", "-o", exe, drv_o, *host_objs, *kernel_objs])
+    for obj in host_objs:
+        syms = subprocess.run(["nm", obj], capture_output=True, text=True).stdout
+        assert "__asan_" in syms and "__ubsan_" in syms      # the instrumentation is really there
     r = subprocess.run([exe], capture_output=True, text=True, timeout=300,
                        env={**os.environ, "ASAN_OPTIONS": "detect_leaks=0:abort_on_error=0"})
     assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-4000:]

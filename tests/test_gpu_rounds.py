@@ -146,6 +146,26 @@ def _run_decoder(shape, seed_p, seed_t, prompt, drafts, n_rounds, lam, max_nodes
     return dec, recs
 
 
+def test_taking_over_a_sequence_continues_it_exactly():
+    """trispec_ternary_resume: a driver that is handed the emitted sequence again (as after rounds the
+    caller ran by other means) goes on exactly like one that never lost it."""
+    shape = SHAPES["tiny"]
+    Wp = oracle_weights(shape, 51)
+    prompt = gen_context_tokens(shape.vocab, 10, 51).tolist()
+    drafts = mixed_drafts(Wp, shape, 51, 12)
+    a, recs_a = _run_decoder(shape, 51, 52, prompt, drafts, 6, 0.35)
+    from paper_2601_23180_amd import TernaryDecoder
+    b = TernaryDecoder(device_model(shape, 51), device_model(shape, 52), 256)
+    b.start(prompt)
+    recs_b = []
+    for r in range(6):
+        b._stale = True                      # forces the take-over path before every round
+        recs_b.append(b.round(*drafts(r, b.seq), 0.35))
+    assert recs_a == recs_b and a.seq == b.seq
+    assert a.kv_p.ctx_len == b.kv_p.ctx_len and a.kv_t.ctx_len == b.kv_t.ctx_len
+    assert any(r["escalate"] for r in recs_a) and not all(r["escalate"] for r in recs_a)
+
+
 @pytest.mark.parametrize("shape_name,lam,max_nodes", [("tiny", 0.0, 64), ("tiny", 0.35, 64), ("tiny", 2.0, 64),
                                                        ("tiny", 0.35, 16), ("tiny_bf16", 0.35, 64)])
 def test_ternary_rounds_match_the_oracle(shape_name, lam, max_nodes):
