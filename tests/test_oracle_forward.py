@@ -247,9 +247,8 @@ def test_tree_pass_equals_sequential_decoding_through_a_bf16_cache(shape):
 
 
 def test_the_two_cache_boundary_readings_differ_by_less_than_the_tie_tolerances():
-    """This build lets the draft nodes of a pass see each other's keys / values unrounded; the
-    other reading rounds them as the cache would.  Measured here on the bf16 test model (the
-    numbers the design doc quotes): logits move by <= 1e-2 absolute (about 2e-4 of their magnitude, a
+    """The draft nodes of a pass see each other's keys / values unrounded; the other reading
+    rounds them as the cache would.  Measured here on the bf16 test model: logits move by <= 1e-2 absolute (about 2e-4 of their magnitude, a
     hundredth of the 2e-2 bf16 bar), the routing statistics by <= 3e-3, and no decision changes
     unless a node of the walk sits that close to the threshold or to a top-2 tie."""
     from oracle import CRIT_MARGIN, CRIT_TOP1, decide, node_stats
