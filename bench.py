@@ -118,6 +118,39 @@ def kernel_classes(ver, step, shape, steps):
     return kernels
 
 
+def measured_rounds(proxy, target, ctx, n_nodes, reps=10):
+    """Whole rounds of the two-level scheme through the library's round driver (trispec_ternary_round:
+    proxy pass, routing on the host, and in Case II prune / re-root + target pass, cache commits),
+    wall clock per round, median of `reps`.  lambda = 0 never escalates (Case I: the proxy alone);
+    lambda > 1 trusts nothing, so every round escalates at the root and the target verifies the
+    whole tree (Case II at its most expensive).  Both caches hold `ctx` tokens of seeded noise."""
+    import torch
+    from paper_2601_23180_amd import TernaryDecoder
+    from workloads import gen_draft_tokens, gen_tree
+    dec = TernaryDecoder(proxy, target, (ctx + 2 * n_nodes + 63) // 64 * 64, max_nodes=64)
+    g = torch.Generator(device="cuda").manual_seed(4)
+    for kv in (dec.kv_p, dec.kv_t):
+        for t in (kv.k, kv.v):
+            t.copy_(torch.randn(t.shape, device="cuda", generator=g, dtype=torch.float32).to(t.dtype))
+    seq = np.random.default_rng(4).integers(0, proxy.cfg.vocab, ctx + 1).tolist()
+    parents = gen_tree(n_nodes, 8, 4, 4)
+    tokens = gen_draft_tokens(parents, proxy.cfg.vocab, 4)
+    out = {}
+    for name, lam in (("case1_proxy_only_lambda0", 0.0), ("case2_proxy_then_target_lambda2", 2.0)):
+        times = []
+        for r in range(reps + 2):
+            dec.kv_p.set_len([ctx]); dec.kv_t.set_len([ctx])
+            dec.resume(seq)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            rec = dec.round(parents, tokens, lam)
+            times.append((time.perf_counter() - t0) * 1e3)
+            assert rec["escalate"] == (1 if lam > 1 else 0)
+        out[name] = float(np.median(times[2:]))
+    dec.close()
+    return out
+
+
 def source_digest():
     """Digest of the kernel sources: counter summaries under profiles/ carry the digest they were
     measured at, and are quoted only while it still matches."""
@@ -389,9 +422,11 @@ def main():
         tp, tt = extra["qwen3_1p7b_tree60_ctx8192"]["ms_per_pass"], extra["qwen3_8b_tree60_ctx8192"]["ms_per_pass"]
         extra["ternary_pipeline_ctx8192"] = {
             "t_proxy_ms": tp, "t_target_ms": tt,
+            "measured_round_ms": measured_rounds(models["qwen3_1p7b"], models["qwen3_8b"], 8192, 60),
             "per_threshold": {lam: {"p_escalate_synthetic": p, "t_verify_ms": tp + p * tt} for lam, p in p_esc.items()},
             "at_paper_derived_p_escalate_0.46": tp + 0.46 * tt,
-            "note": "t_verify = t_proxy + P_esc * t_target (margin criterion); P_esc counted over 16 seeded synthetic draft "
+            "note": "measured_round_ms: whole rounds through trispec_ternary_round (host routing, copies of the decision and "
+                    "cache commits included).  t_verify = t_proxy + P_esc * t_target (margin criterion); P_esc counted over 16 seeded synthetic draft "
                     "trees on random-init weights (not an acceptance statistic of trained models); 0.46 is the escalation "
                     "frequency implied by the paper's Table 3 (r_t * tau for Qwen3 on MATH500)"}
         out["workloads"] = extra

@@ -64,11 +64,15 @@ class TernaryDecoder:
         except Exception:
             pass
 
-    def _pull(self) -> None:
-        """Sequence and cache lengths as the library holds them now."""
+    def _pull(self, n_new: int = -1) -> None:
+        """Sequence (its last n_new tokens; all of it if negative) and cache lengths as the library
+        holds them now."""
         p, n = C.POINTER(C.c_int32)(), C.c_int32()
         check(lib().trispec_ternary_sequence(self.handle, C.byref(p), C.byref(n)))
-        self.seq = [int(p[i]) for i in range(n.value)]
+        if n_new < 0 or len(self.seq) + n_new != n.value:
+            self.seq = p[:n.value]
+        else:
+            self.seq += p[n.value - n_new:n.value]
         self.kv_p.sync_len()
         self.kv_t.sync_len()
 
@@ -79,6 +83,15 @@ class TernaryDecoder:
         torch.cuda.current_stream().synchronize()
         check(lib().trispec_ternary_start(self.handle, arr, len(prompt)))
         self._pull()
+        self._stale = False
+
+    def resume(self, seq: Sequence[int]) -> None:
+        """Take over a sequence whose caches were advanced by other means (trispec_ternary_resume)."""
+        self.seq = [int(t) for t in seq]
+        self.kv_p.sync_len()
+        self.kv_t.sync_len()
+        arr = (C.c_int32 * len(self.seq))(*self.seq)
+        check(lib().trispec_ternary_resume(self.handle, arr, len(self.seq)))
         self._stale = False
 
     def round(self, parents: Sequence[int], tokens: Sequence[int], lam: float) -> Dict[str, object]:
@@ -93,7 +106,7 @@ class TernaryDecoder:
         tok = (C.c_int32 * n)(*[int(t) for t in tokens])
         info = RoundInfo()
         check(lib().trispec_ternary_round(self.handle, par, tok, n, float(lam), C.byref(info)))
-        self._pull()
+        self._pull(int(info.n_emitted))
         rec = {"proxy": _pass_dict(info.proxy), "escalate": int(info.escalate), "catch_up": int(info.catch_up)}
         if info.escalate:
             self.target_passes += 1
