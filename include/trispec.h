@@ -469,6 +469,34 @@ int trispec_ternary_resume(trispec_ternary *t, const int32_t *seq_host, int32_t 
  * outside the vocabulary, or a device-side status bit after a pass), TRISPEC_ESTATE (no sequence started). */
 int trispec_ternary_round(trispec_ternary *t, const int32_t *parents_host, const int32_t *tokens_host,
                           int32_t n_nodes, float lambda, trispec_round_info *info_host);
+/*
+ * One round of the sampling form (temperature > 0) on a draft CHAIN tokens_host[0 .. n_nodes-1]
+ * (tokens_host[0] is ignored: the root is the last token of the sequence), Algorithm 1 as printed:
+ * the proxy accepts draft tokens by the Bernoulli rule of Eq. 6 and routes by Eq. 8 / 9 on its
+ * tempered distribution (trispec_sample_decide on the pass's logits); in Case II the target verifies
+ * the whole chain behind the tokens it has not cached yet, with x_1 .. x_tau_m taken as approved,
+ * and its draw ends the round.  No random numbers are drawn here: the uniforms are the caller's.
+ *   p_draft_dev           device [n_nodes - 1, vocab] fp32: row i = the drafter's distribution from
+ *                         which draft token i + 1 was drawn (may be NULL when n_nodes = 1)
+ *   u_accept_*_host       HOST [n_nodes] uniforms in [0, 1): entry i decides draft token i in the
+ *                         proxy's / the target's pass; u_sample_*: the uniform of that pass's draw
+ *   logits_dev            device work buffer [max_nodes, vocab] fp32 (the pass's logits)
+ *   p_draft_work_dev      device work buffer [max_nodes - 1, vocab] fp32 (the draft rows shifted
+ *                         behind the lagging tokens of the target's longer chain)
+ * The decision kernels run on the library's own scratch area (trispec_sample_decide_static: calls
+ * that overlap on one GPU race).  Errors: those of trispec_ternary_round and trispec_sample_decide.
+ */
+typedef struct {
+  float temperature;                 /* T > 0 */
+  int32_t resample;                  /* TRISPEC_RESAMPLE_* */
+  const float *p_draft_dev;
+  const float *u_accept_proxy_host, *u_accept_target_host;
+  float u_sample_proxy, u_sample_target;
+  float *logits_dev;
+  float *p_draft_work_dev;
+} trispec_sample_round;
+int trispec_ternary_round_sample(trispec_ternary *t, const int32_t *tokens_host, int32_t n_nodes, float lambda,
+                                 const trispec_sample_round *s, trispec_round_info *info_host);
 /* View of the sequence emitted so far (prompt included), valid until the next call on `t`. */
 int trispec_ternary_sequence(const trispec_ternary *t, const int32_t **tokens_host, int32_t *n_tokens);
 

@@ -32,7 +32,7 @@ EXPORTS = [
     "trispec_sample_decide_static", "trispec_debug_set_spin_limit", "trispec_wait_probe",
     "trispec_prune_reroot", "trispec_draft_ranks", "trispec_pack_matrix_bytes", "trispec_pack_matrix",
     "trispec_kv_get_len", "trispec_ternary_create", "trispec_ternary_destroy", "trispec_ternary_start",
-    "trispec_ternary_resume", "trispec_ternary_round", "trispec_ternary_sequence",
+    "trispec_ternary_resume", "trispec_ternary_round", "trispec_ternary_sequence", "trispec_ternary_round_sample",
 ]
 K_GEMM, K_HEAD, K_ATTN = 0, 1, 2
 LAUNCH_PER_MATMUL, LAUNCH_PER_LAYER = 0, 1
@@ -59,6 +59,13 @@ class TernaryConfig(C.Structure):
 class PassResult(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("accepted_len", "token", "escalate", "status", "path_len")] + \
                [("path", C.c_int32 * 64)]
+
+
+class SampleRound(C.Structure):
+    _fields_ = [("temperature", C.c_float), ("resample", C.c_int32), ("p_draft_dev", C.c_void_p),
+                ("u_accept_proxy_host", C.POINTER(C.c_float)), ("u_accept_target_host", C.POINTER(C.c_float)),
+                ("u_sample_proxy", C.c_float), ("u_sample_target", C.c_float),
+                ("logits_dev", C.c_void_p), ("p_draft_work_dev", C.c_void_p)]
 
 
 class RoundInfo(C.Structure):
@@ -133,6 +140,8 @@ def lib() -> C.CDLL:
         l.trispec_ternary_resume.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.c_int32]
         l.trispec_ternary_round.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int32,
                                             C.c_float, C.POINTER(RoundInfo)]
+        l.trispec_ternary_round_sample.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.c_int32, C.c_float,
+                                                   C.POINTER(SampleRound), C.POINTER(RoundInfo)]
         l.trispec_ternary_sequence.argtypes = [C.c_void_p, C.POINTER(C.POINTER(C.c_int32)), C.POINTER(C.c_int32)]
         l.trispec_kv_destroy.argtypes = [C.c_void_p]
         l.trispec_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]

@@ -1,10 +1,9 @@
 """The ternary scheme's rounds (Alg. 1 of the paper) for one sequence (batch 1).
 
-The greedy form on draft trees runs inside the library (`trispec_ternary_*`: proxy pass, routing
-into Case I / Case II, prune and re-root, target pass, cache commits and target catch-up); this
-class allocates the device buffers and marshals arguments.  The sampling form on draft chains
-(`round_sample`) is host control flow here on top of trispec_verify / trispec_sample_decide /
-trispec_kv_commit: a few dozen integers per round.
+The rounds run inside the library (`trispec_ternary_*`: proxy pass, routing into Case I /
+Case II, prune and re-root, target pass, cache commits and target catch-up); this
+class allocates the device buffers and marshals arguments, for the greedy form on draft trees
+(`round`) and the sampling form on draft chains (`round_sample`).
 """
 from __future__ import annotations
 
@@ -15,7 +14,7 @@ import numpy as np
 import torch
 
 from .binding import (CRIT_MARGIN, MAX_NODES, RESAMPLE_RESIDUAL, TERNARY_SCRATCH_INTS, KVCache, Model, RoundInfo,
-                      SampleDecider, TernaryConfig, Verifier, check, lib)
+                      SampleRound, TernaryConfig, check, lib)
 
 
 def _aligned(n_bytes: int):
@@ -34,8 +33,6 @@ class TernaryDecoder:
         self.proxy, self.target = proxy, target
         self.kv_p, self.kv_t = KVCache(proxy, 1, capacity), KVCache(target, 1, capacity)
         self.criterion, self.max_nodes = criterion, max_nodes
-        self._ver: Dict[tuple, Verifier] = {}
-        self._dec: Dict[tuple, SampleDecider] = {}
         self.seq: List[int] = []
         self.target_passes = 0          # passes of the target that verified drafts (not catch-up)
         cfg = TernaryConfig()
@@ -52,6 +49,7 @@ class TernaryDecoder:
         self.handle = C.c_void_p()
         check(lib().trispec_ternary_create(C.byref(cfg), C.byref(self.handle)))
         self._stale = False             # the library's copy of the sequence is behind self.seq
+        self._logits = self._pd_work = None   # work buffers of the sampling form, made on first use
 
     def close(self):
         if self.handle:
@@ -114,98 +112,37 @@ class TernaryDecoder:
                         "n_forced_t": int(info.n_forced_target)})
         return rec
 
-    # -- passes driven from here (sampling form) ------------------------------------------------
-    def _pass(self, which: str, tokens, parents, positions, lam: float, criterion: int, n_forced: int):
-        model, kv = (self.proxy, self.kv_p) if which == "p" else (self.target, self.kv_t)
-        n = len(tokens)
-        ver = self._ver.get((which, n))
-        if ver is None:
-            ver = self._ver[(which, n)] = Verifier(model, 1, n)
-        tok = torch.tensor([list(map(int, tokens))], dtype=torch.int32, device="cuda")
-        pos = torch.tensor([list(map(int, positions))], dtype=torch.int32, device="cuda")
-        par = np.asarray([list(map(int, parents))], dtype=np.int32)
-        ver.verify(kv, tok, par, pos, lam, criterion, n_forced, want_logits=False)
-        torch.cuda.synchronize()
-
-    def _ingest(self, which: str, tokens: Sequence[int]) -> None:
-        """Plain passes over certain tokens: a forced chain, everything committed."""
-        kv = self.kv_p if which == "p" else self.kv_t
-        tokens = list(tokens)
-        while tokens:
-            chunk, tokens = tokens[: self.max_nodes], tokens[self.max_nodes:]
-            n, c = len(chunk), kv.ctx_len[0]
-            self._pass(which, chunk, range(-1, n - 1), range(c, c + n), 0.0, CRIT_MARGIN, n)
-            kv.commit([list(range(n))])
-
-    # -- sampling form (temperature > 0), draft chains -----------------------------------------
-    def _pass_sample(self, which: str, tokens, positions, p_draft, u_accept, u_sample, lam: float, criterion: int,
-                     n_forced: int, temperature: float, resample: int):
-        """One pass over a chain with its logits kept, then trispec_sample_decide on them."""
-        model, kv = (self.proxy, self.kv_p) if which == "p" else (self.target, self.kv_t)
-        n = len(tokens)
-        ver = self._ver.get((which, n, "logits"))
-        if ver is None:
-            ver = self._ver[(which, n, "logits")] = Verifier(model, 1, n, debug_logits=True)
-        dec = self._dec.get((which, n))
-        if dec is None:
-            dec = self._dec[(which, n)] = SampleDecider(1, n, model.cfg.vocab)
-        tok = torch.tensor([list(map(int, tokens))], dtype=torch.int32, device="cuda")
-        pos = torch.tensor([list(map(int, positions))], dtype=torch.int32, device="cuda")
-        par = np.arange(-1, n - 1, dtype=np.int32)[None]
-        ver.verify(kv, tok, par, pos, 0.0, CRIT_MARGIN, n_forced, want_logits=True)
-        f32 = dict(dtype=torch.float32, device="cuda")
-        pd = torch.as_tensor(np.ascontiguousarray(p_draft, dtype=np.float32)[None], **f32)
-        ua = torch.as_tensor(np.ascontiguousarray(u_accept, dtype=np.float32)[None], **f32)
-        us = torch.as_tensor(np.asarray([u_sample], dtype=np.float32), **f32)
-        out = dec.decide(ver.logits, tok, pd, ua, us, temperature, lam, criterion, n_forced, resample)
-        torch.cuda.synchronize()
-        return {"accepted_len": int(out["accepted_len"][0]), "token": int(out["token"][0]),
-                "escalate": int(out["escalate"][0]),
-                "path": [int(v) for v in out["path"][0].cpu().numpy() if v >= 0]}
-
     def round_sample(self, tokens: Sequence[int], p_draft: np.ndarray, u_accept_p, u_sample_p: float, u_accept_t,
                      u_sample_t: float, lam: float, temperature: float,
                      resample: int = RESAMPLE_RESIDUAL) -> Dict[str, object]:
         """One round at temperature > 0 on a draft chain tokens[0..k] (tokens[0] is replaced by the
         current root): p_draft [k, vocab] are the drafter's distributions, the uniforms are the
         caller's.  The proxy accepts by Eq. 6 and routes by Eq. 8 / 9; on escalation the target
-        verifies the whole chain with x_1..x_tau_m taken as approved."""
-        tokens = [int(t) for t in tokens]
-        tokens[0] = self.seq[-1]
-        M = len(tokens)
-        p_draft = np.asarray(p_draft, dtype=np.float32)
-        cp = self.kv_p.ctx_len[0]
-        pr = self._pass_sample("p", tokens, range(cp, cp + M), p_draft, u_accept_p, u_sample_p, lam, self.criterion,
-                               1, temperature, resample)
-        rec = {"proxy": pr, "escalate": pr["escalate"], "catch_up": 0}
-        path = pr["path"]
-        if not pr["escalate"]:                                               # Case I
-            self.kv_p.commit([path])
-            self.seq += [tokens[i] for i in path[1:]] + [pr["token"]]
-            self._stale = True
-            return rec
-        tau_m = pr["accepted_len"]                                           # Case II
-        t_len = self.kv_t.ctx_len[0]
-        unseen = self.seq[t_len:-1]
-        if len(unseen) + M > self.max_nodes:
-            before = self.kv_t.ctx_len[0]
-            self._ingest("t", unseen)
-            rec["catch_up"] = (self.kv_t.ctx_len[0] - before + self.max_nodes - 1) // self.max_nodes
-            t_len, unseen = self.kv_t.ctx_len[0], []
-        u = len(unseen)
-        tok_t = unseen + tokens
-        pd_t = np.zeros((u + M - 1, p_draft.shape[1]), dtype=np.float32)
-        pd_t[u:] = p_draft                                                   # row u + i judges draft i + 1
-        ua_t = np.zeros(u + M, dtype=np.float32)
-        ua_t[u:] = np.asarray(u_accept_t, dtype=np.float32)
-        n_forced = u + tau_m + 1
-        tr = self._pass_sample("t", tok_t, range(t_len, t_len + u + M), pd_t, ua_t, u_sample_t, 0.0, CRIT_MARGIN,
-                               n_forced, temperature, resample)
-        self.target_passes += 1
-        self.kv_t.commit([list(range(n_forced - 1)) + tr["path"]])
-        extra = [n - u for n in tr["path"][1:]]                              # drafts the target accepted, chain ids
-        self.kv_p.commit([path + extra])
-        self.seq += [tokens[i] for i in path[1:] + extra] + [tr["token"]]
-        self._stale = True
-        rec.update({"target": tr, "target_nodes": u + M, "n_forced_t": n_forced})
+        verifies the whole chain with x_1..x_tau_m taken as approved (trispec_ternary_round_sample)."""
+        n, vocab = len(tokens), self.proxy.cfg.vocab
+        if self._stale:
+            self.resume(self.seq)
+        if self._logits is None:
+            f32 = dict(dtype=torch.float32, device="cuda")
+            self._logits = torch.zeros((self.max_nodes, vocab), **f32)
+            self._pd_work = torch.zeros((max(self.max_nodes - 1, 1), vocab), **f32)
+        pd = torch.as_tensor(np.ascontiguousarray(p_draft, dtype=np.float32), dtype=torch.float32, device="cuda")
+        s = SampleRound()
+        s.temperature, s.resample = float(temperature), int(resample)
+        s.p_draft_dev = pd.data_ptr() if n > 1 else None
+        ua_p = (C.c_float * n)(*[float(u) for u in u_accept_p])
+        ua_t = (C.c_float * n)(*[float(u) for u in u_accept_t])
+        s.u_accept_proxy_host, s.u_accept_target_host = ua_p, ua_t
+        s.u_sample_proxy, s.u_sample_target = float(u_sample_p), float(u_sample_t)
+        s.logits_dev, s.p_draft_work_dev = self._logits.data_ptr(), self._pd_work.data_ptr()
+        tok = (C.c_int32 * n)(*[int(t) for t in tokens])
+        info = RoundInfo()
+        torch.cuda.current_stream().synchronize()          # p_draft is on the device before the library reads it
+        check(lib().trispec_ternary_round_sample(self.handle, tok, n, float(lam), C.byref(s), C.byref(info)))
+        self._pull(int(info.n_emitted))
+        rec = {"proxy": _pass_dict(info.proxy), "escalate": int(info.escalate), "catch_up": int(info.catch_up)}
+        if info.escalate:
+            self.target_passes += 1
+            rec.update({"target": _pass_dict(info.target), "target_nodes": int(info.target_nodes),
+                        "n_forced_t": int(info.n_forced_target)})
         return rec

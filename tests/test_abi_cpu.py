@@ -326,6 +326,19 @@ def test_ternary_driver_rejects_bad_arguments_and_kv_len_round_trip():
     assert lib.trispec_ternary_round(t, (C.c_int32 * 4)(0, 0, 1, 1), tok, 4, 0.5, C.byref(info)) == -4
     assert lib.trispec_ternary_round(t, par, (C.c_int32 * 4)(0, 5, -1, 7), 4, 0.5, C.byref(info)) == -8
     assert lib.trispec_ternary_round(t, None, tok, 4, 0.5, C.byref(info)) == -1
+    # the sampling form's round: required buffers, chain length, token ids
+    ua = (C.c_float * 4)(0.1, 0.2, 0.3, 0.4)
+    sr = B.SampleRound()
+    sr.temperature, sr.resample = 1.0, 0
+    sr.p_draft_dev, sr.logits_dev, sr.p_draft_work_dev = 0x400000, 0x500000, 0x600000
+    sr.u_accept_proxy_host, sr.u_accept_target_host = ua, ua
+    assert lib.trispec_ternary_round_sample(t, tok, 4, 0.5, None, C.byref(info)) == -1
+    assert lib.trispec_ternary_round_sample(t, tok, 17, 0.5, C.byref(sr), C.byref(info)) == -3
+    assert lib.trispec_ternary_round_sample(t, (C.c_int32 * 4)(0, 5, 4096, 7), 4, 0.5, C.byref(sr), C.byref(info)) == -8
+    sr.logits_dev = None
+    assert lib.trispec_ternary_round_sample(t, tok, 4, 0.5, C.byref(sr), C.byref(info)) == -1
+    sr.logits_dev, sr.p_draft_dev = 0x500000, None
+    assert lib.trispec_ternary_round_sample(t, tok, 4, 0.5, C.byref(sr), C.byref(info)) == -1
     assert lib.trispec_ternary_destroy(t) == 0
     for h in kvs:
         lib.trispec_kv_destroy(h)
