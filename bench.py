@@ -45,9 +45,9 @@ EXTRA = ["qwen3_0p6b_chain8_ctx2048", "qwen3_1p7b_tree60_ctx8192", "qwen3_8b_tre
          "llama3_8b_b4_tree60_ctx16384"]
 
 
-def build_inputs(shape, batch, ctx, n_nodes, kind, seed, model=None, debug_logits=False):
+def build_inputs(shape, batch, ctx, n_nodes, kind, seed, model=None, debug_logits=False, paged=False):
     import torch
-    from paper_2601_23180_amd import KVCache, Verifier, fill_kv_layer, model_from_arrays
+    from paper_2601_23180_amd import KVCache, PagedKVCache, Verifier, fill_kv_layer, model_from_arrays
     from workloads import (WeightSource, gen_chain, gen_draft_tokens, gen_kv_cache, gen_tree, tree_depths)
 
     ws = WeightSource(shape, seed)
@@ -55,7 +55,7 @@ def build_inputs(shape, batch, ctx, n_nodes, kind, seed, model=None, debug_logit
     if model is None:
         model = model_from_arrays(shape, ws.bits if shape.dtype == "bf16" else ws.get)
     cap = (ctx + n_nodes + 63) // 64 * 64
-    kv = KVCache(model, batch, cap)
+    kv = PagedKVCache(model, batch, cap, seed=seed) if paged else KVCache(model, batch, cap)
     for l in range(shape.n_layers):
         k, v = gen_kv_cache(shape, batch, ctx, seed, l)
         fill_kv_layer(kv, l, k, v)
@@ -259,6 +259,8 @@ def main():
     ap.add_argument("--launch-mode", choices=("per-matmul", "per-layer"), default="per-matmul",
                     help="per-matmul: one launch per matmul (default, the faster cut); per-layer: the matmuls "
                          "between two attention calls as one launch with device-side barriers")
+    ap.add_argument("--kv-layout", choices=("contiguous", "paged"), default="contiguous",
+                    help="paged: the cache in 256-slot pages behind a shuffled page table (same results)")
     ap.add_argument("--launch", choices=("eager", "graph"), default="eager",
                     help="graph: the pass is captured once into a HIP graph and the timed steps replay it")
     args = ap.parse_args()
@@ -281,7 +283,7 @@ def main():
     seed = args.seed if args.seed is not None else wseed
     shape = SHAPES[key]
     mode = LAUNCH_PER_LAYER if args.launch_mode == "per-layer" else LAUNCH_PER_MATMUL
-    inp = build_inputs(shape, batch, ctx, n_nodes, kind, seed)
+    inp = build_inputs(shape, batch, ctx, n_nodes, kind, seed, paged=args.kv_layout == "paged")
     ver, kv, tok, pos, parents = inp["ver"], inp["kv"], inp["tok"], inp["pos"], inp["parents"]
     ver.launch_mode = mode
 
@@ -360,7 +362,7 @@ def main():
         "dtype": "bf16" if shape.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "batch": batch, "ctx_len": ctx, "n_nodes": n_nodes,
                    "tree": kind, "threshold": args.threshold, "launch": args.launch,
-                   "launch_mode": args.launch_mode},
+                   "launch_mode": args.launch_mode, "kv_layout": args.kv_layout},
         "verify_latency_ms": ms,
         "latency_ms": latency,
         "pass_bytes": pass_bytes,

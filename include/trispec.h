@@ -194,6 +194,25 @@ int trispec_prune_reroot(const int32_t *tokens, const int32_t *parents, const in
                          int32_t *out_tokens, int32_t *out_parents, int32_t *out_positions,
                          int32_t *out_old_id, int32_t *out_n_nodes, int32_t *out_n_forced);
 
+/*
+ * The same cache in PAGES of TRISPEC_KV_PAGE slots, for callers that hand out cache memory in
+ * blocks (a serving layer's block manager; not something the paper needs).  Two pools of
+ * trispec_kv_paged_bytes(m, n_pages) bytes each, dtype of the model:
+ *   K: [n_layers][n_pages][n_kv_heads][TRISPEC_KV_PAGE][head_dim]
+ *   V: [n_layers][n_pages][n_kv_heads][head_dim][TRISPEC_KV_PAGE]     (transposed, as above)
+ * and a page table page_table_dev, DEVICE int32 [batch][max_pages_per_seq]: slot s of sequence b is
+ * slot s % TRISPEC_KV_PAGE of page page_table[b][s / TRISPEC_KV_PAGE].  The kernels read the table
+ * when they run, so the caller may rewrite it between calls (in stream order); entries must lie in
+ * [0, n_pages) and cover slots [0, ctx_len + n_nodes) of every sequence when a pass runs — they are
+ * device data: an entry outside the pool is clamped into it (wrong results, no stray access).  Capacity = max_pages_per_seq * TRISPEC_KV_PAGE.  Every other
+ * call takes such a cache like a contiguous one; results are identical.
+ * Errors: TRISPEC_ENULL, TRISPEC_ENODES (batch), TRISPEC_ECAPACITY (page counts), TRISPEC_EARG (alignment).
+ */
+#define TRISPEC_KV_PAGE 256
+int trispec_kv_paged_bytes(const trispec_model *m, int32_t n_pages, size_t *bytes);
+int trispec_kv_create_paged(const trispec_model *m, void *k_pool_dev, void *v_pool_dev, const int32_t *page_table_dev,
+                            int32_t batch, int32_t max_pages_per_seq, int32_t n_pages, trispec_kv **out);
+
 /* The context lengths a cache object holds now (they grow with trispec_kv_commit).
  *   ctx_len_host  HOST [batch], written.   Errors: TRISPEC_ENULL. */
 int trispec_kv_get_len(const trispec_kv *kv, int32_t *ctx_len_host);

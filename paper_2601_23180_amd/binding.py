@@ -31,7 +31,7 @@ EXPORTS = [
     "trispec_kv_commit", "trispec_sample_scratch_bytes", "trispec_sample_decide",
     "trispec_sample_decide_static", "trispec_debug_set_spin_limit", "trispec_wait_probe",
     "trispec_prune_reroot", "trispec_draft_ranks", "trispec_pack_matrix_bytes", "trispec_pack_matrix",
-    "trispec_kv_get_len", "trispec_ternary_create", "trispec_ternary_destroy", "trispec_ternary_start",
+    "trispec_kv_get_len", "trispec_kv_paged_bytes", "trispec_kv_create_paged", "trispec_ternary_create", "trispec_ternary_destroy", "trispec_ternary_start",
     "trispec_ternary_resume", "trispec_ternary_round", "trispec_ternary_sequence", "trispec_ternary_round_sample",
 ]
 K_GEMM, K_HEAD, K_ATTN = 0, 1, 2
@@ -134,6 +134,9 @@ def lib() -> C.CDLL:
                                         C.POINTER(C.c_void_p)]
         l.trispec_kv_set_len.argtypes = [C.c_void_p, C.POINTER(C.c_int32)]
         l.trispec_kv_get_len.argtypes = [C.c_void_p, C.POINTER(C.c_int32)]
+        l.trispec_kv_paged_bytes.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_size_t)]
+        l.trispec_kv_create_paged.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                              C.c_int32, C.POINTER(C.c_void_p)]
         l.trispec_ternary_create.argtypes = [C.POINTER(TernaryConfig), C.POINTER(C.c_void_p)]
         l.trispec_ternary_destroy.argtypes = [C.c_void_p]
         l.trispec_ternary_start.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.c_int32]
@@ -288,6 +291,17 @@ class KVCache:
         check(lib().trispec_kv_set_len(self.handle, arr))
         self.ctx_len = list(ctx_len)
 
+    def load_dense(self, k: torch.Tensor, v: torch.Tensor) -> None:
+        """k [L, B, n_kv, capacity, d], v [L, B, n_kv, d, capacity] (the layout of self.k / self.v)."""
+        self.k.copy_(k)
+        self.v.copy_(v)
+
+    def write_layer(self, layer: int, k: torch.Tensor, v: torch.Tensor) -> None:
+        """The first C slots of one layer: k, v [B, n_kv, C, d] (V is stored transposed)."""
+        C_ = k.shape[2]
+        self.k[layer, :, :, :C_, :] = k.to(self.k.dtype)
+        self.v[layer, :, :, :, :C_] = v.to(self.v.dtype).transpose(-1, -2)
+
     def sync_len(self) -> None:
         """Re-read the context lengths from the library (after calls that commit inside it)."""
         arr = (C.c_int32 * self.batch)()
@@ -316,6 +330,73 @@ class KVCache:
             self.close()
         except Exception:
             pass
+
+
+KV_PAGE = 256
+
+
+class PagedKVCache(KVCache):
+    """trispec_kv over two page pools and a device page table (trispec_kv_create_paged):
+    K pool [L, n_pages, n_kv, KV_PAGE, d], V pool [L, n_pages, n_kv, d, KV_PAGE]; slot s of sequence b is
+    slot s % KV_PAGE of page table[b, s // KV_PAGE].  `table` (int array [batch, max_pages]) defaults to a
+    seeded shuffle of the pool with `spare_pages` pages left unmapped.  `k` and `v` READ the cache as
+    dense tensors in the contiguous layout (copies); `load_dense` writes such tensors into the pages."""
+
+    def __init__(self, model: Model, batch: int, capacity: int, table=None, spare_pages: int = 3, seed: int = 0,
+                 device="cuda"):
+        c = model.cfg
+        self.max_pages = (capacity + KV_PAGE - 1) // KV_PAGE
+        if table is None:
+            self.n_pages = batch * self.max_pages + spare_pages
+            g = torch.Generator().manual_seed(seed)
+            table = torch.randperm(self.n_pages, generator=g)[: batch * self.max_pages].reshape(batch, self.max_pages)
+        else:
+            table = torch.as_tensor(table).reshape(batch, self.max_pages)
+            self.n_pages = int(table.max()) + 1 + spare_pages
+        self.table = table.to(torch.int32).to(device).contiguous()
+        n = C.c_size_t()
+        check(lib().trispec_kv_paged_bytes(model.handle, self.n_pages, C.byref(n)))
+        dt = _torch_dtype(c.dtype)
+        self.k_pool = torch.zeros((c.n_layers, self.n_pages, c.n_kv_heads, KV_PAGE, c.head_dim), dtype=dt, device=device)
+        self.v_pool = torch.zeros((c.n_layers, self.n_pages, c.n_kv_heads, c.head_dim, KV_PAGE), dtype=dt, device=device)
+        assert self.k_pool.numel() * self.k_pool.element_size() == n.value
+        self.model, self.batch, self.capacity = model, batch, self.max_pages * KV_PAGE
+        self.handle = C.c_void_p()
+        check(lib().trispec_kv_create_paged(model.handle, self.k_pool.data_ptr(), self.v_pool.data_ptr(),
+                                            self.table.data_ptr(), batch, self.max_pages, self.n_pages,
+                                            C.byref(self.handle)))
+        self.ctx_len = [0] * batch
+
+    @property
+    def k(self) -> torch.Tensor:          # [L, B, n_kv, capacity, d]
+        t = self.k_pool[:, self.table.long()]                      # [L, B, P, n_kv, page, d]
+        L, B, P, H, S, D = t.shape
+        return t.permute(0, 1, 3, 2, 4, 5).reshape(L, B, H, P * S, D)
+
+    @property
+    def v(self) -> torch.Tensor:          # [L, B, n_kv, d, capacity]
+        t = self.v_pool[:, self.table.long()]                      # [L, B, P, n_kv, d, page]
+        L, B, P, H, D, S = t.shape
+        return t.permute(0, 1, 3, 4, 2, 5).reshape(L, B, H, D, P * S)
+
+    def load_dense(self, k: torch.Tensor, v: torch.Tensor) -> None:
+        """k [L, B, n_kv, capacity, d], v [L, B, n_kv, d, capacity] -> the mapped pages."""
+        L, B, H, Cc, D = k.shape
+        P, S = self.max_pages, KV_PAGE
+        assert Cc == self.capacity
+        kp = k.reshape(L, B, H, P, S, D).permute(0, 1, 3, 2, 4, 5)  # [L, B, P, H, S, D]
+        vp = v.reshape(L, B, H, D, P, S).permute(0, 1, 4, 2, 3, 5)  # [L, B, P, H, D, S]
+        idx = self.table.long()
+        self.k_pool[:, idx] = kp.to(self.k_pool.dtype)
+        self.v_pool[:, idx] = vp.to(self.v_pool.dtype)
+
+    def write_layer(self, layer: int, k: torch.Tensor, v: torch.Tensor) -> None:
+        C_ = k.shape[2]
+        for p0 in range(0, C_, KV_PAGE):
+            n = min(KV_PAGE, C_ - p0)
+            pages = self.table[:, p0 // KV_PAGE].long()                                  # [B]
+            self.k_pool[layer, pages, :, :n, :] = k[:, :, p0:p0 + n, :].to(self.k_pool.dtype)
+            self.v_pool[layer, pages, :, :, :n] = v[:, :, p0:p0 + n, :].to(self.v_pool.dtype).transpose(-1, -2)
 
 
 class KernelTimer:

@@ -410,6 +410,40 @@ int trispec_kv_create(const trispec_model *m, void *k_dev, void *v_dev, int32_t 
   kv->v = v_dev;
   kv->batch = batch;
   kv->capacity = capacity;
+  kv->page_table = nullptr;
+  kv->max_pages = kv->n_pages = 0;
+  for (int b = 0; b < kMaxBatch; ++b) kv->ctx_len[b] = 0;
+  *out = kv;
+  return TRISPEC_OK;
+}
+
+int trispec_kv_paged_bytes(const trispec_model *m, int32_t n_pages, size_t *bytes) {
+  if (!m || !bytes) return TRISPEC_ENULL;
+  if (n_pages < 1 || n_pages > (1 << 22)) return TRISPEC_ECAPACITY;
+  const trispec_model_config &c = m->cfg;
+  *bytes = (size_t)c.n_layers * n_pages * c.n_kv_heads * kKvPage * c.head_dim * esize(c.dtype);
+  return TRISPEC_OK;
+}
+
+int trispec_kv_create_paged(const trispec_model *m, void *k_pool_dev, void *v_pool_dev, const int32_t *page_table_dev,
+                            int32_t batch, int32_t max_pages_per_seq, int32_t n_pages, trispec_kv **out) {
+  if (!m || !k_pool_dev || !v_pool_dev || !page_table_dev || !out) return TRISPEC_ENULL;
+  if (batch < 1 || batch > kMaxBatch) return TRISPEC_ENODES;
+  size_t bytes;
+  const int rc = trispec_kv_paged_bytes(m, n_pages, &bytes);
+  if (rc) return rc;
+  if (max_pages_per_seq < 1 || max_pages_per_seq > (1 << 22) / kKvPage) return TRISPEC_ECAPACITY;
+  if ((((uintptr_t)k_pool_dev) | ((uintptr_t)v_pool_dev)) & 15) return TRISPEC_EARG;
+  trispec_kv *kv = new (std::nothrow) trispec_kv;
+  if (!kv) return TRISPEC_EARG;
+  kv->model = m;
+  kv->k = k_pool_dev;
+  kv->v = v_pool_dev;
+  kv->batch = batch;
+  kv->capacity = max_pages_per_seq * kKvPage;
+  kv->page_table = page_table_dev;
+  kv->max_pages = max_pages_per_seq;
+  kv->n_pages = n_pages;
   for (int b = 0; b < kMaxBatch; ++b) kv->ctx_len[b] = 0;
   *out = kv;
   return TRISPEC_OK;
@@ -541,7 +575,7 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
   int32_t *status = (int32_t *)(ws + L.status);
   CtxLens ctx;
   for (int b = 0; b < kMaxBatch; ++b) ctx.v[b] = b < B ? kv->ctx_len[b] : 0;
-  const size_t kv_layer = (size_t)B * c.n_kv_heads * kv->capacity * c.head_dim * es;
+  const size_t kv_layer = kv->layer_elems() * es;
 
   HeadStats hs;
   hs.l1 = (float *)(ws + L.head_l1);
@@ -556,7 +590,7 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
   at.anc = (const uint64_t *)(ws + L.anc);
   at.ctx = ctx;
   at.batch = B; at.n_nodes = n_nodes; at.n_q_heads = c.n_q_heads; at.n_kv_heads = c.n_kv_heads;
-  at.head_dim = c.head_dim; at.capacity = kv->capacity;
+  at.head_dim = c.head_dim; at.kv = kv->map();
   {
     // context split: aim at one workgroup per CU over (sequence, kv head, row group, split), at
     // least 256 keys per workgroup, at most kMaxAttnSplits splits.  Long contexts and batches then
@@ -572,7 +606,8 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
     const int per_split = B * c.n_kv_heads * at.n_row_groups;
     int want = (256 + per_split - 1) / per_split;
     if (want > kMaxAttnSplits) want = kMaxAttnSplits;
-    int kps = (int)align_up((size_t)((max_keys + want - 1) / want), 64);
+    // (a paged cache: every split starts at a multiple of the largest key tile, so that no tile straddles two pages)
+    int kps = (int)align_up((size_t)((max_keys + want - 1) / want), kv->page_table ? 128 : 64);
     if (kps < 256) kps = 256;
     at.keys_per_split = kps;
     at.n_splits = (max_keys + kps - 1) / kps;
@@ -625,7 +660,7 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
       gemm(h, c.hidden, 3, m->wq[l], qd, m->wk[l], kvd, m->wv[l], kvd, part);
       char *kl = (char *)kv->k + (size_t)l * kv_layer, *vl = (char *)kv->v + (size_t)l * kv_layer;
       launch_qkv_epilogue(st, c.dtype, part, 1, rows, rp, c.n_q_heads, c.n_kv_heads, c.head_dim, cos_t, sin_t,
-                          n_nodes, ctx, kv->capacity, q, kl, vl, c.qk_norm ? (const float *)m->q_norm[l] : nullptr,
+                          n_nodes, ctx, kv->map(), q, kl, vl, c.qk_norm ? (const float *)m->q_norm[l] : nullptr,
                           c.qk_norm ? (const float *)m->k_norm[l] : nullptr, c.rms_eps);
       attention(kl, vl);
       gemm((const float *)attn_out, qd, 1, m->wo[l], c.hidden, nullptr, 0, nullptr, 0, part);
@@ -708,7 +743,7 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
       g.k_cache = (char *)kv->k + (size_t)l * kv_layer;
       g.v_cache = (char *)kv->v + (size_t)l * kv_layer;
       g.n_nodes = n_nodes; g.n_q_heads = c.n_q_heads; g.n_kv_heads = c.n_kv_heads; g.head_dim = c.head_dim;
-      g.capacity = kv->capacity;
+      g.kv = kv->map();
       g.q_norm_w = c.qk_norm ? m->q_norm[l] : nullptr;
       g.k_norm_w = c.qk_norm ? m->k_norm[l] : nullptr;
       return g;
@@ -1102,8 +1137,8 @@ int trispec_kv_commit(trispec_kv *kv, const int32_t *nodes_host, const int32_t *
   }
   if (any) {
     (void)hipGetLastError();
-    launch_kv_commit((hipStream_t)stream, c.dtype, kv->k, kv->v, c.n_layers, kv->batch, c.n_kv_heads, c.head_dim,
-                     kv->capacity, t);
+    launch_kv_commit((hipStream_t)stream, c.dtype, kv->k, kv->v, c.n_layers, kv->layer_elems(), kv->batch, kv->map(),
+                     t);
     if (hipGetLastError() != hipSuccess) return TRISPEC_ELAUNCH;
   }
   for (int b = 0; b < kv->batch; ++b) kv->ctx_len[b] += t.n[b];

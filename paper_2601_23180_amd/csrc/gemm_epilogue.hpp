@@ -275,6 +275,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, f32x16 (&acc)[N
       // a tile holds whole heads; thread = (row, 4 rotation pairs)
       const int d = a.head_dim, half = d >> 1;
       const int n_q = a.n_q_heads, n_kv = a.n_kv_heads;
+      const bool paged = a.kv.page_table != nullptr;          // uniform: the contiguous cache's addresses stay plain arithmetic
       constexpr int quads = TN / 8;                           // 4-pair groups per row
 #pragma unroll
       for (int u = 0; u < QKV_PASSES; ++u) {
@@ -328,18 +329,21 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, f32x16 (&acc)[N
           *(bf16x4 *)(qo + half + a.q_panel) = hl4;
         }
         if (hh >= n_q && hh < n_q + n_kv) {
-          bf16 *kc = (bf16 *)a.k_cache + (((size_t)b * n_kv + (hh - n_q)) * a.capacity + slot) * d;
+          bf16 *kc = (bf16 *)a.k_cache + (paged ? a.kv.k_row(b, hh - n_q, slot)
+                                               : (((size_t)b * n_kv + (hh - n_q)) * a.kv.capacity + slot) * d);
           bf16x4 l4, h4;
 #pragma unroll
           for (int e = 0; e < 4; ++e) { l4[e] = (bf16)lo[e]; h4[e] = (bf16)hi[e]; }
           *(bf16x4 *)(kc + j) = l4;
           *(bf16x4 *)(kc + j + half) = h4;
         } else if (hh >= n_q + n_kv) {
-          bf16 *vc = (bf16 *)a.v_cache + ((size_t)b * n_kv + (hh - n_q - n_kv)) * d * a.capacity;
+          bf16 *vc = (bf16 *)a.v_cache + (paged ? a.kv.v_col(b, hh - n_q - n_kv, slot)
+                                               : ((size_t)b * n_kv + (hh - n_q - n_kv)) * d * a.kv.capacity + slot);
+          const size_t vs = paged ? (size_t)kKvPage : (size_t)a.kv.capacity;
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            vc[(size_t)(j + e) * a.capacity + slot] = (bf16)lo[e];
-            vc[(size_t)(j + e + half) * a.capacity + slot] = (bf16)hi[e];
+            vc[(size_t)(j + e) * vs] = (bf16)lo[e];
+            vc[(size_t)(j + e + half) * vs] = (bf16)hi[e];
           }
         }
       }

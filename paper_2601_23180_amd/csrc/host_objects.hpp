@@ -20,6 +20,17 @@ struct trispec_kv {
   void *k, *v;
   int32_t batch, capacity;
   int32_t ctx_len[ts::kMaxBatch];
+  // paged cache: device page table [batch][max_pages] and the pool size; contiguous cache: nullptr, 0, 0
+  const int32_t *page_table;
+  int32_t max_pages, n_pages;
+  // elements of one layer of K (= of V), and the slot map the kernels address the cache through
+  size_t layer_elems() const {
+    const trispec_model_config &c = model->cfg;
+    return (page_table ? (size_t)n_pages * ts::kKvPage : (size_t)batch * capacity) * c.n_kv_heads * c.head_dim;
+  }
+  ts::KvMap map() const {
+    return ts::KvMap{page_table, max_pages, n_pages, capacity, model->cfg.n_kv_heads, model->cfg.head_dim};
+  }
 };
 
 struct trispec_timer {

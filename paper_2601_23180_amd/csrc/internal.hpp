@@ -46,6 +46,33 @@ struct HeadStats {
 };
 
 // One weight-streaming matmul  y[r][col] = sum_k X[r][k] * W[col][k]  (see kernels_gemm.hip).
+// Where the slots of a sequence live inside ONE layer of the cache.  Contiguous cache:
+// K [B][nkv][capacity][d], V^T [B][nkv][d][capacity].  Paged cache: pages of kKvPage slots,
+// K [n_pages][nkv][kKvPage][d], V^T [n_pages][nkv][d][kKvPage]; slot s of sequence b is slot
+// s % kKvPage of page page_table[b][s / kKvPage].  All results are element offsets from the layer's base.
+constexpr int kKvPage = 256;
+struct KvMap {
+  const int32_t *page_table;   // device [batch][max_pages], or nullptr: contiguous
+  int32_t max_pages, n_pages;  // page ids are clamped into [0, n_pages): a bad table reads the wrong page, not foreign memory
+  int32_t capacity;            // slots per sequence
+  int32_t n_kv, d;
+  __device__ __forceinline__ int page_of(int b, int slot) const {
+    const int p = page_table[(size_t)b * max_pages + min(slot / kKvPage, max_pages - 1)];
+    return min(max(p, 0), n_pages - 1);
+  }
+  __device__ __forceinline__ size_t k_row(int b, int h, int slot) const {          // K[slot][0]
+    if (!page_table) return (((size_t)b * n_kv + h) * capacity + slot) * d;
+    const int page = page_of(b, slot);
+    return (((size_t)page * n_kv + h) * kKvPage + (slot % kKvPage)) * d;
+  }
+  __device__ __forceinline__ size_t v_col(int b, int h, int slot) const {          // V^T[0][slot]; feature f is f * v_stride() further
+    if (!page_table) return ((size_t)b * n_kv + h) * d * capacity + slot;
+    const int page = page_of(b, slot);
+    return ((size_t)page * n_kv + h) * d * kKvPage + (slot % kKvPage);
+  }
+  __device__ __forceinline__ size_t v_stride() const { return page_table ? (size_t)kKvPage : (size_t)capacity; }
+};
+
 struct GemmSeg {
   const void *w;   // bf16 models: the PACKED copy of the [n_rows, K] matrix; fp32: the matrix
   int32_t n_rows;
@@ -84,7 +111,8 @@ struct GemmArgs {
   void *k_cache, *v_cache;
   const void *q_norm_w, *k_norm_w;   // [head_dim] each, or nullptr: no per-head norm of q / k
   CtxLens ctx;
-  int32_t n_nodes, n_q_heads, n_kv_heads, head_dim, capacity;
+  int32_t n_nodes, n_q_heads, n_kv_heads, head_dim;
+  KvMap kv;
   // RESID epilogue
   const float *x_resid;  // [rows_pad][n_total] residual stream before this matmul
   float *x_resid_out;  // the same after it (may be x_resid itself: every element is read and written by one thread)
@@ -129,12 +157,13 @@ struct AttnArgs {
   size_t q_panel;
   int32_t rows_per_wg;  // query rows (group * n_nodes of them per kv head) one workgroup covers: 128 or 256
   int32_t n_row_groups; // ceil(group * n_nodes / rows_per_wg)
-  const void *k_cache;  // this layer: [B][nkv][cap][d]
-  const void *v_cache;  // this layer: [B][nkv][d][cap]
+  const void *k_cache;  // this layer's K and V^T, addressed through `kv`
+  const void *v_cache;
+  KvMap kv;
   const uint64_t *anc;  // [B*M]
   const float *qkv;     // [B*M][(nq + 2 nkv) * d] this layer's q, k (rotated) and v in fp32
   CtxLens ctx;
-  int32_t batch, n_nodes, n_q_heads, n_kv_heads, head_dim, capacity;
+  int32_t batch, n_nodes, n_q_heads, n_kv_heads, head_dim;
   int32_t keys_per_split;   // multiple of 64
   int32_t n_splits;
   float *part_o;        // [B][nkv][n_splits][group*M][d]  unnormalised
@@ -199,8 +228,8 @@ struct CommitTable {
   int32_t n[kMaxBatch];
   int32_t ctx[kMaxBatch];
 };
-void launch_kv_commit(hipStream_t st, int dtype, void *k_cache, void *v_cache, int n_layers, int batch,
-                      int n_kv_heads, int head_dim, int capacity, const CommitTable &t);
+void launch_kv_commit(hipStream_t st, int dtype, void *k_cache, void *v_cache, int n_layers, size_t layer_elems,
+                      int batch, const KvMap &kv, const CommitTable &t);
 void launch_copy_probe(hipStream_t st, void *dst, const void *src, size_t bytes);
 // out[r][c] = x[r][c] * rstd(r) * w[c]; rstd from the per-tile sums of squares ss[tile][rows_pad]
 // (ss == nullptr: x is already normalised and weighted, plain copy)
@@ -210,7 +239,7 @@ void launch_zero_counters(hipStream_t st, int32_t *counters, int n_counters);
 void launch_qkv_epilogue(hipStream_t st, int dtype, const float *part, int n_splits, int rows,
                          int rows_pad, int n_q_heads, int n_kv_heads, int head_dim,
                          const float *cos_t, const float *sin_t, int n_nodes, CtxLens ctx,
-                         int capacity, void *q_out, void *k_cache, void *v_cache, const float *q_norm_w,
+                         const KvMap &kvm, void *q_out, void *k_cache, void *v_cache, const float *q_norm_w,
                          const float *k_norm_w, float eps);
 void launch_reduce_residual_norm(hipStream_t st, int dtype, const float *part, int n_splits, int rows,
                                  int rows_pad, int hidden, const void *norm_w, float eps, float *x,

@@ -29,15 +29,14 @@ __global__ __launch_bounds__(64) void k_attn_f32(AttnArgs a) {
   const int n_keys = ctx + a.n_nodes;
   const uint64_t mask = a.anc[r];
   const float *q = (const float *)a.q + (size_t)r * a.n_q_heads * d + (size_t)head * d;
-  const float *kc = (const float *)a.k_cache + ((size_t)b * a.n_kv_heads + kvh) * a.capacity * d;
-  const float *vc = (const float *)a.v_cache + ((size_t)b * a.n_kv_heads + kvh) * d * a.capacity;
+  const float *kc = (const float *)a.k_cache, *vc = (const float *)a.v_cache;   // slots through a.kv
   const float scale = 1.0f / sqrtf((float)d);
   float mx = -INFINITY;
   for (int k = lane; k < n_keys; k += 64) {
     const bool ok = (k < ctx) || ((mask >> (k - ctx)) & 1ull);
     float s = -INFINITY;
     if (ok) {
-      const float *kr = kc + (size_t)k * d;
+      const float *kr = kc + a.kv.k_row(b, kvh, k);
       float acc = 0.f;
       for (int j = 0; j < d; ++j) acc += q[j] * kr[j];
       s = acc * scale;
@@ -56,9 +55,9 @@ __global__ __launch_bounds__(64) void k_attn_f32(AttnArgs a) {
   __syncthreads();
   float *o = (float *)a.out + (size_t)r * a.n_q_heads * d + (size_t)head * d;
   for (int j = lane; j < d; j += 64) {
-    const float *vr = vc + (size_t)j * a.capacity;
+    const size_t vj = (size_t)j * a.kv.v_stride();
     float acc = 0.f;
-    for (int k = 0; k < n_keys; ++k) acc += sc[k] * vr[k];
+    for (int k = 0; k < n_keys; ++k) acc += sc[k] * vc[a.kv.v_col(b, kvh, k) + vj];
     o[j] = acc / sum;
   }
 }
@@ -85,7 +84,9 @@ struct AttnLds {
 // <KT 128, NW 4>: one workgroup per CU.  <KT 64, NW 8>: 256 rows share every staged K/V tile
 // (trees of more than 128 rows read the cache once, not twice) and two waves per SIMD overlap
 // one another's softmax arithmetic and matrix work.
-template <int D, int RBW, int KT, int NW>
+// PAGED: the cache is in pages of kKvPage slots (a multiple of KT, and every split starts at a
+// multiple of KT, so a tile never straddles two pages): one scalar page lookup per tile.
+template <int D, int RBW, int KT, int NW, bool PAGED>
 __global__ __launch_bounds__(64 * NW) void k_attn_bf16(AttnArgs a) {
   using L = AttnLds<D, KT>;
   constexpr int NT = 64 * NW;
@@ -118,8 +119,13 @@ __global__ __launch_bounds__(64 * NW) void k_attn_bf16(AttnArgs a) {
     return;
   }
 
-  const bf16 *kc = (const bf16 *)a.k_cache + ((size_t)b * a.n_kv_heads + kvh) * a.capacity * D;
-  const bf16 *vc = (const bf16 *)a.v_cache + ((size_t)b * a.n_kv_heads + kvh) * D * a.capacity;
+  static_assert(kKvPage % KT == 0, "a tile must not straddle pages");
+  const int cap = PAGED ? kKvPage : a.kv.capacity;   // slots behind kc / vc, and the V^T row stride
+  const bf16 *kc0 = (const bf16 *)a.k_cache, *vc0 = (const bf16 *)a.v_cache;
+  if (!PAGED) {
+    kc0 += ((size_t)b * a.n_kv_heads + kvh) * a.kv.capacity * D;
+    vc0 += ((size_t)b * a.n_kv_heads + kvh) * D * a.kv.capacity;
+  }
 
   // ---- tile staging: K tile = KT rows of D*2 bytes (16-byte vectors), V^T tile = D rows of KT*2 bytes
   constexpr int KV_PER_T = KT * D * 2 / 16 / NT;   // 16-byte vectors per thread, each of K and V^T
@@ -128,18 +134,27 @@ __global__ __launch_bounds__(64 * NW) void k_attn_bf16(AttnArgs a) {
   u32x4 kreg[KV_PER_T], vreg[KV_PER_T];
   // load_tile only ISSUES loads — anything that looked at a loaded value here would make the
   // compiler wait for each load in turn; the slots past the context are zeroed in store_tile.
-  auto load_tile = [&](int k0) {
+  auto load_tile = [&](int k0g) {
+    // contiguous: k0 counts from the sequence's first slot; paged: from the first slot of the tile's page
+    const bf16 *kc = kc0, *vc = vc0;
+    int k0 = k0g;
+    if (PAGED) {
+      const int page = a.kv.page_of(b, k0g);
+      kc += ((size_t)page * a.n_kv_heads + kvh) * kKvPage * D;
+      vc += ((size_t)page * a.n_kv_heads + kvh) * D * kKvPage;
+      k0 = k0g % kKvPage;
+    }
 #pragma unroll
     for (int i = 0; i < KV_PER_T; ++i) {
       const int v = tid + NT * i;
       {  // K: vector v -> key v / (D/8), 16-byte column v % (D/8)
         const int key = v / (D / 8), c = v % (D / 8);
         // rows past the context hold no token (their scores are masked); clamped into the cache
-        kreg[i] = *(const u32x4 *)(kc + (size_t)min(k0 + key, a.capacity - 1) * D + c * 8);
+        kreg[i] = *(const u32x4 *)(kc + (size_t)min(k0 + key, cap - 1) * D + c * 8);
       }
       {  // V^T: vector v -> feature v / (KT/8), 8 keys starting at (v % (KT/8)) * 8
         const int f = v / (KT / 8), c = v % (KT / 8);
-        vreg[i] = *(const u32x4 *)(vc + (size_t)f * a.capacity + min(k0 + c * 8, a.capacity - 8));
+        vreg[i] = *(const u32x4 *)(vc + (size_t)f * cap + min(k0 + c * 8, cap - 8));
       }
     }
   };
@@ -478,8 +493,13 @@ __global__ __launch_bounds__(512) void k_attn_merge(AttnArgs a) {
 template <int D>
 static void launch_attn_bf16_d(hipStream_t st, const AttnArgs &a) {
   dim3 grid(a.n_splits, a.n_kv_heads, a.batch * a.n_row_groups);
-  if (a.rows_per_wg == 256) hipLaunchKernelGGL((k_attn_bf16<D, 1, 64, 8>), grid, dim3(512), 0, st, a);
-  else hipLaunchKernelGGL((k_attn_bf16<D, 1, 128, 4>), grid, dim3(256), 0, st, a);
+  if (a.kv.page_table) {
+    if (a.rows_per_wg == 256) hipLaunchKernelGGL((k_attn_bf16<D, 1, 64, 8, true>), grid, dim3(512), 0, st, a);
+    else hipLaunchKernelGGL((k_attn_bf16<D, 1, 128, 4, true>), grid, dim3(256), 0, st, a);
+  } else {
+    if (a.rows_per_wg == 256) hipLaunchKernelGGL((k_attn_bf16<D, 1, 64, 8, false>), grid, dim3(512), 0, st, a);
+    else hipLaunchKernelGGL((k_attn_bf16<D, 1, 128, 4, false>), grid, dim3(256), 0, st, a);
+  }
   const int group = a.n_q_heads / a.n_kv_heads;
   const int merge_threads = group * D / 2 < 64 ? 64 : group * D / 2;   // <= 512 (group <= 8, d <= 128)
   hipLaunchKernelGGL(k_attn_merge<D>, dim3(a.batch * a.n_nodes, a.n_kv_heads), dim3(merge_threads), 0, st, a);

@@ -160,7 +160,7 @@ __device__ __forceinline__ float sum_splits(const float *part, int n_splits, siz
 // attention operand buffer, k and v to cache slot ctx_len + node (v transposed).
 __global__ void k_qkv_epilogue_f32(const float *part, int n_splits, int rows_pad, int n_q_heads,
                                    int n_kv_heads, int head_dim, const float *cos_t, const float *sin_t,
-                                   int n_nodes, CtxLens ctx, int capacity, float *q_out, float *k_cache,
+                                   int n_nodes, CtxLens ctx, KvMap kvm, float *q_out, float *k_cache,
                                    float *v_cache, const float *q_norm_w, const float *k_norm_w, float eps) {
   __shared__ float s_sq[64];
   const int r = blockIdx.x, hh = blockIdx.y, j = threadIdx.x;   // head_dim / 2 threads
@@ -194,26 +194,26 @@ __global__ void k_qkv_epilogue_f32(const float *part, int n_splits, int rows_pad
     q[j + half] = b;
   } else if (hh < n_q_heads + n_kv_heads) {
     const int kvh = hh - n_q_heads;
-    float *k = k_cache + (((size_t)bidx * n_kv_heads + kvh) * capacity + slot) * head_dim;
+    float *k = k_cache + kvm.k_row(bidx, kvh, slot);
     k[j] = a;
     k[j + half] = b;
   } else {
     const int kvh = hh - n_q_heads - n_kv_heads;
-    float *v = v_cache + ((size_t)bidx * n_kv_heads + kvh) * head_dim * capacity;
-    v[(size_t)j * capacity + slot] = a;
-    v[(size_t)(j + half) * capacity + slot] = b;
+    float *v = v_cache + kvm.v_col(bidx, kvh, slot);
+    v[(size_t)j * kvm.v_stride()] = a;
+    v[(size_t)(j + half) * kvm.v_stride()] = b;
   }
 }
 
 void launch_qkv_epilogue(hipStream_t st, int dtype, const float *part, int n_splits, int rows,
                          int rows_pad, int n_q_heads, int n_kv_heads, int head_dim,
                          const float *cos_t, const float *sin_t, int n_nodes, CtxLens ctx,
-                         int capacity, void *q_out, void *k_cache, void *v_cache, const float *q_norm_w,
+                         const KvMap &kvm, void *q_out, void *k_cache, void *v_cache, const float *q_norm_w,
                          const float *k_norm_w, float eps) {
   (void)dtype;
   dim3 grid(rows, n_q_heads + 2 * n_kv_heads), block(head_dim / 2);
   hipLaunchKernelGGL(k_qkv_epilogue_f32, grid, block, 0, st, part, n_splits, rows_pad, n_q_heads,
-                     n_kv_heads, head_dim, cos_t, sin_t, n_nodes, ctx, capacity, (float *)q_out,
+                     n_kv_heads, head_dim, cos_t, sin_t, n_nodes, ctx, kvm, (float *)q_out,
                      (float *)k_cache, (float *)v_cache, q_norm_w, k_norm_w, eps);
 }
 
@@ -507,13 +507,14 @@ void launch_export_hidden(hipStream_t st, int dtype, const float *x, const void 
 // path's nodes move from slot ctx + node[i] to slot ctx + i.  node[i] >= i, so a destination may
 // be another row's source: everything is read into registers, then a barrier, then written.
 template <typename T>
-__global__ __launch_bounds__(256) void k_kv_commit(T *k_cache, T *v_cache, int batch, int n_kv_heads, int d,
-                                                    int capacity, CommitTable t) {
+__global__ __launch_bounds__(256) void k_kv_commit(T *k_cache, T *v_cache, size_t layer_elems, KvMap kvm,
+                                                    CommitTable t) {
   const int h = blockIdx.x, b = blockIdx.y, l = blockIdx.z, tid = threadIdx.x;
-  const int n = t.n[b], ctx = t.ctx[b];
+  const int n = t.n[b], ctx = t.ctx[b], d = kvm.d;
   if (n == 0) return;   // uniform over the workgroup
-  T *kc = k_cache + (((size_t)l * batch + b) * n_kv_heads + h) * (size_t)capacity * d;
-  T *vc = v_cache + (((size_t)l * batch + b) * n_kv_heads + h) * (size_t)d * capacity;
+  T *kc = k_cache + (size_t)l * layer_elems;   // this layer; rows and columns through the slot map
+  T *vc = v_cache + (size_t)l * layer_elems;
+  const size_t vs = kvm.v_stride();
   constexpr int VEC = 16 / sizeof(T);                       // elements per 16-byte vector
   constexpr int MAXV = kMaxNodes * 128 / VEC / 256;         // vectors per thread at d = 128
   constexpr int MAXE = kMaxNodes * 128 / 256;               // V^T elements per thread at d = 128
@@ -524,35 +525,35 @@ __global__ __launch_bounds__(256) void k_kv_commit(T *k_cache, T *v_cache, int b
 #pragma unroll
   for (int u = 0; u < MAXV; ++u) {
     const int idx = tid + 256 * u, i = idx / vec_per_row, c = idx - i * vec_per_row;
-    if (i < n) kv[u] = *(const u32x4 *)(kc + (size_t)(ctx + t.node[b][i]) * d + c * VEC);
+    if (i < n) kv[u] = *(const u32x4 *)(kc + kvm.k_row(b, h, ctx + t.node[b][i]) + c * VEC);
   }
 #pragma unroll
   for (int u = 0; u < MAXE; ++u) {
     const int idx = tid + 256 * u, f = idx / kMaxNodes, i = idx - f * kMaxNodes;   // 64 consecutive threads: one feature
-    if (f < d && i < n) ve[u] = vc[(size_t)f * capacity + ctx + t.node[b][i]];
+    if (f < d && i < n) ve[u] = vc[kvm.v_col(b, h, ctx + t.node[b][i]) + (size_t)f * vs];
   }
   __syncthreads();
 #pragma unroll
   for (int u = 0; u < MAXV; ++u) {
     const int idx = tid + 256 * u, i = idx / vec_per_row, c = idx - i * vec_per_row;
-    if (i < n) *(u32x4 *)(kc + (size_t)(ctx + i) * d + c * VEC) = kv[u];
+    if (i < n) *(u32x4 *)(kc + kvm.k_row(b, h, ctx + i) + c * VEC) = kv[u];
   }
 #pragma unroll
   for (int u = 0; u < MAXE; ++u) {
     const int idx = tid + 256 * u, f = idx / kMaxNodes, i = idx - f * kMaxNodes;
-    if (f < d && i < n) vc[(size_t)f * capacity + ctx + i] = ve[u];
+    if (f < d && i < n) vc[kvm.v_col(b, h, ctx + i) + (size_t)f * vs] = ve[u];
   }
 }
 
-void launch_kv_commit(hipStream_t st, int dtype, void *k_cache, void *v_cache, int n_layers, int batch,
-                      int n_kv_heads, int head_dim, int capacity, const CommitTable &t) {
-  dim3 grid(n_kv_heads, batch, n_layers);
+void launch_kv_commit(hipStream_t st, int dtype, void *k_cache, void *v_cache, int n_layers, size_t layer_elems,
+                      int batch, const KvMap &kvm, const CommitTable &t) {
+  dim3 grid(kvm.n_kv, batch, n_layers);
   if (dtype == TRISPEC_F32)
-    hipLaunchKernelGGL(k_kv_commit<float>, grid, dim3(256), 0, st, (float *)k_cache, (float *)v_cache, batch,
-                       n_kv_heads, head_dim, capacity, t);
+    hipLaunchKernelGGL(k_kv_commit<float>, grid, dim3(256), 0, st, (float *)k_cache, (float *)v_cache, layer_elems,
+                       kvm, t);
   else
-    hipLaunchKernelGGL(k_kv_commit<bf16>, grid, dim3(256), 0, st, (bf16 *)k_cache, (bf16 *)v_cache, batch,
-                       n_kv_heads, head_dim, capacity, t);
+    hipLaunchKernelGGL(k_kv_commit<bf16>, grid, dim3(256), 0, st, (bf16 *)k_cache, (bf16 *)v_cache, layer_elems,
+                       kvm, t);
 }
 
 }  // namespace ts

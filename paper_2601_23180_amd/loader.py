@@ -40,8 +40,7 @@ def model_from_arrays(shape, get: Callable[[str, int], np.ndarray], device="cuda
 def fill_kv_layer(kv: KVCache, layer: int, k: np.ndarray, v: np.ndarray) -> None:
     """k, v: [batch, n_kv, C, d] values of the first C cache slots of one layer
     (keys after the rotary embedding).  V is stored transposed."""
-    C = k.shape[2]
-    kt = torch.from_numpy(np.ascontiguousarray(k, dtype=np.float32)).to(kv.k.device).to(kv.k.dtype)
-    vt = torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).to(kv.v.device).to(kv.v.dtype)
-    kv.k[layer, :, :, :C, :] = kt
-    kv.v[layer, :, :, :, :C] = vt.transpose(-1, -2)
+    dev = kv.table.device if hasattr(kv, "table") else kv.k.device
+    kt = torch.from_numpy(np.ascontiguousarray(k, dtype=np.float32)).to(dev)
+    vt = torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).to(dev)
+    kv.write_layer(layer, kt, vt)

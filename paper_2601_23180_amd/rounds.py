@@ -13,7 +13,7 @@ from typing import Dict, List, Sequence
 import numpy as np
 import torch
 
-from .binding import (CRIT_MARGIN, MAX_NODES, RESAMPLE_RESIDUAL, TERNARY_SCRATCH_INTS, KVCache, Model, RoundInfo,
+from .binding import (CRIT_MARGIN, MAX_NODES, RESAMPLE_RESIDUAL, TERNARY_SCRATCH_INTS, KVCache, Model, PagedKVCache, RoundInfo,
                       SampleRound, TernaryConfig, check, lib)
 
 
@@ -29,9 +29,10 @@ def _pass_dict(r) -> Dict[str, object]:
 
 class TernaryDecoder:
     def __init__(self, proxy: Model, target: Model, capacity: int, criterion: int = CRIT_MARGIN,
-                 max_nodes: int = MAX_NODES):
+                 max_nodes: int = MAX_NODES, paged: bool = False):
         self.proxy, self.target = proxy, target
-        self.kv_p, self.kv_t = KVCache(proxy, 1, capacity), KVCache(target, 1, capacity)
+        cache = PagedKVCache if paged else KVCache
+        self.kv_p, self.kv_t = cache(proxy, 1, capacity), cache(target, 1, capacity)
         self.criterion, self.max_nodes = criterion, max_nodes
         self.seq: List[int] = []
         self.target_passes = 0          # passes of the target that verified drafts (not catch-up)

@@ -5,7 +5,7 @@ import torch
 
 from oracle import (CRIT_ENTROPY, CRIT_MARGIN, OracleWeights, causal_forward, decide, node_stats, tie_flags,
                     verify_forward)
-from paper_2601_23180_amd import KVCache, Model, Verifier, fill_kv_layer, model_from_arrays
+from paper_2601_23180_amd import KVCache, Model, PagedKVCache, Verifier, fill_kv_layer, model_from_arrays
 from workloads import WeightSource, gen_kv_cache, tree_depths
 
 
@@ -43,19 +43,27 @@ class Case:
         return outs
 
     def run_gpu(self, threshold, criterion=CRIT_MARGIN, n_forced=1, model=None, want_logits=True,
-                export_hidden=False, launch_mode=0):
+                export_hidden=False, launch_mode=0, paged=False):
         model = model or device_model(self.shape, self.seed)
         cap = capacity_for(max(self.ctx_len) + self.n_nodes)
-        kv = KVCache(model, self.batch, cap)
-        # poison the unused slots so that a kernel reading them shows up
-        kv.k.fill_(float("nan")); kv.v.fill_(float("nan"))
+        kv = PagedKVCache(model, self.batch, cap, seed=self.seed) if paged else KVCache(model, self.batch, cap)
+        cap = kv.capacity
+        c = model.cfg
+        dt = torch.float32 if self.shape.dtype == "f32" else torch.bfloat16
+        # poison the unused slots (and, paged, the unmapped pages) so that a kernel reading them shows up
+        kd = torch.full((c.n_layers, self.batch, c.n_kv_heads, cap, c.head_dim), float("nan"), dtype=dt, device="cuda")
+        vd = torch.full((c.n_layers, self.batch, c.n_kv_heads, c.head_dim, cap), float("nan"), dtype=dt, device="cuda")
+        if paged:
+            kv.k_pool.fill_(float("nan")); kv.v_pool.fill_(float("nan"))
         for l in range(self.shape.n_layers):
             for b in range(self.batch):
                 C = self.ctx_len[b]
-                kt = torch.from_numpy(np.asarray(self.k_ctx[b][l], dtype=np.float32)).cuda().to(kv.k.dtype)
-                vt = torch.from_numpy(np.asarray(self.v_ctx[b][l], dtype=np.float32)).cuda().to(kv.v.dtype)
-                kv.k[l, b, :, :C, :] = kt
-                kv.v[l, b, :, :, :C] = vt.transpose(-1, -2)
+                kt = torch.from_numpy(np.asarray(self.k_ctx[b][l], dtype=np.float32)).cuda().to(dt)
+                vt = torch.from_numpy(np.asarray(self.v_ctx[b][l], dtype=np.float32)).cuda().to(dt)
+                kd[l, b, :, :C, :] = kt
+                vd[l, b, :, :, :C] = vt.transpose(-1, -2)
+        kv.load_dense(kd, vd)
+        del kd, vd
         kv.set_len(self.ctx_len)
         ver = Verifier(model, self.batch, self.n_nodes, debug_logits=want_logits, export_hidden=export_hidden)
         ver.launch_mode = launch_mode

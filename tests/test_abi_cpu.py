@@ -344,3 +344,25 @@ def test_ternary_driver_rejects_bad_arguments_and_kv_len_round_trip():
         lib.trispec_kv_destroy(h)
     for m in (mp, mt, mv):
         lib.trispec_model_destroy(m)
+
+
+def test_paged_cache_creation_is_validated():
+    lib = B.lib()
+    _, m, keep = _model()
+    n = C.c_size_t()
+    assert lib.trispec_kv_paged_bytes(m, 10, C.byref(n)) == 0
+    assert n.value == 2 * 10 * 2 * 256 * 64 * 4                 # layers x pages x kv heads x page x head_dim x fp32
+    assert lib.trispec_kv_paged_bytes(m, 0, C.byref(n)) == -6 and lib.trispec_kv_paged_bytes(m, 10, None) == -1
+    h = C.c_void_p()
+    ok = lambda **kw: lib.trispec_kv_create_paged(m, kw.get("k", 0x10000), kw.get("v", 0x20000), kw.get("t", 0x30000),
+                                                  kw.get("batch", 2), kw.get("mp", 4), kw.get("np", 10), C.byref(h))
+    assert ok() == 0
+    lens = (C.c_int32 * 2)(1024, 3)
+    assert lib.trispec_kv_set_len(h, lens) == 0                 # capacity = 4 pages of 256 slots
+    lens[0] = 1025
+    assert lib.trispec_kv_set_len(h, lens) == -6
+    lib.trispec_kv_destroy(h)
+    assert ok(t=None) == -1 and ok(k=None) == -1
+    assert ok(batch=9) == -3 and ok(mp=0) == -6 and ok(np=0) == -6
+    assert ok(k=0x10004) == -8
+    lib.trispec_model_destroy(m)

@@ -67,9 +67,9 @@ def plant_paths(case, leaves):
             case.tokens[b][c] = node_stats(lg)["argmax"][a]
 
 
-def full_check(case, thresholds=(0.0, 0.3, 0.5, 0.9, 1.5), n_forced=1, launch_mode=0):
+def full_check(case, thresholds=(0.0, 0.3, 0.5, 0.9, 1.5), n_forced=1, launch_mode=0, paged=False):
     oracle_out = case.run_oracle()
-    gpu = case.run_gpu(thresholds[0], CRIT_MARGIN, n_forced, launch_mode=launch_mode)
+    gpu = case.run_gpu(thresholds[0], CRIT_MARGIN, n_forced, launch_mode=launch_mode, paged=paged)
     assert gpu["status"][0] == 0
     for b in range(case.batch):
         logits_ok(case.shape, gpu["logits"][b], oracle_out[b]["logits"])
