@@ -34,7 +34,8 @@
 extern "C" {
 #endif
 
-#define TRISPEC_MAX_NODES 64   /* nodes per sequence (ancestor mask = one 64-bit word) */
+#define TRISPEC_MAX_NODES 128  /* nodes per sequence (ancestor mask = two 64-bit words); the paper's trees hold 60.
+                                  The sampling form (trispec_sample_decide*) takes chains of up to 64 nodes */
 #define TRISPEC_MAX_BATCH 8
 #define TRISPEC_MAX_ROWS 256   /* batch * n_nodes */
 
@@ -360,8 +361,8 @@ int trispec_decide(trispec_model *m, int32_t batch, const int32_t *draft_tokens,
  * never accepted; bit 1: a draw found no usable mass — a logit, a draft probability or a uniform
  * that is NaN or infinite — and returned that node's argmax instead).  Any out pointer may be NULL.  Enqueues four kernels on `stream`, allocates
  * nothing, does not synchronise.
- * Errors (host side, before any launch): TRISPEC_ENULL, TRISPEC_ENODES, TRISPEC_EFORCED,
- * TRISPEC_EWORKSPACE (scratch), TRISPEC_EARG (temperature not finite and positive, threshold NaN,
+ * Errors (host side, before any launch): TRISPEC_ENULL, TRISPEC_ENODES (a chain of more than 64
+ * nodes included), TRISPEC_EFORCED, TRISPEC_EWORKSPACE (scratch), TRISPEC_EARG (temperature not finite and positive, threshold NaN,
  * criterion, resample, vocab outside [1, 4194304]); TRISPEC_ELAUNCH afterwards.
  */
 #define TRISPEC_RESAMPLE_RESIDUAL 0
@@ -440,7 +441,7 @@ int trispec_timer_destroy(trispec_timer *t);
  * The drafter is the caller's: every round brings its own tree.
  */
 typedef struct trispec_ternary trispec_ternary;
-#define TRISPEC_TERNARY_SCRATCH_INTS 512
+#define TRISPEC_TERNARY_SCRATCH_INTS 1024
 typedef struct {
   trispec_model *proxy, *target;              /* M_p and M_t; the same vocabulary */
   trispec_kv *kv_proxy, *kv_target;           /* caches of ONE sequence (batch 1), one per model */

@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libtrispec.so")
 TRISPEC_F32, TRISPEC_BF16 = 0, 1
 CRIT_MARGIN, CRIT_TOP1, CRIT_ENTROPY = 0, 1, 2
 RESAMPLE_RESIDUAL, RESAMPLE_DIRECT = 0, 1
-MAX_NODES, MAX_BATCH, MAX_ROWS, PATH_STRIDE = 64, 8, 256, 64
+MAX_NODES, MAX_BATCH, MAX_ROWS, PATH_STRIDE = 128, 8, 256, 128
 
 EXPORTS = [
     "trispec_model_create", "trispec_model_destroy", "trispec_kv_bytes", "trispec_kv_create",
@@ -45,7 +45,7 @@ class ModelConfig(C.Structure):
 
 
 _PP = C.POINTER(C.c_void_p)
-TERNARY_SCRATCH_INTS = 512
+TERNARY_SCRATCH_INTS = 1024
 
 
 class TernaryConfig(C.Structure):
@@ -58,7 +58,7 @@ class TernaryConfig(C.Structure):
 
 class PassResult(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("accepted_len", "token", "escalate", "status", "path_len")] + \
-               [("path", C.c_int32 * 64)]
+               [("path", C.c_int32 * PATH_STRIDE)]
 
 
 class SampleRound(C.Structure):

@@ -131,7 +131,7 @@ Layout make_layout(const trispec_model_config &c, int batch, int max_nodes) {
   L.head_tiles = f32 ? 1 : plan_gemm(EPI_HEAD, c.vocab, c.hidden, rp).n_tiles;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
-  L.anc = take(sizeof(uint64_t) * kMaxRows);
+  L.anc = take(sizeof(AncMask) * kMaxRows);
   L.parent = take(sizeof(int32_t) * kMaxRows);
   L.status = take(256);
   L.cos_t = take(sizeof(float) * rows * (c.head_dim / 2));
@@ -210,7 +210,7 @@ int check_shape(const trispec_model_config &c) {
   return TRISPEC_OK;
 }
 
-// parents -> ancestor-or-self bit masks; validates topological order and the forced chain.
+// Validates topological order and the forced chain; the set-up kernel turns the parents into root-path masks.
 int build_nodes(const int32_t *parents, int batch, int n_nodes, int n_forced, NodeTable &tab) {
   for (int b = 0; b < batch; ++b) {
     const int32_t *p = parents + (size_t)b * n_nodes;
@@ -218,8 +218,6 @@ int build_nodes(const int32_t *parents, int batch, int n_nodes, int n_forced, No
     for (int i = 0; i < n_nodes; ++i) {
       if (i > 0 && (p[i] < 0 || p[i] >= i)) return TRISPEC_ETREE;
       if (i > 0 && i < n_forced && p[i] != i - 1) return TRISPEC_EFORCED;
-      const uint64_t up = i == 0 ? 0ull : tab.anc[b * n_nodes + p[i]];
-      tab.anc[b * n_nodes + i] = up | (1ull << i);
       tab.parent[b * n_nodes + i] = p[i];
     }
   }
@@ -534,7 +532,7 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
   if (n_nodes < 1 || n_nodes > kMaxNodes || B * n_nodes > kMaxRows) return TRISPEC_ENODES;
   if (opts->n_forced < 1 || opts->n_forced > n_nodes) return TRISPEC_EFORCED;
   const int group = c.n_q_heads / c.n_kv_heads;
-  if (c.dtype == TRISPEC_BF16 && group * n_nodes > 256) return TRISPEC_ENODES;
+  if (c.dtype == TRISPEC_BF16 && group * n_nodes > 512) return TRISPEC_ENODES;
   int max_keys = 0;
   for (int b = 0; b < B; ++b) {
     if (kv->ctx_len[b] + n_nodes > kv->capacity) return TRISPEC_ECAPACITY;
@@ -587,7 +585,7 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
 
   AttnArgs at;
   memset(&at, 0, sizeof(at));
-  at.anc = (const uint64_t *)(ws + L.anc);
+  at.anc = (const AncMask *)(ws + L.anc);
   at.ctx = ctx;
   at.batch = B; at.n_nodes = n_nodes; at.n_q_heads = c.n_q_heads; at.n_kv_heads = c.n_kv_heads;
   at.head_dim = c.head_dim; at.kv = kv->map();
@@ -628,7 +626,7 @@ int trispec_verify(trispec_model *m, trispec_kv *kv, const int32_t *draft_tokens
   };
 
   (void)hipGetLastError();
-  launch_setup(st, tab, rows, (uint64_t *)(ws + L.anc), (int32_t *)(ws + L.parent), status,
+  launch_setup(st, tab, rows, n_nodes, (AncMask *)(ws + L.anc), (int32_t *)(ws + L.parent), status,
                (int32_t *)(ws + L.counters), L.n_zero);
   launch_rope_table(st, positions, rows, c.head_dim, c.rope_base, cos_t, sin_t);
 
@@ -921,7 +919,7 @@ int trispec_decide(trispec_model *m, int32_t batch, const int32_t *draft_tokens,
   (void)hipGetLastError();
   // the tree of THIS call (it may differ from the last verify's, e.g. after pruning): parents into
   // the workspace, the status word and the counters left alone
-  launch_setup(st, tab, batch * n_nodes, (uint64_t *)(ws + L.anc), (int32_t *)(ws + L.parent), nullptr, nullptr, 0);
+  launch_setup(st, tab, batch * n_nodes, n_nodes, (AncMask *)(ws + L.anc), (int32_t *)(ws + L.parent), nullptr, nullptr, 0);
   DecideArgs d = make_decide(L, ws, draft_tokens, batch, n_nodes, threshold, opts, out);
   launch_decide(st, d);
   return hipGetLastError() == hipSuccess ? TRISPEC_OK : TRISPEC_ELAUNCH;
@@ -953,8 +951,9 @@ SampleLayout sample_layout(int batch, int n_nodes, int vocab) {
   L.total = off;
   return L;
 }
+constexpr int kMaxChain = 64;   // nodes of a chain in the sampling form (one lane of a wavefront per node)
 bool sample_shape_ok(int batch, int n_nodes) {
-  return batch >= 1 && batch <= kMaxBatch && n_nodes >= 1 && n_nodes <= kMaxNodes && batch * n_nodes <= kMaxRows;
+  return batch >= 1 && batch <= kMaxBatch && n_nodes >= 1 && n_nodes <= kMaxChain && batch * n_nodes <= kMaxRows;
 }
 }  // namespace
 

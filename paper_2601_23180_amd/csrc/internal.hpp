@@ -25,10 +25,27 @@ constexpr int kMaxAttnSplits = 64;   // context splits of one attention call
 constexpr int kAttnWideMinKeys = 6144;   // longest context from which trees of > 128 rows take 256-row workgroups
 constexpr int kGemmTileN = 128;      // output columns per workgroup (4 waves x 32)
 
-// Per-call node table, passed to the set-up kernel by value (3 KB < 4 KB kernarg limit).
+// Per-call node table, passed to the set-up kernel by value (1 KB of kernel arguments).
 struct NodeTable {
-  uint64_t anc[kMaxRows];   // bit j set <=> node j (same sequence) is an ancestor-or-self
   int32_t parent[kMaxRows];
+};
+// Root path of a node as a bit set over the nodes of its sequence: bit j set <=> node j is an
+// ancestor of the node or the node itself.  Built by the set-up kernel from the parents.
+// (two named words, selected by comparison: an array indexed by a run-time value would live in
+// scratch memory)
+struct AncMask {
+  uint64_t lo, hi;   // nodes 0..63, nodes 64..127
+  static_assert(kMaxNodes == 128, "two mask words");
+  __device__ __forceinline__ bool has(int j) const { return (((j < 64) ? lo : hi) >> (j & 63)) & 1ull; }
+  __device__ __forceinline__ void set(int j) {
+    const uint64_t bit = 1ull << (j & 63);
+    if (j < 64) lo |= bit; else hi |= bit;
+  }
+  __device__ __forceinline__ int count() const { return __popcll(lo) + __popcll(hi); }
+  __device__ __forceinline__ int rank(int j) const {   // members below j
+    const uint64_t below = (1ull << (j & 63)) - 1ull;
+    return j < 64 ? __popcll(lo & below) : __popcll(lo) + __popcll(hi & below);
+  }
 };
 
 struct CtxLens {
@@ -160,7 +177,7 @@ struct AttnArgs {
   const void *k_cache;  // this layer's K and V^T, addressed through `kv`
   const void *v_cache;
   KvMap kv;
-  const uint64_t *anc;  // [B*M]
+  const AncMask *anc;   // [B*M]
   const float *qkv;     // [B*M][(nq + 2 nkv) * d] this layer's q, k (rotated) and v in fp32
   CtxLens ctx;
   int32_t batch, n_nodes, n_q_heads, n_kv_heads, head_dim;
@@ -215,7 +232,7 @@ struct DecideArgs {
 
 // ---- launchers (one per kernel family); all enqueue on `st` and return nothing:
 // the caller checks hipGetLastError once at the end of the pass.
-void launch_setup(hipStream_t st, const NodeTable &tab, int rows, uint64_t *anc, int32_t *parent,
+void launch_setup(hipStream_t st, const NodeTable &tab, int rows, int n_nodes, AncMask *anc, int32_t *parent,
                   int32_t *status, int32_t *zero, int n_zero);
 void launch_rope_table(hipStream_t st, const int32_t *positions, int rows, int head_dim, float base,
                        float *cos_t, float *sin_t);

@@ -27,13 +27,13 @@ __global__ __launch_bounds__(64) void k_attn_f32(AttnArgs a) {
   const int b = r / a.n_nodes, node = r - b * a.n_nodes;
   const int ctx = a.ctx.v[b];
   const int n_keys = ctx + a.n_nodes;
-  const uint64_t mask = a.anc[r];
+  const AncMask mask = a.anc[r];
   const float *q = (const float *)a.q + (size_t)r * a.n_q_heads * d + (size_t)head * d;
   const float *kc = (const float *)a.k_cache, *vc = (const float *)a.v_cache;   // slots through a.kv
   const float scale = 1.0f / sqrtf((float)d);
   float mx = -INFINITY;
   for (int k = lane; k < n_keys; k += 64) {
-    const bool ok = (k < ctx) || ((mask >> (k - ctx)) & 1ull);
+    const bool ok = (k < ctx) || mask.has(k - ctx);
     float s = -INFINITY;
     if (ok) {
       const float *kr = kc + a.kv.k_row(b, kvh, k);
@@ -370,9 +370,10 @@ __global__ __launch_bounds__(512) void k_attn_merge(AttnArgs a) {
 
   // ---- the ancestor list first: one word per workgroup arrives quickly, and every address of
   // the second group of loads depends on it
-  const uint64_t mask = a.anc[r];          // bit j: node j is on the root path of this node (self included)
-  const int n_anc = __popcll(mask);        // >= 1
-  if (tid < kMaxNodes && ((mask >> tid) & 1ull)) s_anc[__popcll(mask & ((1ull << tid) - 1ull))] = tid;
+  const AncMask mask = a.anc[r];           // bit j: node j is on the root path of this node (self included)
+  const int n_anc = mask.count();          // >= 1
+  for (int j = tid; j < kMaxNodes; j += nt)
+    if (mask.has(j)) s_anc[mask.rank(j)] = j;
   __syncthreads();
 
   // ---- one round trip for everything else: the query rows, the

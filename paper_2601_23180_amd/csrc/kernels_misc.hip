@@ -9,20 +9,28 @@ namespace ts {
 // ------------------------------------------------------------------ set-up
 // Also clears `zero[0 .. n_zero)`: the tile counters of the split-K matmuls and the barrier
 // counters / abort word of the layer kernels, which must be zero when the pass starts.
-__global__ void k_setup(NodeTable tab, int rows, uint64_t *anc, int32_t *parent, int32_t *status, int32_t *zero,
-                        int n_zero) {
+__global__ void k_setup(NodeTable tab, int rows, int n_nodes, AncMask *anc, int32_t *parent, int32_t *status,
+                        int32_t *zero, int n_zero) {
   const int i = threadIdx.x;
   if (i < rows) {
-    anc[i] = tab.anc[i];
+    // root path of node i: walk up the parents (validated on the host: parent < node, root = -1)
+    const int base = (i / n_nodes) * n_nodes;
+    AncMask m;
+    m.lo = m.hi = 0ull;
+    for (int j = i - base, guard = 0; j >= 0 && guard < kMaxNodes; ++guard) {
+      m.set(j);
+      j = tab.parent[base + j];
+    }
+    anc[i] = m;
     parent[i] = tab.parent[i];
   }
   if (i == 0 && status != nullptr) *status = 0;
   for (int j = i; j < n_zero; j += kMaxRows) zero[j] = 0;
 }
 
-void launch_setup(hipStream_t st, const NodeTable &tab, int rows, uint64_t *anc, int32_t *parent,
+void launch_setup(hipStream_t st, const NodeTable &tab, int rows, int n_nodes, AncMask *anc, int32_t *parent,
                   int32_t *status, int32_t *zero, int n_zero) {
-  hipLaunchKernelGGL(k_setup, dim3(1), dim3(kMaxRows), 0, st, tab, rows, anc, parent, status, zero, n_zero);
+  hipLaunchKernelGGL(k_setup, dim3(1), dim3(kMaxRows), 0, st, tab, rows, n_nodes, anc, parent, status, zero, n_zero);
 }
 
 __global__ void k_wait_probe(int32_t *counter, int expect, unsigned long long limit, int32_t *abort_word,
@@ -397,7 +405,7 @@ void launch_draft_ranks(hipStream_t st, const float *logits, const int32_t *toke
 // One workgroup per sequence.  Threads fill the per-node outputs; thread 0 then walks the tree:
 // at the current node test the trust predicate first (tau_a = tau_m is an escalation), then
 // follow the lowest-numbered child whose draft token equals the verifier's argmax.
-__global__ __launch_bounds__(64) void k_decide(DecideArgs a) {
+__global__ __launch_bounds__(kMaxNodes) void k_decide(DecideArgs a) {
   __shared__ float s_conf[kMaxNodes], s_margin[kMaxNodes], s_ent[kMaxNodes];
   __shared__ int s_arg[kMaxNodes], s_tok[kMaxNodes], s_par[kMaxNodes], s_rank[kMaxNodes];
   const int b = blockIdx.x, i = threadIdx.x, M = a.n_nodes;
@@ -446,7 +454,7 @@ __global__ __launch_bounds__(64) void k_decide(DecideArgs a) {
 }
 
 void launch_decide(hipStream_t st, const DecideArgs &a) {
-  hipLaunchKernelGGL(k_decide, dim3(a.batch), dim3(64), 0, st, a);
+  hipLaunchKernelGGL(k_decide, dim3(a.batch), dim3(kMaxNodes), 0, st, a);
 }
 
 // Plain streaming copy: grid-stride over blocks of 4 x 256 16-byte vectors, four independent

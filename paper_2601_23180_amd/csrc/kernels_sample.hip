@@ -168,7 +168,8 @@ __global__ __launch_bounds__(64) void k_sample_walk(SampleArgs a) {
     if (a.out.confidence) a.out.confidence[r] = conf;
     if (a.out.margin) a.out.margin[r] = s_margin[i];
   }
-  if (a.out.path) a.out.path[b * TRISPEC_PATH_STRIDE + i] = -1;
+  if (a.out.path)
+    for (int j = i; j < TRISPEC_PATH_STRIDE; j += 64) a.out.path[b * TRISPEC_PATH_STRIDE + j] = -1;
   __syncthreads();
   if (i != 0) return;
   int cur = a.n_forced - 1, acc = 0, esc = 0, row = -1, mode = 0;   // mode: 0 none, 1 direct, 2 residual

@@ -20,6 +20,7 @@ static uint32_t rnd() {   // splitmix64, seeded: the run is reproducible
 }
 static int rint_in(int lo, int hi) { return lo + (int)(rnd() % (uint32_t)(hi - lo + 1)); }
 
+constexpr int kCap = TRISPEC_MAX_NODES + 16;   // room of the driver's own arrays: node counts up to a little past the limit
 static long g_calls = 0;
 #define EXPECT(cond)                                                              \
   do {                                                                            \
@@ -63,7 +64,7 @@ static void shapes() {
     if (rc == TRISPEC_OK) {
       size_t b = 0;
       for (int j = 0; j < 8; ++j) {
-        int r = trispec_workspace_bytes(m, rint_in(-1, 10), rint_in(-1, 70), &b);
+        int r = trispec_workspace_bytes(m, rint_in(-1, 10), rint_in(-1, kCap - 10), &b);
         EXPECT(r == TRISPEC_OK || r == TRISPEC_ENODES || r == TRISPEC_ESHAPE);
         r = trispec_kv_bytes(m, rint_in(-1, 10), 64 * rint_in(-1, 40) + (rnd() % 5 == 0), &b);
         EXPECT(r == TRISPEC_OK || r == TRISPEC_ENODES || r == TRISPEC_ECAPACITY);
@@ -88,13 +89,13 @@ static void shapes() {
 // Random tree, random root path (or a broken one), random prefix: the outputs must stay inside
 // their TRISPEC_MAX_NODES entries and, when the call succeeds, describe a valid tree.
 static void prune() {
-  int32_t tok[80], par[80], pos[80], path[80], pre[80];
+  int32_t tok[kCap], par[kCap], pos[kCap], path[kCap], pre[kCap];
   int32_t o_tok[TRISPEC_MAX_NODES + 1], o_par[TRISPEC_MAX_NODES + 1], o_pos[TRISPEC_MAX_NODES + 1],
       o_old[TRISPEC_MAX_NODES + 1];
   const int32_t guard = 0x5a5a5a5a;
   for (int it = 0; it < 20000; ++it) {
-    const int n = (rnd() % 50 == 0) ? rint_in(-2, 70) : rint_in(1, TRISPEC_MAX_NODES);
-    const int nn = n < 1 ? 1 : (n > 80 ? 80 : n);
+    const int n = (rnd() % 50 == 0) ? rint_in(-2, kCap - 10) : rint_in(1, TRISPEC_MAX_NODES);
+    const int nn = n < 1 ? 1 : (n > kCap ? kCap : n);
     par[0] = -1; pos[0] = 100; tok[0] = rint_in(0, 999);
     for (int i = 1; i < nn; ++i) {
       par[i] = rint_in(0, i - 1);
@@ -107,7 +108,7 @@ static void prune() {
     int plen = 0, cur = 0;
     path[plen++] = 0;
     while (true) {
-      int kids[80], nk = 0;
+      int kids[kCap], nk = 0;
       for (int i = cur + 1; i < nn; ++i) if (par[i] == cur) kids[nk++] = i;
       if (!nk || rnd() % 3 == 0) break;
       cur = kids[rnd() % nk];
@@ -115,11 +116,11 @@ static void prune() {
     }
     const bool break_path = rnd() % 40 == 0;
     if (break_path) path[rint_in(0, plen - 1)] = rint_in(-2, nn + 2);
-    const int n_pre = (rnd() % 4 == 0) ? rint_in(-1, 70) : 0;
-    for (int i = 0; i < 80; ++i) pre[i] = rint_in(0, 999);
+    const int n_pre = (rnd() % 4 == 0) ? rint_in(-1, kCap - 10) : 0;
+    for (int i = 0; i < kCap; ++i) pre[i] = rint_in(0, 999);
     o_tok[TRISPEC_MAX_NODES] = o_par[TRISPEC_MAX_NODES] = o_pos[TRISPEC_MAX_NODES] = o_old[TRISPEC_MAX_NODES] = guard;
     int32_t on = -7, of = -7;
-    const int rc = trispec_prune_reroot(tok, par, pos, n, path, (rnd() % 60 == 0) ? rint_in(-1, 70) : plen,
+    const int rc = trispec_prune_reroot(tok, par, pos, n, path, (rnd() % 60 == 0) ? rint_in(-1, kCap - 10) : plen,
                                         n_pre > 0 ? pre : nullptr, n_pre, 100 - (n_pre > 0 ? n_pre : 0),
                                         o_tok, o_par, o_pos, o_old, &on, &of);
     EXPECT(o_tok[TRISPEC_MAX_NODES] == guard && o_par[TRISPEC_MAX_NODES] == guard &&
@@ -155,7 +156,7 @@ static void verify_args() {
   trispec_verify_opts o;
   trispec_verify_out out;
   memset(&out, 0, sizeof out);
-  int32_t parents[2 * 80];
+  int32_t parents[2 * kCap];
   for (int it = 0; it < 3000; ++it) {
     memset(&o, 0, sizeof o);
     o.criterion = (rnd() % 8 == 0) ? rint_in(-1, 4) : TRISPEC_CRIT_MARGIN;
@@ -171,7 +172,7 @@ static void verify_args() {
     o.accept_top_k = (rnd() % 6 == 0) ? rint_in(-1, 5) : 0;
     o.adapter_dim = (rnd() % 6 == 0) ? rint_in(-4, 9) : 0;
     o.adapter_w = (rnd() % 6 == 0) ? (const void *)0x400000 : nullptr;
-    const int n = (rnd() % 6 == 0) ? rint_in(-1, 70) : 16;
+    const int n = (rnd() % 6 == 0) ? rint_in(-1, kCap - 10) : 16;
     // Two sequences of 16 nodes would be a valid call: something is wrong every time, so that
     // nothing is ever enqueued (a parent that is not an earlier node; NaN threshold for one node).
     const int stride = n > 0 ? n : 1;
@@ -223,7 +224,7 @@ static void ternary_args() {
   for (int it = 0; it < 200; ++it) {
     trispec_ternary_config d = c;
     switch (rnd() % 6) {
-      case 0: d.max_nodes = rint_in(-3, 80); break;
+      case 0: d.max_nodes = rint_in(-3, kCap); break;
       case 1: d.criterion = rint_in(-2, 6); break;
       case 2: d.kv_target = kp; break;
       case 3: d.workspace_proxy_bytes = rnd() % 4096; break;
@@ -237,7 +238,7 @@ static void ternary_args() {
     if (rc == TRISPEC_OK) EXPECT(trispec_ternary_destroy(x) == TRISPEC_OK);
   }
   EXPECT(trispec_ternary_create(&c, &t) == TRISPEC_OK && t);
-  int32_t par[80], tok[80];
+  int32_t par[kCap], tok[kCap];
   trispec_round_info info;
   EXPECT(trispec_ternary_round(t, par, tok, 4, 0.5f, &info) == TRISPEC_ESTATE);
   const int32_t one = 17;

@@ -87,7 +87,7 @@ def test_kv_and_workspace_sizes():
     assert lib.trispec_workspace_bytes(m, 1, 9, C.byref(n)) == 0 and n.value > 0
     small = n.value
     assert lib.trispec_workspace_bytes(m, 4, 60, C.byref(n)) == 0 and n.value > small
-    assert lib.trispec_workspace_bytes(m, 1, 65, C.byref(n)) == -3
+    assert lib.trispec_workspace_bytes(m, 1, 129, C.byref(n)) == -3
     assert lib.trispec_workspace_bytes(m, 8, 64, C.byref(n)) == -3  # 512 rows
     d = C.c_double()
     ctx = (C.c_int32 * 1)(128)
@@ -116,7 +116,7 @@ def test_verify_rejects_bad_arguments_before_any_launch():
     chain = [-1, 0, 1, 2]
     assert _verify_rc(m, kv, chain, 4, tokens=None) == -1
     assert _verify_rc(m, kv, chain, 0) == -3
-    assert _verify_rc(m, kv, list(range(-1, 64)), 65) == -3
+    assert _verify_rc(m, kv, list(range(-1, 128)), 129) == -3
     assert _verify_rc(m, kv, [0, 0, 1, 2], 4) == -4            # parents[0] must be -1
     assert _verify_rc(m, kv, [-1, 0, 2, 1], 4) == -4           # parents[i] < i
     assert _verify_rc(m, kv, [-1, 0, -1, 1], 4) == -4
@@ -158,11 +158,11 @@ def test_kv_commit_rejects_bad_arguments_before_any_launch():
         return lib.trispec_kv_commit(kv, arr, (C.c_int32 * 1)(n), None)
 
     assert lib.trispec_kv_commit(kv, None, (C.c_int32 * 1)(0), None) == -1
-    assert commit([0, 1], 65) == -3                     # count out of range
+    assert commit([0, 1], 129) == -3                    # count out of range
     assert commit([0, 1], -1) == -3
     assert commit([0, 2, 2], 3) == -4                   # not strictly increasing
     assert commit([1, 0], 2) == -4
-    assert commit([0, 64], 2) == -4                     # node id out of range
+    assert commit([0, 128], 2) == -4                    # node id out of range
     assert commit([0, 3, 6], 3) == -6                   # 250 + 6 >= 256
     assert commit([], 0) == 0                           # nothing to move: no launch, length unchanged
     assert _verify_rc(m, kv, list(range(-1, 6)), 7) == -6   # still 250 cached: 250 + 7 > 256
@@ -261,9 +261,9 @@ def test_prune_reroot_errors():
         B.prune_reroot(tok, [-1, 2, 0, 1], pos, [0])
     assert e.value.code == -4
     with pytest.raises(B.TriSpecError) as e:      # prefix + kept nodes exceed the node limit
-        B.prune_reroot(tok, par, pos, [0], list(range(62)), 0)
+        B.prune_reroot(tok, par, pos, [0], list(range(126)), 0)
     assert e.value.code == -3
-    assert len(B.prune_reroot(tok, par, pos, [0], list(range(60)), 0)["tokens"]) == 64
+    assert len(B.prune_reroot(tok, par, pos, [0], list(range(124)), 0)["tokens"]) == 128
 
 
 def test_ternary_driver_rejects_bad_arguments_and_kv_len_round_trip():
@@ -299,7 +299,7 @@ def test_ternary_driver_rejects_bad_arguments_and_kv_len_round_trip():
     rc, t = make()
     assert rc == 0
     assert make(scratch_dev=None)[0] == -1 and make(proxy=None)[0] == -1
-    assert make(max_nodes=0)[0] == -3 and make(max_nodes=65)[0] == -3
+    assert make(max_nodes=0)[0] == -3 and make(max_nodes=129)[0] == -3
     assert make(kv_target=kv_t2)[0] == -3                        # a cache of two sequences
     assert make(kv_target=kv_p)[0] == -9                         # the other model's cache
     assert make(target=mv, kv_target=kv_v)[0] == -9              # vocabularies differ

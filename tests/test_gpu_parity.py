@@ -110,6 +110,12 @@ def test_config1_tiny_fp32_chain_threshold_half():
     assert out["accepted_len"].item() == 0 and out["escalate"].item() == 1 and out["token"].item() == -1
 
 
+def test_fp32_model_with_100_nodes():
+    shape = SHAPES["tiny"]
+    case = make_case(shape, 29, [90], [gen_tree(100, 10, 4, 29)])
+    full_check(case, thresholds=(0.0, 0.5))
+
+
 def test_fp32_model_with_qk_norm():
     shape = SHAPES["tiny"].with_(qk_norm=True)
     case = make_case(shape, 23, [100], [gen_tree(20, 6, 3, 23)])
@@ -143,6 +149,12 @@ BF16_CASES = [
     ("max_nodes_64", TB, [130], lambda s: gen_tree(64, 8, 4, s)),
     ("chain64_deepest_paths", TB.with_(n_layers=1), [100], lambda s: gen_chain(64)),
     ("group4_nodes64_rows256", TB.with_(n_layers=1, n_q_heads=8), [150], lambda s: gen_tree(64, 12, 3, s)),
+    # more than 64 nodes per sequence (two mask words): up to the limit of 128, deep chains, 512 query rows per kv head
+    ("tree100_two_mask_words", TB, [200], lambda s: gen_tree(100, 10, 4, s)),
+    ("max_nodes_128", TB.with_(n_layers=1), [130], lambda s: gen_tree(128, 12, 4, s)),
+    ("chain128_deepest_paths", TB.with_(n_layers=1), [100], lambda s: gen_chain(128)),
+    ("group4_nodes128_rows512_per_kv_head", TB.with_(n_layers=1, n_q_heads=8), [150], lambda s: gen_tree(128, 12, 3, s)),
+    ("batch2_nodes128_rows256", TB.with_(n_layers=1), [70, 301], lambda s: gen_tree(128, 9, 4, s)),
     ("single_node", TB, [64], lambda s: gen_chain(1)),
     ("empty_context", TB, [0], lambda s: gen_tree(20, 5, 3, s)),
     ("many_splits", TB.with_(n_layers=1), [1100], lambda s: gen_tree(33, 8, 4, s)),
@@ -472,8 +484,9 @@ def test_pass_replayed_from_a_captured_graph_equals_eager():
 
 @pytest.mark.parametrize("ctx_lens,n_nodes,n_q_heads", [
     ((40000,), 33, 4), ((1000,), 33, 4),
-    ((7000,), 60, 8), ((6144,), 40, 8), ((6500, 300), 60, 8), ((6100,), 60, 8),
-], ids=["ctx40000", "ctx1000", "ctx7000_rows240", "ctx6144_rows160", "ctx6500_300_rows240", "ctx6100_rows240"])
+    ((7000,), 60, 8), ((6144,), 40, 8), ((6500, 300), 60, 8), ((6100,), 60, 8), ((6400,), 128, 8),
+], ids=["ctx40000", "ctx1000", "ctx7000_rows240", "ctx6144_rows160", "ctx6500_300_rows240", "ctx6100_rows240",
+        "ctx6400_nodes128_rows512"])
 def test_long_context_with_synthetic_cache(ctx_lens, n_nodes, n_q_heads):
     """Contexts beyond what the oracle can prefill: N(0,1) caches as in the full-size workloads.
     40000 keys: 63 key splits of 640 keys (the merge walks more than one batch of splits, a split
