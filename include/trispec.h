@@ -504,7 +504,9 @@ int trispec_ternary_round(trispec_ternary *t, const int32_t *parents_host, const
  *   p_draft_work_dev      device work buffer [max_nodes - 1, vocab] fp32 (the draft rows shifted
  *                         behind the lagging tokens of the target's longer chain)
  * The decision kernels run on the library's own scratch area (trispec_sample_decide_static: calls
- * that overlap on one GPU race).  Errors: those of trispec_ternary_round and trispec_sample_decide.
+ * that overlap on one GPU race).  A chain — the draft chain, and the target's longer chain of lagging
+ * tokens + draft chain — holds at most min(max_nodes, 64) nodes; a longer lag is taken in by plain
+ * target passes first.  Errors: those of trispec_ternary_round and trispec_sample_decide.
  */
 typedef struct {
   float temperature;                 /* T > 0 */

@@ -951,7 +951,6 @@ SampleLayout sample_layout(int batch, int n_nodes, int vocab) {
   L.total = off;
   return L;
 }
-constexpr int kMaxChain = 64;   // nodes of a chain in the sampling form (one lane of a wavefront per node)
 bool sample_shape_ok(int batch, int n_nodes) {
   return batch >= 1 && batch <= kMaxBatch && n_nodes >= 1 && n_nodes <= kMaxChain && batch * n_nodes <= kMaxRows;
 }

@@ -19,6 +19,7 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 constexpr int kMaxRows = TRISPEC_MAX_ROWS;
 constexpr int kMaxBatch = TRISPEC_MAX_BATCH;
 constexpr int kMaxNodes = TRISPEC_MAX_NODES;
+constexpr int kMaxChain = 64;        // nodes of a chain in the sampling form (one lane of a wavefront per node)
 constexpr int kMaxGroup = 8;         // query heads per kv head (bf16 attention)
 constexpr int kMaxSplitK = 32;       // k-splits of one matmul
 constexpr int kMaxAttnSplits = 64;   // context splits of one attention call

@@ -328,7 +328,10 @@ int trispec_ternary_round_sample(trispec_ternary *t, const int32_t *tokens_host,
       !sr->u_accept_target_host || (n_nodes > 1 && !sr->p_draft_dev))
     return TRISPEC_ENULL;
   if (!t->started) return TRISPEC_ESTATE;
-  if (n_nodes < 1 || n_nodes > t->cfg.max_nodes) return TRISPEC_ENODES;
+  // the sampling decision takes chains of up to kMaxChain nodes: that bounds the draft chain and
+  // the target's longer chain (lagging tokens + draft chain) alike
+  const int chain_cap = t->cfg.max_nodes < kMaxChain ? t->cfg.max_nodes : kMaxChain;
+  if (n_nodes < 1 || n_nodes > chain_cap) return TRISPEC_ENODES;
   if (!tokens_ok(t, tokens_host + 1, n_nodes - 1)) return TRISPEC_EARG;
   trispec_round_info info;
   memset(&info, 0, sizeof info);
@@ -356,7 +359,7 @@ int trispec_ternary_round_sample(trispec_ternary *t, const int32_t *tokens_host,
     const int tau_m = pr.accepted_len;
     int t_len = kvt->ctx_len[0];
     int u = (int)t->seq.size() - 1 - t_len;                  // tokens the target has not cached yet
-    if (u + M > t->cfg.max_nodes) {
+    if (u + M > chain_cap) {
       rc = ingest(t, true, t->seq.data() + t_len, u, &info.catch_up);
       if (rc != TRISPEC_OK) return rc;
       t_len = kvt->ctx_len[0];

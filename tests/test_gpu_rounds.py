@@ -295,3 +295,31 @@ def _sampling_rounds_vs_oracle(shape_name, lam, max_nodes, seed_p, seed_t):
     if max_nodes == 12:
         assert any(w["catch_up"] for w in want["rounds"]) or any(w["escalate"] and w["u"] > 0 for w in want["rounds"])
     return True
+
+
+def test_sampling_rounds_after_a_long_lag_with_the_default_node_limit():
+    """With the library's largest pass (128 nodes) the target may lag by more tokens than a sampling
+    chain can hold (64 nodes): the driver must then take the lagging tokens in by plain passes first,
+    and end where a driver limited to 64-node passes ends."""
+    from paper_2601_23180_amd import TernaryDecoder
+    shape, T, k = SHAPES["tiny"], 0.8, 4
+    Wp = oracle_weights(shape, 71)
+    prompt = gen_context_tokens(shape.vocab, 12, 71).tolist()
+    drafter = _model_drafter(Wp, shape, k, T, 71, noise=0.6)
+    runs = []
+    for max_nodes in (128, 64):
+        dec = TernaryDecoder(device_model(shape, 71), device_model(shape, 72), 512, max_nodes=max_nodes)
+        dec.start(prompt)
+        recs = []
+        for r in range(34):
+            lam = 0.0 if r < 32 else 2.0              # 32 rounds that end at the proxy, then two escalations
+            d = drafter(r, dec.seq, dec.kv_p.ctx_len[0])
+            recs.append(dec.round_sample(d["tokens"], d["p_draft"], d["u_accept_p"], d["u_sample_p"], d["u_accept_t"],
+                                         d["u_sample_t"], lam, T))
+        lag = len(dec.seq) - len(prompt)
+        runs.append((dec.seq, dec.kv_p.ctx_len, dec.kv_t.ctx_len, [r["escalate"] for r in recs], recs[32]["catch_up"]))
+        dec.close()
+        assert lag > 64
+    assert runs[0][:4] == runs[1][:4]
+    assert runs[0][3][:32] == [0] * 32 and runs[0][3][32:] == [1, 1]
+    assert runs[0][4] >= 1 and runs[1][4] >= 1        # both had to catch up before the escalated round
